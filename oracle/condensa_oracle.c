@@ -1,0 +1,285 @@
+/*
+ * CPU oracle for the compression (C) step of the L-C algorithm.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, scalar statement of
+ * what the compression step computes; the GPU library is checked against it.
+ * It shares no code with the GPU library and must never be called from it.
+ *
+ * What is written out here (paper passages in brackets):
+ *   - unstructured magnitude pruning to an exact kept count: the weights of
+ *     lower magnitude are set to zero [Background, "thresholding (magnitude
+ *     based)"; Section 3.3, pruning as D(Theta) = Theta with fewer non-zeros;
+ *     Section 3.1 "magnitude threshold computation from a sparsity"];
+ *     sparsity is the proportion of zero-valued parameters [Introduction];
+ *   - low-precision approximation, binary32 -> binary16 and back [Background;
+ *     Section 3.1 quantize/dequantize; Section 3.3 w_i = theta_i];
+ *   - aggregation of filters (3-D blocks) and 2-D blocks followed by
+ *     selection [Table 1, FilterPrune / BlockPrune; Section 3.1];
+ *   - the C step as C(w) = argmin ||w - D(Theta)||^2 inside one augmented
+ *     Lagrangian iteration with multipliers lambda and penalty mu
+ *     [Section 3.3; constants in "L-C Optimizer Settings"].
+ *
+ * Readings where the paper is silent (identical on the GPU side by
+ * specification, not by shared code):
+ *   - kept count k = llround(density * N) (half away from zero), clamped;
+ *   - order is by the bit pattern of |x| (so -0 == +0, inf above finite, NaN
+ *     patterns above inf); ties go to the lowest flat index;
+ *   - pruned positions hold +0.0; kept values are copied bit for bit;
+ *   - structure keys are sums of squares accumulated in binary64 in memory
+ *     order inside the structure (row-major inside a 2-D block);
+ *   - L-C arithmetic is binary32, one rounding per operation, in the order
+ *     t = lambda/mu; v = w - t; theta = prune(v); e = w - theta; p = mu*e;
+ *     lambda' = lambda - p; g = p - lambda'.
+ *
+ * Selection is sort based: the k-th largest key of a fully sorted copy.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    uint64_t n;             /* population size                                   */
+    uint64_t k;             /* kept count                                        */
+    uint64_t n_gt;          /* keys strictly above the threshold key             */
+    uint64_t n_tie_kept;    /* keys equal to the threshold that are kept         */
+    uint64_t n_tie;         /* keys equal to the threshold                       */
+    uint64_t threshold_key; /* k-th largest key; all ones when k == 0            */
+    uint64_t tie_end;       /* ties with index < tie_end are the kept ones; n    */
+                            /* when every tie is kept, 0 when k == 0             */
+} oracle_select;
+
+/* ---- kept count -------------------------------------------------------- */
+
+uint64_t oracle_kept_count(double density, uint64_t n)
+{
+    double x = density * (double)n;
+    long long r = llround(x);
+    if (r < 0) return 0;
+    if ((uint64_t)r > n) return n;
+    return (uint64_t)r;
+}
+
+/* ---- keys -------------------------------------------------------------- */
+
+static uint32_t f32_bits(float x) { uint32_t b; memcpy(&b, &x, 4); return b; }
+static float bits_f32(uint32_t b) { float x; memcpy(&x, &b, 4); return x; }
+static uint64_t f64_bits(double x) { uint64_t b; memcpy(&b, &x, 8); return b; }
+
+/* magnitude key of a binary32 value: its bit pattern without the sign */
+void oracle_magnitude_keys(const float* x, uint64_t n, uint64_t* keys)
+{
+    for (uint64_t i = 0; i < n; ++i) keys[i] = (uint64_t)(f32_bits(x[i]) & 0x7FFFFFFFu);
+}
+
+/* key of a non-negative binary64 aggregate: its bit pattern without the sign */
+void oracle_aggregate_keys(const double* s, uint64_t n, uint64_t* keys)
+{
+    for (uint64_t i = 0; i < n; ++i) keys[i] = f64_bits(s[i]) & 0x7FFFFFFFFFFFFFFFull;
+}
+
+static int cmp_desc_u64(const void* a, const void* b)
+{
+    uint64_t x = *(const uint64_t*)a, y = *(const uint64_t*)b;
+    return (x < y) - (x > y);
+}
+
+void oracle_sort_desc(uint64_t* keys, uint64_t n)
+{
+    qsort(keys, (size_t)n, sizeof(uint64_t), cmp_desc_u64);
+}
+
+/* ---- selection --------------------------------------------------------- */
+
+/*
+ * keys        : the population in flat-index order
+ * sorted_desc : the same keys sorted in descending order
+ * keep[i]     : 1 for the k elements of largest key, ties to the lowest index
+ */
+void oracle_select_keep(const uint64_t* keys, const uint64_t* sorted_desc, uint64_t n,
+                        uint64_t k, oracle_select* sel, uint8_t* keep)
+{
+    sel->n = n;
+    sel->k = k;
+    if (k == 0) {
+        sel->n_gt = 0; sel->n_tie_kept = 0; sel->n_tie = 0;
+        sel->threshold_key = UINT64_MAX; sel->tie_end = 0;
+        for (uint64_t i = 0; i < n; ++i) keep[i] = 0;
+        return;
+    }
+    const uint64_t T = sorted_desc[k - 1];
+    uint64_t n_gt = 0, n_tie = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (keys[i] > T) ++n_gt;
+        else if (keys[i] == T) ++n_tie;
+    }
+    const uint64_t r = k - n_gt;
+    uint64_t seen = 0, last_kept_tie = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        if (keys[i] > T) keep[i] = 1;
+        else if (keys[i] == T && seen < r) { keep[i] = 1; ++seen; last_kept_tie = i; }
+        else keep[i] = 0;
+    }
+    sel->n_gt = n_gt;
+    sel->n_tie_kept = r;
+    sel->n_tie = n_tie;
+    sel->threshold_key = T;
+    sel->tie_end = (r == n_tie) ? n : last_kept_tie + 1;
+}
+
+/* theta[i] = keep ? x[i] : +0.0  (values copied bit for bit) */
+void oracle_apply_keep(const float* x, const uint8_t* keep, uint64_t n, float* theta)
+{
+    for (uint64_t i = 0; i < n; ++i) theta[i] = keep[i] ? x[i] : bits_f32(0u);
+}
+
+/* ---- binary32 <-> binary16 -------------------------------------------- */
+
+/* round to nearest, ties to even; overflow to infinity; gradual underflow */
+static uint16_t f32_to_f16_bits(uint32_t b)
+{
+    const uint16_t sign = (uint16_t)((b >> 16) & 0x8000u);
+    const uint32_t a = b & 0x7FFFFFFFu;
+    if (a > 0x7F800000u)                         /* NaN: quiet, top payload bits */
+        return (uint16_t)(sign | 0x7E00u | ((a >> 13) & 0x03FFu));
+    if (a == 0x7F800000u) return (uint16_t)(sign | 0x7C00u);
+    const uint32_t e = a >> 23;                  /* biased binary32 exponent     */
+    const uint32_t m = a & 0x007FFFFFu;
+    if (e >= 143u) return (uint16_t)(sign | 0x7C00u);          /* |x| >= 2^16    */
+    if (e >= 113u) {                             /* normal binary16 (before rounding) */
+        uint32_t h = ((e - 112u) << 10) | (m >> 13);
+        const uint32_t rem = m & 0x1FFFu;
+        if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h; /* carry may reach inf */
+        return (uint16_t)(sign | h);
+    }
+    if (e < 102u) return sign;                   /* |x| < 2^-25 -> zero          */
+    /* subnormal binary16: value = M * 2^(e-150), unit 2^-24, shift = 126 - e in [14,24] */
+    const uint32_t M = m | 0x00800000u;
+    const uint32_t s = 126u - e;
+    uint32_t h = M >> s;
+    const uint32_t rem = M & ((1u << s) - 1u);
+    const uint32_t half = 1u << (s - 1u);
+    if (rem > half || (rem == half && (h & 1u))) ++h;
+    return (uint16_t)(sign | h);
+}
+
+/* exact widening */
+static uint32_t f16_to_f32_bits(uint16_t h)
+{
+    const uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    const uint32_t e = (h >> 10) & 0x1Fu;
+    uint32_t m = h & 0x03FFu;
+    if (e == 31u) return sign | 0x7F800000u | (m << 13);
+    if (e == 0u) {
+        if (m == 0u) return sign;
+        int shift = 0;                           /* normalise the subnormal      */
+        while (!(m & 0x0400u)) { m <<= 1; ++shift; }
+        m &= 0x03FFu;
+        return sign | ((uint32_t)(113 - shift) << 23) | (m << 13);
+    }
+    return sign | ((e + 112u) << 23) | (m << 13);
+}
+
+void oracle_quantize_f16(const float* x, uint64_t n, uint16_t* q, float* dq /* nullable */)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint16_t h = f32_to_f16_bits(f32_bits(x[i]));
+        q[i] = h;
+        if (dq) dq[i] = bits_f32(f16_to_f32_bits(h));
+    }
+}
+
+void oracle_dequantize_f16(const uint16_t* q, uint64_t n, float* dq)
+{
+    for (uint64_t i = 0; i < n; ++i) dq[i] = bits_f32(f16_to_f32_bits(q[i]));
+}
+
+/* ---- structure aggregates --------------------------------------------- */
+
+/* filters of one tensor [n_filters, len]: S_f = sum of squares, binary64, memory order */
+void oracle_filter_sumsq(const float* w, uint64_t n_filters, uint64_t len, double* s)
+{
+    for (uint64_t f = 0; f < n_filters; ++f) {
+        double acc = 0.0;
+        for (uint64_t e = 0; e < len; ++e) {
+            const double x = (double)w[f * len + e];
+            acc = acc + x * x;
+        }
+        s[f] = acc;
+    }
+}
+
+/* 2-D blocks of one matrix [rows, cols]; block id row-major over the block grid;
+ * inside a block the elements are added in row-major order */
+void oracle_block_sumsq(const float* w, uint64_t rows, uint64_t cols, uint64_t bh, uint64_t bw, double* s)
+{
+    const uint64_t gr = rows / bh, gc = cols / bw;
+    for (uint64_t br = 0; br < gr; ++br)
+        for (uint64_t bc = 0; bc < gc; ++bc) {
+            double acc = 0.0;
+            for (uint64_t y = 0; y < bh; ++y)
+                for (uint64_t x = 0; x < bw; ++x) {
+                    const double v = (double)w[(br * bh + y) * cols + bc * bw + x];
+                    acc = acc + v * v;
+                }
+            s[br * gc + bc] = acc;
+        }
+}
+
+void oracle_norms(const double* s, uint64_t n, float* norms)
+{
+    for (uint64_t i = 0; i < n; ++i) norms[i] = (float)sqrt(s[i]);
+}
+
+/* theta/mask of one tensor given the keep flag of each of its structures */
+void oracle_filter_apply(const float* w, uint64_t n_filters, uint64_t len, const uint8_t* keep,
+                         float* theta, uint8_t* mask)
+{
+    for (uint64_t f = 0; f < n_filters; ++f)
+        for (uint64_t e = 0; e < len; ++e) {
+            const uint64_t i = f * len + e;
+            theta[i] = keep[f] ? w[i] : bits_f32(0u);
+            mask[i] = keep[f] ? 1 : 0;
+        }
+}
+
+void oracle_block_apply(const float* w, uint64_t rows, uint64_t cols, uint64_t bh, uint64_t bw,
+                        const uint8_t* keep, float* theta, uint8_t* mask)
+{
+    const uint64_t gc = cols / bw;
+    for (uint64_t r = 0; r < rows; ++r)
+        for (uint64_t c = 0; c < cols; ++c) {
+            const uint64_t b = (r / bh) * gc + (c / bw);
+            const uint64_t i = r * cols + c;
+            theta[i] = keep[b] ? w[i] : bits_f32(0u);
+            mask[i] = keep[b] ? 1 : 0;
+        }
+}
+
+/* ---- L-C step ---------------------------------------------------------- */
+
+/* v = w - lambda/mu, binary32, one rounding per operation */
+void oracle_lc_shifted(const float* w, const float* lambda, uint64_t n, float mu, float* v)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        volatile float t = lambda[i] / mu;
+        volatile float d = w[i] - t;
+        v[i] = d;
+    }
+}
+
+/* theta = keep ? v : +0; e = w - theta; p = mu*e; lambda' = lambda - p; g = p - lambda' */
+void oracle_lc_update(const float* w, const float* lambda, const float* v, const uint8_t* keep,
+                      uint64_t n, float mu, float* theta, float* lambda_out, float* grad)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        const float th = keep[i] ? v[i] : bits_f32(0u);
+        volatile float e = w[i] - th;
+        volatile float p = mu * e;
+        volatile float l = lambda[i] - p;
+        volatile float g = p - l;
+        theta[i] = th;
+        lambda_out[i] = l;
+        grad[i] = g;
+    }
+}

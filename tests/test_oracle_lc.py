@@ -1,0 +1,91 @@
+"""Pins for the oracle's L-C compression step with multiplier update (CPU only).
+
+Section 3.3: augmented-Lagrangian L-C; the C step is the best compression of the
+shifted weights w - lambda/mu; constants mu_0 = 1e-3, a = 1.1 ("L-C Optimizer
+Settings").  Pins: numpy float32 re-evaluation one rounded operation at a time,
+the lambda = 0 reduction to plain pruning, and algebraic identities.
+"""
+import numpy as np
+
+import oracle
+
+
+def _case(n=5000, seed=0):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    lam = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    return w, lam
+
+
+def test_matches_numpy_float32_one_rounding_per_operation():
+    w, lam = _case()
+    mu = np.float32(1e-3)
+    res = oracle.lc_step([w], [lam], float(mu), 0.1)
+    t = lam / mu                                  # float32 ufuncs round once per op
+    v = w - t
+    assert np.array_equal(res["v"][0].view(np.uint32), v.view(np.uint32))
+    pr = oracle.prune([v], [0.1])[0]
+    assert np.array_equal(res["mask"][0], pr["mask"][0]) and res["select"] == pr["select"]
+    theta = np.where(pr["mask"][0] == 1, v, np.float32(0))
+    e = w - theta
+    p = mu * e
+    lam2 = lam - p
+    g = p - lam2
+    for name, want in (("theta", theta), ("lambda", lam2), ("grad", g)):
+        assert np.array_equal(res[name][0].view(np.uint32), want.view(np.uint32)), name
+
+
+def test_augmented_lagrangian_algebra_in_float64():
+    """Exact-arithmetic statement lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
+    evaluated in binary64; the binary32 oracle agrees to rounding (kept entries cancel to ~0,
+    so the bound is absolute: a few ulp of |lambda|)."""
+    w, lam = _case(seed=1)
+    res = oracle.lc_step([w], [lam], 1e-3, 0.1)
+    mu = float(np.float32(1e-3))
+    m = res["mask"][0].astype(bool)
+    th = res["theta"][0].astype(np.float64)
+    lam2 = lam.astype(np.float64) - mu * (w.astype(np.float64) - th)
+    assert np.allclose(res["lambda"][0], lam2, rtol=0, atol=1e-8)
+    assert np.allclose(res["grad"][0], mu * (w.astype(np.float64) - th) - lam2, rtol=0, atol=1e-8)
+    assert np.all(th[~m] == 0)
+    # a sign slip (lambda + mu e) or a dropped term would be off by ~|lambda| ~ 1e-2
+    assert not np.allclose(res["lambda"][0], lam.astype(np.float64) + mu * (w - th), rtol=0, atol=1e-4)
+
+
+def test_zero_multipliers_reduce_to_direct_compression():
+    """lambda = 0: theta = prune(w) (direct compression, Section 3.3) and lambda' = -mu (w - theta)."""
+    w, _ = _case(seed=2)
+    lam = np.zeros_like(w)
+    res = oracle.lc_step([w], [lam], 1e-3, 0.25)
+    pr = oracle.prune([w], [0.25])[0]
+    assert np.array_equal(res["mask"][0], pr["mask"][0])
+    assert np.array_equal(res["theta"][0].view(np.uint32), pr["theta"][0].view(np.uint32))
+    m = res["mask"][0].astype(bool)
+    assert np.all(res["lambda"][0][m] == 0)                        # e = w - w = 0 on kept
+    assert np.array_equal(res["lambda"][0][~m], -(np.float32(1e-3) * w[~m]))
+
+
+def test_identities_kept_and_dropped():
+    w, lam = _case(seed=3)
+    mu = np.float32(1e-3)
+    res = oracle.lc_step([w], [lam], float(mu), 0.1)
+    m = res["mask"][0].astype(bool)
+    assert int(m.sum()) == oracle.kept_count(0.1, w.size)
+    assert np.array_equal(res["theta"][0][m].view(np.uint32), res["v"][0][m].view(np.uint32))
+    # dropped: e = w exactly, so lambda' = lambda - mu*w
+    assert np.array_equal(res["lambda"][0][~m], lam[~m] - mu * w[~m])
+    # g uses the NEW multiplier: with the old one it would be -lambda' bit for bit
+    p = mu * (w - res["theta"][0])
+    assert np.array_equal(p - lam, -res["lambda"][0])            # equal as values (+0 == -0)
+    assert not np.array_equal(res["grad"][0].view(np.uint32), (p - lam).view(np.uint32))
+    assert np.array_equal(res["grad"][0].view(np.uint32), (p - res["lambda"][0]).view(np.uint32))
+
+
+def test_global_over_several_tensors():
+    rng = np.random.default_rng(4)
+    ws = [(rng.standard_normal(s) * 0.01).astype(np.float32) for s in ((7, 9), (33,), (4, 4, 3, 3))]
+    ls = [(rng.standard_normal(t.shape) * 0.01).astype(np.float32) for t in ws]
+    res = oracle.lc_step(ws, ls, 1e-3, 0.3)
+    flat = oracle.lc_step([np.concatenate([t.reshape(-1) for t in ws])], [np.concatenate([t.reshape(-1) for t in ls])], 1e-3, 0.3)
+    assert res["select"] == flat["select"]
+    assert np.array_equal(np.concatenate([t.reshape(-1) for t in res["grad"]]).view(np.uint32), flat["grad"][0].view(np.uint32))
