@@ -1,0 +1,219 @@
+/*
+ * condensa.h -- C ABI of the compression step of Condensa's L-C optimizer on MI355X (gfx950).
+ *
+ * The library applies the paper's per-layer compression operators (Section 3.1: quantize /
+ * dequantize, prune, filter_prune, blockprune) in their whole-model "scheme" form (Table 1:
+ * Quantize, Prune, FilterPrune, BlockPrune, Compose) to a list of weight tensors, and the
+ * compression (C) step of the L-C algorithm with its multiplier update (Section 3.3).  A target
+ * sparsity s (Introduction: proportion of zero-valued parameters) is passed as the density
+ * d = 1 - s; the library turns it into an exact kept count and a magnitude threshold
+ * (Section 3.1: "magnitude threshold computation from a sparsity").
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Pointers named *_dev and every pointer stored inside a table are DEVICE pointers.  The
+ *    tables themselves (arrays of condensa_tensor, arrays of pointers, arrays of densities) are
+ *    HOST memory; they are consumed before the call returns and may be freed right after.
+ *  - The caller owns all memory, including the workspace.  The library allocates no device
+ *    memory and frees none.  (It keeps a small pinned host staging ring for the tables.)
+ *  - All device work is enqueued on `stream` (a hipStream_t, NULL = the default stream) and the
+ *    call returns without waiting.  Results, including condensa_select records, are in device
+ *    memory once the stream has reached that point.
+ *  - Return value: CONDENSA_OK or a negative error code.  Argument errors are found before
+ *    anything is enqueued, so a failing call has no side effect.
+ *  - Tensors are fp32, row-major, contiguous.  16-byte aligned pointers get 128-bit accesses,
+ *    any other alignment is accepted and takes a scalar path.
+ *  - The flat index of an element is its position in the concatenation of the call's tensors in
+ *    table order.  Tensors with zero elements and calls with zero tensors are valid.
+ *  - kept count  k = llround(density * N) (binary64 product, halves away from zero), clamped to
+ *    [0, N]; density must lie in [0, 1].
+ *  - Ordering key of a value x is the bit pattern of |x|: -0 equals +0, infinities rank above
+ *    every finite value and NaN patterns above infinity.  Among equal keys the lowest index is
+ *    kept first.  Pruned positions are written as +0.0; kept values are copied bit for bit.
+ *  - Masks are one byte per element, 1 = kept, 0 = pruned.
+ *  - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef CONDENSA_H
+#define CONDENSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t condensa_status;
+
+enum {
+    CONDENSA_OK            = 0,
+    CONDENSA_ERR_NULL      = -1,  /* a required pointer is NULL                                  */
+    CONDENSA_ERR_SIZE      = -2,  /* negative count, too many tensors/densities, size overflow   */
+    CONDENSA_ERR_DENSITY   = -3,  /* density outside [0,1] or NaN; mu not finite and positive    */
+    CONDENSA_ERR_SHAPE     = -4,  /* ndim/shape not valid for the operator, block does not divide */
+    CONDENSA_ERR_WORKSPACE = -5,  /* workspace NULL, misaligned (256 B) or too small             */
+    CONDENSA_ERR_ARG       = -6,  /* bad scope / option / aliasing                               */
+    CONDENSA_ERR_HIP       = -7   /* a HIP runtime call failed (see condensa_last_hip_error)     */
+};
+
+enum { CONDENSA_SCOPE_GLOBAL = 0,       /* one ranking over all tensors of the call              */
+       CONDENSA_SCOPE_PER_TENSOR = 1 }; /* every tensor ranked on its own                         */
+
+enum { CONDENSA_OP_PRUNE = 0, CONDENSA_OP_FILTER_PRUNE = 1, CONDENSA_OP_BLOCK_PRUNE = 2,
+       CONDENSA_OP_QUANTIZE = 3, CONDENSA_OP_LC_STEP = 4 };
+
+#define CONDENSA_MAX_DENSITIES 16
+#define CONDENSA_MAX_TENSORS   65536
+
+/* One weight tensor (Section 3.1: operators are applied per layer; schemes walk all layers). */
+typedef struct {
+    const float* w;        /* device, fp32 row-major contiguous; may be NULL iff it has 0 elements */
+    int64_t      shape[4]; /* conv [Cout,Cin,kh,kw]; matrix [R,C]; vector [n]; unused dims ignored */
+    int32_t      ndim;     /* 1..4                                                                 */
+    int32_t      reserved; /* must be 0                                                            */
+} condensa_tensor;
+
+/*
+ * Outcome of one ranking (one per density, and per tensor under PER_TENSOR scope).  Element
+ * pruning ranks the 31-bit |x| patterns, structure pruning the binary64 patterns of the
+ * structures' sums of squares.  An element/structure with key K and index i (flat index for
+ * GLOBAL scope, index inside the tensor for PER_TENSOR) is kept iff
+ *      K > threshold_key  ||  (K == threshold_key && i < tie_end).
+ */
+typedef struct {
+    uint64_t n;             /* population size                                                     */
+    uint64_t k;             /* kept count                                                          */
+    uint64_t n_gt;          /* keys strictly above the threshold                                   */
+    uint64_t n_tie_kept;    /* keys equal to the threshold that are kept ( = k - n_gt )            */
+    uint64_t n_tie;         /* keys equal to the threshold                                         */
+    uint64_t threshold_key; /* the k-th largest key; UINT64_MAX when k == 0                        */
+    uint64_t tie_end;       /* n when all ties are kept, else 1 + index of the last kept tie; 0 if k == 0 */
+    uint64_t path;          /* diagnostic: 1 = radix levels over the data, 2 = sampled window      */
+} condensa_select;
+
+/*
+ * Bytes of workspace (256-byte aligned device memory) the operator needs for the given problem:
+ * total_elems = sum of tensor sizes, n_structures = number of filters/blocks (0 for element
+ * operators).  Returns 0 for invalid arguments.  CONDENSA_OP_QUANTIZE needs none (returns 0).
+ */
+size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures,
+                                int n_tensors, int n_densities, int scope);
+
+/*
+ * Prune() scheme / prune operator: unstructured magnitude pruning (Background: magnitude
+ * thresholding; Section 3.3: Theta has fewer non-zeros "by removing lower magnitude weights";
+ * Table 1).  Serves n_densities target densities from one sweep over the weights, which is what a
+ * sparsity search with up to 10 samples per search (Results) asks of the same reference weights.
+ * Optionally fuses Quantize(float16) (Evaluation, Objective 1: Compose([Prune(), Quantize(float16)])).
+ *
+ *  tensors, n_tensors     host table of the weight tensors
+ *  densities, n_densities host array, 1..CONDENSA_MAX_DENSITIES values in [0,1]
+ *  scope                  GLOBAL: one threshold for the whole call; PER_TENSOR: one per tensor
+ *  theta                  NULL, or host table [n_densities * n_tensors] (entry j*n_tensors + t) of
+ *                         device fp32 outputs shaped like tensor t; entries may be NULL (skipped).
+ *                         theta may alias w only when n_densities == 1.
+ *  theta_f16              same layout, binary16 bit patterns of round-to-nearest-even(theta)
+ *  mask                   same layout, bytes
+ *  results_dev            device array: [n_densities] for GLOBAL, [n_densities * n_tensors] for
+ *                         PER_TENSOR (entry j*n_tensors + t)
+ *  workspace_dev/bytes    see condensa_workspace_bytes(CONDENSA_OP_PRUNE, ...)
+ * With theta, theta_f16 and mask all NULL only the thresholds are computed.
+ */
+condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors,
+                               const double* densities, int n_densities, int scope,
+                               float* const* theta, uint16_t* const* theta_f16, uint8_t* const* mask,
+                               condensa_select* results_dev,
+                               void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * FilterPrune scheme / filter_prune operator (Table 1: "aggregates and prunes filters (3D
+ * blocks)"; Section 3.1: filter aggregation).  Every tensor must have ndim == 4; filter f of a
+ * tensor is the contiguous run of Cin*kh*kw weights of output channel f.  Aggregate: sum of
+ * squares in binary64, added in memory order (the ranking of L2 norms); `density` counts filters.
+ * Structure ids run over all filters of the call in table order.
+ *
+ *  theta, mask        NULL or host tables [n_tensors] of device outputs (entries may be NULL)
+ *  sumsq_dev          NULL or device double [F]: the aggregates (the ranking keys)
+ *  norms_dev          NULL or device float  [F]: (float)sqrt(sumsq)
+ *  keep_idx_dev       NULL or device int32  [F]: ids of kept filters, ascending; entries past the
+ *                     kept count are left untouched
+ *  structure_mask_dev NULL or device bytes  [F]
+ *  results_dev        device: 1 record (GLOBAL) or n_tensors records (PER_TENSOR)
+ */
+condensa_status condensa_filter_prune(const condensa_tensor* tensors, int n_tensors,
+                                      double density, int scope,
+                                      float* const* theta, uint8_t* const* mask,
+                                      double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                      uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                      void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * BlockPrune scheme / blockprune operator for 2-D blocks (Table 1: "aggregates and prunes n-D
+ * blocks of size bs").  Every tensor must have ndim == 2 with block_h | R and block_w | C
+ * (CONDENSA_ERR_SHAPE otherwise).  Block ids are row-major over the block grid of a matrix,
+ * matrices in table order; inside a block the squares are added in row-major order.
+ * Other arguments as for condensa_filter_prune.
+ */
+condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tensors,
+                                     int block_h, int block_w, double density, int scope,
+                                     float* const* theta, uint8_t* const* mask,
+                                     double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                     uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                     void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * Quantize(float16) scheme / quantize + dequantize operators (Section 3.1; Background:
+ * low-precision approximation = quantisation with a fixed codebook).  q = binary16 bits of x
+ * rounded to nearest even (overflow to infinity, gradual underflow, NaN -> quiet NaN keeping the
+ * sign and the top ten payload bits); dq = exact widening of q.  q_dev or dq_dev may be NULL (not
+ * both).  n may be 0.  x_dev may alias dq_dev.
+ */
+condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev,
+                                  void* stream);
+
+/* dequantize operator alone: dq = exact widening of the binary16 bit patterns q. */
+condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream);
+
+/*
+ * One compression step of the L-C algorithm with the augmented-Lagrangian updates (Section 3.3;
+ * mu_j = mu_0 a^j is the caller's schedule, "L-C Optimizer Settings").  Per element, in binary32
+ * with one rounding per operation and no fused multiply-add:
+ *      t = lambda / mu;  v = w - t;
+ *      theta = prune(v) at `density`, one global ranking over all tensors of the call;
+ *      e = w - theta;  p = mu * e;  lambda' = lambda - p;  g = p - lambda'.
+ * theta is C(w - lambda/mu), lambda' the new multiplier estimate and g = mu (w - theta) - lambda'
+ * the gradient of the penalty that the next learning step adds to the loss gradient.
+ *
+ *  lambda      host table [n_tensors] of device fp32 multipliers shaped like the weights
+ *  lambda_out  NULL (update lambda in place) or host table of device outputs
+ *  theta, grad, mask  NULL or host tables [n_tensors]; entries may be NULL (skipped).  None of
+ *              them may alias w or lambda.
+ *  result_dev  device, one record
+ */
+condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors,
+                                 float* const* lambda, float* const* lambda_out,
+                                 float mu, double density,
+                                 float* const* theta, float* const* grad, uint8_t* const* mask,
+                                 condensa_select* result_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* ---- tuning / test knobs (process wide; not needed for normal use) ---------------------------- */
+enum {
+    CONDENSA_OPT_SELECT_PATH   = 0, /* 0 auto, 1 radix levels over the data only, 2 sampled window even for small N */
+    CONDENSA_OPT_SAMPLE_LOG2   = 1, /* log2 of the sample size of the window path; 0 = auto             */
+    CONDENSA_OPT_WINDOW_MARGIN = 2, /* half-width of the sampled window in 1/16 standard deviations of
+                                       the sample rank; default 112 (= 7 sigma); 0 makes windows miss    */
+    CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
+    CONDENSA_OPT_COUNT         = 4
+};
+condensa_status condensa_set_option(int option, int64_t value);
+int64_t         condensa_get_option(int option);
+
+const char* condensa_status_string(condensa_status s);
+int         condensa_last_hip_error(void);   /* hipError_t of the last failing runtime call, 0 if none */
+int         condensa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONDENSA_H */

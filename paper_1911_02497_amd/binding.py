@@ -1,0 +1,282 @@
+"""ctypes binding of libcondensa.so: same names as the C entry points, marshalling only.
+
+torch is used for device memory and the current stream; no arithmetic happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcondensa.so")
+
+SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
+OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP = range(5)
+OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT = range(4)
+MAX_DENSITIES = 16
+
+SELECT_FIELDS = ("n", "k", "n_gt", "n_tie_kept", "n_tie", "threshold_key", "tie_end", "path")
+
+
+class CondensaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"condensa status {code}: {msg}")
+        self.code = code
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("shape", ctypes.c_int64 * 4), ("ndim", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+_PROTOTYPES = {
+    "condensa_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
+                                                   ctypes.c_int, ctypes.c_int]),
+    "condensa_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                        ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_filter_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_block_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_quantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p]),
+    "condensa_dequantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "condensa_lc_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                          ctypes.c_void_p]),
+    "condensa_set_option": (ctypes.c_int32, [ctypes.c_int, ctypes.c_int64]),
+    "condensa_get_option": (ctypes.c_int64, [ctypes.c_int]),
+    "condensa_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
+    "condensa_last_hip_error": (ctypes.c_int, []),
+    "condensa_version": (ctypes.c_int, []),
+}
+
+
+def exported_symbols() -> List[str]:
+    """Names every entry point declared in include/condensa.h must be exported under."""
+    return sorted(_PROTOTYPES)
+
+
+_lib = None
+
+
+def library() -> ctypes.CDLL:
+    """Loads libcondensa.so (after torch, so both share one HIP runtime).  No fallback exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_1911_02497_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        import torch  # noqa: F401  (brings in the HIP runtime the library binds to)
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        lib = library()
+        msg = lib.condensa_status_string(code).decode()
+        if code == -7:
+            msg += f" (hipError {lib.condensa_last_hip_error()})"
+        raise CondensaError(code, msg)
+
+
+def _stream(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _tensor_table(tensors):
+    import torch
+    arr = (Tensor * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise TypeError("weights must be contiguous float32 device tensors")
+        if t.dim() < 1 or t.dim() > 4:
+            raise ValueError("weights must have 1 to 4 dimensions")
+        arr[i].w = t.data_ptr() if t.numel() else None
+        for d in range(t.dim()):
+            arr[i].shape[d] = t.shape[d]
+        arr[i].ndim = t.dim()
+        arr[i].reserved = 0
+    return arr
+
+
+def _ptr_table(tensors: Optional[Sequence]):
+    """Host array of device pointers (None entries become NULL); None -> NULL table."""
+    if tensors is None:
+        return None, None
+    arr = (ctypes.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if (t is None or t.numel() == 0) else t.data_ptr()
+    return arr, ctypes.cast(arr, ctypes.c_void_p)
+
+
+def _workspace(op, total, n_struct, n_tensors, n_dens, scope, device, workspace=None):
+    import torch
+    need = int(library().condensa_workspace_bytes(op, total, n_struct, n_tensors, n_dens, scope))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, need
+
+
+def condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope) -> int:
+    return int(library().condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope))
+
+
+def condensa_set_option(option: int, value: int) -> None:
+    _check(library().condensa_set_option(option, value))
+
+
+def condensa_get_option(option: int) -> int:
+    return int(library().condensa_get_option(option))
+
+
+def select_records(results) -> List[Dict[str, int]]:
+    """Device int64 [m, 8] record tensor -> list of dicts (synchronises)."""
+    host = results.cpu().numpy().view(np.uint64).reshape(-1, len(SELECT_FIELDS))
+    return [{f: int(row[i]) for i, f in enumerate(SELECT_FIELDS)} for row in host]
+
+
+def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16=False, mask=True,
+                   in_place=False, workspace=None, stream=None):
+    """Marshals a call of the C entry point condensa_prune.  ``theta`` / ``theta_f16`` / ``mask`` choose
+    which outputs are allocated ([density][tensor] lists of device tensors); ``in_place`` passes the
+    weights themselves as theta (one density only).  Returns the outputs and the record tensor."""
+    import torch
+    lib = library()
+    dev = tensors[0].device if tensors else torch.device("cuda")
+    nt, J = len(tensors), len(densities)
+    tab = _tensor_table(tensors)
+    dens = (ctypes.c_double * max(J, 1))(*[float(d) for d in densities])
+    total = sum(t.numel() for t in tensors)
+
+    def outs(flag, dtype):
+        if not flag:
+            return None
+        return [[torch.empty(t.shape, dtype=dtype, device=dev) for t in tensors] for _ in range(J)]
+
+    th = [list(tensors)] if (theta and in_place) else outs(theta, torch.float32)
+    th16 = outs(theta_f16, torch.int16)
+    mk = outs(mask, torch.uint8)
+    flat = lambda x: None if x is None else [t for row in x for t in row]  # noqa: E731
+    k1, p1 = _ptr_table(flat(th))
+    k2, p2 = _ptr_table(flat(th16))
+    k3, p3 = _ptr_table(flat(mk))
+    n_rec = J * (nt if scope == SCOPE_PER_TENSOR else 1)
+    results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
+    ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace)
+    _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
+                              _stream(stream)))
+    return {"theta": th, "theta_f16": th16, "mask": mk, "results": results[:n_rec], "workspace": ws,
+            "_keep": (k1, k2, k3)}
+
+
+def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask, extra_args, workspace, stream):
+    import torch
+    lib = library()
+    dev = tensors[0].device if tensors else torch.device("cuda")
+    nt = len(tensors)
+    tab = _tensor_table(tensors)
+    total = sum(t.numel() for t in tensors)
+    th = [torch.empty_like(t) for t in tensors] if theta else None
+    mk = [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors] if mask else None
+    k1, p1 = _ptr_table(th)
+    k2, p2 = _ptr_table(mk)
+    F = max(n_struct, 1)
+    sumsq = torch.empty(F, dtype=torch.float64, device=dev)
+    norms = torch.empty(F, dtype=torch.float32, device=dev)
+    keep_idx = torch.full((F,), -1, dtype=torch.int32, device=dev)
+    smask = torch.empty(F, dtype=torch.uint8, device=dev)
+    n_rec = nt if scope == SCOPE_PER_TENSOR else 1
+    results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
+    ws, need = _workspace(op, total, n_struct, nt, 1, scope, dev, workspace)
+    args = [tab, nt] + extra_args + [float(density), scope, p1, p2, sumsq.data_ptr(), norms.data_ptr(),
+                                     keep_idx.data_ptr(), smask.data_ptr(), results.data_ptr(), ws.data_ptr(),
+                                     ws.numel(), _stream(stream)]
+    _check(getattr(lib, fn_name)(*args))
+    return {"theta": th, "mask": mk, "sumsq": sumsq[:n_struct], "norms": norms[:n_struct],
+            "keep_idx": keep_idx[:n_struct], "structure_mask": smask[:n_struct], "results": results[:n_rec],
+            "workspace": ws, "_keep": (k1, k2)}
+
+
+def condensa_filter_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    return _structure_call("condensa_filter_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
+                           [], workspace, stream)
+
+
+def condensa_block_prune(tensors, block_h, block_w, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
+                         workspace=None, stream=None):
+    n_struct = sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2)
+    return _structure_call("condensa_block_prune", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
+                           [int(block_h), int(block_w)], workspace, stream)
+
+
+def condensa_quantize(x, want_q=True, want_dq=True, stream=None):
+    import torch
+    lib = library()
+    q = torch.empty(x.shape, dtype=torch.int16, device=x.device) if want_q else None
+    dq = torch.empty_like(x) if want_dq else None
+    _check(lib.condensa_quantize(x.data_ptr() if x.numel() else None, x.numel(),
+                                 q.data_ptr() if q is not None else None,
+                                 dq.data_ptr() if dq is not None else None, _stream(stream)))
+    return q, dq
+
+
+def condensa_dequantize(q, stream=None):
+    import torch
+    lib = library()
+    dq = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(lib.condensa_dequantize(q.data_ptr() if q.numel() else None, q.numel(), dq.data_ptr(), _stream(stream)))
+    return dq
+
+
+def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,
+                     mask=True, outputs=None, workspace=None, stream=None):
+    """Marshals condensa_lc_step.  By default fresh lambda_out tensors are allocated (lambda is left
+    untouched); ``in_place`` updates lambda itself.  ``outputs`` may carry preallocated
+    theta / grad / mask / lambda_out lists to reuse."""
+    import torch
+    lib = library()
+    dev = tensors[0].device if tensors else torch.device("cuda")
+    nt = len(tensors)
+    tab = _tensor_table(tensors)
+    total = sum(t.numel() for t in tensors)
+    outputs = outputs or {}
+    th = outputs.get("theta") or ([torch.empty_like(t) for t in tensors] if theta else None)
+    gr = outputs.get("grad") or ([torch.empty_like(t) for t in tensors] if grad else None)
+    mk = outputs.get("mask") or ([torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors] if mask else None)
+    if in_place:
+        lo = None
+    else:
+        lo = lambda_out or outputs.get("lambda") or [torch.empty_like(t) for t in tensors]
+    kl, pl = _ptr_table(lambdas)
+    klo, plo = _ptr_table(lo)
+    k1, p1 = _ptr_table(th)
+    k2, p2 = _ptr_table(gr)
+    k3, p3 = _ptr_table(mk)
+    results = outputs.get("results")
+    if results is None:
+        results = torch.zeros((1, len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
+    ws, need = _workspace(OP_LC_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
+    _check(lib.condensa_lc_step(tab, nt, pl, plo, float(mu), float(density), p1, p2, p3, results.data_ptr(),
+                                ws.data_ptr(), ws.numel(), _stream(stream)))
+    return {"theta": th, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo, "results": results,
+            "workspace": ws, "_keep": (kl, klo, k1, k2, k3)}

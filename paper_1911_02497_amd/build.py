@@ -1,0 +1,33 @@
+"""Compiles the HIP sources of this package for gfx950 into libcondensa.so (in-tree)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "csrc", "api.hip")
+LIB = os.path.join(HERE, "libcondensa.so")
+
+FLAGS = [
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",                                   # one rounding per operation, as specified
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def build(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + ["-o", LIB, SRC]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "packed-fp32-ops"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if verbose and err.strip():
+        print(err)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,675 @@
+// C-ABI entry points of the compression-step library (see include/condensa.h): argument checks,
+// table building, workspace carving and the kernel launch sequences.
+#include "host.h"
+#include "k_apply.h"
+#include "k_quantize.h"
+#include "k_select.h"
+#include "k_structure.h"
+#include "k_window.h"
+
+namespace condensa {
+
+std::atomic<int> g_last_hip_error{0};
+std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {};
+
+// ---- pinned staging ring -------------------------------------------------------------------------
+
+namespace {
+struct Stage {
+    void* host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+constexpr int kRing = 8;
+Stage g_ring[kRing];
+int g_ring_next = 0;
+std::mutex g_ring_mu;
+}  // namespace
+
+condensa_status stage_upload(void* dst_dev, const void* src_host, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return CONDENSA_OK;
+    std::lock_guard<std::mutex> lock(g_ring_mu);
+    Stage& s = g_ring[g_ring_next];
+    g_ring_next = (g_ring_next + 1) % kRing;
+    if (s.pending) {
+        CONDENSA_HIP(hipEventSynchronize(s.ev));
+        s.pending = false;
+    }
+    if (s.cap < bytes) {
+        if (s.host) CONDENSA_HIP(hipHostFree(s.host));
+        s.host = nullptr;
+        s.cap = 0;
+        const size_t cap = align_up(bytes < (64u << 10) ? (64u << 10) : bytes, 4096);
+        CONDENSA_HIP(hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        s.cap = cap;
+    }
+    if (!s.ev) CONDENSA_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    std::memcpy(s.host, src_host, bytes);
+    CONDENSA_HIP(hipMemcpyAsync(dst_dev, s.host, bytes, hipMemcpyHostToDevice, stream));
+    CONDENSA_HIP(hipEventRecord(s.ev, stream));
+    s.pending = true;
+    return CONDENSA_OK;
+}
+
+// ---- workspace layout ----------------------------------------------------------------------------
+
+static u64 window_sample_size(u64 N) {
+    const int64_t opt = g_options[CONDENSA_OPT_SAMPLE_LOG2].load();
+    u64 s;
+    if (opt > 0) s = static_cast<u64>(1) << (opt > 26 ? 26 : opt);
+    else {
+        s = N / 256;
+        if (s < (1u << 18)) s = 1u << 18;
+        if (s > (1u << 21)) s = 1u << 21;
+    }
+    s = (s + kSampleUnit - 1) / kSampleUnit * kSampleUnit;
+    return s;
+}
+
+static u64 window_cand_capacity(u64 N) {
+    const int64_t opt = g_options[CONDENSA_OPT_CAND_SHIFT].load();
+    const int shift = (opt > 0 && opt < 40) ? static_cast<int>(opt) : 4;
+    u64 c = N >> shift;
+    if (c < 4096) c = 4096;
+    return c;
+}
+
+Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
+    Layout L;
+    const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
+    const bool structure = (op == CONDENSA_OP_FILTER_PRUNE || op == CONDENSA_OP_BLOCK_PRUNE);
+    if (structure || op == CONDENSA_OP_LC_STEP) J = 1;
+    L.n_groups = per_tensor ? (n_tensors > 0 ? n_tensors : 1) : 1;
+    L.n_slots = L.n_groups * J;
+    L.max_chunks = N / kChunk + static_cast<u64>(n_tensors);
+    L.max_schunks = F / kChunk + static_cast<u64>(n_tensors);
+    size_t off = 0;
+    L.td = off;     off += align_up(static_cast<size_t>(n_tensors + 1) * sizeof(TensorDesc));
+    L.out = off;    off += align_up(static_cast<size_t>(J) * (n_tensors > 0 ? n_tensors : 1) * sizeof(OutDesc));
+    L.slots = off;  off += align_up(static_cast<size_t>(L.n_slots) * sizeof(Slot) + (structure ? 0 : 2 * kMaxJ * sizeof(Slot)));
+    L.upload_bytes = off;
+    L.zero_begin = off;
+    L.ctl = off;    off += align_up(sizeof(Control));
+    L.hist0 = off;  off += align_up(static_cast<size_t>(L.n_groups) * kBins * sizeof(u64));
+    // later-level histograms: one per ranking, and room for the 2J window-boundary rankings
+    const size_t n_hx = static_cast<size_t>(L.n_slots) > 2u * kMaxJ ? L.n_slots : 2u * kMaxJ;
+    L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
+    L.zero_bytes = off - L.zero_begin;
+    const u64 tie_chunks = structure ? L.max_schunks : L.max_chunks;
+    L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
+    if (structure) {
+        L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
+        L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
+        L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
+    } else if (!per_tensor) {
+        L.sample_cap = window_sample_size(N);
+        L.cand_cap = window_cand_capacity(N);
+        L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
+        L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
+        L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));
+    }
+    L.total = off;
+    return L;
+}
+
+// ---- tables ---------------------------------------------------------------------------------------
+
+struct Tables {
+    std::vector<TensorDesc> td;      // n_tensors + 1 (sentinel)
+    u64 N = 0, n_chunks = 0, F = 0, n_schunks = 0;
+    bool vec = true;
+};
+
+static condensa_status build_tensor_table(const condensa_tensor* tensors, int n_tensors, Tables* tb) {
+    if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return CONDENSA_ERR_SIZE;
+    if (n_tensors > 0 && tensors == nullptr) return CONDENSA_ERR_NULL;
+    tb->td.assign(static_cast<size_t>(n_tensors) + 1, TensorDesc{});
+    u64 flat = 0, chunk = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        u64 n;
+        if (!tensor_elems(tensors[t], &n)) return CONDENSA_ERR_SHAPE;
+        if (n > 0 && tensors[t].w == nullptr) return CONDENSA_ERR_NULL;
+        TensorDesc& d = tb->td[t];
+        d.w = tensors[t].w;
+        d.n = n;
+        d.flat_start = flat;
+        d.chunk_start = chunk;
+        flat += n;
+        if (flat > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+        chunk += (n + kChunk - 1) / kChunk;
+        if (n > 0 && !aligned16(d.w)) tb->vec = false;
+    }
+    TensorDesc& end = tb->td[n_tensors];
+    end.flat_start = flat;
+    end.chunk_start = chunk;
+    tb->N = flat;
+    tb->n_chunks = chunk;
+    return CONDENSA_OK;
+}
+
+static condensa_status check_workspace(const void* ws, size_t bytes, const Layout& L) {
+    if (ws == nullptr) return CONDENSA_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return CONDENSA_ERR_WORKSPACE;
+    if (bytes < L.total) return CONDENSA_ERR_WORKSPACE;
+    return CONDENSA_OK;
+}
+
+static void init_slot(Slot* s, u64 n, u64 k, u32 path) {
+    std::memset(s, 0, sizeof(Slot));
+    s->n = n;
+    s->k = k;
+    s->path = path;
+    if (k == 0) {
+        s->state = kInactive;
+        s->prefix = ~static_cast<u64>(0);
+        s->remaining = 0;
+        s->tie_end = 0;
+    } else {
+        s->state = kSelecting;
+        s->prefix = 0;
+        s->remaining = k;
+        s->tie_end = n;
+    }
+}
+
+template <typename T>
+static T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+static unsigned fill_grid(u64 words) {
+    u64 b = (words + kBlock - 1) / kBlock;
+    if (b > 4096) b = 4096;
+    if (b == 0) b = 1;
+    return static_cast<unsigned>(b);
+}
+
+// Radix levels over the weights: 3 x (histogram sweep + bin search).
+template <bool LC, bool VEC>
+static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st) {
+    if (a.n_chunks > 0) {
+        u64 blocks = a.n_chunks < 2048 ? a.n_chunks : 2048;
+        const u64 cpb = (a.n_chunks + blocks - 1) / blocks;
+        blocks = (a.n_chunks + cpb - 1) / cpb;
+        for (int level = 0; level < n_levels(31); ++level) {
+            hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_scan_level, dim3(n_slots), dim3(kBlock), 0, st, a.slots, a.hist0, a.histx, a.J, 31,
+                               level, a.ctl, a.only_failed);
+            CONDENSA_LAUNCH_CHECK();
+        }
+    }
+    return CONDENSA_OK;
+}
+
+template <bool LC, bool VEC>
+static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, int n_groups,
+                                               condensa_select* results, hipStream_t st) {
+    if (a.n_chunks > 0) {
+        hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL((k_tie_locate<LC, VEC>), dim3(n_slots), dim3(kBlock), 0, st, a, results, n_groups);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+template <bool LC, bool VEC>
+static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool use_window, int n_slots,
+                                     int n_groups, condensa_select* results, hipStream_t st) {
+    condensa_status rc;
+    if (use_window) {
+        rc = launch_window_path<LC, VEC>(a, L, ws, st);
+        if (rc != CONDENSA_OK) return rc;
+        a.only_failed = 1;
+    }
+    rc = launch_radix_levels<LC, VEC>(a, n_slots, st);
+    if (rc != CONDENSA_OK) return rc;
+    return launch_ties_and_results<LC, VEC>(a, n_slots, n_groups, results, st);
+}
+
+static bool want_window(u64 N, bool per_tensor) {
+    if (per_tensor) return false;
+    const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
+    if (mode == 1) return false;
+    if (mode == 2) return false;
+    return false;  // TODO window path
+    (void)N;
+}
+
+}  // namespace condensa
+
+using namespace condensa;
+
+// =====================================================================================================
+
+extern "C" {
+
+size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures, int n_tensors,
+                                int n_densities, int scope) {
+    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_LC_STEP) return 0;
+    if (op == CONDENSA_OP_QUANTIZE) return 0;
+    if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
+    if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return 0;
+    if (total_elems > (static_cast<u64>(1) << 40) || n_structures > total_elems) return 0;
+    return make_layout(op, total_elems, n_structures, n_tensors, n_densities, scope).total;
+}
+
+condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, const double* densities,
+                               int n_densities, int scope, float* const* theta, uint16_t* const* theta_f16,
+                               uint8_t* const* mask, condensa_select* results_dev, void* workspace_dev,
+                               size_t workspace_bytes, void* stream) {
+    if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return CONDENSA_ERR_SIZE;
+    if (densities == nullptr || results_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
+    for (int j = 0; j < n_densities; ++j)
+        if (!density_ok(densities[j])) return CONDENSA_ERR_DENSITY;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    const int J = n_densities;
+    const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
+    if (per_tensor && n_tensors == 0) return CONDENSA_OK;
+    const Layout L = make_layout(CONDENSA_OP_PRUNE, tb.N, 0, n_tensors, J, scope);
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+
+    // output table and aliasing / alignment checks
+    const bool any_out = theta || theta_f16 || mask;
+    std::vector<OutDesc> out(static_cast<size_t>(J) * (n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    bool vec = tb.vec;
+    for (int j = 0; j < J; ++j)
+        for (int t = 0; t < n_tensors; ++t) {
+            OutDesc& o = out[static_cast<size_t>(j) * n_tensors + t];
+            const size_t i = static_cast<size_t>(j) * n_tensors + t;
+            if (tb.td[t].n == 0) continue;
+            o.theta = theta ? theta[i] : nullptr;
+            o.theta16 = theta_f16 ? theta_f16[i] : nullptr;
+            o.mask = mask ? mask[i] : nullptr;
+            if (o.theta == tb.td[t].w && J > 1) return CONDENSA_ERR_ARG;
+            if (static_cast<const void*>(o.theta16) == tb.td[t].w || static_cast<const void*>(o.mask) == tb.td[t].w)
+                return CONDENSA_ERR_ARG;
+            if (o.theta && !aligned16(o.theta)) vec = false;
+            if (o.theta16 && (reinterpret_cast<uintptr_t>(o.theta16) & 7u)) vec = false;
+            if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
+        }
+
+    const bool window = want_window(tb.N, per_tensor);
+    std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
+    for (int g = 0; g < L.n_groups; ++g)
+        for (int j = 0; j < J; ++j) {
+            const u64 n = per_tensor ? tb.td[g].n : tb.N;
+            init_slot(&slots[static_cast<size_t>(g) * J + j], n, kept_count(densities[j], n), window ? 2u : 1u);
+        }
+
+    // one upload: [tensor table | output table | rankings]
+    std::vector<char> up(L.upload_bytes, 0);
+    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
+    std::memcpy(up.data() + L.slots, slots.data(), slots.size() * sizeof(Slot));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    if (rc != CONDENSA_OK) return rc;
+    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    CONDENSA_LAUNCH_CHECK();
+
+    DataArgs a{};
+    a.td = at<TensorDesc>(workspace_dev, L.td);
+    a.slots = at<Slot>(workspace_dev, L.slots);
+    a.hist0 = at<u64>(workspace_dev, L.hist0);
+    a.histx = at<u64>(workspace_dev, L.histx);
+    a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
+    a.ctl = at<Control>(workspace_dev, L.ctl);
+    a.n_chunks = tb.n_chunks;
+    a.n_tensors = n_tensors;
+    a.J = J;
+    a.per_tensor = per_tensor ? 1 : 0;
+    a.only_failed = 0;
+    a.mu = 0.0f;
+
+    rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st)
+                : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st);
+    if (rc != CONDENSA_OK) return rc;
+
+    if (any_out && tb.n_chunks > 0) {
+        const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+        if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        else     hipLaunchKernelGGL((k_prune_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    return CONDENSA_OK;
+}
+
+condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
+                                 float* const* lambda_out, float mu, double density, float* const* theta,
+                                 float* const* grad, uint8_t* const* mask, condensa_select* result_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (result_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (n_tensors > 0 && lambda == nullptr) return CONDENSA_ERR_NULL;
+    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
+    if (!(mu > 0.0f) || !std::isfinite(mu)) return CONDENSA_ERR_DENSITY;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_LC_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+
+    std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    bool vec = tb.vec;
+    for (int t = 0; t < n_tensors; ++t) {
+        TensorDesc& d = tb.td[t];
+        if (d.n == 0) continue;
+        if (lambda[t] == nullptr) return CONDENSA_ERR_NULL;
+        d.lam = lambda[t];
+        d.lam_out = lambda_out ? lambda_out[t] : lambda[t];
+        if (d.lam_out == nullptr) return CONDENSA_ERR_NULL;
+        d.grad = grad ? grad[t] : nullptr;
+        OutDesc& o = out[t];
+        o.theta = theta ? theta[t] : nullptr;
+        o.mask = mask ? mask[t] : nullptr;
+        const void* ins[2] = {d.w, d.lam};
+        const void* outs[4] = {o.theta, d.grad, o.mask, (d.lam_out != d.lam) ? d.lam_out : nullptr};
+        for (const void* o_ : outs)
+            for (const void* i_ : ins)
+                if (o_ != nullptr && o_ == i_) return CONDENSA_ERR_ARG;
+        if (static_cast<const void*>(d.lam) == static_cast<const void*>(d.w)) return CONDENSA_ERR_ARG;
+        if (!aligned16(d.lam) || !aligned16(d.lam_out)) vec = false;
+        if (o.theta && !aligned16(o.theta)) vec = false;
+        if (d.grad && !aligned16(d.grad)) vec = false;
+        if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
+    }
+    const bool window = want_window(tb.N, false);
+    Slot slot;
+    init_slot(&slot, tb.N, kept_count(density, tb.N), window ? 2u : 1u);
+
+    std::vector<char> up(L.upload_bytes, 0);
+    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
+    std::memcpy(up.data() + L.slots, &slot, sizeof(Slot));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    if (rc != CONDENSA_OK) return rc;
+    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    CONDENSA_LAUNCH_CHECK();
+
+    DataArgs a{};
+    a.td = at<TensorDesc>(workspace_dev, L.td);
+    a.slots = at<Slot>(workspace_dev, L.slots);
+    a.hist0 = at<u64>(workspace_dev, L.hist0);
+    a.histx = at<u64>(workspace_dev, L.histx);
+    a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
+    a.ctl = at<Control>(workspace_dev, L.ctl);
+    a.n_chunks = tb.n_chunks;
+    a.n_tensors = n_tensors;
+    a.J = 1;
+    a.per_tensor = 0;
+    a.only_failed = 0;
+    a.mu = mu;
+
+    // the selection sweeps read w and lambda only, so their vector path depends on those alone
+    bool vec_in = tb.vec;
+    for (int t = 0; t < n_tensors; ++t)
+        if (tb.td[t].n > 0 && !aligned16(tb.td[t].lam)) vec_in = false;
+    rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st)
+                : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st);
+    if (rc != CONDENSA_OK) return rc;
+
+    if (tb.n_chunks > 0) {
+        const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+        if (vec) hipLaunchKernelGGL((k_lc_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        else     hipLaunchKernelGGL((k_lc_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    return CONDENSA_OK;
+}
+
+}  // extern "C" (reopened below)
+
+// ---- structure pruning (filters, 2-D blocks) ---------------------------------------------------------
+
+namespace condensa {
+
+static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, double density, int scope,
+                                           float* const* theta, uint8_t* const* mask, double* sumsq_dev,
+                                           float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                           condensa_select* results_dev, void* workspace_dev,
+                                           size_t workspace_bytes, void* stream) {
+    const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
+    if (per_tensor && n_tensors == 0) return CONDENSA_OK;
+    const Layout L = make_layout(op, tb.N, tb.F, n_tensors, 1, scope);
+    condensa_status rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+
+    std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    bool vec = tb.vec;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (tb.td[t].n == 0) continue;
+        OutDesc& o = out[t];
+        o.theta = theta ? theta[t] : nullptr;
+        o.mask = mask ? mask[t] : nullptr;
+        if (static_cast<const void*>(o.mask) == tb.td[t].w) return CONDENSA_ERR_ARG;
+        if (o.theta && !aligned16(o.theta)) vec = false;
+        if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
+    }
+    std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
+    for (int g = 0; g < L.n_groups; ++g) {
+        const u64 n = per_tensor ? tb.td[g].n_struct : tb.F;
+        init_slot(&slots[g], n, kept_count(density, n), 1u);
+    }
+    std::vector<char> up(L.upload_bytes, 0);
+    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
+    std::memcpy(up.data() + L.slots, slots.data(), slots.size() * sizeof(Slot));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    if (rc != CONDENSA_OK) return rc;
+    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    CONDENSA_LAUNCH_CHECK();
+
+    StructArgs a{};
+    a.td = at<TensorDesc>(workspace_dev, L.td);
+    a.slots = at<Slot>(workspace_dev, L.slots);
+    a.histx = at<u64>(workspace_dev, L.histx);
+    a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
+    a.ctl = at<Control>(workspace_dev, L.ctl);
+    a.keys = at<u64>(workspace_dev, L.skeys);
+    a.smask = at<u8>(workspace_dev, L.smask);
+    a.sblock = at<u32>(workspace_dev, L.sblock);
+    a.F = tb.F;
+    a.n_schunks = tb.n_schunks;
+    a.n_chunks = tb.n_chunks;
+    a.n_tensors = n_tensors;
+    a.per_tensor = per_tensor ? 1 : 0;
+
+    const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
+    if (tb.F > 0) {
+        hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+        CONDENSA_LAUNCH_CHECK();
+        u64 blocks = tb.n_schunks < 1024 ? tb.n_schunks : 1024;
+        const u64 cpb = (tb.n_schunks + blocks - 1) / blocks;
+        blocks = (tb.n_schunks + cpb - 1) / cpb;
+        for (int level = 0; level < n_levels(63); ++level) {
+            hipLaunchKernelGGL(k_hist_keys, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_scan_level, dim3(L.n_slots), dim3(kBlock), 0, st, a.slots,
+                               static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0);
+            CONDENSA_LAUNCH_CHECK();
+        }
+        hipLaunchKernelGGL(k_tie_count_keys, dim3(static_cast<unsigned>(tb.n_schunks)), dim3(kBlock), 0, st, a);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_tie_locate_keys, dim3(L.n_slots), dim3(kBlock), 0, st, a, results_dev);
+    CONDENSA_LAUNCH_CHECK();
+    if (tb.F > 0) {
+        hipLaunchKernelGGL(k_struct_mask, dim3(sblocks), dim3(kBlock), 0, st, a, structure_mask_dev);
+        CONDENSA_LAUNCH_CHECK();
+        if (keep_idx_dev) {
+            hipLaunchKernelGGL(k_struct_scan_blocks, dim3(1), dim3(kBlock), 0, st, a.sblock, static_cast<u64>(sblocks));
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_struct_keep_idx, dim3(sblocks), dim3(kBlock), 0, st, a, keep_idx_dev);
+            CONDENSA_LAUNCH_CHECK();
+        }
+        if ((theta || mask) && tb.n_chunks > 0) {
+            const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+            if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+            else     hipLaunchKernelGGL((k_struct_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+            CONDENSA_LAUNCH_CHECK();
+        }
+    }
+    return CONDENSA_OK;
+}
+
+// fills the structure geometry of the tensor table; filter: block_h == 0
+static condensa_status add_structure_geometry(const condensa_tensor* tensors, int n_tensors, int block_h,
+                                              int block_w, Tables* tb) {
+    u64 F = 0, sc = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        TensorDesc& d = tb->td[t];
+        d.struct_start = F;
+        d.pad = sc;
+        u64 f = 0;
+        if (block_h == 0) {                                   // filters of a [Cout, Cin, kh, kw] tensor
+            if (tensors[t].ndim != 4) return CONDENSA_ERR_SHAPE;
+            if (d.n > 0) {
+                f = static_cast<u64>(tensors[t].shape[0]);
+                const u64 len = d.n / f;
+                if (len > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
+                d.s_rows = 1; d.s_len = static_cast<u32>(len); d.s_ld = static_cast<u32>(len); d.s_per_row = 1;
+            }
+        } else {                                              // 2-D blocks of a [R, C] matrix
+            if (tensors[t].ndim != 2) return CONDENSA_ERR_SHAPE;
+            const u64 R = static_cast<u64>(tensors[t].shape[0]), C = static_cast<u64>(tensors[t].shape[1]);
+            if (R % block_h != 0 || C % block_w != 0) return CONDENSA_ERR_SHAPE;
+            if (C > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
+            if (d.n > 0) {
+                f = (R / block_h) * (C / block_w);
+                d.s_rows = static_cast<u32>(block_h); d.s_len = static_cast<u32>(block_w);
+                d.s_ld = static_cast<u32>(C); d.s_per_row = static_cast<u32>(C / block_w);
+            }
+        }
+        if (d.n == 0) { d.s_rows = 1; d.s_len = 1; d.s_ld = 1; d.s_per_row = 1; }
+        d.n_struct = f;
+        F += f;
+        sc += (f + kChunk - 1) / kChunk;
+    }
+    if (F > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;         // ids are reported as int32
+    tb->td[n_tensors].struct_start = F;
+    tb->td[n_tensors].pad = sc;
+    tb->F = F;
+    tb->n_schunks = sc;
+    return CONDENSA_OK;
+}
+
+}  // namespace condensa
+
+extern "C" {
+
+condensa_status condensa_filter_prune(const condensa_tensor* tensors, int n_tensors, double density, int scope,
+                                      float* const* theta, uint8_t* const* mask, double* sumsq_dev,
+                                      float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                      condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
+                                      void* stream) {
+    if (results_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
+    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    rc = add_structure_geometry(tensors, n_tensors, 0, 0, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    return run_structure_prune(CONDENSA_OP_FILTER_PRUNE, tb, n_tensors, density, scope, theta, mask, sumsq_dev,
+                               norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
+                               workspace_bytes, stream);
+}
+
+condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tensors, int block_h, int block_w,
+                                     double density, int scope, float* const* theta, uint8_t* const* mask,
+                                     double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                     uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                     void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (results_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
+    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
+    if (block_h < 1 || block_w < 1) return CONDENSA_ERR_SHAPE;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    rc = add_structure_geometry(tensors, n_tensors, block_h, block_w, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    return run_structure_prune(CONDENSA_OP_BLOCK_PRUNE, tb, n_tensors, density, scope, theta, mask, sumsq_dev,
+                               norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
+                               workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+extern "C" {
+
+condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
+    if (n > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (n == 0) return CONDENSA_OK;
+    if (q_dev == nullptr && dq_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (x_dev == nullptr) return CONDENSA_ERR_NULL;
+    const bool vec = aligned16(x_dev) && (!dq_dev || aligned16(dq_dev)) &&
+                     (!q_dev || (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0);
+    u64 blocks = ((n + 3) / 4 + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (vec) hipLaunchKernelGGL((k_quantize<true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, x_dev, n, q_dev, dq_dev);
+    else     hipLaunchKernelGGL((k_quantize<false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, x_dev, n, q_dev, dq_dev);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
+    if (n > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (n == 0) return CONDENSA_OK;
+    if (dq_dev == nullptr || q_dev == nullptr) return CONDENSA_ERR_NULL;
+    const bool vec = aligned16(dq_dev) && (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0;
+    u64 blocks = ((n + 3) / 4 + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (vec) hipLaunchKernelGGL((k_dequantize<true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, q_dev, n, dq_dev);
+    else     hipLaunchKernelGGL((k_dequantize<false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, q_dev, n, dq_dev);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+condensa_status condensa_set_option(int option, int64_t value) {
+    if (option < 0 || option >= CONDENSA_OPT_COUNT) return CONDENSA_ERR_ARG;
+    if (value < 0) return CONDENSA_ERR_ARG;
+    if (option == CONDENSA_OPT_SELECT_PATH && value > 2) return CONDENSA_ERR_ARG;
+    if (option == CONDENSA_OPT_SAMPLE_LOG2 && value != 0 && (value < 10 || value > 26)) return CONDENSA_ERR_ARG;
+    if (option == CONDENSA_OPT_CAND_SHIFT && value > 30) return CONDENSA_ERR_ARG;
+    g_options[option].store(value);
+    return CONDENSA_OK;
+}
+
+int64_t condensa_get_option(int option) {
+    if (option < 0 || option >= CONDENSA_OPT_COUNT) return -1;
+    return g_options[option].load();
+}
+
+const char* condensa_status_string(condensa_status s) {
+    switch (s) {
+        case CONDENSA_OK: return "ok";
+        case CONDENSA_ERR_NULL: return "required pointer is NULL";
+        case CONDENSA_ERR_SIZE: return "count or size out of range";
+        case CONDENSA_ERR_DENSITY: return "density outside [0,1], or mu not finite and positive";
+        case CONDENSA_ERR_SHAPE: return "tensor shape not valid for this operator";
+        case CONDENSA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case CONDENSA_ERR_ARG: return "invalid scope, option or aliasing";
+        case CONDENSA_ERR_HIP: return "HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+int condensa_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int condensa_version(void) { return 100; }
+
+}  // extern "C"

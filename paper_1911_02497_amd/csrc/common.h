@@ -1,0 +1,200 @@
+// Shared definitions of the gfx950 compression-step kernels: device tables, key helpers,
+// chunk addressing and radix-level geometry.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/condensa.h"
+
+typedef uint8_t u8;
+typedef uint16_t u16;
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+namespace condensa {
+
+constexpr int kBlock = 256;            // threads per workgroup (4 wavefronts of 64)
+constexpr int kChunk = 8192;           // elements of one tensor handled as a unit of work
+constexpr int kQuadsPerThread = kChunk / (kBlock * 4);   // 8 float4 per thread and chunk
+constexpr int kMaxJ = CONDENSA_MAX_DENSITIES;
+constexpr int kBins = 2048;            // bins of one radix level (digits are at most 11 bits)
+constexpr int kSlotBatch = 8;          // rankings that share one sweep's LDS histograms
+
+// One weight tensor as the kernels see it (device table, one entry per tensor plus a sentinel).
+struct TensorDesc {
+    const float* w;
+    const float* lam;      // L-C multipliers (NULL for plain pruning)
+    float* lam_out;
+    float* grad;
+    u64 n;                 // elements
+    u64 flat_start;        // flat index of element 0
+    u64 chunk_start;       // id of this tensor's first chunk
+    u64 struct_start;      // id of this tensor's first structure (structure pruning)
+    u32 s_rows;            // structure geometry: rows of one structure (1 for filters)
+    u32 s_len;             // contiguous elements per structure row
+    u32 s_ld;              // row stride of the tensor in elements (matrix columns)
+    u32 s_per_row;         // structures per structure-row of the grid (blocks per block row)
+    u64 n_struct;          // structures in this tensor
+    u64 pad;
+};
+static_assert(sizeof(TensorDesc) == 96, "TensorDesc layout");
+
+struct OutDesc {           // outputs of tensor t for density j, entry j * n_tensors + t
+    float* theta;
+    u16* theta16;
+    u8* mask;
+    u64 pad;
+};
+
+// State of one ranking (one density of one group).  Filled by the host, advanced level by level.
+struct Slot {
+    u64 prefix;            // key bits decided so far
+    u64 remaining;         // 1-based descending rank still to resolve inside the prefix
+    u64 k;
+    u64 n;
+    u64 n_tie;
+    u64 tie_end;
+    u64 lo, hi;            // sampled key window (window path)
+    u32 state;             // kInactive (k == 0), kSelecting, kDone
+    u32 need_tie;          // index search among ties required
+    u32 path;
+    u32 pad0;
+    u64 pad1;
+};
+static_assert(sizeof(Slot) == 88, "Slot layout");
+
+enum : u32 { kInactive = 0, kSelecting = 1, kDone = 2 };
+
+// Radix level geometry for keys of `key_bits` significant bits (31 for |fp32|, 63 for fp64 sums,
+// fewer for index keys): ceil(key_bits / 11) levels of at most 11 bits, most significant first.
+struct Level {
+    int shift;             // position of the digit
+    int bits;              // digit width
+    int hi_shift;          // shift + bits: key >> hi_shift must equal prefix >> hi_shift
+};
+
+__host__ __device__ inline int n_levels(int key_bits) { return (key_bits + 10) / 11; }
+
+// Digits are as even as possible, wider ones first: 31 -> 11,10,10; 63 -> 11,11,11,10,10,10.
+__host__ __device__ inline Level level_of(int key_bits, int level) {
+    const int nl = n_levels(key_bits);
+    const int base = key_bits / nl, extra = key_bits % nl;
+    Level L;
+    L.bits = base + (level < extra ? 1 : 0);
+    L.hi_shift = key_bits - (level * base + (level < extra ? level : extra));
+    L.shift = L.hi_shift - L.bits;
+    return L;
+}
+
+__device__ inline u32 mag_key(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+// v = w - lambda / mu in binary32, one rounding per operation (no contraction).
+__device__ inline float lc_shift(float w, float lam, float mu) {
+    const float t = __fdiv_rn(lam, mu);
+    return __fsub_rn(w, t);
+}
+
+// Loads up to four consecutive elements e0 .. e0+3 of an n-element array; missing ones read 0.
+template <bool VEC>
+__device__ inline void load4(const float* __restrict__ p, u64 e0, u64 n, float v[4]) {
+    if (VEC && e0 + 4 <= n) {
+        const float4 t = *reinterpret_cast<const float4*>(p + e0);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = (e0 + k < n) ? p[e0 + k] : 0.0f;
+    }
+}
+
+template <bool VEC>
+__device__ inline void store4(float* __restrict__ p, u64 e0, u64 n, const float v[4]) {
+    if (VEC && e0 + 4 <= n) {
+        *reinterpret_cast<float4*>(p + e0) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (e0 + k < n) p[e0 + k] = v[k];
+    }
+}
+
+template <bool VEC>
+__device__ inline void store4_u8(u8* __restrict__ p, u64 e0, u64 n, const u8 v[4]) {
+    if (VEC && e0 + 4 <= n) {
+        *reinterpret_cast<uchar4*>(p + e0) = make_uchar4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (e0 + k < n) p[e0 + k] = v[k];
+    }
+}
+
+template <bool VEC>
+__device__ inline void store4_u16(u16* __restrict__ p, u64 e0, u64 n, const u16 v[4]) {
+    if (VEC && e0 + 4 <= n) {
+        *reinterpret_cast<ushort4*>(p + e0) = make_ushort4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) if (e0 + k < n) p[e0 + k] = v[k];
+    }
+}
+
+// Tensor that owns chunk c: largest t with chunk_start[t] <= c (table has a sentinel at n_tensors).
+__device__ inline int tensor_of_chunk(const TensorDesc* __restrict__ td, int n_tensors, u64 c) {
+    int lo = 0, hi = n_tensors - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (td[mid].chunk_start <= c) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// binary32 -> binary16 bits, round to nearest even (overflow to inf, gradual underflow, quiet NaN
+// with the sign and top ten payload bits).  Integer-only so the result does not depend on the
+// rounding or denormal mode of the conversion instructions.
+__device__ inline u16 f32_to_f16_rne(float x) {
+    const u32 b = __float_as_uint(x);
+    const u32 sign = (b >> 16) & 0x8000u;
+    const u32 a = b & 0x7FFFFFFFu;
+    u32 h;
+    if (a >= 0x47800000u) {                                  // |x| >= 2^16, inf or NaN
+        h = (a > 0x7F800000u) ? (0x7E00u | ((a >> 13) & 0x3FFu)) : 0x7C00u;
+    } else if (a >= 0x38800000u) {                           // normal binary16 range
+        const u32 r = a - 0x38000000u;                       // rebias exponent by 112
+        h = r >> 13;
+        const u32 rem = r & 0x1FFFu;
+        h += (rem > 0x1000u) | ((rem == 0x1000u) & (h & 1u));
+    } else if (a >= 0x33000000u) {                           // subnormal binary16 (2^-25 <= |x| < 2^-14)
+        const u32 e = a >> 23;                               // 102 .. 112
+        const u32 m = (a & 0x007FFFFFu) | 0x00800000u;
+        const u32 s = 126u - e;                              // 14 .. 24
+        h = m >> s;
+        const u32 rem = m & ((1u << s) - 1u);
+        const u32 half = 1u << (s - 1u);
+        h += (rem > half) | ((rem == half) & (h & 1u));
+    } else {
+        h = 0u;
+    }
+    return static_cast<u16>(sign | h);
+}
+
+// exact widening binary16 -> binary32
+__device__ inline float f16_bits_to_f32(u16 hb) {
+    const u32 h = hb;
+    const u32 sign = (h & 0x8000u) << 16;
+    const u32 e = (h >> 10) & 0x1Fu;
+    const u32 m = h & 0x3FFu;
+    u32 out;
+    if (e == 31u) {
+        out = sign | 0x7F800000u | (m << 13);
+    } else if (e != 0u) {
+        out = sign | ((e + 112u) << 23) | (m << 13);
+    } else if (m == 0u) {
+        out = sign;
+    } else {
+        const int lz = __clz(static_cast<int>(m)) - 21;      // shifts needed to reach bit 10
+        const u32 mm = (m << lz) & 0x3FFu;
+        out = sign | (static_cast<u32>(113 - lz) << 23) | (mm << 13);
+    }
+    return __uint_as_float(out);
+}
+
+}  // namespace condensa

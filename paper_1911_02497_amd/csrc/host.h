@@ -1,0 +1,81 @@
+// Host-side plumbing shared by the entry points: status bookkeeping, option store, the pinned
+// staging ring that carries the small per-call tables to the device, workspace carving.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+#include "k_select.h"
+
+namespace condensa {
+
+extern std::atomic<int> g_last_hip_error;
+extern std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT];
+
+#define CONDENSA_HIP(expr)                                                      \
+    do {                                                                        \
+        hipError_t err__ = (expr);                                              \
+        if (err__ != hipSuccess) {                                              \
+            ::condensa::g_last_hip_error.store(static_cast<int>(err__));        \
+            return CONDENSA_ERR_HIP;                                            \
+        }                                                                       \
+    } while (0)
+
+#define CONDENSA_LAUNCH_CHECK() CONDENSA_HIP(hipGetLastError())
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// k = llround(density * n) clamped to [0, n]; the product is taken in binary64.
+inline u64 kept_count(double density, u64 n) {
+    const double x = density * static_cast<double>(n);
+    const long long r = std::llround(x);
+    if (r < 0) return 0;
+    if (static_cast<u64>(r) > n) return n;
+    return static_cast<u64>(r);
+}
+
+inline bool density_ok(double d) { return d >= 0.0 && d <= 1.0; }   // false for NaN
+
+// Copies `bytes` of host data to device memory on `stream` through a pinned ring, so the caller's
+// tables can be released as soon as the entry point returns and the call never waits for the GPU
+// unless all ring slots are still in flight.
+condensa_status stage_upload(void* dst_dev, const void* src_host, size_t bytes, hipStream_t stream);
+
+// Element count of a tensor; false if the descriptor is malformed.
+inline bool tensor_elems(const condensa_tensor& t, u64* n) {
+    if (t.ndim < 1 || t.ndim > 4 || t.reserved != 0) return false;
+    u64 p = 1;
+    for (int i = 0; i < t.ndim; ++i) {
+        if (t.shape[i] < 0) return false;
+        const u64 d = static_cast<u64>(t.shape[i]);
+        if (d != 0 && p > (static_cast<u64>(1) << 40) / d) return false;   // cap at 2^40 elements
+        p *= d;
+    }
+    *n = p;
+    return true;
+}
+
+// Carving of the caller's workspace.  Offsets are multiples of 256 bytes.
+struct Layout {
+    size_t td = 0, out = 0, slots = 0, upload_bytes = 0;   // [td | out | slots] is uploaded in one copy
+    size_t zero_begin = 0, zero_bytes = 0;                 // [ctl | hist0 | histx] is cleared by one kernel
+    size_t ctl = 0, hist0 = 0, histx = 0;
+    size_t tiecnt = 0;
+    size_t skeys = 0, sblock = 0, smask = 0;                // structure keys, per-block kept counts, keep flags
+    size_t sample = 0, cand_key = 0, cand_idx = 0;          // window path
+    u64 sample_cap = 0, cand_cap = 0;
+    size_t total = 0;
+    u64 max_chunks = 0, max_schunks = 0;
+    int n_groups = 1, n_slots = 1;
+};
+
+Layout make_layout(int op, u64 total_elems, u64 n_structures, int n_tensors, int n_densities, int scope);
+
+}  // namespace condensa

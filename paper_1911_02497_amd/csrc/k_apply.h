@@ -1,0 +1,109 @@
+// Streaming mask/apply kernels: theta = keep ? x : +0 with optional fp16 rounding (Prune and
+// Compose([Prune, Quantize]), Table 1) and the fused L-C multiplier / penalty-gradient update
+// (Section 3.3).  One workgroup per chunk of one tensor, 128-bit accesses when aligned.
+#pragma once
+#include "k_select.h"
+
+namespace condensa {
+
+// keep rule of the selection: key above the threshold, or equal to it with index below tie_end
+__device__ inline bool keep_rule(u32 key, u32 T, u64 idx, u64 tie_end) {
+    return key > T || (key == T && idx < tie_end);
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    __shared__ u32 s_T[kMaxJ];
+    __shared__ u64 s_end[kMaxJ];
+    __shared__ OutDesc s_out[kMaxJ];
+    const u64 c = blockIdx.x;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const u64 g = a.per_tensor ? t : 0;
+    if (tid < a.J) {
+        const Slot& s = a.slots[g * a.J + tid];
+        s_T[tid] = static_cast<u32>(s.prefix);
+        s_end[tid] = s.tie_end;
+        s_out[tid] = out[static_cast<u64>(tid) * a.n_tensors + t];
+    }
+    __syncthreads();
+    const TensorDesc& td = a.td[t];
+    const u64 base = (c - td.chunk_start) * kChunk;
+    const u64 idx0 = a.per_tensor ? 0 : td.flat_start;
+#pragma unroll 2
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) break;
+        float v[4];
+        load4<VEC>(td.w, e0, td.n, v);
+        u32 key[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) key[k] = mag_key(v[k]);
+        for (int j = 0; j < a.J; ++j) {
+            const u32 T = s_T[j];
+            const u64 end = s_end[j];
+            float th[4];
+            u8 m[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool keep = keep_rule(key[k], T, idx0 + e0 + k, end);
+                m[k] = keep ? 1 : 0;
+                th[k] = keep ? v[k] : 0.0f;
+            }
+            const OutDesc& o = s_out[j];
+            if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+            if (o.theta16) {
+                u16 h[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) h[k] = f32_to_f16_rne(th[k]);
+                store4_u16<VEC>(o.theta16, e0, td.n, h);
+            }
+            if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+        }
+    }
+}
+
+// theta = C(w - lambda/mu) entries, lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
+// each operation rounded once in binary32.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    const u64 c = blockIdx.x;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const Slot& s = a.slots[0];
+    const u32 T = static_cast<u32>(s.prefix);
+    const u64 end = s.tie_end;
+    const TensorDesc& td = a.td[t];
+    const OutDesc o = out[t];
+    const float mu = a.mu;
+    const u64 base = (c - td.chunk_start) * kChunk;
+#pragma unroll 2
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) break;
+        float w[4], l[4];
+        load4<VEC>(td.w, e0, td.n, w);
+        load4<VEC>(td.lam, e0, td.n, l);
+        float th[4], ln[4], gr[4];
+        u8 m[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float v = lc_shift(w[k], l[k], mu);
+            const bool keep = keep_rule(mag_key(v), T, td.flat_start + e0 + k, end);
+            m[k] = keep ? 1 : 0;
+            th[k] = keep ? v : 0.0f;
+            const float e = __fsub_rn(w[k], th[k]);
+            const float p = __fmul_rn(mu, e);
+            ln[k] = __fsub_rn(l[k], p);
+            gr[k] = __fsub_rn(p, ln[k]);
+        }
+        if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+        store4<VEC>(td.lam_out, e0, td.n, ln);
+        if (td.grad) store4<VEC>(td.grad, e0, td.n, gr);
+        if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    }
+}
+
+}  // namespace condensa

@@ -1,0 +1,376 @@
+// Exact k-th-largest selection by most-significant-digit radix levels with workgroup-private LDS
+// histograms, and the deterministic tie rule (lowest index first).
+// Section 3.1: "magnitude threshold computation from a sparsity"; Section 3.3: the C step.
+#pragma once
+#include "common.h"
+
+namespace condensa {
+
+// Small block of device-side flags and counters, zeroed at the start of every call.
+struct Control {
+    u32 need_tie;          // some ranking needs the index search among ties
+    u32 window_failed;     // some ranking of the window path must fall back to the radix levels
+    u64 cand_count;        // candidates written by the window sweep
+    u64 region[2 * kMaxJ + 2];   // window sweep: population of each key region
+    u64 pad[4];
+};
+
+struct DataArgs {
+    const TensorDesc* td;
+    Slot* slots;
+    u64* hist0;            // [n_groups][kBins]   first level, shared by the densities of a group
+    u64* histx;            // [n_slots][kBins]    later levels
+    u32* tiecnt;           // [J][n_chunks]
+    Control* ctl;
+    u64 n_chunks;
+    int n_tensors;
+    int J;                 // rankings (densities) per group
+    int per_tensor;        // 1: group = tensor, 0: one group
+    int only_failed;       // 1: runs as the fallback of the window path (skip when nothing failed)
+    float mu;
+};
+
+// ---- wavefront / workgroup scans ---------------------------------------------------------------
+
+__device__ inline u64 shfl_up_u64(u64 v, int d) {
+    const u32 lo = __shfl_up(static_cast<u32>(v), d, 64);
+    const u32 hi = __shfl_up(static_cast<u32>(v >> 32), d, 64);
+    return (static_cast<u64>(hi) << 32) | lo;
+}
+
+__device__ inline u64 wave_incl_scan_u64(u64 v) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const u64 o = shfl_up_u64(v, d);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan over the 256 threads of a workgroup in thread order; *total gets the sum.
+// s_wave must hold kBlock / 64 entries.  All threads must call it.
+__device__ inline u64 block_excl_scan_u64(u64 v, u64* s_wave, u64* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u64 incl = wave_incl_scan_u64(v);
+    __syncthreads();                       // s_wave may still be read from a previous call
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    u64 before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) {
+        const u64 t = s_wave[w];
+        if (w < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_fill_zero(u64* p, u64 n_words) {
+    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
+    for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x; i < n_words; i += stride) p[i] = 0;
+}
+
+// ---- histogram of one radix level over the weights ----------------------------------------------
+//
+// Every workgroup sweeps a contiguous range of chunks and keeps its counts in LDS; they are added
+// to the global histogram when the group (tensor under PER_TENSOR scope) changes and at the end.
+// Level 0 has no prefix to match, so the densities of a group share one histogram; later levels
+// keep one histogram per ranking, kSlotBatch rankings per sweep of the range.
+template <bool LC, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64 chunks_per_block) {
+    __shared__ u32 s_hist[kSlotBatch * 1024 > kBins ? kSlotBatch * 1024 : kBins];
+    __shared__ u32 s_prefix[kSlotBatch];
+    __shared__ u32 s_active[kSlotBatch];
+    __shared__ u32 s_any;
+
+    if (a.only_failed && a.ctl->window_failed == 0) return;
+    const u64 c0 = static_cast<u64>(blockIdx.x) * chunks_per_block;
+    if (c0 >= a.n_chunks) return;
+    const u64 c1 = (c0 + chunks_per_block < a.n_chunks) ? c0 + chunks_per_block : a.n_chunks;
+
+    const Level L = level_of(31, level);
+    const int nb = 1 << L.bits;
+    const int tid = threadIdx.x;
+    const int n_batches = (level == 0) ? 1 : (a.J + kSlotBatch - 1) / kSlotBatch;
+
+    for (int batch = 0; batch < n_batches; ++batch) {
+        const int j0 = batch * kSlotBatch;
+        const int nj = (level == 0) ? a.J : ((a.J - j0 < kSlotBatch) ? a.J - j0 : kSlotBatch);
+        const int n_hist = (level == 0) ? 1 : nj;
+        long long cur_group = -1;
+        for (u64 c = c0; c < c1; ++c) {
+            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const long long g = a.per_tensor ? t : 0;
+            if (g != cur_group) {
+                if (cur_group >= 0) {                     // flush the previous group's counts
+                    __syncthreads();
+                    for (int i = tid; i < n_hist * nb; i += kBlock) {
+                        const u32 v = s_hist[i];
+                        if (v) {
+                            u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(cur_group) * kBins + i
+                                                    : a.histx + (static_cast<u64>(cur_group) * a.J + j0 + i / nb) * kBins + (i % nb);
+                            atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
+                        }
+                    }
+                }
+                __syncthreads();
+                if (tid == 0) s_any = 0;
+                __syncthreads();
+                if (level == 0) {
+                    if (tid < a.J && a.slots[g * a.J + tid].state == kSelecting) s_any = 1;
+                } else if (tid < nj) {
+                    const Slot& s = a.slots[g * a.J + j0 + tid];
+                    s_prefix[tid] = static_cast<u32>(s.prefix);
+                    s_active[tid] = (s.state == kSelecting) ? 1u : 0u;
+                    if (s.state == kSelecting) s_any = 1;
+                }
+                for (int i = tid; i < n_hist * nb; i += kBlock) s_hist[i] = 0;
+                __syncthreads();
+                cur_group = g;
+            }
+            if (!s_any) continue;
+            const TensorDesc& td = a.td[t];
+            const u64 base = (c - td.chunk_start) * kChunk;
+#pragma unroll 2
+            for (int q = 0; q < kQuadsPerThread; ++q) {
+                const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+                if (e0 >= td.n) break;
+                float v[4];
+                load4<VEC>(td.w, e0, td.n, v);
+                if (LC) {
+                    float l[4];
+                    load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (e0 + k >= td.n) break;
+                    const u32 key = mag_key(v[k]);
+                    if (level == 0) {
+                        atomicAdd(&s_hist[key >> L.shift], 1u);
+                    } else {
+                        const u32 digit = (key >> L.shift) & (nb - 1);
+                        for (int j = 0; j < nj; ++j)
+                            if (s_active[j] && ((key ^ s_prefix[j]) >> L.hi_shift) == 0)
+                                atomicAdd(&s_hist[j * nb + digit], 1u);
+                    }
+                }
+            }
+        }
+        if (cur_group >= 0) {
+            __syncthreads();
+            for (int i = tid; i < n_hist * nb; i += kBlock) {
+                const u32 v = s_hist[i];
+                if (v) {
+                    u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(cur_group) * kBins + i
+                                            : a.histx + (static_cast<u64>(cur_group) * a.J + j0 + i / nb) * kBins + (i % nb);
+                    atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---- one level of the search: locate the bin that holds the wanted rank -------------------------
+//
+// One workgroup per ranking.  Bins are walked from the top; the bin b with
+//   #(keys in higher bins) < remaining <= #(keys in bins >= b)
+// extends the prefix.  After the last level the prefix is the threshold key, `remaining` the number
+// of ties to keep and n_tie the number of keys equal to the threshold.
+__global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* hist_shared, u64* hist_slot,
+                                                       int J, int key_bits, int level, Control* ctl,
+                                                       int only_failed) {
+    __shared__ u64 s_wave[kBlock / 64];
+    if (only_failed && ctl->window_failed == 0) return;
+    const int s = blockIdx.x;
+    Slot& slot = slots[s];
+    if (slot.state != kSelecting) return;             // uniform over the workgroup
+    const Level L = level_of(key_bits, level);
+    const int nb = 1 << L.bits;
+    const bool shared = (level == 0 && hist_shared != nullptr);
+    const u64* hist = shared ? hist_shared + static_cast<u64>(s / J) * kBins : hist_slot + static_cast<u64>(s) * kBins;
+    constexpr int kPer = kBins / kBlock;              // 8 bins per thread, from the top
+    const int tid = threadIdx.x;
+    u64 cnt[kPer];
+    u64 sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int b = nb - 1 - (tid * kPer + i);
+        cnt[i] = (b >= 0) ? hist[b] : 0;
+        sum += cnt[i];
+    }
+    const u64 remaining = slot.remaining;
+    u64 total;
+    u64 cum = block_excl_scan_u64(sum, s_wave, &total);
+    __syncthreads();                                   // every thread has read slot.remaining
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int b = nb - 1 - (tid * kPer + i);
+        if (b >= 0 && cum < remaining && remaining <= cum + cnt[i]) {
+            const u64 rem = remaining - cum;
+            slot.prefix |= static_cast<u64>(b) << L.shift;
+            slot.remaining = rem;
+            slot.n_tie = cnt[i];
+            if (level == n_levels(key_bits) - 1) {
+                slot.state = kDone;
+                if (rem < cnt[i]) {
+                    slot.need_tie = 1;
+                    atomicOr(&ctl->need_tie, 1u);
+                } else {
+                    slot.need_tie = 0;
+                    slot.tie_end = slot.n;
+                }
+            }
+        }
+        cum += cnt[i];
+    }
+    if (!shared) {                                     // leave the ranking's histogram clean for the next level
+        u64* h = hist_slot + static_cast<u64>(s) * kBins;
+        for (int i = tid; i < nb; i += kBlock) h[i] = 0;
+    }
+}
+
+// ---- ties: count per chunk, then find the chunk and the element that ends the kept ties ---------
+
+template <bool LC, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
+    __shared__ u32 s_T[kMaxJ];
+    __shared__ u32 s_need[kMaxJ];
+    __shared__ u32 s_cnt[kMaxJ];
+    __shared__ u32 s_any;
+    if (a.ctl->need_tie == 0) return;
+    const u64 c = blockIdx.x;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const u64 g = a.per_tensor ? t : 0;
+    if (tid == 0) s_any = 0;
+    __syncthreads();
+    if (tid < a.J) {
+        const Slot& s = a.slots[g * a.J + tid];
+        s_T[tid] = static_cast<u32>(s.prefix);
+        s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
+        s_cnt[tid] = 0;
+        if (s_need[tid]) s_any = 1;
+    }
+    __syncthreads();
+    if (!s_any) return;
+    const TensorDesc& td = a.td[t];
+    const u64 base = (c - td.chunk_start) * kChunk;
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) break;
+        float v[4];
+        load4<VEC>(td.w, e0, td.n, v);
+        if (LC) {
+            float l[4];
+            load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (e0 + k >= td.n) break;
+            const u32 key = mag_key(v[k]);
+            for (int j = 0; j < a.J; ++j)
+                if (s_need[j] && key == s_T[j]) atomicAdd(&s_cnt[j], 1u);
+        }
+    }
+    __syncthreads();
+    if (tid < a.J && s_need[tid]) a.tiecnt[static_cast<u64>(tid) * a.n_chunks + c] = s_cnt[tid];
+}
+
+// One workgroup per ranking: finishes the tie search (if any) and writes the public record.
+template <bool LC, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_select* results, int n_groups) {
+    __shared__ u64 s_wave[kBlock / 64];
+    __shared__ u64 s_found[3];                 // chunk, rank inside it, flag
+    const int s = blockIdx.x;
+    const int g = s / a.J, j = s % a.J;
+    const int tid = threadIdx.x;
+    Slot& slot = a.slots[s];
+    const bool need = (slot.state == kDone && slot.need_tie);
+    if (need) {
+        const u64 r = slot.remaining;          // 1-based rank of the last kept tie
+        const u32 T = static_cast<u32>(slot.prefix);
+        const u64 cb = a.per_tensor ? a.td[g].chunk_start : 0;
+        const u64 ce = a.per_tensor ? a.td[g + 1].chunk_start : a.n_chunks;
+        const u32* cnt = a.tiecnt + static_cast<u64>(j) * a.n_chunks;
+        // every thread owns a contiguous run of the chunk range
+        const u64 per = (ce - cb + kBlock - 1) / kBlock;
+        const u64 my0 = cb + per * tid < ce ? cb + per * tid : ce;
+        const u64 my1 = my0 + per < ce ? my0 + per : ce;
+        u64 mine = 0;
+        for (u64 c = my0; c < my1; ++c) mine += cnt[c];
+        u64 total;
+        u64 before = block_excl_scan_u64(mine, s_wave, &total);
+        if (tid == 0) s_found[2] = 0;
+        __syncthreads();
+        if (before < r && r <= before + mine) {
+            u64 cum = before;
+            for (u64 c = my0; c < my1; ++c) {
+                const u64 x = cnt[c];
+                if (r <= cum + x) { s_found[0] = c; s_found[1] = r - cum; s_found[2] = 1; break; }
+                cum += x;
+            }
+        }
+        __syncthreads();
+        if (s_found[2]) {
+            const u64 c = s_found[0];
+            const u64 rr = s_found[1];
+            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const TensorDesc& td = a.td[t];
+            const u64 base = (c - td.chunk_start) * kChunk;
+            constexpr int kRun = kChunk / kBlock;              // 32 consecutive elements per thread
+            const u64 e_begin = base + static_cast<u64>(tid) * kRun;
+            u32 hits = 0;
+            for (int k = 0; k < kRun; ++k) {
+                const u64 e = e_begin + k;
+                if (e >= td.n) break;
+                const float x = LC ? lc_shift(td.w[e], td.lam[e], a.mu) : td.w[e];
+                hits += (mag_key(x) == T) ? 1u : 0u;
+            }
+            u64 tot2;
+            const u64 bef2 = block_excl_scan_u64(hits, s_wave, &tot2);
+            if (bef2 < rr && rr <= bef2 + hits) {
+                u64 seen = bef2;
+                for (int k = 0; k < kRun; ++k) {
+                    const u64 e = e_begin + k;
+                    if (e >= td.n) break;
+                    const float x = LC ? lc_shift(td.w[e], td.lam[e], a.mu) : td.w[e];
+                    if (mag_key(x) == T) {
+                        ++seen;
+                        if (seen == rr) { slot.tie_end = (a.per_tensor ? 0 : td.flat_start) + e + 1; break; }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (tid == 0) {
+        condensa_select out;
+        out.n = slot.n;
+        out.k = slot.k;
+        if (slot.state == kDone) {
+            out.n_gt = slot.k - slot.remaining;
+            out.n_tie_kept = slot.remaining;
+            out.n_tie = slot.n_tie;
+            out.threshold_key = slot.prefix;
+            out.tie_end = slot.tie_end;
+        } else {                                  // k == 0: nothing is kept
+            out.n_gt = 0; out.n_tie_kept = 0; out.n_tie = 0;
+            out.threshold_key = ~static_cast<u64>(0);
+            out.tie_end = 0;
+        }
+        out.path = slot.path;
+        results[static_cast<u64>(j) * n_groups + g] = out;
+    }
+}
+
+}  // namespace condensa

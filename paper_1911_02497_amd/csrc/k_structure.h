@@ -1,0 +1,334 @@
+// Structure pruning: per-filter / per-block sums of squares, ranking of the aggregates, structure
+// masks, kept-index lists and the element-wise apply.
+// Table 1: FilterPrune ("aggregates and prunes filters (3D blocks)"), BlockPrune ("n-D blocks of size
+// bs"); Section 3.1: "filter/neuron/block aggregation".
+#pragma once
+#include "k_apply.h"
+#include "k_select.h"
+
+namespace condensa {
+
+struct StructArgs {
+    const TensorDesc* td;
+    Slot* slots;
+    u64* histx;            // [n_slots][kBins]
+    u32* tiecnt;           // [n_schunks]
+    Control* ctl;
+    u64* keys;             // [F] sign-less binary64 patterns of the aggregates
+    u8* smask;             // [F]
+    u32* sblock;           // [ceil(F / kBlock) + 1] kept structures per block of 256, then its scan
+    u64 F;
+    u64 n_schunks;
+    u64 n_chunks;
+    int n_tensors;
+    int per_tensor;
+};
+
+__device__ inline int tensor_of_struct(const TensorDesc* __restrict__ td, int n_tensors, u64 u) {
+    int lo = 0, hi = n_tensors - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (td[mid].struct_start <= u) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ inline int tensor_of_schunk(const TensorDesc* __restrict__ td, int n_tensors, u64 c) {
+    int lo = 0, hi = n_tensors - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (td[mid].pad <= c) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// One thread per structure; squares are added in binary64 in memory order (row-major inside a
+// block), so the aggregate does not depend on the launch shape.  x*x is exact in binary64.
+__global__ __launch_bounds__(kBlock) void k_struct_sumsq(StructArgs a, double* sumsq, float* norms) {
+    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x;
+    if (u >= a.F) return;
+    const int t = tensor_of_struct(a.td, a.n_tensors, u);
+    const TensorDesc& td = a.td[t];
+    const u64 s = u - td.struct_start;
+    const u64 br = s / td.s_per_row, bc = s % td.s_per_row;
+    const float* p = td.w + br * td.s_rows * static_cast<u64>(td.s_ld) + bc * td.s_len;
+    const bool vec = ((td.s_len | td.s_ld) & 3u) == 0 && (reinterpret_cast<uintptr_t>(td.w) & 15u) == 0;
+    double acc = 0.0;
+    for (u32 r = 0; r < td.s_rows; ++r) {
+        const float* row = p + static_cast<u64>(r) * td.s_ld;
+        if (vec) {
+            for (u32 x = 0; x < td.s_len; x += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(row + x);
+                acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x);
+                acc = acc + static_cast<double>(v.y) * static_cast<double>(v.y);
+                acc = acc + static_cast<double>(v.z) * static_cast<double>(v.z);
+                acc = acc + static_cast<double>(v.w) * static_cast<double>(v.w);
+            }
+        } else {
+            for (u32 x = 0; x < td.s_len; ++x) {
+                const double v = static_cast<double>(row[x]);
+                acc = acc + v * v;
+            }
+        }
+    }
+    a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
+    if (sumsq) sumsq[u] = acc;
+    if (norms) norms[u] = static_cast<float>(sqrt(acc));
+}
+
+// Histogram of one radix level over the aggregate keys (one ranking per group).
+__global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u64 chunks_per_block) {
+    __shared__ u32 s_hist[kBins];
+    __shared__ u64 s_prefix;
+    __shared__ u32 s_active;
+    const u64 c0 = static_cast<u64>(blockIdx.x) * chunks_per_block;
+    if (c0 >= a.n_schunks) return;
+    const u64 c1 = (c0 + chunks_per_block < a.n_schunks) ? c0 + chunks_per_block : a.n_schunks;
+    const Level L = level_of(63, level);
+    const int nb = 1 << L.bits;
+    const int tid = threadIdx.x;
+    long long cur_group = -1;
+    for (u64 c = c0; c < c1; ++c) {
+        const int t = tensor_of_schunk(a.td, a.n_tensors, c);
+        const long long g = a.per_tensor ? t : 0;
+        if (g != cur_group) {
+            if (cur_group >= 0) {
+                __syncthreads();
+                for (int i = tid; i < nb; i += kBlock) {
+                    const u32 v = s_hist[i];
+                    if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.histx + static_cast<u64>(cur_group) * kBins + i),
+                                     static_cast<unsigned long long>(v));
+                }
+            }
+            __syncthreads();
+            if (tid == 0) {
+                const Slot& s = a.slots[g];
+                s_prefix = s.prefix;
+                s_active = (s.state == kSelecting) ? 1u : 0u;
+            }
+            for (int i = tid; i < nb; i += kBlock) s_hist[i] = 0;
+            __syncthreads();
+            cur_group = g;
+        }
+        if (!s_active) continue;
+        const TensorDesc& td = a.td[t];
+        const u64 base = (c - td.pad) * kChunk;
+        const u64 prefix = s_prefix;
+        for (u64 i = base + tid; i < base + kChunk && i < td.n_struct; i += kBlock) {
+            const u64 key = a.keys[td.struct_start + i];
+            if (((key ^ prefix) >> L.hi_shift) == 0)
+                atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
+        }
+    }
+    if (cur_group >= 0) {
+        __syncthreads();
+        for (int i = tid; i < nb; i += kBlock) {
+            const u32 v = s_hist[i];
+            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.histx + static_cast<u64>(cur_group) * kBins + i),
+                             static_cast<unsigned long long>(v));
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_tie_count_keys(StructArgs a) {
+    __shared__ u32 s_cnt;
+    if (a.ctl->need_tie == 0) return;
+    const u64 c = blockIdx.x;
+    if (c >= a.n_schunks) return;
+    const int tid = threadIdx.x;
+    const int t = tensor_of_schunk(a.td, a.n_tensors, c);
+    const u64 g = a.per_tensor ? t : 0;
+    const Slot& s = a.slots[g];
+    if (!(s.state == kDone && s.need_tie)) return;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    const u64 T = s.prefix;
+    const TensorDesc& td = a.td[t];
+    const u64 base = (c - td.pad) * kChunk;
+    u32 mine = 0;
+    for (u64 i = base + tid; i < base + kChunk && i < td.n_struct; i += kBlock)
+        mine += (a.keys[td.struct_start + i] == T) ? 1u : 0u;
+    if (mine) atomicAdd(&s_cnt, mine);
+    __syncthreads();
+    if (tid == 0) a.tiecnt[c] = s_cnt;
+}
+
+// One workgroup per ranking: index search among tied aggregates, then the public record.
+__global__ __launch_bounds__(kBlock) void k_tie_locate_keys(StructArgs a, condensa_select* results) {
+    __shared__ u64 s_wave[kBlock / 64];
+    __shared__ u64 s_found[3];
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x;
+    Slot& slot = a.slots[g];
+    const bool need = (slot.state == kDone && slot.need_tie);
+    if (need) {
+        const u64 r = slot.remaining;
+        const u64 T = slot.prefix;
+        const u64 cb = a.per_tensor ? a.td[g].pad : 0;
+        const u64 ce = a.per_tensor ? a.td[g + 1].pad : a.n_schunks;
+        const u64 per = (ce - cb + kBlock - 1) / kBlock;
+        const u64 my0 = cb + per * tid < ce ? cb + per * tid : ce;
+        const u64 my1 = my0 + per < ce ? my0 + per : ce;
+        u64 mine = 0;
+        for (u64 c = my0; c < my1; ++c) mine += a.tiecnt[c];
+        u64 total;
+        const u64 before = block_excl_scan_u64(mine, s_wave, &total);
+        if (tid == 0) s_found[2] = 0;
+        __syncthreads();
+        if (before < r && r <= before + mine) {
+            u64 cum = before;
+            for (u64 c = my0; c < my1; ++c) {
+                const u64 x = a.tiecnt[c];
+                if (r <= cum + x) { s_found[0] = c; s_found[1] = r - cum; s_found[2] = 1; break; }
+                cum += x;
+            }
+        }
+        __syncthreads();
+        if (s_found[2]) {
+            const u64 c = s_found[0];
+            const u64 rr = s_found[1];
+            const int t = tensor_of_schunk(a.td, a.n_tensors, c);
+            const TensorDesc& td = a.td[t];
+            const u64 base = (c - td.pad) * kChunk;
+            constexpr int kRun = kChunk / kBlock;
+            const u64 i_begin = base + static_cast<u64>(tid) * kRun;
+            u32 hits = 0;
+            for (int k = 0; k < kRun; ++k) {
+                const u64 i = i_begin + k;
+                if (i >= td.n_struct) break;
+                hits += (a.keys[td.struct_start + i] == T) ? 1u : 0u;
+            }
+            u64 tot2;
+            const u64 bef2 = block_excl_scan_u64(hits, s_wave, &tot2);
+            if (bef2 < rr && rr <= bef2 + hits) {
+                u64 seen = bef2;
+                for (int k = 0; k < kRun; ++k) {
+                    const u64 i = i_begin + k;
+                    if (i >= td.n_struct) break;
+                    if (a.keys[td.struct_start + i] == T) {
+                        ++seen;
+                        if (seen == rr) { slot.tie_end = (a.per_tensor ? 0 : td.struct_start) + i + 1; break; }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (tid == 0) {
+        condensa_select out;
+        out.n = slot.n;
+        out.k = slot.k;
+        if (slot.state == kDone) {
+            out.n_gt = slot.k - slot.remaining;
+            out.n_tie_kept = slot.remaining;
+            out.n_tie = slot.n_tie;
+            out.threshold_key = slot.prefix;
+            out.tie_end = slot.tie_end;
+        } else {
+            out.n_gt = 0; out.n_tie_kept = 0; out.n_tie = 0;
+            out.threshold_key = ~static_cast<u64>(0);
+            out.tie_end = 0;
+        }
+        out.path = slot.path;
+        results[g] = out;
+    }
+}
+
+// keep flag of every structure and the number of kept structures of every block of 256
+__global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask) {
+    __shared__ u32 s_cnt;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + tid;
+    u32 keep = 0;
+    if (u < a.F) {
+        const int t = tensor_of_struct(a.td, a.n_tensors, u);
+        const Slot& s = a.slots[a.per_tensor ? t : 0];
+        const u64 idx = a.per_tensor ? u - a.td[t].struct_start : u;
+        const u64 key = a.keys[u];
+        keep = (key > s.prefix || (key == s.prefix && idx < s.tie_end)) ? 1u : 0u;
+        if (s.state == kInactive) keep = 0;
+        a.smask[u] = static_cast<u8>(keep);
+        if (user_mask) user_mask[u] = static_cast<u8>(keep);
+    }
+    if (keep) atomicAdd(&s_cnt, 1u);
+    __syncthreads();
+    if (tid == 0) a.sblock[blockIdx.x] = s_cnt;
+}
+
+// exclusive scan of the per-block counts (single workgroup)
+__global__ __launch_bounds__(kBlock) void k_struct_scan_blocks(u32* sblock, u64 n_blocks) {
+    __shared__ u64 s_wave[kBlock / 64];
+    u64 running = 0;
+    for (u64 base = 0; base < n_blocks; base += kBlock) {
+        const u64 i = base + threadIdx.x;
+        const u64 v = (i < n_blocks) ? sblock[i] : 0;
+        u64 total;
+        const u64 ex = block_excl_scan_u64(v, s_wave, &total);
+        if (i < n_blocks) sblock[i] = static_cast<u32>(running + ex);
+        running += total;
+    }
+}
+
+// ascending ids of the kept structures
+__global__ __launch_bounds__(kBlock) void k_struct_keep_idx(StructArgs a, int32_t* keep_idx) {
+    __shared__ u64 s_wave[kBlock / 64];
+    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x;
+    const u32 keep = (u < a.F) ? a.smask[u] : 0u;
+    u64 total;
+    const u64 ex = block_excl_scan_u64(keep, s_wave, &total);
+    if (keep) keep_idx[a.sblock[blockIdx.x] + ex] = static_cast<int32_t>(u);
+}
+
+// theta = w on kept structures, +0 elsewhere; element mask = structure mask broadcast
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const OutDesc* __restrict__ out) {
+    const u64 c = blockIdx.x;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const TensorDesc& td = a.td[t];
+    const OutDesc o = out[t];
+    const u8* __restrict__ sm = a.smask + td.struct_start;
+    const u64 base = (c - td.chunk_start) * kChunk;
+    const u32 ld = td.s_ld, rows = td.s_rows, len = td.s_len, per_row = td.s_per_row;
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) break;
+        float v[4];
+        load4<VEC>(td.w, e0, td.n, v);
+        u64 row;
+        u32 col;
+        if (td.n <= 0xFFFFFFFFull) {
+            const u32 e32 = static_cast<u32>(e0);
+            row = e32 / ld;
+            col = e32 % ld;
+        } else {
+            row = e0 / ld;
+            col = static_cast<u32>(e0 % ld);
+        }
+        float th[4];
+        u8 m[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            while (col >= ld) { col -= ld; ++row; }
+            u8 keep = 0;
+            if (e0 + k < td.n) {
+                const u64 s = (row <= 0xFFFFFFFFull)
+                                  ? static_cast<u64>(static_cast<u32>(row) / rows) * per_row + col / len
+                                  : (row / rows) * per_row + col / len;
+                keep = sm[s];
+            }
+            m[k] = keep;
+            th[k] = keep ? v[k] : 0.0f;
+            ++col;
+        }
+        if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+        if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    }
+}
+
+}  // namespace condensa

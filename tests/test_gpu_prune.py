@@ -1,0 +1,119 @@
+"""GPU parity: condensa_prune against the oracle (masks, thetas, fp16 thetas, records bit exact)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1911_02497_amd as P
+import workloads
+from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
+
+pytestmark = pytest.mark.gpu
+
+
+def _prune_both(arrs, densities, scope=P.SCOPE_GLOBAL, what="", **kw):
+    res = P.condensa_prune(up(arrs), densities, scope=scope, **kw)
+    torch.cuda.synchronize()
+    ora = oracle.prune(arrs, densities, scope)
+    check_prune_against_oracle(res, ora, scope, len(arrs), what)
+    return res, ora
+
+
+def test_single_matrix_density_002_with_fp16():
+    (w,) = workloads.single_matrix()
+    res, ora = _prune_both([w], [0.02], theta_f16=True)
+    rec = P.select_records(res["results"])[0]
+    assert rec["k"] == 20972 and int(res["mask"][0][0].sum().item()) == 20972
+    q = res["theta_f16"][0][0].cpu().numpy().view(np.uint16)
+    oq, _ = oracle.quantize_f16(ora[0]["theta"][0])
+    assert np.array_equal(q, oq)
+    # unfused: prune then quantize gives the same bits
+    q2, _ = P.condensa_quantize(res["theta"][0][0])
+    assert np.array_equal(q2.cpu().numpy().view(np.uint16), oq)
+
+
+CASES = {
+    "all_equal": [np.full(1000, 0.5, np.float32)],
+    "all_zero": [np.zeros(777, np.float32)],
+    "signed_zeros": [np.tile(np.array([0.0, -0.0, 1.0, -0.0], np.float32), 300)],
+    "few_values_many_ties": [np.random.default_rng(1).integers(-3, 4, 20001).astype(np.float32)],
+    "inf_nan_denormal": [np.array([1.0, np.inf, -np.inf, np.nan, 0.0, -3.0, 1e-40, -1e-40, 2e-45] * 5, np.float32)],
+    "ragged_multi": [np.random.default_rng(2).standard_normal(s).astype(np.float32)
+                     for s in ((8192 * 2 + 5,), (1,), (3, 7), (0,), (4, 3, 3, 3), (8192,), (8193,))],
+    "spans_many_chunks": [np.random.default_rng(3).standard_normal(8192 * 37 + 11).astype(np.float32)],
+    "empty_first_and_last": [np.zeros((0,), np.float32), np.arange(100, dtype=np.float32), np.zeros((0, 4), np.float32)],
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+@pytest.mark.parametrize("scope", [P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR])
+def test_adversarial_shapes(name, scope):
+    arrs = CASES[name]
+    _prune_both(arrs, [0.0, 0.001, 0.1, 0.5, 0.9, 1.0], scope=scope, what=name)
+
+
+def test_ties_planted_across_tensors_and_chunks():
+    rng = np.random.default_rng(4)
+    a = rng.standard_normal(8192 * 3).astype(np.float32)
+    b = rng.standard_normal(5000).astype(np.float32)
+    t = np.float32(0.731)
+    for arr, pos in ((a, [5, 8191, 8192, 20000]), (b, [0, 4999, 77])):
+        for p in pos:
+            arr[p] = t if p % 2 else -t
+    n = a.size + b.size
+    n_gt = int((np.abs(np.concatenate([a, b])) > t).sum())
+    for extra in (1, 3, 6, 7):                      # keep only some of the 7 tied magnitudes
+        d = (n_gt + extra) / n
+        res, ora = _prune_both([a, b], [d])
+        assert ora[0]["select"]["n_tie"] == 7 and ora[0]["select"]["n_tie_kept"] == extra
+
+
+def test_vgg19_shapes_ten_densities_one_call():
+    ws = workloads.vgg19_cifar()
+    assert sum(w.size for w in ws) == 20024000
+    ds = workloads.search_densities()
+    dev = up(ws)
+    res = P.condensa_prune(dev, ds, theta=False, mask=False)          # thresholds only
+    torch.cuda.synchronize()
+    ora = oracle.prune(ws, ds)
+    recs = P.select_records(res["results"])
+    for j in range(len(ds)):
+        assert_select_equal(recs[j], ora[j]["select"], f"density {j}")
+    # masks for three of the densities in one apply sweep
+    sub = [ds[0], ds[4], ds[9]]
+    res = P.condensa_prune(dev, sub, theta=False, mask=True)
+    torch.cuda.synchronize()
+    for j, jj in enumerate((0, 4, 9)):
+        for t in range(len(ws)):
+            assert np.array_equal(res["mask"][j][t].cpu().numpy(), ora[jj]["mask"][t])
+
+
+def test_in_place_and_misaligned():
+    rng = np.random.default_rng(6)
+    w = rng.standard_normal(30011).astype(np.float32)
+    ora = oracle.prune([w], [0.3])[0]
+    dw = torch.from_numpy(w).to(DEV)
+    res = P.condensa_prune([dw], [0.3], in_place=True)
+    assert_bits_equal(dw, ora["theta"][0], "in place")
+    big = torch.from_numpy(np.concatenate([[9.0], w]).astype(np.float32)).to(DEV)
+    res = P.condensa_prune([big[1:]], [0.3])
+    assert_bits_equal(res["theta"][0][0], ora["theta"][0], "misaligned input")
+    assert np.array_equal(res["mask"][0][0].cpu().numpy(), ora["mask"][0])
+
+
+def test_argument_errors_have_no_side_effects():
+    w = torch.ones(16, device=DEV)
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(P.CondensaError) as e:
+            P.condensa_prune([w], [bad])
+        assert e.value.code == -3
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_prune([w], [0.5] * 17)
+    assert e.value.code == -2
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_prune([w], [0.5], workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -5
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_prune([w], [0.5], scope=7)
+    assert e.value.code == -6
+    assert torch.all(w == 1)

@@ -1,0 +1,74 @@
+"""GPU parity: condensa_quantize / condensa_dequantize against the oracle, bit for bit."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1911_02497_amd as P
+from gpu_util import DEV, assert_bits_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(x):
+    q, dq = P.condensa_quantize(torch.from_numpy(x).to(DEV))
+    torch.cuda.synchronize()
+    return q.cpu().numpy().view(np.uint16), dq.cpu().numpy()
+
+
+def _compare(x, what):
+    q, dq = _run(x)
+    oq, odq = oracle.quantize_f16(x)
+    nan = np.isnan(x)
+    assert np.array_equal(q[~nan], oq[~nan]), what
+    assert np.array_equal(q[nan], oq[nan]), what + " (NaN payload rule)"
+    assert_bits_equal(dq, odq, what + " dq")
+
+
+def test_golden_points():
+    path = os.path.join(os.path.dirname(__file__), "golden", "binary16_points.txt")
+    pts = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    x = np.array([int(a, 16) for a, _ in pts], np.uint32).view(np.float32)
+    q, _ = _run(x)
+    assert [hex(v) for v in q.tolist()] == [hex(int(b, 16)) for _, b in pts]
+
+
+def test_stratified_bit_patterns_and_band_sweeps():
+    hi10 = np.array([0, 1, 0x2AA, 0x3FF], np.uint32)
+    low = np.arange(1 << 13, dtype=np.uint32)
+    se = np.arange(1 << 9, dtype=np.uint32)
+    bits = ((se[:, None, None] << 23) | (hi10[None, :, None] << 13) | low[None, None, :]).reshape(-1)
+    _compare(bits.view(np.float32), "stratified")
+    for e in (101, 102, 112, 113, 142, 143, 255):
+        b = np.arange(e << 23, (e + 1) << 23, dtype=np.uint64).astype(np.uint32)
+        _compare(b.view(np.float32), f"exponent band {e}")
+
+
+def test_ragged_sizes_and_misaligned_views():
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 3, 5, 255, 1023, 1025, 8191, 70001):
+        x = (rng.standard_normal(n) * 0.02).astype(np.float32)
+        _compare(x, f"n={n}")
+    big = torch.from_numpy((rng.standard_normal(10007) * 3).astype(np.float32)).to(DEV)
+    view = big[1:]                                         # 4-byte aligned only: scalar path
+    q, dq = P.condensa_quantize(view)
+    oq, odq = oracle.quantize_f16(view.cpu().numpy())
+    assert np.array_equal(q.cpu().numpy().view(np.uint16), oq)
+    assert_bits_equal(dq, odq, "misaligned dq")
+
+
+def test_empty_and_dequantize_all_patterns():
+    q, dq = P.condensa_quantize(torch.empty(0, dtype=torch.float32, device=DEV))
+    assert q.numel() == 0 and dq.numel() == 0
+    allh = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    got = P.condensa_dequantize(torch.from_numpy(allh.view(np.int16)).to(DEV)).cpu().numpy()
+    want = oracle.dequantize_f16(allh)
+    assert_bits_equal(got, want, "dequantize")
+
+
+def test_errors():
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_quantize(torch.zeros(4, device=DEV), want_q=False, want_dq=False)
+    assert e.value.code == -1
