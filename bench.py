@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the compression step on one MI355X.
+
+One step = one full L-C compression step (condensa_lc_step) over the large-model stress workload:
+64 fp32 matrices of 4096x4608 (1.2 G weights) with multipliers, mu = 1e-3, density 0.1 -- global
+selection on w - lambda/mu, theta, lambda' and the penalty gradient written out.  Inputs are seeded
+synthetic tensors already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: whole-step throughput in weights/s, the roofline of the dominant kernel
+(measured with HIP events on the launch stream, inside the timed region) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--tensors", type=int, default=64, help="number of 4096x4608 matrices (64 = the full workload)")
+    ap.add_argument("--mask", action="store_true", help="also write the byte mask (+N bytes per step)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tensors", type=int, default=2)
+    ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1911_02497_amd as P
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    P.library()                                     # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    rows, cols, T = 4096, 4608, args.tensors
+    mu, density = workloads.LC_MU, workloads.LC_DENSITY
+
+    # ---- inputs: generated on the host from the seeded recipe, then made resident -------------------
+    t0 = time.time()
+    w_dev, lam_dev, cpu_w, cpu_l = [], [], [], []
+    batch = 8
+    for b in range(0, T, batch):
+        idx = list(range(b, min(b + batch, T)))
+        ws, ls = workloads.lc_stress(indices=idx, n_tensors=T, rows=rows, cols=cols, threads=16)
+        for i, w, l in zip(idx, ws, ls):
+            w_dev.append(torch.from_numpy(w).to(dev))
+            lam_dev.append(torch.from_numpy(l).to(dev))
+            if i < args.cpu_sample_tensors and not args.no_cpu_baseline:
+                cpu_w.append(w)
+                cpu_l.append(l)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    N = sum(t.numel() for t in w_dev)
+
+    outputs = {
+        "theta": [torch.empty_like(t) for t in w_dev],
+        "grad": [torch.empty_like(t) for t in w_dev],
+        "lambda": [torch.empty_like(t) for t in w_dev],
+        "results": torch.zeros((1, 8), dtype=torch.int64, device=dev),
+    }
+    if args.mask:
+        outputs["mask"] = [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in w_dev]
+    ws_bytes = P.condensa_workspace_bytes(P.binding.OP_LC_STEP, N, 0, T, 1, P.SCOPE_GLOBAL)
+    workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
+
+    def step():
+        return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,
+                                  workspace=workspace)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    P.condensa_profile_reset()
+    P.condensa_set_option(P.OPT_PROFILE, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    P.condensa_set_option(P.OPT_PROFILE, 0)
+    phases = P.condensa_profile_read()
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    rec = P.select_records(outputs["results"])[0]
+    assert rec["k"] == int(np.floor(density * N + 0.5)) and rec["n"] == N, rec
+
+    # ---- roofline of the dominant kernel: the fused apply/update sweep -------------------------------
+    # algorithmic bytes per element of that launch: read w, lambda (8) + write theta, lambda', g (12) [+1 mask]
+    apply_bytes_per_elem = 20 + (1 if args.mask else 0)
+    step_bytes_per_elem = 28 + (1 if args.mask else 0)      # plus the one selection read of w, lambda
+    apply = phases["apply"]
+    apply_ms = apply["ms"] / max(apply["intervals"], 1)
+    achieved = apply_bytes_per_elem * N / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "k_lc_apply", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_ms": round(apply_ms, 4), "algorithmic_bytes_per_launch": apply_bytes_per_elem * N}
+    step_gbps = step_bytes_per_elem * N / (ms_per_step * 1e-3) / 1e9
+    phase_ms = {k: round(v["ms"] / args.steps, 4) for k, v in phases.items() if v["intervals"]}
+
+    # ---- CPU oracle on a bounded sample of the same workload -----------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline and cpu_w:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.lc_step(cpu_w, cpu_l, mu, density)
+        dt = time.perf_counter() - t0
+        n_cpu = sum(t.size for t in cpu_w)
+        cpu = {"value": round(n_cpu / dt, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {len(cpu_w)} of the {T} tensors ({n_cpu} weights), one L-C step, {dt:.1f} s",
+               "host_cpus": os.cpu_count()}
+
+    out = {
+        "metric": "weights pruned/sec and achieved HBM GB/s (% of peak) per compression step",
+        "value": round(N / (ms_per_step * 1e-3), 1),
+        "unit": "weights/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"L-C compression step, {T} fp32 tensors of {rows}x{cols} ({N} weights) + multipliers, "
+                               f"mu={mu}, density={density}, outputs theta/lambda'/grad" + ("/mask" if args.mask else ""),
+                   "select_path": {1: "radix", 2: "window"}.get(rec["path"], str(rec["path"])),
+                   "threshold_key": rec["threshold_key"], "n_tie": rec["n_tie"]},
+        "step_algorithmic_GBps": round(step_gbps, 1),
+        "step_frac_of_hbm_peak": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "phase_ms_per_step": phase_ms,
+        "input_generation_s": round(gen_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

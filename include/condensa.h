@@ -204,10 +204,28 @@ enum {
     CONDENSA_OPT_WINDOW_MARGIN = 2, /* half-width of the sampled window in 1/16 standard deviations of
                                        the sample rank; default 112 (= 7 sigma); 0 makes windows miss    */
     CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
-    CONDENSA_OPT_COUNT         = 4
+    CONDENSA_OPT_PROFILE       = 4, /* 1: bracket the phases of every call with HIP events on the call's stream */
+    CONDENSA_OPT_COUNT         = 5
 };
 condensa_status condensa_set_option(int option, int64_t value);
 int64_t         condensa_get_option(int option);
+
+/*
+ * Phase timing (benchmarks).  With CONDENSA_OPT_PROFILE set, every entry point records a pair of
+ * timing events on the caller's stream around each phase it enqueues.  condensa_profile_read waits
+ * for the recorded events, adds the elapsed milliseconds of all finished intervals of `phase` to
+ * its running totals and returns those totals; condensa_profile_reset drops totals and events.
+ */
+enum {
+    CONDENSA_PHASE_SAMPLE    = 0,  /* sampling and the ranking of the sample                        */
+    CONDENSA_PHASE_SWEEP     = 1,  /* full sweeps over the weights that feed the selection          */
+    CONDENSA_PHASE_RESOLVE   = 2,  /* ranking of candidates / aggregates, tie search, records       */
+    CONDENSA_PHASE_APPLY     = 3,  /* the mask / theta / L-C update kernel                          */
+    CONDENSA_PHASE_AGGREGATE = 4,  /* per-structure sums of squares                                 */
+    CONDENSA_PHASE_COUNT     = 5
+};
+condensa_status condensa_profile_read(int phase, double* total_ms, uint64_t* intervals);
+condensa_status condensa_profile_reset(void);
 
 const char* condensa_status_string(condensa_status s);
 int         condensa_last_hip_error(void);   /* hipError_t of the last failing runtime call, 0 if none */

@@ -15,7 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libcondensa.so")
 
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
 OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP = range(5)
-OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT = range(4)
+OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE = range(5)
+PHASES = ("sample", "sweep", "resolve", "apply", "aggregate")
 MAX_DENSITIES = 16
 
 SELECT_FIELDS = ("n", "k", "n_gt", "n_tie_kept", "n_tie", "threshold_key", "tie_end", "path")
@@ -55,6 +56,9 @@ _PROTOTYPES = {
                                           ctypes.c_void_p]),
     "condensa_set_option": (ctypes.c_int32, [ctypes.c_int, ctypes.c_int64]),
     "condensa_get_option": (ctypes.c_int64, [ctypes.c_int]),
+    "condensa_profile_read": (ctypes.c_int32, [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(ctypes.c_uint64)]),
+    "condensa_profile_reset": (ctypes.c_int32, []),
     "condensa_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "condensa_last_hip_error": (ctypes.c_int, []),
     "condensa_version": (ctypes.c_int, []),
@@ -146,6 +150,20 @@ def condensa_set_option(option: int, value: int) -> None:
 
 def condensa_get_option(option: int) -> int:
     return int(library().condensa_get_option(option))
+
+
+def condensa_profile_reset() -> None:
+    _check(library().condensa_profile_reset())
+
+
+def condensa_profile_read() -> Dict[str, Dict[str, float]]:
+    """Totals of the phase intervals recorded since the last reset: {phase: {ms, intervals}}."""
+    out = {}
+    for i, name in enumerate(PHASES):
+        ms, n = ctypes.c_double(0.0), ctypes.c_uint64(0)
+        _check(library().condensa_profile_read(i, ctypes.byref(ms), ctypes.byref(n)))
+        out[name] = {"ms": ms.value, "intervals": int(n.value)}
+    return out
 
 
 def select_records(results) -> List[Dict[str, int]]:

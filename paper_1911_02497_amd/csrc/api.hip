@@ -52,6 +52,50 @@ condensa_status stage_upload(void* dst_dev, const void* src_host, size_t bytes, 
     return CONDENSA_OK;
 }
 
+// ---- phase timing ----------------------------------------------------------------------------------
+
+namespace {
+struct Interval {
+    hipEvent_t a = nullptr, b = nullptr;
+    int phase = 0;
+};
+std::vector<Interval> g_intervals;          // recorded, not yet read
+std::vector<hipEvent_t> g_event_pool;
+double g_phase_ms[CONDENSA_PHASE_COUNT] = {};
+u64 g_phase_n[CONDENSA_PHASE_COUNT] = {};
+std::mutex g_prof_mu;
+
+hipEvent_t take_event() {
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+PhaseTimer::PhaseTimer(int phase, hipStream_t stream) : stream_(stream) {
+    if (g_options[CONDENSA_OPT_PROFILE].load() == 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    Interval iv;
+    iv.phase = phase;
+    iv.a = take_event();
+    iv.b = take_event();
+    if (!iv.a || !iv.b) return;
+    if (hipEventRecord(iv.a, stream_) != hipSuccess) return;
+    g_intervals.push_back(iv);
+    slot_ = static_cast<int>(g_intervals.size()) - 1;
+}
+
+PhaseTimer::~PhaseTimer() {
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    if (slot_ < static_cast<int>(g_intervals.size())) (void)hipEventRecord(g_intervals[slot_].b, stream_);
+}
+
 // ---- workspace layout ----------------------------------------------------------------------------
 
 static u64 window_sample_size(u64 N) {
@@ -187,6 +231,7 @@ static unsigned fill_grid(u64 words) {
 template <bool LC, bool VEC>
 static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st) {
     if (a.n_chunks > 0) {
+        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
         u64 blocks = a.n_chunks < 2048 ? a.n_chunks : 2048;
         const u64 cpb = (a.n_chunks + blocks - 1) / blocks;
         blocks = (a.n_chunks + cpb - 1) / cpb;
@@ -204,6 +249,7 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
 template <bool LC, bool VEC>
 static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, int n_groups,
                                                condensa_select* results, hipStream_t st) {
+    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
     if (a.n_chunks > 0) {
         hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a);
         CONDENSA_LAUNCH_CHECK();
@@ -333,6 +379,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     if (rc != CONDENSA_OK) return rc;
 
     if (any_out && tb.n_chunks > 0) {
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
         else     hipLaunchKernelGGL((k_prune_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
@@ -418,6 +465,7 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
     if (rc != CONDENSA_OK) return rc;
 
     if (tb.n_chunks > 0) {
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         if (vec) hipLaunchKernelGGL((k_lc_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
         else     hipLaunchKernelGGL((k_lc_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
@@ -487,8 +535,12 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
 
     const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
     if (tb.F > 0) {
-        hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
-        CONDENSA_LAUNCH_CHECK();
+        {
+            PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st);
+            hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            CONDENSA_LAUNCH_CHECK();
+        }
+        PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
         u64 blocks = tb.n_schunks < 1024 ? tb.n_schunks : 1024;
         const u64 cpb = (tb.n_schunks + blocks - 1) / blocks;
         blocks = (tb.n_schunks + cpb - 1) / cpb;
@@ -514,6 +566,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             CONDENSA_LAUNCH_CHECK();
         }
         if ((theta || mask) && tb.n_chunks > 0) {
+            PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
             if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
             else     hipLaunchKernelGGL((k_struct_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
@@ -639,12 +692,44 @@ condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq
     return CONDENSA_OK;
 }
 
+condensa_status condensa_profile_read(int phase, double* total_ms, uint64_t* intervals) {
+    if (phase < 0 || phase >= CONDENSA_PHASE_COUNT) return CONDENSA_ERR_ARG;
+    if (total_ms == nullptr || intervals == nullptr) return CONDENSA_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    for (Interval& iv : g_intervals) {
+        CONDENSA_HIP(hipEventSynchronize(iv.b));
+        float ms = 0.0f;
+        CONDENSA_HIP(hipEventElapsedTime(&ms, iv.a, iv.b));
+        g_phase_ms[iv.phase] += ms;
+        g_phase_n[iv.phase] += 1;
+        g_event_pool.push_back(iv.a);
+        g_event_pool.push_back(iv.b);
+    }
+    g_intervals.clear();
+    *total_ms = g_phase_ms[phase];
+    *intervals = g_phase_n[phase];
+    return CONDENSA_OK;
+}
+
+condensa_status condensa_profile_reset(void) {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    for (Interval& iv : g_intervals) {
+        (void)hipEventSynchronize(iv.b);
+        g_event_pool.push_back(iv.a);
+        g_event_pool.push_back(iv.b);
+    }
+    g_intervals.clear();
+    for (int i = 0; i < CONDENSA_PHASE_COUNT; ++i) { g_phase_ms[i] = 0.0; g_phase_n[i] = 0; }
+    return CONDENSA_OK;
+}
+
 condensa_status condensa_set_option(int option, int64_t value) {
     if (option < 0 || option >= CONDENSA_OPT_COUNT) return CONDENSA_ERR_ARG;
     if (value < 0) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_SELECT_PATH && value > 2) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_SAMPLE_LOG2 && value != 0 && (value < 10 || value > 26)) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_CAND_SHIFT && value > 30) return CONDENSA_ERR_ARG;
+    if (option == CONDENSA_OPT_PROFILE && value > 1) return CONDENSA_ERR_ARG;
     g_options[option].store(value);
     return CONDENSA_OK;
 }

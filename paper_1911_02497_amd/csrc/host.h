@@ -48,6 +48,16 @@ inline bool density_ok(double d) { return d >= 0.0 && d <= 1.0; }   // false for
 // unless all ring slots are still in flight.
 condensa_status stage_upload(void* dst_dev, const void* src_host, size_t bytes, hipStream_t stream);
 
+// Phase timing: records an event pair around the launches made while the object lives.
+class PhaseTimer {
+public:
+    PhaseTimer(int phase, hipStream_t stream);
+    ~PhaseTimer();
+private:
+    int slot_ = -1;
+    hipStream_t stream_;
+};
+
 // Element count of a tensor; false if the descriptor is malformed.
 inline bool tensor_elems(const condensa_tensor& t, u64* n) {
     if (t.ndim < 1 || t.ndim > 4 || t.reserved != 0) return false;
