@@ -10,7 +10,7 @@
 namespace condensa {
 
 std::atomic<int> g_last_hip_error{0};
-std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {};
+std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {112}, {0}, {0}};
 
 // ---- pinned staging ring -------------------------------------------------------------------------
 
@@ -103,7 +103,7 @@ static u64 window_sample_size(u64 N) {
     u64 s;
     if (opt > 0) s = static_cast<u64>(1) << (opt > 26 ? 26 : opt);
     else {
-        s = N / 256;
+        s = N / 8;
         if (s < (1u << 18)) s = 1u << 18;
         if (s > (1u << 21)) s = 1u << 21;
     }
@@ -111,9 +111,9 @@ static u64 window_sample_size(u64 N) {
     return s;
 }
 
-static u64 window_cand_capacity(u64 N) {
+static u64 window_cand_capacity(u64 N, int J) {
     const int64_t opt = g_options[CONDENSA_OPT_CAND_SHIFT].load();
-    const int shift = (opt > 0 && opt < 40) ? static_cast<int>(opt) : 4;
+    const int shift = (opt > 0 && opt < 40) ? static_cast<int>(opt) : (J > 1 ? 3 : 5);
     u64 c = N >> shift;
     if (c < 4096) c = 4096;
     return c;
@@ -137,7 +137,7 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
     L.ctl = off;    off += align_up(sizeof(Control));
     L.hist0 = off;  off += align_up(static_cast<size_t>(L.n_groups) * kBins * sizeof(u64));
     // later-level histograms: one per ranking, and room for the 2J window-boundary rankings
-    const size_t n_hx = static_cast<size_t>(L.n_slots) > 2u * kMaxJ ? L.n_slots : 2u * kMaxJ;
+    const size_t n_hx = static_cast<size_t>(L.n_slots) + 2u * kMaxJ;
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
     L.zero_bytes = off - L.zero_begin;
     const u64 tie_chunks = structure ? L.max_schunks : L.max_chunks;
@@ -148,7 +148,7 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
         L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
     } else if (!per_tensor) {
         L.sample_cap = window_sample_size(N);
-        L.cand_cap = window_cand_capacity(N);
+        L.cand_cap = window_cand_capacity(N, J);
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
         L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
         L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));
@@ -239,7 +239,7 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
             hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_scan_level, dim3(n_slots), dim3(kBlock), 0, st, a.slots, a.hist0, a.histx, a.J, 31,
-                               level, a.ctl, a.only_failed);
+                               level, a.ctl, a.only_failed, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();
         }
     }
@@ -277,9 +277,8 @@ static bool want_window(u64 N, bool per_tensor) {
     if (per_tensor) return false;
     const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
     if (mode == 1) return false;
-    if (mode == 2) return false;
-    return false;  // TODO window path
-    (void)N;
+    if (mode == 2) return N >= 1;
+    return N >= (static_cast<u64>(1) << 22);
 }
 
 }  // namespace condensa
@@ -368,6 +367,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.n_chunks = tb.n_chunks;
+    a.N = tb.N;
     a.n_tensors = n_tensors;
     a.J = J;
     a.per_tensor = per_tensor ? 1 : 0;
@@ -450,6 +450,7 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.n_chunks = tb.n_chunks;
+    a.N = tb.N;
     a.n_tensors = n_tensors;
     a.J = 1;
     a.per_tensor = 0;
@@ -548,7 +549,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             hipLaunchKernelGGL(k_hist_keys, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_scan_level, dim3(L.n_slots), dim3(kBlock), 0, st, a.slots,
-                               static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0);
+                               static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();
         }
         hipLaunchKernelGGL(k_tie_count_keys, dim3(static_cast<unsigned>(tb.n_schunks)), dim3(kBlock), 0, st, a);

@@ -64,7 +64,7 @@ struct Slot {
 };
 static_assert(sizeof(Slot) == 88, "Slot layout");
 
-enum : u32 { kInactive = 0, kSelecting = 1, kDone = 2 };
+enum : u32 { kInactive = 0, kSelecting = 1, kDone = 2, kFailed = 3 };
 
 // Radix level geometry for keys of `key_bits` significant bits (31 for |fp32|, 63 for fp64 sums,
 // fewer for index keys): ceil(key_bits / 11) levels of at most 11 bits, most significant first.

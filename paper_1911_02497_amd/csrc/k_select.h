@@ -8,10 +8,13 @@ namespace condensa {
 
 // Small block of device-side flags and counters, zeroed at the start of every call.
 struct Control {
-    u32 need_tie;          // some ranking needs the index search among ties
+    u32 need_tie;          // radix path: some ranking needs the index search among ties
     u32 window_failed;     // some ranking of the window path must fall back to the radix levels
-    u64 cand_count;        // candidates written by the window sweep
-    u64 region[2 * kMaxJ + 2];   // window sweep: population of each key region
+    u32 need_tie_w;        // window path: some ranking needs the index search among candidates
+    u32 unused_flag;       // sink for rankings whose tie state does not matter
+    u64 cand_count;        // candidates written by the window sweep (may exceed the capacity)
+    u64 sample_count;      // valid sample elements
+    u64 above[kMaxJ];      // window sweep: keys above each window's upper bound
     u64 pad[4];
 };
 
@@ -23,6 +26,7 @@ struct DataArgs {
     u32* tiecnt;           // [J][n_chunks]
     Control* ctl;
     u64 n_chunks;
+    u64 N;                 // total elements of the call
     int n_tensors;
     int J;                 // rankings (densities) per group
     int per_tensor;        // 1: group = tensor, 0: one group
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64
 // of ties to keep and n_tie the number of keys equal to the threshold.
 __global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* hist_shared, u64* hist_slot,
                                                        int J, int key_bits, int level, Control* ctl,
-                                                       int only_failed) {
+                                                       int only_failed, u32* tie_flag) {
     __shared__ u64 s_wave[kBlock / 64];
     if (only_failed && ctl->window_failed == 0) return;
     const int s = blockIdx.x;
@@ -219,7 +223,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* h
                 slot.state = kDone;
                 if (rem < cnt[i]) {
                     slot.need_tie = 1;
-                    atomicOr(&ctl->need_tie, 1u);
+                    atomicOr(tie_flag, 1u);
                 } else {
                     slot.need_tie = 0;
                     slot.tie_end = slot.n;
@@ -227,6 +231,10 @@ __global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* h
             }
         }
         cum += cnt[i];
+    }
+    if (tid == 0 && total < remaining) {               // the wanted rank is not in this population
+        slot.state = kFailed;
+        atomicOr(&ctl->window_failed, 1u);
     }
     if (!shared) {                                     // leave the ranking's histogram clean for the next level
         u64* h = hist_slot + static_cast<u64>(s) * kBins;

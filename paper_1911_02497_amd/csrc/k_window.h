@@ -1,8 +1,422 @@
-// Sampled-window selection: one sweep over the weights per call instead of one per radix level.
+// Sampled-window selection: the exact k-th largest key with ONE sweep over the weights.
+//
+// A jittered, stratified sample of the keys is ranked exactly; the keys at two sample ranks around
+// the expected position of the threshold bound a key window [lo, hi] that holds the true threshold
+// unless the sample was unlucky.  One sweep over all weights then counts the keys above hi and
+// compacts the (key, flat index) of the keys inside the window; the threshold and the tie rule are
+// resolved exactly on that short candidate list.  A window that turns out not to hold the wanted
+// rank (or a candidate list that overflows) is detected on the device and the ranking falls back to
+// the radix levels over the weights, so the result never depends on the sample.
+// Section 3.1: "magnitude threshold computation from a sparsity"; several target sparsities of one
+// search (Results: up to 10 samples per search) are served by the same sweep.
 #pragma once
 #include "host.h"
+#include "k_select.h"
+
 namespace condensa {
-constexpr int kSampleUnit = 32;        // consecutive elements read per sample position
+
+constexpr int kSampleUnit = 4;         // consecutive elements read at one sample position
+constexpr int kArrayBatch = 4;         // rankings per pass over a key array (LDS histograms)
+constexpr u32 kNoKey = 0xFFFFFFFFu;    // marks sample entries that fell past the end of a tensor
+
+struct WindowArgs {
+    u32* sample;           // [n_units * kSampleUnit]
+    u32* cand_key;         // [cand_cap]
+    u64* cand_idx;         // [cand_cap]
+    Slot* wslots;          // [2J] boundary rankings, later [J] index rankings
+    u64 n_units;
+    u64 stride;            // sample positions are one per stride of quads
+    u64 cand_cap;
+    int margin16;
+};
+
+struct ArrayArgs {
+    const u32* keys;       // sample or candidate keys
+    const u64* idx;        // candidate flat indices (index ranking only)
+    u64 n_host;            // upper bound of the number of entries
+    const u64* n_dev;      // device-side entry count (NULL: n_host entries)
+    u64 N;                 // index ranking: the ranked key is N - 1 - idx
+    Slot* slots;
+    u64* hist;             // [n_slots][kBins]
+    const u32* gate;       // NULL, or skip the kernel when *gate == 0
+    int n_slots;
+    int key_bits;
+};
+
+__device__ inline u32 mix32(u32 x) {
+    x ^= x >> 16; x *= 0x9E3779B1u;
+    x ^= x >> 13; x *= 0x85EBCA77u;
+    x ^= x >> 16;
+    return x;
+}
+
+// ---- sample -----------------------------------------------------------------------------------------
 template <bool LC, bool VEC>
-static condensa_status launch_window_path(const DataArgs&, const Layout&, void*, hipStream_t) { return CONDENSA_OK; }
+__global__ __launch_bounds__(kBlock) void k_sample(DataArgs a, WindowArgs w) {
+    __shared__ u32 s_valid;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_valid = 0;
+    __syncthreads();
+    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + tid;
+    u32 n_valid = 0;
+    if (u < w.n_units) {
+        const u64 jitter = (w.stride > 1) ? static_cast<u64>(mix32(static_cast<u32>(u) ^ static_cast<u32>(u >> 32))) % w.stride : 0;
+        const u64 p = u * w.stride + jitter;             // quad position in chunk space
+        const u64 c = p / (kChunk / 4);
+        const u64 q = p % (kChunk / 4);
+        u32 key[4] = {kNoKey, kNoKey, kNoKey, kNoKey};
+        if (c < a.n_chunks) {
+            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const TensorDesc& td = a.td[t];
+            const u64 e0 = (c - td.chunk_start) * kChunk + q * 4;
+            if (e0 < td.n) {
+                float v[4];
+                load4<VEC>(td.w, e0, td.n, v);
+                if (LC) {
+                    float l[4];
+                    load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (e0 + k < td.n) { key[k] = mag_key(v[k]); ++n_valid; }
+            }
+        }
+        *reinterpret_cast<uint4*>(w.sample + u * 4) = make_uint4(key[0], key[1], key[2], key[3]);
+    }
+    if (n_valid) atomicAdd(&s_valid, n_valid);
+    __syncthreads();
+    if (tid == 0 && s_valid) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->sample_count), static_cast<unsigned long long>(s_valid));
+}
+
+// Sample ranks that bound each density's threshold.  The number of sample keys above the true
+// threshold is (close to) binomial; sample units of kSampleUnit neighbours may be correlated, so the
+// standard deviation is taken as if every unit were one draw.
+__global__ __launch_bounds__(kBlock) void k_window_ranks(DataArgs a, WindowArgs w) {
+    const int j = threadIdx.x;
+    if (j >= a.J) return;
+    const Slot& main = a.slots[j];
+    const u64 S = a.ctl->sample_count;
+    Slot hi{}, lo{};
+    hi.n = lo.n = S;
+    hi.lo = lo.lo = 0;
+    hi.hi = lo.hi = 0x7FFFFFFFu;
+    hi.state = lo.state = kDone;
+    hi.prefix = 0x7FFFFFFFu;                             // no upper bound
+    lo.prefix = 0;                                       // no lower bound
+    if (main.state == kSelecting && S > 0) {
+        const double p = static_cast<double>(main.k) / static_cast<double>(main.n);
+        const double ks = p * static_cast<double>(S);
+        const double sd = sqrt(static_cast<double>(kSampleUnit) * static_cast<double>(S) * p * (1.0 - p));
+        const double m = static_cast<double>(w.margin16) / 16.0 * sd + 2.0;
+        const double rhi = floor(ks - m);
+        const double rlo = ceil(ks + m) + 1.0;
+        if (rhi >= 1.0) { hi.state = kSelecting; hi.prefix = 0; hi.remaining = static_cast<u64>(rhi); }
+        if (rlo <= static_cast<double>(S)) { lo.state = kSelecting; lo.prefix = 0; lo.remaining = static_cast<u64>(rlo); }
+    }
+    w.wslots[2 * j] = hi;
+    w.wslots[2 * j + 1] = lo;
+}
+
+// ---- histogram of one radix level over a key array -------------------------------------------------
+// Entry i takes part in ranking j when its key lies in [slot.lo, slot.hi] and the ranked key (the key
+// itself, or N - 1 - idx for the index ranking) matches the ranking's prefix.
+template <bool IDX>
+__global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
+    __shared__ u32 s_hist[kArrayBatch * kBins];
+    __shared__ u64 s_prefix[kArrayBatch];
+    __shared__ u32 s_lo[kArrayBatch], s_hi[kArrayBatch], s_active[kArrayBatch];
+    __shared__ u32 s_any;
+    if (a.gate && *a.gate == 0) return;
+    u64 n = a.n_host;
+    if (a.n_dev) { const u64 d = *a.n_dev; if (d < n) n = d; }
+    const Level L = level_of(a.key_bits, level);
+    const int nb = 1 << L.bits;
+    const int tid = threadIdx.x;
+    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
+    for (int j0 = 0; j0 < a.n_slots; j0 += kArrayBatch) {
+        const int nj = (a.n_slots - j0 < kArrayBatch) ? a.n_slots - j0 : kArrayBatch;
+        __syncthreads();
+        if (tid == 0) s_any = 0;
+        __syncthreads();
+        if (tid < nj) {
+            const Slot& s = a.slots[j0 + tid];
+            s_prefix[tid] = s.prefix;
+            s_lo[tid] = static_cast<u32>(s.lo);
+            s_hi[tid] = static_cast<u32>(s.hi);
+            s_active[tid] = (s.state == kSelecting) ? 1u : 0u;
+            if (s.state == kSelecting) s_any = 1;
+        }
+        for (int i = tid; i < nj * nb; i += kBlock) s_hist[i] = 0;
+        __syncthreads();
+        if (!s_any) continue;
+        for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < n; i += stride) {
+            const u32 ck = a.keys[i];
+            const u64 rk = IDX ? (a.N - 1 - a.idx[i]) : static_cast<u64>(ck);
+            const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
+            for (int j = 0; j < nj; ++j)
+                if (s_active[j] && ck >= s_lo[j] && ck <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
+                    atomicAdd(&s_hist[j * nb + digit], 1u);
+        }
+        __syncthreads();
+        for (int i = tid; i < nj * nb; i += kBlock) {
+            const u32 v = s_hist[i];
+            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.hist + static_cast<u64>(j0 + i / nb) * kBins + (i % nb)),
+                             static_cast<unsigned long long>(v));
+        }
+    }
+}
+
+// ---- the one sweep over the weights -----------------------------------------------------------------
+template <bool LC, bool VEC, bool MULTI>
+__global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs w) {
+    constexpr int JM = MULTI ? kMaxJ : 1;
+    __shared__ u32 s_lo[kMaxJ], s_hi[kMaxJ];
+    __shared__ u32 s_above[kMaxJ];
+    __shared__ u64 s_wave[kBlock / 64];
+    __shared__ u64 s_base;
+    const u64 c = blockIdx.x;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int J = MULTI ? a.J : 1;
+    if (tid < J) {
+        const bool act = (a.slots[tid].state == kSelecting);
+        s_hi[tid] = act ? static_cast<u32>(w.wslots[2 * tid].prefix) : 0u;       // inactive: empty window
+        s_lo[tid] = act ? static_cast<u32>(w.wslots[2 * tid + 1].prefix) : 1u;
+        s_above[tid] = 0;
+    }
+    __syncthreads();
+    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const TensorDesc& td = a.td[t];
+    const u64 base = (c - td.chunk_start) * kChunk;
+
+    u32 key[kQuadsPerThread][4];
+    u32 cmask = 0;
+    u32 above[JM];
+#pragma unroll
+    for (int j = 0; j < JM; ++j) above[j] = 0;
+    u32 lo0 = s_lo[0], hi0 = s_hi[0];
+
+#pragma unroll
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (e0 < td.n) {
+            load4<VEC>(td.w, e0, td.n, v);
+            if (LC) {
+                float l[4];
+                load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            key[q][k] = mag_key(v[k]);
+            if (e0 + k < td.n) {
+                const u32 x = key[q][k];
+                bool cand;
+                if (MULTI) {
+                    cand = false;
+#pragma unroll
+                    for (int j = 0; j < JM; ++j) {
+                        if (j < J) {
+                            above[j] += (x > s_hi[j]) ? 1u : 0u;
+                            cand = cand || (x >= s_lo[j] && x <= s_hi[j]);
+                        }
+                    }
+                } else {
+                    above[0] += (x > hi0) ? 1u : 0u;
+                    cand = (x >= lo0 && x <= hi0);
+                }
+                if (cand) cmask |= 1u << (q * 4 + k);
+            }
+        }
+    }
+
+    // keys above each window: wavefront sums, then one LDS and one global atomic per workgroup
+#pragma unroll
+    for (int j = 0; j < JM; ++j) {
+        if (j < J) {
+            u32 s = above[j];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
+            if ((tid & 63) == 0 && s) atomicAdd(&s_above[j], s);
+        }
+    }
+    // candidates: one reservation per workgroup, then every thread writes its own in order
+    u64 total;
+    const u64 off = block_excl_scan_u64(__popc(cmask), s_wave, &total);    // syncs the workgroup
+    if (tid < J && s_above[tid])
+        atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->above[tid]), static_cast<unsigned long long>(s_above[tid]));
+    if (total == 0) return;
+    if (tid == 0)
+        s_base = atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->cand_count), static_cast<unsigned long long>(total));
+    __syncthreads();
+    if (cmask == 0) return;
+    u64 pos = s_base + off;
+#pragma unroll
+    for (int q = 0; q < kQuadsPerThread; ++q) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (cmask & (1u << (q * 4 + k))) {
+                if (pos < w.cand_cap) {
+                    w.cand_key[pos] = key[q][k];
+                    w.cand_idx[pos] = td.flat_start + base + static_cast<u64>(q) * (kBlock * 4) + tid * 4 + k;
+                }
+                ++pos;
+            }
+        }
+    }
+}
+
+// After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
+__global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
+    const int j = threadIdx.x;
+    if (j >= a.J) return;
+    Slot& s = a.slots[j];
+    if (s.state != kSelecting) return;
+    const u64 above = a.ctl->above[j];
+    if (a.ctl->cand_count > w.cand_cap || above >= s.k) {
+        s.state = kFailed;
+        atomicOr(&a.ctl->window_failed, 1u);
+        return;
+    }
+    s.remaining = s.k - above;
+    s.prefix = 0;
+    s.hi = static_cast<u32>(w.wslots[2 * j].prefix);
+    s.lo = static_cast<u32>(w.wslots[2 * j + 1].prefix);
+}
+
+// Index rankings for the rankings whose ties are only partly kept.
+__global__ __launch_bounds__(kBlock) void k_window_tie_setup(DataArgs a, WindowArgs w) {
+    const int j = threadIdx.x;
+    if (j >= a.J) return;
+    const Slot& s = a.slots[j];
+    Slot r{};
+    r.state = kInactive;
+    if (s.state == kDone && s.need_tie) {
+        r.state = kSelecting;
+        r.remaining = s.remaining;                       // the r-th lowest index = r-th largest N-1-idx
+        r.k = s.remaining;
+        r.n = s.n_tie;
+        r.lo = r.hi = static_cast<u32>(s.prefix);        // only candidates equal to the threshold
+    }
+    w.wslots[j] = r;
+}
+
+// Takes over the index rankings, and re-arms the rankings that must fall back to the radix levels.
+__global__ __launch_bounds__(kBlock) void k_window_finish(DataArgs a, WindowArgs w) {
+    const int j = threadIdx.x;
+    if (j >= a.J) return;
+    Slot& s = a.slots[j];
+    if (s.state == kDone && s.need_tie) {
+        const Slot& r = w.wslots[j];
+        if (r.state == kDone) {
+            s.tie_end = a.N - r.prefix;                  // 1 + (N - 1 - ranked key)
+            s.need_tie = 0;
+        } else {
+            s.state = kFailed;
+            atomicOr(&a.ctl->window_failed, 1u);
+        }
+    }
+    if (s.state == kFailed) {
+        s.prefix = 0;
+        s.remaining = s.k;
+        s.n_tie = 0;
+        s.tie_end = s.n;
+        s.need_tie = 0;
+        s.lo = s.hi = 0;
+        s.path = 3;
+        s.state = kSelecting;
+    }
+}
+
+static inline unsigned array_grid(u64 n) {
+    u64 b = (n + kBlock * 8 - 1) / (kBlock * 8);
+    if (b > 1024) b = 1024;
+    if (b == 0) b = 1;
+    return static_cast<unsigned>(b);
+}
+
+static inline int bits_for(u64 max_value) {
+    int b = 1;
+    while (b < 63 && (max_value >> b) != 0) ++b;
+    return b;
+}
+
+template <bool IDX>
+static condensa_status rank_array(const ArrayArgs& ar, Control* ctl, u32* tie_flag, hipStream_t st) {
+    for (int level = 0; level < n_levels(ar.key_bits); ++level) {
+        hipLaunchKernelGGL((k_hist_array<IDX>), dim3(array_grid(ar.n_host)), dim3(kBlock), 0, st, ar, level);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_scan_level, dim3(ar.n_slots), dim3(kBlock), 0, st, ar.slots,
+                           static_cast<const u64*>(nullptr), ar.hist, 1, ar.key_bits, level, ctl, 0, tie_flag);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    return CONDENSA_OK;
+}
+
+template <bool LC, bool VEC>
+static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st) {
+    if (a.n_chunks == 0) return CONDENSA_OK;
+    char* base = static_cast<char*>(ws);
+    WindowArgs w{};
+    w.sample = reinterpret_cast<u32*>(base + L.sample);
+    w.cand_key = reinterpret_cast<u32*>(base + L.cand_key);
+    w.cand_idx = reinterpret_cast<u64*>(base + L.cand_idx);
+    w.wslots = a.slots + a.J;
+    const u64 quads = a.n_chunks * (kChunk / 4);
+    w.n_units = L.sample_cap / kSampleUnit < quads ? L.sample_cap / kSampleUnit : quads;
+    w.stride = quads / w.n_units;
+    w.cand_cap = L.cand_cap;
+    const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
+    w.margin16 = static_cast<int>(m);
+    u64* hist_main = a.histx;                                    // [J]
+    u64* hist_aux = a.histx + static_cast<u64>(a.J) * kBins;     // [2J]
+    condensa_status rc;
+    {
+        PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st);
+        hipLaunchKernelGGL((k_sample<LC, VEC>), dim3(static_cast<unsigned>((w.n_units + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_window_ranks, dim3(1), dim3(kBlock), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+        ArrayArgs ar{};
+        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J;
+        ar.hist = hist_aux; ar.key_bits = 31;
+        rc = rank_array<false>(ar, a.ctl, &a.ctl->unused_flag, st);
+        if (rc != CONDENSA_OK) return rc;
+    }
+    {
+        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
+        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep<LC, VEC, false>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        else          hipLaunchKernelGGL((k_window_sweep<LC, VEC, true>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
+    hipLaunchKernelGGL(k_window_check, dim3(1), dim3(kBlock), 0, st, a, w);
+    CONDENSA_LAUNCH_CHECK();
+    {
+        ArrayArgs ar{};
+        ar.keys = w.cand_key; ar.n_host = w.cand_cap; ar.n_dev = &a.ctl->cand_count; ar.slots = a.slots; ar.n_slots = a.J;
+        ar.hist = hist_main; ar.key_bits = 31;
+        rc = rank_array<false>(ar, a.ctl, &a.ctl->need_tie_w, st);
+        if (rc != CONDENSA_OK) return rc;
+    }
+    hipLaunchKernelGGL(k_window_tie_setup, dim3(1), dim3(kBlock), 0, st, a, w);
+    CONDENSA_LAUNCH_CHECK();
+    {
+        ArrayArgs ar{};
+        ar.keys = w.cand_key; ar.idx = w.cand_idx; ar.n_host = w.cand_cap; ar.n_dev = &a.ctl->cand_count; ar.N = a.N;
+        ar.slots = w.wslots; ar.n_slots = a.J; ar.hist = hist_aux; ar.key_bits = bits_for(a.N - 1);
+        ar.gate = &a.ctl->need_tie_w;
+        rc = rank_array<true>(ar, a.ctl, &a.ctl->unused_flag, st);
+        if (rc != CONDENSA_OK) return rc;
+    }
+    hipLaunchKernelGGL(k_window_finish, dim3(1), dim3(kBlock), 0, st, a, w);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
 }  // namespace condensa

@@ -10,6 +10,17 @@ from gpu_util import DEV, assert_bits_equal, assert_select_equal, up
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["radix", "window", "window_narrow"], autouse=True)
+def select_path(request):
+    """Every case runs through the radix levels, the sampled window, and a window whose margin is
+    cut to a couple of sample ranks so that it regularly misses and falls back."""
+    P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else 112)
+    yield request.param
+    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 112)
+
+
 def _check(ws, ls, mu, d, what="", **kw):
     res = P.condensa_lc_step(up(ws), up(ls), mu, d, **kw)
     torch.cuda.synchronize()
