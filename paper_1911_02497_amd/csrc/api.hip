@@ -139,7 +139,9 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
     // later-level histograms: one per ranking, and room for the 2J window-boundary rankings
     const size_t n_hx = static_cast<size_t>(L.n_slots) + 2u * kMaxJ;
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
+    if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (1 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
+    L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
     const u64 tie_chunks = structure ? L.max_schunks : L.max_chunks;
     L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
     if (structure) {
@@ -251,7 +253,8 @@ static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, i
                                                condensa_select* results, hipStream_t st) {
     PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
     if (a.n_chunks > 0) {
-        hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a);
+        const unsigned tie_blocks = static_cast<unsigned>(a.n_chunks < 4096 ? a.n_chunks : 4096);
+        hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(tie_blocks), dim3(kBlock), 0, st, a);
         CONDENSA_LAUNCH_CHECK();
     }
     hipLaunchKernelGGL((k_tie_locate<LC, VEC>), dim3(n_slots), dim3(kBlock), 0, st, a, results, n_groups);
@@ -355,8 +358,9 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
-    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
-                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
+                       at<TensorDesc>(workspace_dev, L.td), n_tensors, at<u32>(workspace_dev, L.chunk_map), tb.n_chunks);
     CONDENSA_LAUNCH_CHECK();
 
     DataArgs a{};
@@ -366,6 +370,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     a.histx = at<u64>(workspace_dev, L.histx);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
+    a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;
     a.N = tb.N;
     a.n_tensors = n_tensors;
@@ -381,8 +386,8 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     if (any_out && tb.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-        if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
-        else     hipLaunchKernelGGL((k_prune_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
+        else     hipLaunchKernelGGL((k_prune_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
         CONDENSA_LAUNCH_CHECK();
     }
     return CONDENSA_OK;
@@ -438,8 +443,9 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
-    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
-                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
+                       at<TensorDesc>(workspace_dev, L.td), n_tensors, at<u32>(workspace_dev, L.chunk_map), tb.n_chunks);
     CONDENSA_LAUNCH_CHECK();
 
     DataArgs a{};
@@ -449,6 +455,7 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
     a.histx = at<u64>(workspace_dev, L.histx);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
+    a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;
     a.N = tb.N;
     a.n_tensors = n_tensors;
@@ -468,8 +475,8 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
     if (tb.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-        if (vec) hipLaunchKernelGGL((k_lc_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
-        else     hipLaunchKernelGGL((k_lc_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+        if (vec) hipLaunchKernelGGL((k_lc_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
+        else     hipLaunchKernelGGL((k_lc_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
         CONDENSA_LAUNCH_CHECK();
     }
     return CONDENSA_OK;
@@ -515,8 +522,9 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
-    hipLaunchKernelGGL(k_fill_zero, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
-                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8));
+    hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
+                       at<TensorDesc>(workspace_dev, L.td), n_tensors, at<u32>(workspace_dev, L.chunk_map), tb.n_chunks);
     CONDENSA_LAUNCH_CHECK();
 
     StructArgs a{};
@@ -528,6 +536,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     a.keys = at<u64>(workspace_dev, L.skeys);
     a.smask = at<u8>(workspace_dev, L.smask);
     a.sblock = at<u32>(workspace_dev, L.sblock);
+    a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.F = tb.F;
     a.n_schunks = tb.n_schunks;
     a.n_chunks = tb.n_chunks;
@@ -569,8 +578,8 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         if ((theta || mask) && tb.n_chunks > 0) {
             PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-            if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
-            else     hipLaunchKernelGGL((k_struct_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks)), dim3(kBlock), 0, st, a, od);
+            if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
+            else     hipLaunchKernelGGL((k_struct_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
             CONDENSA_LAUNCH_CHECK();
         }
     }

@@ -1,10 +1,14 @@
 // Streaming mask/apply kernels: theta = keep ? x : +0 with optional fp16 rounding (Prune and
 // Compose([Prune, Quantize]), Table 1) and the fused L-C multiplier / penalty-gradient update
-// (Section 3.3).  One workgroup per chunk of one tensor, 128-bit accesses when aligned.
+// (Section 3.3).  128-bit accesses when every pointer is aligned.
 #pragma once
 #include "k_select.h"
 
 namespace condensa {
+
+// The apply sweeps run one workgroup per 1024 elements (one float4 per thread): many short
+// workgroups keep more independent HBM streams in flight than long ones.
+constexpr int kSubPerChunk = kChunk / (kBlock * 4);     // 8 workgroups share a chunk
 
 // keep rule of the selection: key above the threshold, or equal to it with index below tie_end
 __device__ inline bool keep_rule(u32 key, u32 T, u64 idx, u64 tie_end) {
@@ -16,11 +20,16 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
     __shared__ u32 s_T[kMaxJ];
     __shared__ u64 s_end[kMaxJ];
     __shared__ OutDesc s_out[kMaxJ];
-    const u64 c = blockIdx.x;
+    const u64 c = blockIdx.x / kSubPerChunk;
+    const u32 sub = blockIdx.x % kSubPerChunk;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const int t = static_cast<int>(a.chunk_map[c]);
     const u64 g = a.per_tensor ? t : 0;
+    {
+        const TensorDesc& td0 = a.td[t];
+        if ((c - td0.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4) >= td0.n) return;   // uniform
+    }
     if (tid < a.J) {
         const Slot& s = a.slots[g * a.J + tid];
         s_T[tid] = static_cast<u32>(s.prefix);
@@ -31,10 +40,9 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
     const TensorDesc& td = a.td[t];
     const u64 base = (c - td.chunk_start) * kChunk;
     const u64 idx0 = a.per_tensor ? 0 : td.flat_start;
-#pragma unroll 2
-    for (int q = 0; q < kQuadsPerThread; ++q) {
-        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) break;
+    {
+        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) return;
         float v[4];
         load4<VEC>(td.w, e0, td.n, v);
         u32 key[4];
@@ -68,10 +76,11 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
 // each operation rounded once in binary32.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
-    const u64 c = blockIdx.x;
+    const u64 c = blockIdx.x / kSubPerChunk;
+    const u32 sub = blockIdx.x % kSubPerChunk;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const int t = static_cast<int>(a.chunk_map[c]);
     const Slot& s = a.slots[0];
     const u32 T = static_cast<u32>(s.prefix);
     const u64 end = s.tie_end;
@@ -79,10 +88,9 @@ __global__ __launch_bounds__(kBlock) void k_lc_apply(DataArgs a, const OutDesc* 
     const OutDesc o = out[t];
     const float mu = a.mu;
     const u64 base = (c - td.chunk_start) * kChunk;
-#pragma unroll 2
-    for (int q = 0; q < kQuadsPerThread; ++q) {
-        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) break;
+    {
+        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) return;
         float w[4], l[4];
         load4<VEC>(td.w, e0, td.n, w);
         load4<VEC>(td.lam, e0, td.n, l);

@@ -25,6 +25,7 @@ struct DataArgs {
     u64* histx;            // [n_slots][kBins]    later levels
     u32* tiecnt;           // [J][n_chunks]
     Control* ctl;
+    const u32* chunk_map;  // [n_chunks] tensor that owns each chunk
     u64 n_chunks;
     u64 N;                 // total elements of the call
     int n_tensors;
@@ -71,9 +72,14 @@ __device__ inline u64 block_excl_scan_u64(u64 v, u64* s_wave, u64* total) {
     return before + incl - v;
 }
 
-__global__ __launch_bounds__(kBlock) void k_fill_zero(u64* p, u64 n_words) {
+// First kernel of every call: clears the flag / counter / histogram region and writes the
+// chunk -> tensor map (a kernel rather than a memset, so that the call can be captured in a graph).
+__global__ __launch_bounds__(kBlock) void k_prepare(u64* zero, u64 n_words, const TensorDesc* td, int n_tensors,
+                                                    u32* chunk_map, u64 n_chunks) {
     const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
-    for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x; i < n_words; i += stride) p[i] = 0;
+    const u64 i0 = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x;
+    for (u64 i = i0; i < n_words; i += stride) zero[i] = 0;
+    for (u64 c = i0; c < n_chunks; c += stride) chunk_map[c] = static_cast<u32>(tensor_of_chunk(td, n_tensors, c));
 }
 
 // ---- histogram of one radix level over the weights ----------------------------------------------
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64
         const int n_hist = (level == 0) ? 1 : nj;
         long long cur_group = -1;
         for (u64 c = c0; c < c1; ++c) {
-            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const int t = static_cast<int>(a.chunk_map[c]);
             const long long g = a.per_tensor ? t : 0;
             if (g != cur_group) {
                 if (cur_group >= 0) {                     // flush the previous group's counts
@@ -251,45 +257,46 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
     __shared__ u32 s_cnt[kMaxJ];
     __shared__ u32 s_any;
     if (a.ctl->need_tie == 0) return;
-    const u64 c = blockIdx.x;
-    if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
-    const u64 g = a.per_tensor ? t : 0;
-    if (tid == 0) s_any = 0;
-    __syncthreads();
-    if (tid < a.J) {
-        const Slot& s = a.slots[g * a.J + tid];
-        s_T[tid] = static_cast<u32>(s.prefix);
-        s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
-        s_cnt[tid] = 0;
-        if (s_need[tid]) s_any = 1;
-    }
-    __syncthreads();
-    if (!s_any) return;
-    const TensorDesc& td = a.td[t];
-    const u64 base = (c - td.chunk_start) * kChunk;
-    for (int q = 0; q < kQuadsPerThread; ++q) {
-        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) break;
-        float v[4];
-        load4<VEC>(td.w, e0, td.n, v);
-        if (LC) {
-            float l[4];
-            load4<VEC>(td.lam, e0, td.n, l);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+    for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+        const int t = static_cast<int>(a.chunk_map[c]);
+        const u64 g = a.per_tensor ? t : 0;
+        __syncthreads();
+        if (tid == 0) s_any = 0;
+        __syncthreads();
+        if (tid < a.J) {
+            const Slot& s = a.slots[g * a.J + tid];
+            s_T[tid] = static_cast<u32>(s.prefix);
+            s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
+            s_cnt[tid] = 0;
+            if (s_need[tid]) s_any = 1;
         }
+        __syncthreads();
+        if (!s_any) continue;
+        const TensorDesc& td = a.td[t];
+        const u64 base = (c - td.chunk_start) * kChunk;
+        for (int q = 0; q < kQuadsPerThread; ++q) {
+            const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+            if (e0 >= td.n) break;
+            float v[4];
+            load4<VEC>(td.w, e0, td.n, v);
+            if (LC) {
+                float l[4];
+                load4<VEC>(td.lam, e0, td.n, l);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (e0 + k >= td.n) break;
-            const u32 key = mag_key(v[k]);
-            for (int j = 0; j < a.J; ++j)
-                if (s_need[j] && key == s_T[j]) atomicAdd(&s_cnt[j], 1u);
+                for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (e0 + k >= td.n) break;
+                const u32 key = mag_key(v[k]);
+                for (int j = 0; j < a.J; ++j)
+                    if (s_need[j] && key == s_T[j]) atomicAdd(&s_cnt[j], 1u);
+            }
         }
+        __syncthreads();
+        if (tid < a.J && s_need[tid]) a.tiecnt[static_cast<u64>(tid) * a.n_chunks + c] = s_cnt[tid];
     }
-    __syncthreads();
-    if (tid < a.J && s_need[tid]) a.tiecnt[static_cast<u64>(tid) * a.n_chunks + c] = s_cnt[tid];
 }
 
 // One workgroup per ranking: finishes the tie search (if any) and writes the public record.
@@ -330,7 +337,7 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
         if (s_found[2]) {
             const u64 c = s_found[0];
             const u64 rr = s_found[1];
-            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const int t = static_cast<int>(a.chunk_map[c]);
             const TensorDesc& td = a.td[t];
             const u64 base = (c - td.chunk_start) * kChunk;
             constexpr int kRun = kChunk / kBlock;              // 32 consecutive elements per thread

@@ -17,6 +17,7 @@ struct StructArgs {
     u64* keys;             // [F] sign-less binary64 patterns of the aggregates
     u8* smask;             // [F]
     u32* sblock;           // [ceil(F / kBlock) + 1] kept structures per block of 256, then its scan
+    const u32* chunk_map;  // [n_chunks] tensor that owns each element chunk
     u64 F;
     u64 n_schunks;
     u64 n_chunks;
@@ -286,18 +287,19 @@ __global__ __launch_bounds__(kBlock) void k_struct_keep_idx(StructArgs a, int32_
 // theta = w on kept structures, +0 elsewhere; element mask = structure mask broadcast
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const OutDesc* __restrict__ out) {
-    const u64 c = blockIdx.x;
+    const u64 c = blockIdx.x / kSubPerChunk;
+    const u32 sub = blockIdx.x % kSubPerChunk;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
     const OutDesc o = out[t];
     const u8* __restrict__ sm = a.smask + td.struct_start;
     const u64 base = (c - td.chunk_start) * kChunk;
     const u32 ld = td.s_ld, rows = td.s_rows, len = td.s_len, per_row = td.s_per_row;
-    for (int q = 0; q < kQuadsPerThread; ++q) {
-        const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) break;
+    {
+        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
+        if (e0 >= td.n) return;
         float v[4];
         load4<VEC>(td.w, e0, td.n, v);
         u64 row;

@@ -18,12 +18,17 @@ namespace condensa {
 constexpr int kSampleUnit = 4;         // consecutive elements read at one sample position
 constexpr int kArrayBatch = 4;         // rankings per pass over a key array (LDS histograms)
 constexpr u32 kNoKey = 0xFFFFFFFFu;    // marks sample entries that fell past the end of a tensor
+constexpr int kSegs = 1024;            // candidate list segments / counter sets (see k_window_sweep)
 
 struct WindowArgs {
     u32* sample;           // [n_units * kSampleUnit]
     u32* cand_key;         // [cand_cap]
     u64* cand_idx;         // [cand_cap]
     Slot* wslots;          // [2J] boundary rankings, later [J] index rankings
+    u64* seg_cnt;          // [kSegs] candidates appended to each segment (may exceed seg_cap)
+    u64* seg_above;        // [kSegs][kMaxJ] keys above each window's upper bound
+    u64 seg_cap;           // entries per segment
+    u32 n_segs;            // segments in use
     u64 n_units;
     u64 stride;            // sample positions are one per stride of quads
     u64 cand_cap;
@@ -33,8 +38,10 @@ struct WindowArgs {
 struct ArrayArgs {
     const u32* keys;       // sample or candidate keys
     const u64* idx;        // candidate flat indices (index ranking only)
-    u64 n_host;            // upper bound of the number of entries
-    const u64* n_dev;      // device-side entry count (NULL: n_host entries)
+    u64 n_host;            // number of entries (plain array)
+    const u64* seg_cnt;    // NULL: plain array; else the array is n_segs segments of seg_cap entries
+    u64 seg_cap;
+    u32 n_segs;
     u64 N;                 // index ranking: the ranked key is N - 1 - idx
     Slot* slots;
     u64* hist;             // [n_slots][kBins]
@@ -66,7 +73,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(DataArgs a, WindowArgs w) {
         const u64 q = p % (kChunk / 4);
         u32 key[4] = {kNoKey, kNoKey, kNoKey, kNoKey};
         if (c < a.n_chunks) {
-            const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+            const int t = static_cast<int>(a.chunk_map[c]);
             const TensorDesc& td = a.td[t];
             const u64 e0 = (c - td.chunk_start) * kChunk + q * 4;
             if (e0 < td.n) {
@@ -129,12 +136,9 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
     __shared__ u32 s_lo[kArrayBatch], s_hi[kArrayBatch], s_active[kArrayBatch];
     __shared__ u32 s_any;
     if (a.gate && *a.gate == 0) return;
-    u64 n = a.n_host;
-    if (a.n_dev) { const u64 d = *a.n_dev; if (d < n) n = d; }
     const Level L = level_of(a.key_bits, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
-    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
     for (int j0 = 0; j0 < a.n_slots; j0 += kArrayBatch) {
         const int nj = (a.n_slots - j0 < kArrayBatch) ? a.n_slots - j0 : kArrayBatch;
         __syncthreads();
@@ -151,13 +155,24 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
         for (int i = tid; i < nj * nb; i += kBlock) s_hist[i] = 0;
         __syncthreads();
         if (!s_any) continue;
-        for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < n; i += stride) {
+        auto take = [&](u64 i) {
             const u32 ck = a.keys[i];
             const u64 rk = IDX ? (a.N - 1 - a.idx[i]) : static_cast<u64>(ck);
             const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
             for (int j = 0; j < nj; ++j)
                 if (s_active[j] && ck >= s_lo[j] && ck <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
                     atomicAdd(&s_hist[j * nb + digit], 1u);
+        };
+        if (a.seg_cnt) {
+            for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
+                u64 cnt = a.seg_cnt[seg];
+                if (cnt > a.seg_cap) cnt = a.seg_cap;
+                const u64 first = static_cast<u64>(seg) * a.seg_cap;
+                for (u64 i = tid; i < cnt; i += kBlock) take(first + i);
+            }
+        } else {
+            const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
+            for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < a.n_host; i += stride) take(i);
         }
         __syncthreads();
         for (int i = tid; i < nj * nb; i += kBlock) {
@@ -169,6 +184,8 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
 }
 
 // ---- the one sweep over the weights -----------------------------------------------------------------
+// Counters and the candidate list are split into segments chosen by the workgroup id: one global
+// atomic address shared by ~10^5 workgroups serialises the whole sweep, a thousand addresses do not.
 template <bool LC, bool VEC, bool MULTI>
 __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs w) {
     constexpr int JM = MULTI ? kMaxJ : 1;
@@ -187,7 +204,7 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
         s_above[tid] = 0;
     }
     __syncthreads();
-    const int t = tensor_of_chunk(a.td, a.n_tensors, c);
+    const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
     const u64 base = (c - td.chunk_start) * kChunk;
 
@@ -248,22 +265,25 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     // candidates: one reservation per workgroup, then every thread writes its own in order
     u64 total;
     const u64 off = block_excl_scan_u64(__popc(cmask), s_wave, &total);    // syncs the workgroup
+    const u32 seg = static_cast<u32>(c % w.n_segs);
     if (tid < J && s_above[tid])
-        atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->above[tid]), static_cast<unsigned long long>(s_above[tid]));
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(seg) * kMaxJ + tid]),
+                  static_cast<unsigned long long>(s_above[tid]));
     if (total == 0) return;
     if (tid == 0)
-        s_base = atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->cand_count), static_cast<unsigned long long>(total));
+        s_base = atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_cnt[seg]), static_cast<unsigned long long>(total));
     __syncthreads();
     if (cmask == 0) return;
     u64 pos = s_base + off;
+    const u64 first = static_cast<u64>(seg) * w.seg_cap;
 #pragma unroll
     for (int q = 0; q < kQuadsPerThread; ++q) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (cmask & (1u << (q * 4 + k))) {
-                if (pos < w.cand_cap) {
-                    w.cand_key[pos] = key[q][k];
-                    w.cand_idx[pos] = td.flat_start + base + static_cast<u64>(q) * (kBlock * 4) + tid * 4 + k;
+                if (pos < w.seg_cap) {
+                    w.cand_key[first + pos] = key[q][k];
+                    w.cand_idx[first + pos] = td.flat_start + base + static_cast<u64>(q) * (kBlock * 4) + tid * 4 + k;
                 }
                 ++pos;
             }
@@ -273,20 +293,38 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
 
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
-    const int j = threadIdx.x;
-    if (j >= a.J) return;
-    Slot& s = a.slots[j];
+    __shared__ unsigned long long s_above[kMaxJ];
+    __shared__ unsigned long long s_total;
+    __shared__ u32 s_overflow;
+    const int tid = threadIdx.x;
+    if (tid < kMaxJ) s_above[tid] = 0;
+    if (tid == 0) { s_total = 0; s_overflow = 0; }
+    __syncthreads();
+    for (u32 seg = tid; seg < w.n_segs; seg += kBlock) {
+        const u64 cnt = w.seg_cnt[seg];
+        if (cnt > w.seg_cap) s_overflow = 1;
+        if (cnt) atomicAdd(&s_total, static_cast<unsigned long long>(cnt));
+        for (int j = 0; j < a.J; ++j) {
+            const u64 v = w.seg_above[static_cast<u64>(seg) * kMaxJ + j];
+            if (v) atomicAdd(&s_above[j], static_cast<unsigned long long>(v));
+        }
+    }
+    __syncthreads();
+    if (tid == 0) a.ctl->cand_count = s_total;
+    if (tid >= a.J) return;
+    Slot& s = a.slots[tid];
     if (s.state != kSelecting) return;
-    const u64 above = a.ctl->above[j];
-    if (a.ctl->cand_count > w.cand_cap || above >= s.k) {
+    const u64 above = s_above[tid];
+    a.ctl->above[tid] = above;
+    if (s_overflow || above >= s.k) {
         s.state = kFailed;
         atomicOr(&a.ctl->window_failed, 1u);
         return;
     }
     s.remaining = s.k - above;
     s.prefix = 0;
-    s.hi = static_cast<u32>(w.wslots[2 * j].prefix);
-    s.lo = static_cast<u32>(w.wslots[2 * j + 1].prefix);
+    s.hi = static_cast<u32>(w.wslots[2 * tid].prefix);
+    s.lo = static_cast<u32>(w.wslots[2 * tid + 1].prefix);
 }
 
 // Index rankings for the rankings whose ties are only partly kept.
@@ -371,6 +409,10 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.n_units = L.sample_cap / kSampleUnit < quads ? L.sample_cap / kSampleUnit : quads;
     w.stride = quads / w.n_units;
     w.cand_cap = L.cand_cap;
+    w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
+    w.seg_above = w.seg_cnt + kSegs;
+    w.n_segs = static_cast<u32>(a.n_chunks < static_cast<u64>(kSegs) ? a.n_chunks : static_cast<u64>(kSegs));
+    w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
     w.margin16 = static_cast<int>(m);
     u64* hist_main = a.histx;                                    // [J]
@@ -399,7 +441,8 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     CONDENSA_LAUNCH_CHECK();
     {
         ArrayArgs ar{};
-        ar.keys = w.cand_key; ar.n_host = w.cand_cap; ar.n_dev = &a.ctl->cand_count; ar.slots = a.slots; ar.n_slots = a.J;
+        ar.keys = w.cand_key; ar.seg_cnt = w.seg_cnt; ar.seg_cap = w.seg_cap; ar.n_segs = w.n_segs;
+        ar.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; ar.slots = a.slots; ar.n_slots = a.J;
         ar.hist = hist_main; ar.key_bits = 31;
         rc = rank_array<false>(ar, a.ctl, &a.ctl->need_tie_w, st);
         if (rc != CONDENSA_OK) return rc;
@@ -408,7 +451,8 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     CONDENSA_LAUNCH_CHECK();
     {
         ArrayArgs ar{};
-        ar.keys = w.cand_key; ar.idx = w.cand_idx; ar.n_host = w.cand_cap; ar.n_dev = &a.ctl->cand_count; ar.N = a.N;
+        ar.keys = w.cand_key; ar.idx = w.cand_idx; ar.seg_cnt = w.seg_cnt; ar.seg_cap = w.seg_cap; ar.n_segs = w.n_segs;
+        ar.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; ar.N = a.N;
         ar.slots = w.wslots; ar.n_slots = a.J; ar.hist = hist_aux; ar.key_bits = bits_for(a.N - 1);
         ar.gate = &a.ctl->need_tie_w;
         rc = rank_array<true>(ar, a.ctl, &a.ctl->unused_flag, st);
