@@ -24,6 +24,22 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 
+# HBM traffic of one k_lc_apply launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# calibrated with a plain copy (profiles/lc_step_large_model_hbm_counters.md).  Reported only while the
+# kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
+MEASURED_TRAFFIC = {"bytes": 24166108438, "tensors": 64,
+                    "sources_sha256": "8319c434fe5e0baf187196e70359a1b73b7c0adb806a601553dadbccbe996430"}
+KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_apply.h")
+
+
+def kernel_sources_hash():
+    import hashlib
+    m = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            m.update(fh.read())
+    return m.hexdigest()
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -34,6 +50,8 @@ def parse():
     ap.add_argument("--mask", action="store_true", help="also write the byte mask (+N bytes per step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tensors", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch plain device copies of one tensor (known bytes) for counter calibration")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
     return ap.parse_args()
 
@@ -98,6 +116,11 @@ def main():
         step()
     torch.cuda.synchronize()
 
+    if args.calibrate_copy:                         # 4 copies, each reads and writes rows*cols*4 bytes
+        for i in range(4):
+            outputs["theta"][i].copy_(w_dev[i])
+        torch.cuda.synchronize()
+
     P.condensa_profile_reset()
     P.condensa_set_option(P.OPT_PROFILE, 1)
     torch.cuda.synchronize()
@@ -120,8 +143,12 @@ def main():
     apply = phases["apply"]
     apply_ms = apply["ms"] / max(apply["intervals"], 1)
     achieved = apply_bytes_per_elem * N / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0
+    traffic = None
+    if (T == MEASURED_TRAFFIC["tensors"] and not args.mask
+            and kernel_sources_hash() == MEASURED_TRAFFIC["sources_sha256"]):
+        traffic = MEASURED_TRAFFIC["bytes"]
     roofline = {"bound": "hbm", "kernel": "k_lc_apply", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_ms": round(apply_ms, 4), "algorithmic_bytes_per_launch": apply_bytes_per_elem * N}
     step_gbps = step_bytes_per_elem * N / (ms_per_step * 1e-3) / 1e9
     phase_ms = {k: round(v["ms"] / args.steps, 4) for k, v in phases.items() if v["intervals"]}
