@@ -52,6 +52,7 @@ def parse():
     ap.add_argument("--cpu-sample-tensors", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch plain device copies of one tensor (known bytes) for counter calibration")
+    ap.add_argument("--apply-threads", type=int, default=0, help="workgroup size of the apply sweep (0 = default)")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
     return ap.parse_args()
 
@@ -107,6 +108,7 @@ def main():
     ws_bytes = P.condensa_workspace_bytes(P.binding.OP_LC_STEP, N, 0, T, 1, P.SCOPE_GLOBAL)
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
+    P.condensa_set_option(P.OPT_APPLY_THREADS, args.apply_threads)
 
     def step():
         return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,

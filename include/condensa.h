@@ -205,7 +205,8 @@ enum {
                                        the sample rank; default 112 (= 7 sigma); 0 makes windows miss    */
     CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
     CONDENSA_OPT_PROFILE       = 4, /* 1: bracket the phases of every call with HIP events on the call's stream */
-    CONDENSA_OPT_COUNT         = 5
+    CONDENSA_OPT_APPLY_THREADS = 5, /* workgroup size of the L-C apply sweep: 0 (default = 64), 64, 128 or 256 */
+    CONDENSA_OPT_COUNT         = 6
 };
 condensa_status condensa_set_option(int option, int64_t value);
 int64_t         condensa_get_option(int option);

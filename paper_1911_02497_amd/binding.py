@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libcondensa.so")
 
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
 OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP = range(5)
-OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE = range(5)
+OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE, OPT_APPLY_THREADS = range(6)
 PHASES = ("sample", "sweep", "resolve", "apply", "aggregate")
 MAX_DENSITIES = 16
 

@@ -73,45 +73,43 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
 }
 
 // theta = C(w - lambda/mu) entries, lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
-// each operation rounded once in binary32.
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
-    const u64 c = blockIdx.x / kSubPerChunk;
-    const u32 sub = blockIdx.x % kSubPerChunk;
+// each operation rounded once in binary32.  THREADS threads per workgroup, one float4 each.
+template <bool VEC, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    constexpr u32 kSub = kChunk / (THREADS * 4);
+    const u64 c = blockIdx.x / kSub;
+    const u32 sub = blockIdx.x % kSub;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
+    const TensorDesc& td = a.td[t];
+    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (THREADS * 4) + tid * 4;
+    if (e0 >= td.n) return;
+    float w[4], l[4];
+    load4<VEC>(td.w, e0, td.n, w);
+    load4<VEC>(td.lam, e0, td.n, l);
     const Slot& s = a.slots[0];
     const u32 T = static_cast<u32>(s.prefix);
     const u64 end = s.tie_end;
-    const TensorDesc& td = a.td[t];
     const OutDesc o = out[t];
     const float mu = a.mu;
-    const u64 base = (c - td.chunk_start) * kChunk;
-    {
-        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) return;
-        float w[4], l[4];
-        load4<VEC>(td.w, e0, td.n, w);
-        load4<VEC>(td.lam, e0, td.n, l);
-        float th[4], ln[4], gr[4];
-        u8 m[4];
+    float th[4], ln[4], gr[4];
+    u8 m[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float v = lc_shift(w[k], l[k], mu);
-            const bool keep = keep_rule(mag_key(v), T, td.flat_start + e0 + k, end);
-            m[k] = keep ? 1 : 0;
-            th[k] = keep ? v : 0.0f;
-            const float e = __fsub_rn(w[k], th[k]);
-            const float p = __fmul_rn(mu, e);
-            ln[k] = __fsub_rn(l[k], p);
-            gr[k] = __fsub_rn(p, ln[k]);
-        }
-        if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
-        store4<VEC>(td.lam_out, e0, td.n, ln);
-        if (td.grad) store4<VEC>(td.grad, e0, td.n, gr);
-        if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    for (int k = 0; k < 4; ++k) {
+        const float v = lc_shift(w[k], l[k], mu);
+        const bool keep = keep_rule(mag_key(v), T, td.flat_start + e0 + k, end);
+        m[k] = keep ? 1 : 0;
+        th[k] = keep ? v : 0.0f;
+        const float e = __fsub_rn(w[k], th[k]);
+        const float p = __fmul_rn(mu, e);
+        ln[k] = __fsub_rn(l[k], p);
+        gr[k] = __fsub_rn(p, ln[k]);
     }
+    if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+    store4<VEC>(td.lam_out, e0, td.n, ln);
+    if (td.grad) store4<VEC>(td.grad, e0, td.n, gr);
+    if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
 }
 
 }  // namespace condensa

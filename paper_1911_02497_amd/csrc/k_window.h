@@ -291,6 +291,86 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     }
 }
 
+// Single-density form of the sweep: one wavefront per workgroup and 1024 elements each, so there is
+// no workgroup barrier; the wavefront reserves its candidate slots with one atomic on its segment.
+constexpr int kWaveQuads = 4;                               // float4 per thread
+constexpr int kWaveElems = 64 * 4 * kWaveQuads;             // 1024 elements per workgroup
+template <bool LC, bool VEC>
+__global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs w) {
+    constexpr u32 kSub = kChunk / kWaveElems;
+    const u64 c = blockIdx.x / kSub;
+    const u32 sub = blockIdx.x % kSub;
+    if (c >= a.n_chunks) return;
+    const int lane = threadIdx.x;
+    const int t = static_cast<int>(a.chunk_map[c]);
+    const TensorDesc& td = a.td[t];
+    const u64 base = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * kWaveElems;
+    if (base >= td.n) return;
+    const bool act = (a.slots[0].state == kSelecting);
+    const u32 hi = act ? static_cast<u32>(w.wslots[0].prefix) : 0u;      // inactive: empty window
+    const u32 lo = act ? static_cast<u32>(w.wslots[1].prefix) : 1u;
+
+    u32 key[kWaveQuads][4];
+    u32 cmask = 0, above = 0;
+#pragma unroll
+    for (int q = 0; q < kWaveQuads; ++q) {
+        const u64 e0 = base + static_cast<u64>(q) * 256 + lane * 4;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (e0 < td.n) {
+            load4<VEC>(td.w, e0, td.n, v);
+            if (LC) {
+                float l[4];
+                load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const u32 x = mag_key(v[k]);
+            key[q][k] = x;
+            if (e0 + k < td.n) {
+                above += (x > hi) ? 1u : 0u;
+                if (x >= lo && x <= hi) cmask |= 1u << (q * 4 + k);
+            }
+        }
+    }
+    const u32 seg = blockIdx.x % w.n_segs;
+    u32 s = above;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
+    if (lane == 0 && s)
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(seg) * kMaxJ]), static_cast<unsigned long long>(s));
+    const u32 cnt = __popc(cmask);
+    u32 incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const u32 o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    const u32 total = __shfl(incl, 63, 64);
+    if (total == 0) return;
+    u64 b = 0;
+    if (lane == 63) b = atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_cnt[seg]), static_cast<unsigned long long>(total));
+    const u32 blo = __shfl(static_cast<u32>(b), 63, 64), bhi = __shfl(static_cast<u32>(b >> 32), 63, 64);
+    if (cmask == 0) return;
+    u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + incl - cnt;
+    const u64 first = static_cast<u64>(seg) * w.seg_cap;
+#pragma unroll
+    for (int q = 0; q < kWaveQuads; ++q) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (cmask & (1u << (q * 4 + k))) {
+                if (pos < w.seg_cap) {
+                    w.cand_key[first + pos] = key[q][k];
+                    w.cand_idx[first + pos] = td.flat_start + base + static_cast<u64>(q) * 256 + lane * 4 + k;
+                }
+                ++pos;
+            }
+        }
+    }
+}
+
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
     __shared__ unsigned long long s_above[kMaxJ];
@@ -411,7 +491,8 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.cand_cap = L.cand_cap;
     w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
     w.seg_above = w.seg_cnt + kSegs;
-    w.n_segs = static_cast<u32>(a.n_chunks < static_cast<u64>(kSegs) ? a.n_chunks : static_cast<u64>(kSegs));
+    const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / kWaveElems) : a.n_chunks;
+    w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
     w.margin16 = static_cast<int>(m);
@@ -432,7 +513,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
-        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep<LC, VEC, false>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
         else          hipLaunchKernelGGL((k_window_sweep<LC, VEC, true>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
     }
