@@ -53,8 +53,85 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch plain device copies of one tensor (known bytes) for counter calibration")
     ap.add_argument("--apply-threads", type=int, default=0, help="workgroup size of the apply sweep (0 = default)")
+    ap.add_argument("--all-phases", action="store_true",
+                    help="time every phase with events (adds ~10 us of idle gap per event); default: the apply sweep only")
+    ap.add_argument("--workload", default="lc_stress",
+                    choices=["lc_stress", "single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
+                             "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
+                    help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
     return ap.parse_args()
+
+
+def run_small_workload(args, P, workloads, torch, np, dev):
+    """The small workloads (launch- and cache-bound): same JSON shape, step = one call of the entry point."""
+    import oracle
+    name = args.workload
+    up = lambda arrs: [torch.from_numpy(a).to(dev) for a in arrs]  # noqa: E731
+    P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
+    if name == "single_prune_fp16":
+        host = workloads.single_matrix()
+        d = up(host)
+        call = lambda: P.condensa_prune(d, [0.02], theta=False, theta_f16=True, mask=True, workspace=ws)  # noqa: E731
+        op, F, J, bytes_per_elem, desc = P.binding.OP_PRUNE, 0, 1, 11, "prune d=0.02 fused with fp16 theta + mask"
+        cpu = lambda: oracle.quantize_f16(oracle.prune(host, [0.02])[0]["theta"][0])  # noqa: E731
+    elif name in ("vgg_thresholds", "vgg_masks"):
+        host = workloads.vgg19_cifar()
+        d = up(host)
+        ds = workloads.search_densities()
+        if name == "vgg_thresholds":
+            call = lambda: P.condensa_prune(d, ds, theta=False, mask=False, workspace=ws)  # noqa: E731
+            bytes_per_elem, desc = 4, "thresholds of 10 densities from one sweep"
+        else:
+            call = lambda: P.condensa_prune(d, ds, theta=False, mask=True, workspace=ws)  # noqa: E731
+            bytes_per_elem, desc = 4 + 4 + 10, "10 densities, one selection sweep + one apply sweep writing 10 masks"
+        op, F, J = P.binding.OP_PRUNE, 0, len(ds)
+        cpu = lambda: oracle.prune(host, ds)  # noqa: E731
+    elif name.startswith("resnet_filter"):
+        host = workloads.resnet56_cifar_convs()
+        d = up(host)
+        scope, dens = (P.SCOPE_GLOBAL, 0.3) if name.endswith("global") else (P.SCOPE_PER_TENSOR, 0.5)
+        call = lambda: P.condensa_filter_prune(d, dens, scope, workspace=ws)  # noqa: E731
+        op, F, J, bytes_per_elem = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in host), 1, 13
+        desc = f"filter prune density {dens}, theta + mask"
+        cpu = lambda: oracle.filter_prune(host, dens, scope)  # noqa: E731
+    else:
+        host = workloads.transformer_base()
+        d = up(host)
+        b = 8 if name.endswith("block8") else 32
+        call = lambda: P.condensa_block_prune(d, b, b, 0.25, P.SCOPE_GLOBAL, workspace=ws)  # noqa: E731
+        op, F, J, bytes_per_elem = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // b) * (t.shape[1] // b) for t in host), 1, 13
+        desc = f"block prune {b}x{b} density 0.25, theta + mask"
+        cpu = lambda: oracle.block_prune(host, b, b, 0.25, P.SCOPE_GLOBAL)  # noqa: E731
+    N = sum(t.size for t in host)
+    scope_ws = P.SCOPE_PER_TENSOR if name == "resnet_filter_per_tensor" else P.SCOPE_GLOBAL
+    ws = torch.empty(max(P.condensa_workspace_bytes(op, N, F, len(host), J, scope_ws), 256), dtype=torch.uint8, device=dev)
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    gbps = bytes_per_elem * N / (ms * 1e-3) / 1e9
+    cpu_rec = None
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        cpu()
+        dt = time.perf_counter() - t0
+        cpu_rec = {"value": round(N / dt, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
+                   "sample": f"the whole workload once, {dt:.2f} s", "host_cpus": os.cpu_count()}
+    print(json.dumps({
+        "metric": "weights pruned/sec and achieved HBM GB/s (% of peak) per compression step",
+        "value": round(N / (ms * 1e-3), 1), "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "config": {"workload": f"{name}: {len(host)} tensors, {N} weights, {desc}",
+                                        "note": "includes the Python binding's per-call marshalling and allocation"},
+        "roofline": {"bound": "hbm", "kernel": "whole call", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_per_elem * N},
+        "cpu_baseline": cpu_rec}))
 
 
 def main():
@@ -76,6 +153,10 @@ def main():
     P.library()                                     # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.workload != "lc_stress":
+        run_small_workload(args, P, workloads, torch, np, dev)
+        return
 
     rows, cols, T = 4096, 4608, args.tensors
     mu, density = workloads.LC_MU, workloads.LC_DENSITY
@@ -124,7 +205,7 @@ def main():
         torch.cuda.synchronize()
 
     P.condensa_profile_reset()
-    P.condensa_set_option(P.OPT_PROFILE, 1)
+    P.condensa_set_option(P.OPT_PROFILE, 0x1F if args.all_phases else (1 << 3))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):

@@ -204,7 +204,7 @@ enum {
     CONDENSA_OPT_WINDOW_MARGIN = 2, /* half-width of the sampled window in 1/16 standard deviations of
                                        the sample rank; default 112 (= 7 sigma); 0 makes windows miss    */
     CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
-    CONDENSA_OPT_PROFILE       = 4, /* 1: bracket the phases of every call with HIP events on the call's stream */
+    CONDENSA_OPT_PROFILE       = 4, /* bit p set: bracket phase p of every call with HIP events on the call's stream */
     CONDENSA_OPT_APPLY_THREADS = 5, /* workgroup size of the L-C apply sweep: 0 (default = 64), 64, 128 or 256 */
     CONDENSA_OPT_COUNT         = 6
 };
@@ -212,8 +212,8 @@ condensa_status condensa_set_option(int option, int64_t value);
 int64_t         condensa_get_option(int option);
 
 /*
- * Phase timing (benchmarks).  With CONDENSA_OPT_PROFILE set, every entry point records a pair of
- * timing events on the caller's stream around each phase it enqueues.  condensa_profile_read waits
+ * Phase timing (benchmarks).  For every phase whose bit (1 << phase) is set in CONDENSA_OPT_PROFILE,
+ * every entry point records a pair of timing events on the caller's stream around that phase.  condensa_profile_read waits
  * for the recorded events, adds the elapsed milliseconds of all finished intervals of `phase` to
  * its running totals and returns those totals; condensa_profile_reset drops totals and events.
  */

@@ -78,7 +78,7 @@ hipEvent_t take_event() {
 }  // namespace
 
 PhaseTimer::PhaseTimer(int phase, hipStream_t stream) : stream_(stream) {
-    if (g_options[CONDENSA_OPT_PROFILE].load() == 0) return;
+    if (((g_options[CONDENSA_OPT_PROFILE].load() >> phase) & 1) == 0) return;
     std::lock_guard<std::mutex> lock(g_prof_mu);
     Interval iv;
     iv.phase = phase;
@@ -744,7 +744,7 @@ condensa_status condensa_set_option(int option, int64_t value) {
     if (option == CONDENSA_OPT_SELECT_PATH && value > 2) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_SAMPLE_LOG2 && value != 0 && (value < 10 || value > 26)) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_CAND_SHIFT && value > 30) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_PROFILE && value > 1) return CONDENSA_ERR_ARG;
+    if (option == CONDENSA_OPT_PROFILE && value >= (1 << CONDENSA_PHASE_COUNT)) return CONDENSA_ERR_ARG;
     if (option == CONDENSA_OPT_APPLY_THREADS && value != 0 && value != 64 && value != 128 && value != 256) return CONDENSA_ERR_ARG;
     g_options[option].store(value);
     return CONDENSA_OK;

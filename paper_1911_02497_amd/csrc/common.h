@@ -59,7 +59,7 @@ struct Slot {
     u32 state;             // kInactive (k == 0), kSelecting, kDone
     u32 need_tie;          // index search among ties required
     u32 path;
-    u32 pad0;
+    u32 level_begin;       // radix levels below this one are already decided by the prefix
     u64 pad1;
 };
 static_assert(sizeof(Slot) == 88, "Slot layout");

@@ -199,6 +199,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* h
     const int s = blockIdx.x;
     Slot& slot = slots[s];
     if (slot.state != kSelecting) return;             // uniform over the workgroup
+    if (static_cast<u32>(level) < slot.level_begin) return;
     const Level L = level_of(key_bits, level);
     const int nb = 1 << L.bits;
     const bool shared = (level == 0 && hist_shared != nullptr);

@@ -26,7 +26,7 @@ struct WindowArgs {
     u64* cand_idx;         // [cand_cap]
     Slot* wslots;          // [2J] boundary rankings, later [J] index rankings
     u64* seg_cnt;          // [kSegs] candidates appended to each segment (may exceed seg_cap)
-    u64* seg_above;        // [kSegs][kMaxJ] keys above each window's upper bound
+    u64* seg_above;        // [kMaxJ][kSegs] keys above each window's upper bound
     u64 seg_cap;           // entries per segment
     u32 n_segs;            // segments in use
     u64 n_units;
@@ -149,12 +149,14 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
             s_prefix[tid] = s.prefix;
             s_lo[tid] = static_cast<u32>(s.lo);
             s_hi[tid] = static_cast<u32>(s.hi);
-            s_active[tid] = (s.state == kSelecting) ? 1u : 0u;
-            if (s.state == kSelecting) s_any = 1;
+            const bool on = (s.state == kSelecting && static_cast<u32>(level) >= s.level_begin);
+            s_active[tid] = on ? 1u : 0u;
+            if (on) s_any = 1;
         }
+        __syncthreads();
+        if (!s_any) continue;                            // uniform: nothing to count in this batch
         for (int i = tid; i < nj * nb; i += kBlock) s_hist[i] = 0;
         __syncthreads();
-        if (!s_any) continue;
         auto take = [&](u64 i) {
             const u32 ck = a.keys[i];
             const u64 rk = IDX ? (a.N - 1 - a.idx[i]) : static_cast<u64>(ck);
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     const u64 off = block_excl_scan_u64(__popc(cmask), s_wave, &total);    // syncs the workgroup
     const u32 seg = static_cast<u32>(c % w.n_segs);
     if (tid < J && s_above[tid])
-        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(seg) * kMaxJ + tid]),
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(tid) * kSegs + seg]),
                   static_cast<unsigned long long>(s_above[tid]));
     if (total == 0) return;
     if (tid == 0)
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
     if (lane == 0 && s)
-        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(seg) * kMaxJ]), static_cast<unsigned long long>(s));
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[seg]), static_cast<unsigned long long>(s));
     const u32 cnt = __popc(cmask);
     u32 incl = cnt;
 #pragma unroll
@@ -373,24 +375,32 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
 
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
-    __shared__ unsigned long long s_above[kMaxJ];
-    __shared__ unsigned long long s_total;
+    __shared__ u64 s_wave[kBlock / 64];
+    __shared__ u64 s_above[kMaxJ];
     __shared__ u32 s_overflow;
     const int tid = threadIdx.x;
-    if (tid < kMaxJ) s_above[tid] = 0;
-    if (tid == 0) { s_total = 0; s_overflow = 0; }
+    if (tid == 0) s_overflow = 0;
     __syncthreads();
+    // every thread sums a strided share of the segments, then the workgroup adds the shares up
+    u64 cnt_sum = 0;
+    bool over = false;
     for (u32 seg = tid; seg < w.n_segs; seg += kBlock) {
         const u64 cnt = w.seg_cnt[seg];
-        if (cnt > w.seg_cap) s_overflow = 1;
-        if (cnt) atomicAdd(&s_total, static_cast<unsigned long long>(cnt));
-        for (int j = 0; j < a.J; ++j) {
-            const u64 v = w.seg_above[static_cast<u64>(seg) * kMaxJ + j];
-            if (v) atomicAdd(&s_above[j], static_cast<unsigned long long>(v));
-        }
+        over = over || (cnt > w.seg_cap);
+        cnt_sum += cnt;
+    }
+    if (over) s_overflow = 1;
+    u64 total;
+    block_excl_scan_u64(cnt_sum, s_wave, &total);
+    if (tid == 0) a.ctl->cand_count = total;
+    for (int j = 0; j < a.J; ++j) {
+        u64 part = 0;
+        for (u32 seg = tid; seg < w.n_segs; seg += kBlock) part += w.seg_above[static_cast<u64>(j) * kSegs + seg];
+        u64 sum;
+        block_excl_scan_u64(part, s_wave, &sum);
+        if (tid == 0) s_above[j] = sum;
     }
     __syncthreads();
-    if (tid == 0) a.ctl->cand_count = s_total;
     if (tid >= a.J) return;
     Slot& s = a.slots[tid];
     if (s.state != kSelecting) return;
@@ -402,9 +412,22 @@ __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs 
         return;
     }
     s.remaining = s.k - above;
-    s.prefix = 0;
-    s.hi = static_cast<u32>(w.wslots[2 * tid].prefix);
-    s.lo = static_cast<u32>(w.wslots[2 * tid + 1].prefix);
+    const u32 hi = static_cast<u32>(w.wslots[2 * tid].prefix);
+    const u32 lo = static_cast<u32>(w.wslots[2 * tid + 1].prefix);
+    s.hi = hi;
+    s.lo = lo;
+    // leading digits shared by lo and hi are shared by every candidate: those levels need no counting
+    u32 begin = 0;
+    u64 prefix = 0;
+    const int nl = n_levels(31);
+    for (int level = 0; level < nl - 1; ++level) {
+        const Level L = level_of(31, level);
+        if (((lo ^ hi) >> L.shift) != 0) break;
+        prefix = static_cast<u64>(lo >> L.shift) << L.shift;
+        begin = level + 1;
+    }
+    s.prefix = prefix;
+    s.level_begin = begin;
 }
 
 // Index rankings for the rankings whose ties are only partly kept.
@@ -446,6 +469,7 @@ __global__ __launch_bounds__(kBlock) void k_window_finish(DataArgs a, WindowArgs
         s.tie_end = s.n;
         s.need_tie = 0;
         s.lo = s.hi = 0;
+        s.level_begin = 0;
         s.path = 3;
         s.state = kSelecting;
     }
