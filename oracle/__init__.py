@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
             "oracle_norms": [vp, u64, vp],
             "oracle_filter_apply": [vp, u64, u64, vp, vp, vp],
             "oracle_block_apply": [vp, u64, u64, u64, u64, vp, vp, vp],
+            "oracle_block_sumsq_nd": [vp, vp, vp, vp],
+            "oracle_block_apply_nd": [vp, vp, vp, vp, vp, vp],
             "oracle_lc_shifted": [vp, vp, u64, f32, vp],
             "oracle_lc_update": [vp, vp, vp, vp, u64, f32, vp, vp, vp],
         }.items():
@@ -267,6 +269,57 @@ def block_prune(tensors: Sequence[np.ndarray], bh: int, bw: int, density: float,
         lib().oracle_block_apply(_p(t), t.shape[0], t.shape[1], bh, bw, _p(keep), _p(th), _p(mk))
 
     return _structure_prune(tensors, [block_sumsq(t, bh, bw) for t in tensors], density, scope, apply_one)
+
+
+def _dims4(shape, block):
+    """Left-pad shape and block with ones to rank 4."""
+    if len(shape) != len(block) or not 1 <= len(shape) <= 4:
+        raise ValueError("block rank must equal tensor rank (1..4)")
+    if any(int(b) < 1 for b in block):
+        raise ValueError("block sizes must be positive")
+    pad = 4 - len(shape)
+    d = np.array([1] * pad + [int(x) for x in shape], np.uint64)
+    b = np.array([1] * pad + [int(x) for x in block], np.uint64)
+    return d, b
+
+
+def block_sumsq_nd(t: np.ndarray, block: Sequence[int]) -> np.ndarray:
+    """Sums of squares of the n-D blocks of one tensor; edge blocks may be smaller (ragged)."""
+    t = _f32(t)
+    d, b = _dims4(t.shape, block)
+    n_blocks = int(np.prod((d + b - np.uint64(1)) // b)) if t.size else 0
+    s = np.empty(n_blocks, np.float64)
+    if n_blocks:
+        lib().oracle_block_sumsq_nd(_p(t), _p(d), _p(b), _p(s))
+    return s
+
+
+def block_prune_nd(tensors: Sequence[np.ndarray], block: Sequence[int], density: float, scope: int = SCOPE_GLOBAL):
+    """BlockPrune with n-D blocks and ragged edges (every tensor has the rank of ``block``)."""
+    tensors = [_f32(t) for t in tensors]
+
+    def apply_one(t, keep, th, mk):
+        if t.size:
+            d, b = _dims4(t.shape, block)
+            lib().oracle_block_apply_nd(_p(t), _p(d), _p(b), _p(keep), _p(th), _p(mk))
+
+    return _structure_prune(tensors, [block_sumsq_nd(t, block) for t in tensors], density, scope, apply_one)
+
+
+def neuron_prune(tensors: Sequence[np.ndarray], density: float, scope: int = SCOPE_GLOBAL):
+    """NeuronPrune: a neuron is a row of a [out, in] matrix (a 1-D block), ranked by sum of squares."""
+    for t in tensors:
+        if t.ndim != 2:
+            raise ValueError("neuron pruning takes [out, in] matrices")
+    return filter_prune(tensors, density, scope)
+
+
+def structure_prune(tensors: Sequence[np.ndarray], density: float, scope: int = SCOPE_GLOBAL):
+    """StructurePrune: neurons of the 2-D tensors and filters of the 4-D tensors in one ranking."""
+    for t in tensors:
+        if t.ndim not in (2, 4):
+            raise ValueError("structure pruning takes [out, in] matrices and [Cout, Cin, kh, kw] tensors")
+    return filter_prune(tensors, density, scope)
 
 
 def lc_step(tensors: Sequence[np.ndarray], lambdas: Sequence[np.ndarray], mu: float, density: float):

@@ -283,3 +283,44 @@ void oracle_lc_update(const float* w, const float* lambda, const float* v, const
         grad[i] = g;
     }
 }
+
+/* ---- n-D blocks with ragged edges (BlockPrune "n-D blocks of size bs", Table 1) ------------------
+ * The tensor is viewed as 4-D [d0,d1,d2,d3] (leading dims 1 for lower ranks), the block as
+ * [b0,b1,b2,b3].  The block grid has ceil(d/b) cells per dim; cells at the far edges are smaller.
+ * Block id is row-major over the grid; inside a block the squares are added in row-major order. */
+static uint64_t ceil_div_u64(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+void oracle_block_sumsq_nd(const float* w, const uint64_t* d, const uint64_t* b, double* s)
+{
+    const uint64_t G0 = ceil_div_u64(d[0], b[0]), G1 = ceil_div_u64(d[1], b[1]),
+                   G2 = ceil_div_u64(d[2], b[2]), G3 = ceil_div_u64(d[3], b[3]);
+    for (uint64_t g0 = 0; g0 < G0; ++g0)
+    for (uint64_t g1 = 0; g1 < G1; ++g1)
+    for (uint64_t g2 = 0; g2 < G2; ++g2)
+    for (uint64_t g3 = 0; g3 < G3; ++g3) {
+        double acc = 0.0;
+        for (uint64_t x0 = g0 * b[0]; x0 < (g0 + 1) * b[0] && x0 < d[0]; ++x0)
+        for (uint64_t x1 = g1 * b[1]; x1 < (g1 + 1) * b[1] && x1 < d[1]; ++x1)
+        for (uint64_t x2 = g2 * b[2]; x2 < (g2 + 1) * b[2] && x2 < d[2]; ++x2)
+        for (uint64_t x3 = g3 * b[3]; x3 < (g3 + 1) * b[3] && x3 < d[3]; ++x3) {
+            const double v = (double)w[((x0 * d[1] + x1) * d[2] + x2) * d[3] + x3];
+            acc = acc + v * v;
+        }
+        s[((g0 * G1 + g1) * G2 + g2) * G3 + g3] = acc;
+    }
+}
+
+void oracle_block_apply_nd(const float* w, const uint64_t* d, const uint64_t* b, const uint8_t* keep,
+                           float* theta, uint8_t* mask)
+{
+    const uint64_t G1 = ceil_div_u64(d[1], b[1]), G2 = ceil_div_u64(d[2], b[2]), G3 = ceil_div_u64(d[3], b[3]);
+    for (uint64_t x0 = 0; x0 < d[0]; ++x0)
+    for (uint64_t x1 = 0; x1 < d[1]; ++x1)
+    for (uint64_t x2 = 0; x2 < d[2]; ++x2)
+    for (uint64_t x3 = 0; x3 < d[3]; ++x3) {
+        const uint64_t i = ((x0 * d[1] + x1) * d[2] + x2) * d[3] + x3;
+        const uint64_t u = (((x0 / b[0]) * G1 + x1 / b[1]) * G2 + x2 / b[2]) * G3 + x3 / b[3];
+        theta[i] = keep[u] ? w[i] : bits_f32(0u);
+        mask[i] = keep[u] ? 1 : 0;
+    }
+}

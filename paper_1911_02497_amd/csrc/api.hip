@@ -281,7 +281,7 @@ static bool want_window(u64 N, bool per_tensor) {
     const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;
-    return N >= (static_cast<u64>(1) << 22);
+    return N >= (static_cast<u64>(1) << 25);   // measured crossover against the radix levels: 2^25 .. 2^26 weights
 }
 
 }  // namespace condensa

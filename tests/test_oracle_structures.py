@@ -118,3 +118,66 @@ def test_transformer_block_counts():
     assert sum((r // 8) * (c // 8) for r, c in shapes) == 688128
     assert sum((r // 32) * (c // 32) for r, c in shapes) == 43008
     assert oracle.kept_count(0.25, 688128) == 172032 and oracle.kept_count(0.25, 43008) == 10752
+
+
+# ---- n-D / ragged blocks, neurons, combined structures (Table 1: NeuronPrune, StructurePrune, BlockPrune) ----
+
+def _py_block_sums(t, block):
+    """Blocks cut with python slices; squares added left to right in row-major order, in binary64."""
+    import itertools
+    pad = 4 - t.ndim
+    t4 = t.reshape((1,) * pad + t.shape)
+    b4 = (1,) * pad + tuple(block)
+    grids = [range(0, t4.shape[k], b4[k]) for k in range(4)]
+    out = []
+    for o in itertools.product(*grids):
+        blk = t4[o[0]:o[0] + b4[0], o[1]:o[1] + b4[1], o[2]:o[2] + b4[2], o[3]:o[3] + b4[3]]
+        acc = 0.0
+        for v in blk.reshape(-1):
+            acc = acc + float(v) * float(v)
+        out.append(acc)
+    return out
+
+
+@pytest.mark.parametrize("shape,block", [((10, 15), (5, 5)), ((10, 15), (4, 7)), ((13,), (5,)), ((6, 5, 3, 3), (4, 2, 3, 3)),
+                                         ((6, 5, 3, 3), (1, 5, 1, 1)), ((7, 9), (1, 4)), ((3, 4, 5), (2, 2, 2))])
+def test_nd_block_sums_against_python_slices(shape, block):
+    t = np.random.default_rng(21).standard_normal(shape).astype(np.float32)
+    s = oracle.block_sumsq_nd(t, block)
+    assert s.tolist() == _py_block_sums(t, block)          # bit exact: same order, same precision
+
+
+def test_nd_blocks_reduce_to_the_2d_case_when_shapes_divide():
+    m = np.random.default_rng(22).standard_normal((12, 20)).astype(np.float32)
+    assert np.array_equal(oracle.block_sumsq_nd(m, (4, 5)), oracle.block_sumsq(m, 4, 5))
+    a = oracle.block_prune_nd([m], (4, 5), 0.5)
+    b = oracle.block_prune([m], 4, 5, 0.5)
+    assert np.array_equal(a["mask"][0], b["mask"][0]) and a["select"] == b["select"]
+
+
+def test_ragged_block_prune_masks_follow_the_structure_mask():
+    rng = np.random.default_rng(23)
+    m = rng.standard_normal((11, 13)).astype(np.float32)
+    res = oracle.block_prune_nd([m], (4, 5), 0.5)
+    s = _py_block_sums(m, (4, 5))
+    want = brute_keep(s, int(math.floor(0.5 * 9 + 0.5)))
+    assert res["structure_mask"].tolist() == want
+    for u in range(9):
+        r0, c0 = (u // 3) * 4, (u % 3) * 5
+        assert np.all(res["mask"][0][r0:r0 + 4, c0:c0 + 5] == want[u])
+    assert np.array_equal(res["theta"][0], m * res["mask"][0])
+
+
+def test_neuron_and_structure_prune():
+    rng = np.random.default_rng(24)
+    lin = rng.standard_normal((6, 10)).astype(np.float32)
+    conv = rng.standard_normal((5, 3, 3, 3)).astype(np.float32)
+    res = oracle.neuron_prune([lin], 0.5)
+    rows = [math.fsum(float(v) ** 2 for v in lin[r]) for r in range(6)]
+    assert res["structure_mask"].tolist() == brute_keep(rows, 3)
+    assert np.array_equal(res["mask"][0], np.repeat(res["structure_mask"][:, None], 10, axis=1))
+    both = oracle.structure_prune([conv, lin], 0.4)
+    filt = [math.fsum(float(v) ** 2 for v in conv[f].reshape(-1)) for f in range(5)]
+    assert both["structure_mask"].tolist() == brute_keep(filt + rows, int(math.floor(0.4 * 11 + 0.5)))
+    with pytest.raises(ValueError):
+        oracle.neuron_prune([conv], 0.5)
