@@ -162,6 +162,47 @@ condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tenso
                                      void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
+ * NeuronPrune scheme / neuron_prune operator (Table 1: "aggregates and prunes neurons (1D blocks)").
+ * Every tensor must have ndim == 2, [out, in]; neuron r is row r (the weights into output unit r).
+ * Aggregate, ranking and arguments as for condensa_filter_prune.
+ */
+condensa_status condensa_neuron_prune(const condensa_tensor* tensors, int n_tensors,
+                                      double density, int scope,
+                                      float* const* theta, uint8_t* const* mask,
+                                      double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                      uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                      void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * StructurePrune scheme (Table 1: "combines neuron and filter pruning"): tensors with ndim == 2
+ * contribute their neurons, tensors with ndim == 4 their filters, to one list of structures (ids in
+ * table order) that is ranked globally or per tensor.  Arguments as for condensa_filter_prune.
+ */
+condensa_status condensa_structure_prune(const condensa_tensor* tensors, int n_tensors,
+                                         double density, int scope,
+                                         float* const* theta, uint8_t* const* mask,
+                                         double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                         uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                         void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * BlockPrune with n-D blocks and ragged edges (Table 1: "n-D blocks of size bs"; the evaluation
+ * prunes blocks of size 5 in LSTM matrices).  block_shape has block_ndim (1..4) positive entries and
+ * every tensor must have ndim == block_ndim.  The block grid has ceil(dim / block) cells per
+ * dimension; cells on the far edge of a dimension that the block does not divide are smaller.
+ * Block ids are row-major over the grid of a tensor, tensors in table order; inside a block the
+ * squares are added in row-major order.  1-D blocks along the rows of a matrix are block_shape
+ * {1, bs}.  Other arguments as for condensa_filter_prune.
+ */
+condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_tensors,
+                                        const int32_t* block_shape, int block_ndim,
+                                        double density, int scope,
+                                        float* const* theta, uint8_t* const* mask,
+                                        double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
+                                        uint8_t* structure_mask_dev, condensa_select* results_dev,
+                                        void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
  * Quantize(float16) scheme / quantize + dequantize operators (Section 3.1; Background:
  * low-precision approximation = quantisation with a fixed codebook).  q = binary16 bits of x
  * rounded to nearest even (overflow to infinity, gradual underflow, NaN -> quiet NaN keeping the

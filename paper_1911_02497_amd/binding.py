@@ -43,6 +43,19 @@ _PROTOTYPES = {
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_neuron_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_structure_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_block_prune_nd": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_int32),
+                                                 ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
+                                                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                                 ctypes.c_void_p]),
     "condensa_block_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -245,6 +258,33 @@ def condensa_block_prune(tensors, block_h, block_w, density, scope=SCOPE_GLOBAL,
     n_struct = sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2)
     return _structure_call("condensa_block_prune", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
                            [int(block_h), int(block_w)], workspace, stream)
+
+
+def condensa_neuron_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    return _structure_call("condensa_neuron_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
+                           [], workspace, stream)
+
+
+def condensa_structure_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    return _structure_call("condensa_structure_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
+                           [], workspace, stream)
+
+
+def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
+                            workspace=None, stream=None):
+    nd = len(block_shape)
+    blk = (ctypes.c_int32 * max(nd, 1))(*[int(b) for b in block_shape])
+    n_struct = 0
+    for t in tensors:
+        if t.dim() == nd and t.numel():
+            c = 1
+            for d, b in zip(t.shape, block_shape):
+                c *= -(-d // max(int(b), 1))
+            n_struct += c
+    return _structure_call("condensa_block_prune_nd", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
+                           [blk, nd], workspace, stream)
 
 
 def condensa_quantize(x, want_q=True, want_dq=True, stream=None):

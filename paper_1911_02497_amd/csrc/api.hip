@@ -591,35 +591,44 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     return CONDENSA_OK;
 }
 
-// fills the structure geometry of the tensor table; filter: block_h == 0
-static condensa_status add_structure_geometry(const condensa_tensor* tensors, int n_tensors, int block_h,
-                                              int block_w, Tables* tb) {
+enum StructKind { kFilters, kNeurons, kNeuronsAndFilters, kBlocks2D, kBlocksND };
+
+// Fills the structure geometry of the tensor table.  Every tensor is seen as 4-D (leading dims 1)
+// with a 4-D block; a filter / neuron is the block [1,1,1,len] of the tensor viewed as [F,1,1,len].
+static condensa_status add_structure_geometry(const condensa_tensor* tensors, int n_tensors, StructKind kind,
+                                              const int32_t* block, int block_ndim, Tables* tb) {
     u64 F = 0, sc = 0;
     for (int t = 0; t < n_tensors; ++t) {
         TensorDesc& d = tb->td[t];
+        const condensa_tensor& T = tensors[t];
         d.struct_start = F;
         d.pad = sc;
+        for (int i = 0; i < 4; ++i) { d.d[i] = 1; d.b[i] = 1; }
         u64 f = 0;
-        if (block_h == 0) {                                   // filters of a [Cout, Cin, kh, kw] tensor
-            if (tensors[t].ndim != 4) return CONDENSA_ERR_SHAPE;
+        if (kind == kFilters || kind == kNeurons || kind == kNeuronsAndFilters) {
+            const bool ok = (kind == kFilters) ? T.ndim == 4 : (kind == kNeurons) ? T.ndim == 2 : (T.ndim == 2 || T.ndim == 4);
+            if (!ok) return CONDENSA_ERR_SHAPE;
             if (d.n > 0) {
-                f = static_cast<u64>(tensors[t].shape[0]);
+                f = static_cast<u64>(T.shape[0]);
                 const u64 len = d.n / f;
-                if (len > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
-                d.s_rows = 1; d.s_len = static_cast<u32>(len); d.s_ld = static_cast<u32>(len); d.s_per_row = 1;
+                if (len > 0x7FFFFFFFull || f > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
+                d.d[0] = static_cast<u32>(f); d.d[3] = static_cast<u32>(len); d.b[3] = static_cast<u32>(len);
             }
-        } else {                                              // 2-D blocks of a [R, C] matrix
-            if (tensors[t].ndim != 2) return CONDENSA_ERR_SHAPE;
-            const u64 R = static_cast<u64>(tensors[t].shape[0]), C = static_cast<u64>(tensors[t].shape[1]);
-            if (R % block_h != 0 || C % block_w != 0) return CONDENSA_ERR_SHAPE;
-            if (C > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
-            if (d.n > 0) {
-                f = (R / block_h) * (C / block_w);
-                d.s_rows = static_cast<u32>(block_h); d.s_len = static_cast<u32>(block_w);
-                d.s_ld = static_cast<u32>(C); d.s_per_row = static_cast<u32>(C / block_w);
+        } else {
+            if (T.ndim != block_ndim) return CONDENSA_ERR_SHAPE;
+            const int pad = 4 - T.ndim;
+            f = d.n > 0 ? 1 : 0;
+            for (int i = 0; i < T.ndim; ++i) {
+                const u64 dim = static_cast<u64>(T.shape[i]), blk = static_cast<u64>(block[i]);
+                if (dim > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
+                if (kind == kBlocks2D && dim % blk != 0) return CONDENSA_ERR_SHAPE;
+                if (d.n > 0) {
+                    d.d[pad + i] = static_cast<u32>(dim);
+                    d.b[pad + i] = static_cast<u32>(blk < dim ? blk : dim);
+                    f *= (dim + blk - 1) / blk;
+                }
             }
         }
-        if (d.n == 0) { d.s_rows = 1; d.s_len = 1; d.s_ld = 1; d.s_per_row = 1; }
         d.n_struct = f;
         F += f;
         sc += (f + kChunk - 1) / kChunk;
@@ -632,6 +641,30 @@ static condensa_status add_structure_geometry(const condensa_tensor* tensors, in
     return CONDENSA_OK;
 }
 
+static condensa_status structure_entry(StructKind kind, int op, const condensa_tensor* tensors, int n_tensors,
+                                       const int32_t* block, int block_ndim, double density, int scope,
+                                       float* const* theta, uint8_t* const* mask, double* sumsq_dev,
+                                       float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                       condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
+                                       void* stream) {
+    if (results_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
+    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
+    if (kind == kBlocks2D || kind == kBlocksND) {
+        if (block == nullptr) return CONDENSA_ERR_NULL;
+        if (block_ndim < 1 || block_ndim > 4) return CONDENSA_ERR_SHAPE;
+        for (int i = 0; i < block_ndim; ++i)
+            if (block[i] < 1) return CONDENSA_ERR_SHAPE;
+    }
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    rc = add_structure_geometry(tensors, n_tensors, kind, block, block_ndim, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    return run_structure_prune(op, tb, n_tensors, density, scope, theta, mask, sumsq_dev, norms_dev, keep_idx_dev,
+                               structure_mask_dev, results_dev, workspace_dev, workspace_bytes, stream);
+}
+
 }  // namespace condensa
 
 extern "C" {
@@ -641,17 +674,29 @@ condensa_status condensa_filter_prune(const condensa_tensor* tensors, int n_tens
                                       float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                       condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
                                       void* stream) {
-    if (results_dev == nullptr) return CONDENSA_ERR_NULL;
-    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
-    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
-    Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
-    if (rc != CONDENSA_OK) return rc;
-    rc = add_structure_geometry(tensors, n_tensors, 0, 0, &tb);
-    if (rc != CONDENSA_OK) return rc;
-    return run_structure_prune(CONDENSA_OP_FILTER_PRUNE, tb, n_tensors, density, scope, theta, mask, sumsq_dev,
-                               norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
-                               workspace_bytes, stream);
+    return structure_entry(kFilters, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope, theta,
+                           mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
+                           workspace_bytes, stream);
+}
+
+condensa_status condensa_neuron_prune(const condensa_tensor* tensors, int n_tensors, double density, int scope,
+                                      float* const* theta, uint8_t* const* mask, double* sumsq_dev,
+                                      float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                      condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
+                                      void* stream) {
+    return structure_entry(kNeurons, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope, theta,
+                           mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
+                           workspace_bytes, stream);
+}
+
+condensa_status condensa_structure_prune(const condensa_tensor* tensors, int n_tensors, double density, int scope,
+                                         float* const* theta, uint8_t* const* mask, double* sumsq_dev,
+                                         float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                         condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
+                                         void* stream) {
+    return structure_entry(kNeuronsAndFilters, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope,
+                           theta, mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev,
+                           workspace_dev, workspace_bytes, stream);
 }
 
 condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tensors, int block_h, int block_w,
@@ -659,18 +704,21 @@ condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tenso
                                      double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                      uint8_t* structure_mask_dev, condensa_select* results_dev,
                                      void* workspace_dev, size_t workspace_bytes, void* stream) {
-    if (results_dev == nullptr) return CONDENSA_ERR_NULL;
-    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
-    if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
-    if (block_h < 1 || block_w < 1) return CONDENSA_ERR_SHAPE;
-    Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
-    if (rc != CONDENSA_OK) return rc;
-    rc = add_structure_geometry(tensors, n_tensors, block_h, block_w, &tb);
-    if (rc != CONDENSA_OK) return rc;
-    return run_structure_prune(CONDENSA_OP_BLOCK_PRUNE, tb, n_tensors, density, scope, theta, mask, sumsq_dev,
-                               norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
-                               workspace_bytes, stream);
+    const int32_t block[2] = {block_h, block_w};
+    return structure_entry(kBlocks2D, CONDENSA_OP_BLOCK_PRUNE, tensors, n_tensors, block, 2, density, scope, theta,
+                           mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
+                           workspace_bytes, stream);
+}
+
+condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_tensors, const int32_t* block_shape,
+                                        int block_ndim, double density, int scope, float* const* theta,
+                                        uint8_t* const* mask, double* sumsq_dev, float* norms_dev,
+                                        int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
+                                        condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
+                                        void* stream) {
+    return structure_entry(kBlocksND, CONDENSA_OP_BLOCK_PRUNE, tensors, n_tensors, block_shape, block_ndim, density,
+                           scope, theta, mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev,
+                           workspace_dev, workspace_bytes, stream);
 }
 
 }  // extern "C"

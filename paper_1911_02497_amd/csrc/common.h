@@ -31,14 +31,13 @@ struct TensorDesc {
     u64 flat_start;        // flat index of element 0
     u64 chunk_start;       // id of this tensor's first chunk
     u64 struct_start;      // id of this tensor's first structure (structure pruning)
-    u32 s_rows;            // structure geometry: rows of one structure (1 for filters)
-    u32 s_len;             // contiguous elements per structure row
-    u32 s_ld;              // row stride of the tensor in elements (matrix columns)
-    u32 s_per_row;         // structures per structure-row of the grid (blocks per block row)
-    u64 n_struct;          // structures in this tensor
-    u64 pad;
+    u32 d[4];              // structure pruning: the tensor as 4-D (leading dims 1 for lower ranks)
+    u32 b[4];              // block shape; a filter / neuron is the block [1,1,1,len] of [F,1,1,len]
+    u64 n_struct;          // structures in this tensor: product of ceil(d/b)
+    u64 pad;               // id of this tensor's first structure chunk
+    u64 reserved[2];
 };
-static_assert(sizeof(TensorDesc) == 96, "TensorDesc layout");
+static_assert(sizeof(TensorDesc) == 128, "TensorDesc layout");
 
 struct OutDesc {           // outputs of tensor t for density j, entry j * n_tensors + t
     float* theta;

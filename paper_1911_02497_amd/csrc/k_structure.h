@@ -43,35 +43,49 @@ __device__ inline int tensor_of_schunk(const TensorDesc* __restrict__ td, int n_
     return lo;
 }
 
-// One thread per structure; squares are added in binary64 in memory order (row-major inside a
-// block), so the aggregate does not depend on the launch shape.  x*x is exact in binary64.
+// One thread per structure; squares are added in binary64 in memory order (row-major inside an
+// n-D block, edge blocks clipped), so the aggregate does not depend on the launch shape.  x*x is
+// exact in binary64.
 __global__ __launch_bounds__(kBlock) void k_struct_sumsq(StructArgs a, double* sumsq, float* norms) {
     const u64 u = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x;
     if (u >= a.F) return;
     const int t = tensor_of_struct(a.td, a.n_tensors, u);
     const TensorDesc& td = a.td[t];
-    const u64 s = u - td.struct_start;
-    const u64 br = s / td.s_per_row, bc = s % td.s_per_row;
-    const float* p = td.w + br * td.s_rows * static_cast<u64>(td.s_ld) + bc * td.s_len;
-    const bool vec = ((td.s_len | td.s_ld) & 3u) == 0 && (reinterpret_cast<uintptr_t>(td.w) & 15u) == 0;
+    const u32 d0 = td.d[0], d1 = td.d[1], d2 = td.d[2], d3 = td.d[3];
+    const u32 b0 = td.b[0], b1 = td.b[1], b2 = td.b[2], b3 = td.b[3];
+    const u32 G1 = (d1 + b1 - 1) / b1, G2 = (d2 + b2 - 1) / b2, G3 = (d3 + b3 - 1) / b3;
+    u64 s = u - td.struct_start;
+    const u32 g3 = static_cast<u32>(s % G3); s /= G3;
+    const u32 g2 = static_cast<u32>(s % G2); s /= G2;
+    const u32 g1 = static_cast<u32>(s % G1);
+    const u32 g0 = static_cast<u32>(s / G1);
+    const u32 x0e = (g0 * b0 + b0 < d0) ? g0 * b0 + b0 : d0;
+    const u32 x1e = (g1 * b1 + b1 < d1) ? g1 * b1 + b1 : d1;
+    const u32 x2e = (g2 * b2 + b2 < d2) ? g2 * b2 + b2 : d2;
+    const u32 x3b = g3 * b3;
+    const u32 len = (x3b + b3 < d3) ? b3 : d3 - x3b;
+    const bool aligned = (reinterpret_cast<uintptr_t>(td.w) & 15u) == 0;
     double acc = 0.0;
-    for (u32 r = 0; r < td.s_rows; ++r) {
-        const float* row = p + static_cast<u64>(r) * td.s_ld;
-        if (vec) {
-            for (u32 x = 0; x < td.s_len; x += 4) {
-                const float4 v = *reinterpret_cast<const float4*>(row + x);
-                acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x);
-                acc = acc + static_cast<double>(v.y) * static_cast<double>(v.y);
-                acc = acc + static_cast<double>(v.z) * static_cast<double>(v.z);
-                acc = acc + static_cast<double>(v.w) * static_cast<double>(v.w);
+    for (u32 x0 = g0 * b0; x0 < x0e; ++x0)
+        for (u32 x1 = g1 * b1; x1 < x1e; ++x1)
+            for (u32 x2 = g2 * b2; x2 < x2e; ++x2) {
+                const u64 off = ((static_cast<u64>(x0) * d1 + x1) * d2 + x2) * d3 + x3b;
+                const float* row = td.w + off;
+                if (aligned && ((off | len) & 3u) == 0) {
+                    for (u32 x = 0; x < len; x += 4) {
+                        const float4 v = *reinterpret_cast<const float4*>(row + x);
+                        acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x);
+                        acc = acc + static_cast<double>(v.y) * static_cast<double>(v.y);
+                        acc = acc + static_cast<double>(v.z) * static_cast<double>(v.z);
+                        acc = acc + static_cast<double>(v.w) * static_cast<double>(v.w);
+                    }
+                } else {
+                    for (u32 x = 0; x < len; ++x) {
+                        const double v = static_cast<double>(row[x]);
+                        acc = acc + v * v;
+                    }
+                }
             }
-        } else {
-            for (u32 x = 0; x < td.s_len; ++x) {
-                const double v = static_cast<double>(row[x]);
-                acc = acc + v * v;
-            }
-        }
-    }
     a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
     if (sumsq) sumsq[u] = acc;
     if (norms) norms[u] = static_cast<float>(sqrt(acc));
@@ -293,44 +307,56 @@ __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const Out
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
+    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
+    if (e0 >= td.n) return;
     const OutDesc o = out[t];
     const u8* __restrict__ sm = a.smask + td.struct_start;
-    const u64 base = (c - td.chunk_start) * kChunk;
-    const u32 ld = td.s_ld, rows = td.s_rows, len = td.s_len, per_row = td.s_per_row;
-    {
-        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) return;
-        float v[4];
-        load4<VEC>(td.w, e0, td.n, v);
-        u64 row;
-        u32 col;
-        if (td.n <= 0xFFFFFFFFull) {
-            const u32 e32 = static_cast<u32>(e0);
-            row = e32 / ld;
-            col = e32 % ld;
-        } else {
-            row = e0 / ld;
-            col = static_cast<u32>(e0 % ld);
-        }
-        float th[4];
-        u8 m[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            while (col >= ld) { col -= ld; ++row; }
-            u8 keep = 0;
-            if (e0 + k < td.n) {
-                const u64 s = (row <= 0xFFFFFFFFull)
-                                  ? static_cast<u64>(static_cast<u32>(row) / rows) * per_row + col / len
-                                  : (row / rows) * per_row + col / len;
-                keep = sm[s];
-            }
-            m[k] = keep;
-            th[k] = keep ? v[k] : 0.0f;
-            ++col;
-        }
-        if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
-        if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    const u32 d1 = td.d[1], d2 = td.d[2], d3 = td.d[3];
+    const u32 b0 = td.b[0], b1 = td.b[1], b2 = td.b[2], b3 = td.b[3];
+    const u32 G1 = (d1 + b1 - 1) / b1, G2 = (d2 + b2 - 1) / b2, G3 = (d3 + b3 - 1) / b3;
+    float v[4];
+    load4<VEC>(td.w, e0, td.n, v);
+    // coordinates of the first element; the others follow by carrying along the last dimension
+    u64 r;
+    u32 x3;
+    if (td.n <= 0xFFFFFFFFull) {
+        const u32 e32 = static_cast<u32>(e0);
+        r = e32 / d3;
+        x3 = e32 % d3;
+    } else {
+        r = e0 / d3;
+        x3 = static_cast<u32>(e0 % d3);
     }
+    auto row_base = [&](u64 row) -> u64 {               // structure id of column block 0 in this row
+        u64 x2, x1, x0;
+        if (row <= 0xFFFFFFFFull) {
+            const u32 r32 = static_cast<u32>(row);
+            x2 = r32 % d2;
+            const u32 q = r32 / d2;
+            x1 = q % d1;
+            x0 = q / d1;
+        } else {
+            x2 = row % d2;
+            const u64 q = row / d2;
+            x1 = q % d1;
+            x0 = q / d1;
+        }
+        return (((x0 / b0) * G1 + x1 / b1) * G2 + x2 / b2) * G3;
+    };
+    u64 gbase = row_base(r);
+    float th[4];
+    u8 m[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        while (x3 >= d3) { x3 -= d3; ++r; gbase = row_base(r); }
+        u8 keep = 0;
+        if (e0 + k < td.n) keep = sm[gbase + x3 / b3];
+        m[k] = keep;
+        th[k] = keep ? v[k] : 0.0f;
+        ++x3;
+    }
+    if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+    if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
 }
 
 }  // namespace condensa

@@ -98,3 +98,65 @@ def test_shape_errors():
     with pytest.raises(P.CondensaError) as e:
         P.condensa_filter_prune([m], 0.5)
     assert e.value.code == -4
+
+
+# ---- neurons, combined structures, n-D and ragged blocks ------------------------------------------------
+
+def test_lstm_shaped_block_size_5():
+    """Two-layer LSTM of hidden size 650: four [2600, 650] matrices, blocks of 5x5 and 1x5."""
+    rng = np.random.default_rng(30)
+    ms = [(rng.standard_normal((2600, 650)) * 0.05).astype(np.float32) for _ in range(4)]
+    dev = up(ms)
+    for block in ((5, 5), (1, 5)):
+        res = P.condensa_block_prune_nd(dev, block, 0.4, P.SCOPE_GLOBAL)
+        torch.cuda.synchronize()
+        _compare(res, oracle.block_prune_nd(ms, block, 0.4, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, ms, f"lstm {block}")
+    both = P.condensa_block_prune(dev, 5, 5, 0.4, P.SCOPE_GLOBAL)
+    nd = P.condensa_block_prune_nd(dev, (5, 5), 0.4, P.SCOPE_GLOBAL)
+    torch.cuda.synchronize()
+    assert torch.equal(both["structure_mask"], nd["structure_mask"])
+
+
+@pytest.mark.parametrize("shapes,block", [
+    ([(650, 650), (33, 47)], (7, 7)),            # ragged in both dimensions
+    ([(100, 64)], (1, 8)),
+    ([(100, 64)], (200, 3)),                     # block taller than the matrix
+    ([(1000,), (5,), (0,)], (7,)),
+    ([(64, 32, 3, 3), (10, 3, 3, 3)], (4, 2, 3, 3)),
+    ([(64, 32, 3, 3)], (8, 8, 1, 1)),
+    ([(6, 10, 12)], (4, 4, 5)),
+])
+def test_nd_and_ragged_blocks(shapes, block):
+    rng = np.random.default_rng(31)
+    ts = [rng.standard_normal(s).astype(np.float32) for s in shapes]
+    if ts[0].size > 100:
+        ts[0].reshape(-1)[:50] = 0.0
+    for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
+        for d in (0.0, 0.3, 1.0):
+            res = P.condensa_block_prune_nd(up(ts), block, d, scope)
+            torch.cuda.synchronize()
+            _compare(res, oracle.block_prune_nd(ts, block, d, scope), scope, ts, f"{shapes} {block} d={d} scope={scope}")
+
+
+def test_neuron_prune_and_structure_prune():
+    rng = np.random.default_rng(32)
+    lin = [rng.standard_normal(s).astype(np.float32) for s in ((10, 512), (300, 77), (4096, 25))]
+    lin[1][7] = lin[1][3]
+    for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
+        res = P.condensa_neuron_prune(up(lin), 0.5, scope)
+        torch.cuda.synchronize()
+        _compare(res, oracle.neuron_prune(lin, 0.5, scope), scope, lin, f"neurons scope={scope}")
+    vgg = workloads.vgg19_cifar()                      # 16 convs + the [10, 512] classifier
+    res = P.condensa_structure_prune(up(vgg), 0.21, P.SCOPE_GLOBAL)    # sparsity 0.79 (Table 2, filter pruning of VGG19)
+    torch.cuda.synchronize()
+    _compare(res, oracle.structure_prune(vgg, 0.21, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, vgg, "vgg structures")
+
+
+def test_new_structure_entry_points_reject_bad_shapes():
+    m = torch.ones((6, 10), device=DEV)
+    c = torch.ones((4, 3, 3, 3), device=DEV)
+    for call in (lambda: P.condensa_neuron_prune([c], 0.5), lambda: P.condensa_structure_prune([torch.ones(5, device=DEV)], 0.5),
+                 lambda: P.condensa_block_prune_nd([m], (2, 2, 2), 0.5), lambda: P.condensa_block_prune_nd([m], (0, 2), 0.5)):
+        with pytest.raises(P.CondensaError) as e:
+            call()
+        assert e.value.code == -4
