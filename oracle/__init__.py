@@ -69,10 +69,15 @@ def lib() -> ctypes.CDLL:
             "oracle_block_apply_nd": [vp, vp, vp, vp, vp, vp],
             "oracle_lc_shifted": [vp, vp, u64, f32, vp],
             "oracle_lc_update": [vp, vp, vp, vp, u64, f32, vp, vp, vp],
+            "oracle_lc_update_pq": [vp, vp, vp, vp, u64, f32, vp, vp, vp, vp],
         }.items():
             fn = getattr(L, name)
             fn.restype = None
             fn.argtypes = args
+        for name in ("oracle_count_nonzero_f32", "oracle_count_nonzero_f16"):
+            fn = getattr(L, name)
+            fn.restype = u64
+            fn.argtypes = [vp, u64]
         _lib = L
     return _lib
 
@@ -338,3 +343,36 @@ def lc_step(tensors: Sequence[np.ndarray], lambdas: Sequence[np.ndarray], mu: fl
     lib().oracle_lc_update(_p(w), _p(lam), _p(v), _p(keep), w.size, mu32, _p(theta), _p(lam_out), _p(grad))
     return {"theta": _split(theta, tensors), "lambda": _split(lam_out, tensors), "grad": _split(grad, tensors),
             "mask": _split(keep, tensors), "select": sel, "v": _split(v, tensors)}
+
+
+def lc_step_pq(tensors: Sequence[np.ndarray], lambdas: Sequence[np.ndarray], mu: float, density: float):
+    """L-C compression step for Compose([Prune(), Quantize(float16)]): theta is stored as binary16 and
+    the multiplier update sees its exact widening."""
+    tensors = [_f32(t) for t in tensors]
+    lambdas = [_f32(t) for t in lambdas]
+    w, lam = _flat(tensors), _flat(lambdas)
+    if w.size != lam.size:
+        raise ValueError("lambda must match w")
+    mu32 = float(np.float32(mu))
+    v = np.empty_like(w)
+    lib().oracle_lc_shifted(_p(w), _p(lam), w.size, mu32, _p(v))
+    sel, keep = select_keep(magnitude_keys(v), kept_count(density, w.size))
+    theta16 = np.empty(w.size, np.uint16)
+    theta, lam_out, grad = np.empty_like(w), np.empty_like(w), np.empty_like(w)
+    lib().oracle_lc_update_pq(_p(w), _p(lam), _p(v), _p(keep), w.size, mu32, _p(theta16), _p(theta), _p(lam_out), _p(grad))
+    return {"theta_f16": _split(theta16, tensors), "theta": _split(theta, tensors), "lambda": _split(lam_out, tensors),
+            "grad": _split(grad, tensors), "mask": _split(keep, tensors), "select": sel, "v": _split(v, tensors)}
+
+
+def count_nonzero(tensors: Sequence[np.ndarray]) -> int:
+    """Non-zero parameters of float32 tensors or of binary16 bit patterns (uint16); -0 is zero."""
+    total = 0
+    for t in tensors:
+        t = np.ascontiguousarray(t)
+        if t.dtype == np.float32:
+            total += int(lib().oracle_count_nonzero_f32(_p(t), t.size))
+        elif t.dtype == np.uint16:
+            total += int(lib().oracle_count_nonzero_f16(_p(t), t.size))
+        else:
+            raise TypeError("float32 values or uint16 binary16 patterns")
+    return total

@@ -324,3 +324,40 @@ void oracle_block_apply_nd(const float* w, const uint64_t* d, const uint64_t* b,
         mask[i] = keep[u] ? 1 : 0;
     }
 }
+
+/* ---- L-C step with the composed scheme Compose([Prune(), Quantize(float16)]) (Evaluation, Objective 1) ----
+ * Theta = binary16(prune(v)); D(Theta) = exact widening; the multiplier update uses D(Theta):
+ * e = w - D(Theta); p = mu*e; lambda' = lambda - p; g = p - lambda'. */
+void oracle_lc_update_pq(const float* w, const float* lambda, const float* v, const uint8_t* keep,
+                         uint64_t n, float mu, uint16_t* theta16, float* theta, float* lambda_out, float* grad)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        const float pruned = keep[i] ? v[i] : bits_f32(0u);
+        const uint16_t h = f32_to_f16_bits(f32_bits(pruned));
+        const float th = bits_f32(f16_to_f32_bits(h));
+        volatile float e = w[i] - th;
+        volatile float p = mu * e;
+        volatile float l = lambda[i] - p;
+        volatile float g = p - l;
+        theta16[i] = h;
+        theta[i] = th;
+        lambda_out[i] = l;
+        grad[i] = g;
+    }
+}
+
+/* Memory footprint objective (Evaluation, Objective 1): the number of non-zero parameters; the
+ * footprint in bytes is that count times the size of the stored type.  -0 counts as zero. */
+uint64_t oracle_count_nonzero_f32(const float* x, uint64_t n)
+{
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n; ++i) c += (f32_bits(x[i]) & 0x7FFFFFFFu) != 0u;
+    return c;
+}
+
+uint64_t oracle_count_nonzero_f16(const uint16_t* x, uint64_t n)
+{
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n; ++i) c += (x[i] & 0x7FFFu) != 0u;
+    return c;
+}

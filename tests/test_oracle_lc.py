@@ -89,3 +89,48 @@ def test_global_over_several_tensors():
     flat = oracle.lc_step([np.concatenate([t.reshape(-1) for t in ws])], [np.concatenate([t.reshape(-1) for t in ls])], 1e-3, 0.3)
     assert res["select"] == flat["select"]
     assert np.array_equal(np.concatenate([t.reshape(-1) for t in res["grad"]]).view(np.uint32), flat["grad"][0].view(np.uint32))
+
+
+# ---- composed scheme P+Q as the compression step, and the footprint objective (Evaluation, Objective 1) ----
+
+def test_pq_step_matches_numpy_float16_roundtrip():
+    w, lam = _case(seed=8)
+    mu = np.float32(1e-3)
+    res = oracle.lc_step_pq([w], [lam], float(mu), 0.1)
+    plain = oracle.lc_step([w], [lam], float(mu), 0.1)
+    assert res["select"] == plain["select"] and np.array_equal(res["mask"][0], plain["mask"][0])
+    with np.errstate(over="ignore"):
+        h = plain["theta"][0].astype(np.float16)             # numpy's own rounding
+    assert np.array_equal(res["theta_f16"][0], h.view(np.uint16))
+    th = h.astype(np.float32)
+    assert np.array_equal(res["theta"][0].view(np.uint32), th.view(np.uint32))
+    e = w - th
+    p = mu * e
+    lam2 = lam - p
+    assert np.array_equal(res["lambda"][0].view(np.uint32), lam2.view(np.uint32))
+    assert np.array_equal(res["grad"][0].view(np.uint32), (p - lam2).view(np.uint32))
+    # the quantised theta differs from the unquantised one, so the update really sees D(theta)
+    assert not np.array_equal(res["theta"][0], plain["theta"][0])
+    assert not np.array_equal(res["lambda"][0], plain["lambda"][0])
+
+
+def test_pq_step_equals_plain_step_when_theta_is_representable():
+    rng = np.random.default_rng(9)
+    w = (rng.integers(-64, 65, 4000) / 8.0).astype(np.float32)     # multiples of 1/8: exact in binary16
+    lam = np.zeros_like(w)
+    a = oracle.lc_step_pq([w], [lam], 1e-3, 0.3)
+    b = oracle.lc_step([w], [lam], 1e-3, 0.3)
+    for name in ("theta", "lambda", "grad"):
+        assert np.array_equal(a[name][0].view(np.uint32), b[name][0].view(np.uint32))
+
+
+def test_footprint_counts_nonzeros_and_reproduces_the_two_times_of_pq():
+    x = np.array([0.0, -0.0, 1e-30, -2.0, 3.0, 0.0], np.float32)
+    assert oracle.count_nonzero([x]) == 3
+    q, _ = oracle.quantize_f16(x)
+    assert oracle.count_nonzero([q]) == 2                          # 1e-30 underflows to zero in binary16
+    w, lam = _case(n=20000, seed=10)
+    res = oracle.lc_step_pq([w], [np.zeros_like(w)], 1e-3, 0.05)
+    nnz = oracle.count_nonzero(res["theta_f16"])
+    assert nnz == res["select"]["k"] == 1000
+    assert 4 * w.size / (2 * nnz) == 2 / 0.05                      # r_c = 2 / (1 - s)
