@@ -59,8 +59,12 @@ enum {
 enum { CONDENSA_SCOPE_GLOBAL = 0,       /* one ranking over all tensors of the call              */
        CONDENSA_SCOPE_PER_TENSOR = 1 }; /* every tensor ranked on its own                         */
 
-enum { CONDENSA_OP_PRUNE = 0, CONDENSA_OP_FILTER_PRUNE = 1, CONDENSA_OP_BLOCK_PRUNE = 2,
-       CONDENSA_OP_QUANTIZE = 3, CONDENSA_OP_LC_STEP = 4 };
+enum { CONDENSA_OP_PRUNE = 0,        /* condensa_prune                                               */
+       CONDENSA_OP_FILTER_PRUNE = 1, /* condensa_filter_prune, _neuron_prune, _structure_prune        */
+       CONDENSA_OP_BLOCK_PRUNE = 2,  /* condensa_block_prune, _block_prune_nd                         */
+       CONDENSA_OP_QUANTIZE = 3,
+       CONDENSA_OP_LC_STEP = 4,      /* condensa_lc_step, _lc_step_pq                                 */
+       CONDENSA_OP_COUNT_NONZERO = 5 };
 
 #define CONDENSA_MAX_DENSITIES 16
 #define CONDENSA_MAX_TENSORS   65536
@@ -237,6 +241,34 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors,
                                  float* const* theta, float* const* grad, uint8_t* const* mask,
                                  condensa_select* result_dev,
                                  void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * The L-C compression step for the composed scheme Compose([Prune(), Quantize(float16)]) (Evaluation,
+ * Objective 1: P+Q).  As condensa_lc_step, except that the pruned v is rounded to binary16
+ * (theta_f16: NULL or host table of device outputs holding the bit patterns) and the updates use the
+ * decompression D(theta) = exact widening of those patterns (Section 3.3: w = D(Theta)):
+ *      theta = widen(binary16(prune(v)));  e = w - theta;  p = mu * e;  lambda' = lambda - p;  g = p - lambda'.
+ * `theta`, if given, receives D(theta) in fp32.  The mask still marks the k selected positions, also
+ * where a kept value underflows to zero in binary16.
+ */
+condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensors,
+                                    float* const* lambda, float* const* lambda_out,
+                                    float mu, double density,
+                                    float* const* theta, uint16_t* const* theta_f16,
+                                    float* const* grad, uint8_t* const* mask,
+                                    condensa_select* result_dev,
+                                    void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * Memory-footprint objective (Evaluation, Objective 1: "the number of bytes consumed by the model's
+ * non-zero parameters"): writes to *count_dev the number of non-zero elements over all tensors; the
+ * footprint is that count times the element size.  is_f16 = 0: tensors hold fp32 values; is_f16 = 1:
+ * `w` of every tensor points to binary16 bit patterns (as written to theta_f16) and shape counts
+ * those.  +0 and -0 are zeros.  Workspace: condensa_workspace_bytes(CONDENSA_OP_COUNT_NONZERO, ...).
+ */
+condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int is_f16,
+                                       uint64_t* count_dev,
+                                       void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /* ---- tuning / test knobs (process wide; not needed for normal use) ---------------------------- */
 enum {

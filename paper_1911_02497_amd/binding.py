@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libcondensa.so")
 
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
-OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP = range(5)
+OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP, OP_COUNT_NONZERO = range(6)
 OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE, OPT_APPLY_THREADS = range(6)
 PHASES = ("sample", "sweep", "resolve", "apply", "aggregate")
 MAX_DENSITIES = 16
@@ -67,6 +67,12 @@ _PROTOTYPES = {
                                           ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                           ctypes.c_void_p]),
+    "condensa_lc_step_pq": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_count_nonzero": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "condensa_set_option": (ctypes.c_int32, [ctypes.c_int, ctypes.c_int64]),
     "condensa_get_option": (ctypes.c_int64, [ctypes.c_int]),
     "condensa_profile_read": (ctypes.c_int32, [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -307,7 +313,7 @@ def condensa_dequantize(q, stream=None):
 
 
 def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,
-                     mask=True, outputs=None, workspace=None, stream=None):
+                     mask=True, outputs=None, workspace=None, stream=None, pq=False):
     """Marshals condensa_lc_step.  By default fresh lambda_out tensors are allocated (lambda is left
     untouched); ``in_place`` updates lambda itself.  ``outputs`` may carry preallocated
     theta / grad / mask / lambda_out lists to reuse."""
@@ -334,7 +340,42 @@ def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=Fa
     if results is None:
         results = torch.zeros((1, len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_LC_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
-    _check(lib.condensa_lc_step(tab, nt, pl, plo, float(mu), float(density), p1, p2, p3, results.data_ptr(),
-                                ws.data_ptr(), ws.numel(), _stream(stream)))
-    return {"theta": th, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo, "results": results,
-            "workspace": ws, "_keep": (kl, klo, k1, k2, k3)}
+    th16, k4 = None, None
+    if pq:
+        th16 = outputs.get("theta_f16") or [torch.empty(t.shape, dtype=torch.int16, device=dev) for t in tensors]
+        k4, p4 = _ptr_table(th16)
+        _check(lib.condensa_lc_step_pq(tab, nt, pl, plo, float(mu), float(density), p1, p4, p2, p3,
+                                       results.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+    else:
+        _check(lib.condensa_lc_step(tab, nt, pl, plo, float(mu), float(density), p1, p2, p3, results.data_ptr(),
+                                    ws.data_ptr(), ws.numel(), _stream(stream)))
+    return {"theta": th, "theta_f16": th16, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo,
+            "results": results, "workspace": ws, "_keep": (kl, klo, k1, k2, k3, k4)}
+
+
+def condensa_lc_step_pq(tensors, lambdas, mu, density, **kw):
+    """condensa_lc_step_pq: the L-C step of the composed prune + fp16 scheme (theta_f16 holds int16 views of the bits)."""
+    return condensa_lc_step(tensors, lambdas, mu, density, pq=True, **kw)
+
+
+def condensa_count_nonzero(tensors, workspace=None, stream=None):
+    """Non-zero count of float32 tensors, or of binary16 bit patterns when the tensors are int16 / float16."""
+    import torch
+    lib = library()
+    dev = tensors[0].device if tensors else torch.device("cuda")
+    is_f16 = 1 if (tensors and tensors[0].dtype in (torch.int16, torch.float16)) else 0
+    nt = len(tensors)
+    arr = (Tensor * max(nt, 1))()
+    for i, t in enumerate(tensors):
+        want = (torch.int16, torch.float16) if is_f16 else (torch.float32,)
+        if not (t.is_cuda and t.is_contiguous() and t.dtype in want and 1 <= t.dim() <= 4):
+            raise TypeError("contiguous device tensors of one element type, 1 to 4 dimensions")
+        arr[i].w = t.data_ptr() if t.numel() else None
+        for d in range(t.dim()):
+            arr[i].shape[d] = t.shape[d]
+        arr[i].ndim = t.dim()
+    total = sum(t.numel() for t in tensors)
+    count = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws, need = _workspace(OP_COUNT_NONZERO, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
+    _check(lib.condensa_count_nonzero(arr, nt, is_f16, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return count

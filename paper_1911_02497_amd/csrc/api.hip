@@ -142,13 +142,13 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (1 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
-    const u64 tie_chunks = structure ? L.max_schunks : L.max_chunks;
+    const u64 tie_chunks = structure ? L.max_schunks : (op == CONDENSA_OP_COUNT_NONZERO ? 0 : L.max_chunks);
     L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
     if (structure) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
         L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
-    } else if (!per_tensor) {
+    } else if (!per_tensor && op != CONDENSA_OP_COUNT_NONZERO) {
         L.sample_cap = window_sample_size(N);
         L.cand_cap = window_cand_capacity(N, J);
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
@@ -294,7 +294,7 @@ extern "C" {
 
 size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures, int n_tensors,
                                 int n_densities, int scope) {
-    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_LC_STEP) return 0;
+    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_COUNT_NONZERO) return 0;
     if (op == CONDENSA_OP_QUANTIZE) return 0;
     if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
     if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
@@ -393,10 +393,15 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     return CONDENSA_OK;
 }
 
-condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
-                                 float* const* lambda_out, float mu, double density, float* const* theta,
-                                 float* const* grad, uint8_t* const* mask, condensa_select* result_dev,
-                                 void* workspace_dev, size_t workspace_bytes, void* stream) {
+}  // extern "C" (reopened below)
+
+namespace condensa {
+
+static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int n_tensors, float* const* lambda,
+                                    float* const* lambda_out, float mu, double density, float* const* theta,
+                                    uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
+                                    condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
+                                    void* stream) {
     if (result_dev == nullptr) return CONDENSA_ERR_NULL;
     if (n_tensors > 0 && lambda == nullptr) return CONDENSA_ERR_NULL;
     if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
@@ -420,9 +425,10 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
         d.grad = grad ? grad[t] : nullptr;
         OutDesc& o = out[t];
         o.theta = theta ? theta[t] : nullptr;
+        o.theta16 = (pq && theta_f16) ? theta_f16[t] : nullptr;
         o.mask = mask ? mask[t] : nullptr;
         const void* ins[2] = {d.w, d.lam};
-        const void* outs[4] = {o.theta, d.grad, o.mask, (d.lam_out != d.lam) ? d.lam_out : nullptr};
+        const void* outs[5] = {o.theta, d.grad, o.mask, (d.lam_out != d.lam) ? d.lam_out : nullptr, o.theta16};
         for (const void* o_ : outs)
             for (const void* i_ : ins)
                 if (o_ != nullptr && o_ == i_) return CONDENSA_ERR_ARG;
@@ -431,6 +437,7 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
         if (o.theta && !aligned16(o.theta)) vec = false;
         if (d.grad && !aligned16(d.grad)) vec = false;
         if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
+        if (o.theta16 && (reinterpret_cast<uintptr_t>(o.theta16) & 7u)) vec = false;
     }
     const bool window = want_window(tb.N, false);
     Slot slot;
@@ -478,12 +485,83 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
         const int64_t at_opt = g_options[CONDENSA_OPT_APPLY_THREADS].load();
         const unsigned nc = static_cast<unsigned>(tb.n_chunks);
         // measured on the 1.2 G-weight workload: 64 threads 3.94 ms, 256 threads 4.28 ms, 128 threads 4.55 ms
-        if (vec && at_opt == 256)      hipLaunchKernelGGL((k_lc_apply<true, 256>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
-        else if (vec && at_opt == 128) hipLaunchKernelGGL((k_lc_apply<true, 128>), dim3(nc * (kChunk / 512)), dim3(128), 0, st, a, od);
-        else if (vec)                  hipLaunchKernelGGL((k_lc_apply<true, 64>), dim3(nc * (kChunk / 256)), dim3(64), 0, st, a, od);
-        else                           hipLaunchKernelGGL((k_lc_apply<false, 256>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
+        if (pq) {
+            if (vec) hipLaunchKernelGGL((k_lc_apply<true, 64, true>), dim3(nc * (kChunk / 256)), dim3(64), 0, st, a, od);
+            else     hipLaunchKernelGGL((k_lc_apply<false, 256, true>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
+        }
+        else if (vec && at_opt == 256) hipLaunchKernelGGL((k_lc_apply<true, 256, false>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
+        else if (vec && at_opt == 128) hipLaunchKernelGGL((k_lc_apply<true, 128, false>), dim3(nc * (kChunk / 512)), dim3(128), 0, st, a, od);
+        else if (vec)                  hipLaunchKernelGGL((k_lc_apply<true, 64, false>), dim3(nc * (kChunk / 256)), dim3(64), 0, st, a, od);
+        else                           hipLaunchKernelGGL((k_lc_apply<false, 256, false>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
         CONDENSA_LAUNCH_CHECK();
     }
+    return CONDENSA_OK;
+}
+
+}  // namespace condensa
+
+extern "C" {
+
+condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
+                                 float* const* lambda_out, float mu, double density, float* const* theta,
+                                 float* const* grad, uint8_t* const* mask, condensa_select* result_dev,
+                                 void* workspace_dev, size_t workspace_bytes, void* stream) {
+    return lc_step_impl(false, tensors, n_tensors, lambda, lambda_out, mu, density, theta, nullptr, grad, mask,
+                        result_dev, workspace_dev, workspace_bytes, stream);
+}
+
+condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
+                                    float* const* lambda_out, float mu, double density, float* const* theta,
+                                    uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
+                                    condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
+                                    void* stream) {
+    return lc_step_impl(true, tensors, n_tensors, lambda, lambda_out, mu, density, theta, theta_f16, grad, mask,
+                        result_dev, workspace_dev, workspace_bytes, stream);
+}
+
+condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int is_f16,
+                                       uint64_t* count_dev, void* workspace_dev, size_t workspace_bytes,
+                                       void* stream) {
+    if (count_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (is_f16 != 0 && is_f16 != 1) return CONDENSA_ERR_ARG;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_COUNT_NONZERO, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+    bool vec = true;
+    for (int t = 0; t < n_tensors; ++t)
+        if (tb.td[t].n > 0 && (reinterpret_cast<uintptr_t>(tb.td[t].w) & (is_f16 ? 7u : 15u))) vec = false;
+    std::vector<char> up(L.upload_bytes, 0);
+    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    if (rc != CONDENSA_OK) return rc;
+    hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
+                       at<TensorDesc>(workspace_dev, L.td), n_tensors, at<u32>(workspace_dev, L.chunk_map), tb.n_chunks);
+    CONDENSA_LAUNCH_CHECK();
+    DataArgs a{};
+    a.td = at<TensorDesc>(workspace_dev, L.td);
+    a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
+    a.n_chunks = tb.n_chunks;
+    a.N = tb.N;
+    a.n_tensors = n_tensors;
+    u64* partial = at<u64>(workspace_dev, L.hist0);            // kBins words, cleared by k_prepare
+    const unsigned blocks = static_cast<unsigned>(tb.n_chunks < static_cast<u64>(kBins) ? (tb.n_chunks ? tb.n_chunks : 1) : kBins);
+    if (tb.n_chunks > 0) {
+        if (is_f16) {
+            if (vec) hipLaunchKernelGGL((k_count_nonzero<true, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            else     hipLaunchKernelGGL((k_count_nonzero<true, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+        } else {
+            if (vec) hipLaunchKernelGGL((k_count_nonzero<false, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            else     hipLaunchKernelGGL((k_count_nonzero<false, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+        }
+        CONDENSA_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(kBlock), 0, st, partial, blocks, count_dev);
+    CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
 }
 

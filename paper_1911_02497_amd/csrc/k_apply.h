@@ -74,7 +74,9 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
 
 // theta = C(w - lambda/mu) entries, lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
 // each operation rounded once in binary32.  THREADS threads per workgroup, one float4 each.
-template <bool VEC, int THREADS>
+// PQ: the composed scheme Compose([Prune(), Quantize(float16)]) -- theta is rounded to binary16 and the
+// update sees its exact widening D(theta).
+template <bool VEC, int THREADS, bool PQ>
 __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
     constexpr u32 kSub = kChunk / (THREADS * 4);
     const u64 c = blockIdx.x / kSub;
@@ -95,21 +97,72 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
     const float mu = a.mu;
     float th[4], ln[4], gr[4];
     u8 m[4];
+    u16 h[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const float v = lc_shift(w[k], l[k], mu);
         const bool keep = keep_rule(mag_key(v), T, td.flat_start + e0 + k, end);
         m[k] = keep ? 1 : 0;
         th[k] = keep ? v : 0.0f;
+        if (PQ) {
+            h[k] = f32_to_f16_rne(th[k]);
+            th[k] = f16_bits_to_f32(h[k]);
+        }
         const float e = __fsub_rn(w[k], th[k]);
         const float p = __fmul_rn(mu, e);
         ln[k] = __fsub_rn(l[k], p);
         gr[k] = __fsub_rn(p, ln[k]);
     }
     if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+    if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, td.n, h);
     store4<VEC>(td.lam_out, e0, td.n, ln);
     if (td.grad) store4<VEC>(td.grad, e0, td.n, gr);
     if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+}
+
+// ---- footprint objective: number of non-zero parameters (Evaluation, Objective 1) ---------------------
+// Per-workgroup counts go to `partial`; k_sum_partials adds them up, so the result needs no atomics
+// and no cleared memory.
+template <bool F16, bool VEC>
+__global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* partial) {
+    __shared__ u64 s_wave[kBlock / 64];
+    const int tid = threadIdx.x;
+    u64 cnt = 0;
+    for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+        const int t = static_cast<int>(a.chunk_map[c]);
+        const TensorDesc& td = a.td[t];
+        const u64 base = (c - td.chunk_start) * kChunk;
+        for (int q = 0; q < kQuadsPerThread; ++q) {
+            const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+            if (e0 >= td.n) break;
+            if (F16) {
+                const u16* p = reinterpret_cast<const u16*>(td.w);
+                if (VEC && e0 + 4 <= td.n) {
+                    const ushort4 v = *reinterpret_cast<const ushort4*>(p + e0);
+                    cnt += ((v.x & 0x7FFFu) != 0) + ((v.y & 0x7FFFu) != 0) + ((v.z & 0x7FFFu) != 0) + ((v.w & 0x7FFFu) != 0);
+                } else {
+                    for (int k = 0; k < 4; ++k) if (e0 + k < td.n) cnt += (p[e0 + k] & 0x7FFFu) != 0;
+                }
+            } else {
+                float v[4];
+                load4<VEC>(td.w, e0, td.n, v);      // missing elements read as 0
+#pragma unroll
+                for (int k = 0; k < 4; ++k) cnt += mag_key(v[k]) != 0;
+            }
+        }
+    }
+    u64 total;
+    block_excl_scan_u64(cnt, s_wave, &total);
+    if (tid == 0) partial[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kBlock) void k_sum_partials(const u64* partial, u32 n, u64* out) {
+    __shared__ u64 s_wave[kBlock / 64];
+    u64 v = 0;
+    for (u32 i = threadIdx.x; i < n; i += kBlock) v += partial[i];
+    u64 total;
+    block_excl_scan_u64(v, s_wave, &total);
+    if (threadIdx.x == 0) *out = total;
 }
 
 }  // namespace condensa

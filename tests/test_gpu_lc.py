@@ -86,3 +86,38 @@ def test_errors():
     with pytest.raises(P.CondensaError) as e:          # theta must not alias w
         P.condensa_lc_step([w], [l], 1e-3, 0.5, outputs={"theta": [w]})
     assert e.value.code == -6
+
+
+# ---- composed scheme P+Q as the compression step, and the footprint objective ---------------------------
+
+def test_pq_step_against_the_oracle():
+    shapes = [(8192 * 2 + 3,), (37, 41), (0,), (16, 8, 3, 3)]
+    ws, ls = _gauss(shapes, 11, 0.01), _gauss(shapes, 12, 0.01)
+    ws[1][0, :8] = np.float32(1e-9)                     # tiny values: underflow to zero in binary16 if kept
+    for mu, d in ((1e-3, 0.1), (1e-3, 1.0), (50.0, 0.5)):
+        res = P.condensa_lc_step_pq(up(ws), up(ls), mu, d)
+        torch.cuda.synchronize()
+        ora = oracle.lc_step_pq(ws, ls, mu, d)
+        assert_select_equal(P.select_records(res["results"])[0], ora["select"], f"mu={mu} d={d}")
+        for t in range(len(ws)):
+            assert np.array_equal(res["mask"][t].cpu().numpy(), ora["mask"][t])
+            assert np.array_equal(res["theta_f16"][t].cpu().numpy().view(np.uint16), ora["theta_f16"][t]), f"theta16 {t}"
+            for name in ("theta", "lambda", "grad"):
+                assert_bits_equal(res[name][t], ora[name][t], f"{name} {t} mu={mu} d={d}")
+        nnz = int(P.condensa_count_nonzero(res["theta_f16"]).item())
+        assert nnz == oracle.count_nonzero(ora["theta_f16"])
+        nnz32 = int(P.condensa_count_nonzero(res["theta"]).item())
+        assert nnz32 == oracle.count_nonzero(ora["theta"])
+
+
+def test_count_nonzero_edge_cases():
+    x = torch.tensor([0.0, -0.0, 1e-30, -2.0, 3.0, float("nan")], device=DEV)
+    assert int(P.condensa_count_nonzero([x]).item()) == 4
+    q, _ = P.condensa_quantize(x)
+    assert int(P.condensa_count_nonzero([q]).item()) == 3
+    big = torch.ones(8192 * 5 + 7, device=DEV)
+    big[::3] = 0
+    want = int((big != 0).sum().item())
+    assert int(P.condensa_count_nonzero([big, x, torch.zeros(0, device=DEV)]).item()) == want + 4
+    assert int(P.condensa_count_nonzero([big[1:]]).item()) == int((big[1:] != 0).sum().item())   # misaligned view
+    assert int(P.condensa_count_nonzero([]).item()) == 0
