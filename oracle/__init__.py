@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
             "oracle_block_apply_nd": [vp, vp, vp, vp, vp, vp],
             "oracle_lc_shifted": [vp, vp, u64, f32, vp],
             "oracle_lc_update": [vp, vp, vp, vp, u64, f32, vp, vp, vp],
+            "oracle_thin": [vp, u64, u64, u64, vp, u64, vp, u64, vp],
             "oracle_lc_update_pq": [vp, vp, vp, vp, u64, f32, vp, vp, vp, vp],
         }.items():
             fn = getattr(L, name)
@@ -376,3 +377,20 @@ def count_nonzero(tensors: Sequence[np.ndarray]) -> int:
         else:
             raise TypeError("float32 values or uint16 binary16 patterns")
     return total
+
+
+def thin(t: np.ndarray, keep_out=None, keep_in=None) -> np.ndarray:
+    """Network thinning of one [Cout, Cin, ...] tensor: keep the listed output structures (filters /
+    neurons) and the listed input channels, in list order, as a dense smaller tensor."""
+    t = _f32(t)
+    c_out, c_in = t.shape[0], t.shape[1]
+    ksize = t.size // (c_out * c_in) if c_out * c_in else 0
+    ko = None if keep_out is None else np.ascontiguousarray(keep_out, dtype=np.int32)
+    ki = None if keep_in is None else np.ascontiguousarray(keep_in, dtype=np.int32)
+    n_out = c_out if ko is None else ko.size
+    n_in = c_in if ki is None else ki.size
+    out = np.empty((n_out, n_in) + t.shape[2:], np.float32)
+    if out.size:
+        lib().oracle_thin(_p(t), c_out, c_in, ksize, None if ko is None else _p(ko), n_out,
+                          None if ki is None else _p(ki), n_in, _p(out))
+    return out

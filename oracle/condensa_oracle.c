@@ -361,3 +361,19 @@ uint64_t oracle_count_nonzero_f16(const uint16_t* x, uint64_t n)
     for (uint64_t i = 0; i < n; ++i) c += (x[i] & 0x7FFFu) != 0u;
     return c;
 }
+
+/* ---- thinning: physically remove zero structures (Section 3.4, "Network Thinning", final phase) ----
+ * out[o', i', r] = w[keep_out[o'], keep_in[i'], r] for a tensor viewed as [Cout, Cin, kh*kw];
+ * a NULL list keeps every index of that dimension. */
+void oracle_thin(const float* w, uint64_t c_out, uint64_t c_in, uint64_t ksize,
+                 const int32_t* keep_out, uint64_t n_out, const int32_t* keep_in, uint64_t n_in, float* out)
+{
+    (void)c_out;
+    for (uint64_t o = 0; o < n_out; ++o)
+        for (uint64_t i = 0; i < n_in; ++i)
+            for (uint64_t r = 0; r < ksize; ++r) {
+                const uint64_t so = keep_out ? (uint64_t)keep_out[o] : o;
+                const uint64_t si = keep_in ? (uint64_t)keep_in[i] : i;
+                out[(o * n_in + i) * ksize + r] = w[(so * c_in + si) * ksize + r];
+            }
+}
