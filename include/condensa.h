@@ -270,6 +270,23 @@ condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_ten
                                        uint64_t* count_dev,
                                        void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/*
+ * Network thinning, final phase (Section 3.4): physically remove the zero structures that structure
+ * pruning left, given the lists of what to keep.  The tensor [Cout, Cin, ...] (ndim 2..4, `shape` is a
+ * HOST array) is gathered into the dense [n_out, n_in, ...] tensor
+ *      out[o, i, ...] = w[keep_out[o] - keep_out_offset, keep_in[i] - keep_in_offset, ...].
+ * keep_out_dev / keep_in_dev are DEVICE arrays of ids (for example slices of the keep_idx output of
+ * the structure-pruning calls, whose ids run over the whole call: pass the tensor's first id as the
+ * offset); a NULL list keeps the whole dimension.  The dependency analysis that decides which
+ * successor loses which input channels is the caller's (the paper's graph phases are not part of this
+ * library).  An id that falls outside the tensor yields zeros, never an out-of-bounds read.
+ * out_dev must hold n_out * n_in * prod(shape[2:]) floats and must not alias w_dev.
+ */
+condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim,
+                              const int32_t* keep_out_dev, int64_t n_keep_out, int64_t keep_out_offset,
+                              const int32_t* keep_in_dev, int64_t n_keep_in, int64_t keep_in_offset,
+                              float* out_dev, void* stream);
+
 /* ---- tuning / test knobs (process wide; not needed for normal use) ---------------------------- */
 enum {
     CONDENSA_OPT_SELECT_PATH   = 0, /* 0 auto, 1 radix levels over the data only, 2 sampled window even for small N */

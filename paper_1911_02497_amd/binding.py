@@ -73,6 +73,9 @@ _PROTOTYPES = {
                                              ctypes.c_size_t, ctypes.c_void_p]),
     "condensa_count_nonzero": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_thin": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_void_p,
+                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_void_p, ctypes.c_void_p]),
     "condensa_set_option": (ctypes.c_int32, [ctypes.c_int, ctypes.c_int64]),
     "condensa_get_option": (ctypes.c_int64, [ctypes.c_int]),
     "condensa_profile_read": (ctypes.c_int32, [ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -379,3 +382,27 @@ def condensa_count_nonzero(tensors, workspace=None, stream=None):
     ws, need = _workspace(OP_COUNT_NONZERO, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
     _check(lib.condensa_count_nonzero(arr, nt, is_f16, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
     return count
+
+
+def condensa_thin(w, keep_out=None, keep_in=None, keep_out_offset=0, keep_in_offset=0, stream=None):
+    """Marshals condensa_thin: ``keep_out`` / ``keep_in`` are device int32 id tensors or None (keep all)."""
+    import torch
+    lib = library()
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and 2 <= w.dim() <= 4):
+        raise TypeError("w must be a contiguous float32 device tensor with 2 to 4 dimensions")
+    for k in (keep_out, keep_in):
+        if k is not None and not (k.is_cuda and k.dtype == torch.int32 and k.is_contiguous() and k.dim() == 1):
+            raise TypeError("keep lists are contiguous 1-D int32 device tensors")
+    n_out = w.shape[0] if keep_out is None else keep_out.numel()
+    n_in = w.shape[1] if keep_in is None else keep_in.numel()
+    out = torch.empty((n_out, n_in) + tuple(w.shape[2:]), dtype=torch.float32, device=w.device)
+    if out.numel() == 0:                     # an empty keep list: nothing to gather (NULL would mean "keep all")
+        return out
+    shape = (ctypes.c_int64 * 4)(*list(w.shape) + [1] * (4 - w.dim()))
+    _check(lib.condensa_thin(w.data_ptr() if w.numel() else None, shape, w.dim(),
+                             None if keep_out is None else (keep_out.data_ptr() if keep_out.numel() else None),
+                             0 if keep_out is None else keep_out.numel(), int(keep_out_offset),
+                             None if keep_in is None else (keep_in.data_ptr() if keep_in.numel() else None),
+                             0 if keep_in is None else keep_in.numel(), int(keep_in_offset),
+                             out.data_ptr() if out.numel() else None, _stream(stream)))
+    return out

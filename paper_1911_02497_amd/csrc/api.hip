@@ -864,6 +864,35 @@ condensa_status condensa_profile_reset(void) {
     return CONDENSA_OK;
 }
 
+condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim, const int32_t* keep_out_dev,
+                              int64_t n_keep_out, int64_t keep_out_offset, const int32_t* keep_in_dev,
+                              int64_t n_keep_in, int64_t keep_in_offset, float* out_dev, void* stream) {
+    if (shape == nullptr) return CONDENSA_ERR_NULL;
+    if (ndim < 2 || ndim > 4) return CONDENSA_ERR_SHAPE;
+    u64 ksize = 1;
+    for (int i = 0; i < ndim; ++i) {
+        if (shape[i] < 0 || shape[i] > 0x7FFFFFFFll) return CONDENSA_ERR_SHAPE;
+        if (i >= 2) ksize *= static_cast<u64>(shape[i]);
+    }
+    const u64 c_out = static_cast<u64>(shape[0]), c_in = static_cast<u64>(shape[1]);
+    if (n_keep_out < 0 || n_keep_in < 0) return CONDENSA_ERR_SIZE;
+    const u64 n_out = keep_out_dev ? static_cast<u64>(n_keep_out) : c_out;
+    const u64 n_in = keep_in_dev ? static_cast<u64>(n_keep_in) : c_in;
+    if (n_out > 0x7FFFFFFFull || n_in > 0x7FFFFFFFull || ksize > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
+    const u64 total = n_out * n_in * ksize;
+    if (total > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (total == 0) return CONDENSA_OK;
+    if (w_dev == nullptr || out_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (static_cast<const void*>(w_dev) == static_cast<const void*>(out_dev)) return CONDENSA_ERR_ARG;
+    u64 blocks = (total + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(k_thin, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
+                       w_dev, c_out, c_in, ksize, keep_out_dev, n_out, keep_out_offset, keep_in_dev, n_in,
+                       keep_in_offset, out_dev);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
 condensa_status condensa_set_option(int option, int64_t value) {
     if (option < 0 || option >= CONDENSA_OPT_COUNT) return CONDENSA_ERR_ARG;
     if (value < 0) return CONDENSA_ERR_ARG;

@@ -359,4 +359,27 @@ __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const Out
     if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
 }
 
+// Thinning gather: out[o', i', r] = w[keep_out[o'] - off_out, keep_in[i'] - off_in, r]; NULL list = identity.
+// An id outside the tensor writes +0 instead of reading out of bounds.
+__global__ __launch_bounds__(kBlock) void k_thin(const float* __restrict__ w, u64 c_out, u64 c_in, u64 ksize,
+                                                 const int32_t* __restrict__ keep_out, u64 n_out, int64_t off_out,
+                                                 const int32_t* __restrict__ keep_in, u64 n_in, int64_t off_in,
+                                                 float* __restrict__ out) {
+    const u64 total = n_out * n_in * ksize;
+    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
+    const u64 per_out = n_in * ksize;
+    for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x; i < total; i += stride) {
+        const u64 o = i / per_out;
+        const u64 rem = i - o * per_out;
+        const u64 ic = rem / ksize;
+        const u64 r = rem - ic * ksize;
+        const int64_t so = keep_out ? static_cast<int64_t>(keep_out[o]) - off_out : static_cast<int64_t>(o);
+        const int64_t si = keep_in ? static_cast<int64_t>(keep_in[ic]) - off_in : static_cast<int64_t>(ic);
+        float v = 0.0f;
+        if (so >= 0 && static_cast<u64>(so) < c_out && si >= 0 && static_cast<u64>(si) < c_in)
+            v = w[(static_cast<u64>(so) * c_in + static_cast<u64>(si)) * ksize + r];
+        out[i] = v;
+    }
+}
+
 }  // namespace condensa
