@@ -182,7 +182,7 @@ static condensa_status build_tensor_table(const condensa_tensor* tensors, int n_
         d.flat_start = flat;
         d.chunk_start = chunk;
         flat += n;
-        if (flat > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+        if (flat > kMaxElems) return CONDENSA_ERR_SIZE;
         chunk += (n + kChunk - 1) / kChunk;
         if (n > 0 && !aligned16(d.w)) tb->vec = false;
     }
@@ -299,7 +299,7 @@ size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structu
     if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
     if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
     if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return 0;
-    if (total_elems > (static_cast<u64>(1) << 40) || n_structures > total_elems) return 0;
+    if (total_elems > kMaxElems || n_structures > total_elems) return 0;
     return make_layout(op, total_elems, n_structures, n_tensors, n_densities, scope).total;
 }
 
@@ -804,7 +804,7 @@ condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_te
 extern "C" {
 
 condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
-    if (n > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (n > kMaxElems) return CONDENSA_ERR_SIZE;
     if (n == 0) return CONDENSA_OK;
     if (q_dev == nullptr && dq_dev == nullptr) return CONDENSA_ERR_NULL;
     if (x_dev == nullptr) return CONDENSA_ERR_NULL;
@@ -820,7 +820,7 @@ condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_de
 }
 
 condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
-    if (n > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (n > kMaxElems) return CONDENSA_ERR_SIZE;
     if (n == 0) return CONDENSA_OK;
     if (dq_dev == nullptr || q_dev == nullptr) return CONDENSA_ERR_NULL;
     const bool vec = aligned16(dq_dev) && (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0;
@@ -880,7 +880,7 @@ condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim
     const u64 n_in = keep_in_dev ? static_cast<u64>(n_keep_in) : c_in;
     if (n_out > 0x7FFFFFFFull || n_in > 0x7FFFFFFFull || ksize > 0x7FFFFFFFull) return CONDENSA_ERR_SIZE;
     const u64 total = n_out * n_in * ksize;
-    if (total > (static_cast<u64>(1) << 40)) return CONDENSA_ERR_SIZE;
+    if (total > kMaxElems) return CONDENSA_ERR_SIZE;
     if (total == 0) return CONDENSA_OK;
     if (w_dev == nullptr || out_dev == nullptr) return CONDENSA_ERR_NULL;
     if (static_cast<const void*>(w_dev) == static_cast<const void*>(out_dev)) return CONDENSA_ERR_ARG;

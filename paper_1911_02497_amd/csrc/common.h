@@ -19,6 +19,7 @@ constexpr int kChunk = 8192;           // elements of one tensor handled as a un
 constexpr int kQuadsPerThread = kChunk / (kBlock * 4);   // 8 float4 per thread and chunk
 constexpr int kMaxJ = CONDENSA_MAX_DENSITIES;
 constexpr int kBins = 2048;            // bins of one radix level (digits are at most 11 bits)
+constexpr u64 kMaxElems = static_cast<u64>(1) << 36;   // elements per call (keeps every grid below 2^31 workgroups)
 constexpr int kSlotBatch = 8;          // rankings that share one sweep's LDS histograms
 
 // One weight tensor as the kernels see it (device table, one entry per tensor plus a sentinel).
