@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
             "oracle_block_apply_nd": [vp, vp, vp, vp, vp, vp],
             "oracle_lc_shifted": [vp, vp, u64, f32, vp],
             "oracle_lc_update": [vp, vp, vp, vp, u64, f32, vp, vp, vp],
+            "oracle_lc_sgd_step": [vp, vp, vp, vp, vp, u64, f32, f32, f32, vp, vp],
             "oracle_thin": [vp, u64, u64, u64, vp, u64, vp, u64, vp],
             "oracle_lc_update_pq": [vp, vp, vp, vp, u64, f32, vp, vp, vp, vp],
         }.items():
@@ -394,3 +395,22 @@ def thin(t: np.ndarray, keep_out=None, keep_in=None) -> np.ndarray:
         lib().oracle_thin(_p(t), c_out, c_in, ksize, None if ko is None else _p(ko), n_out,
                           None if ki is None else _p(ki), n_in, _p(out))
     return out
+
+
+def lc_sgd_step(ws, grads, thetas, lambdas, bufs, mu: float, lr: float, momentum: float):
+    """One SGD-with-momentum update of the learning step with the L-C penalty gradient folded in.
+    Returns (new weights, new momentum buffers) as lists."""
+    w_out, b_out = [], []
+    for w, g, th, lam, b in zip(ws, grads, thetas, lambdas, bufs):
+        w, g, th, lam, b = (_f32(x) for x in (w, g, th, lam, b))
+        wn, bn = np.empty_like(w), np.empty_like(w)
+        lib().oracle_lc_sgd_step(_p(w), _p(g), _p(th), _p(lam), _p(b), w.size, float(np.float32(mu)),
+                                 float(np.float32(lr)), float(np.float32(momentum)), _p(wn), _p(bn))
+        w_out.append(wn)
+        b_out.append(bn)
+    return w_out, b_out
+
+
+def mu_schedule(mu0: float, a: float, j: int) -> float:
+    """mu_j = mu_0 a^j ("L-C Optimizer Settings": mu_0 = 1e-3, a = 1.1), evaluated in binary64, returned as binary32."""
+    return float(np.float32(float(mu0) * float(a) ** int(j)))

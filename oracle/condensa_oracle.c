@@ -377,3 +377,25 @@ void oracle_thin(const float* w, uint64_t c_out, uint64_t c_in, uint64_t ksize,
                 out[(o * n_in + i) * ksize + r] = w[(so * c_in + si) * ksize + r];
             }
 }
+
+/* ---- learning-step update with the L-C penalty folded in (Section 3.3: the L step trains w with a
+ * quadratic regularisation term; "L-C Optimizer Settings": SGD with momentum 0.9) ------------------
+ * gradient of  L(w) + mu/2 ||w - theta - lambda/mu||^2  is  grad L + mu (w - theta) - lambda;
+ * momentum update  buf' = m buf + g;  w' = w - lr buf'.  binary32, one rounding per operation. */
+void oracle_lc_sgd_step(const float* w, const float* grad_loss, const float* theta, const float* lambda,
+                        const float* buf, uint64_t n, float mu, float lr, float momentum,
+                        float* w_out, float* buf_out)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        volatile float t1 = w[i] - theta[i];
+        volatile float t2 = mu * t1;
+        volatile float t3 = grad_loss[i] + t2;
+        volatile float t4 = t3 - lambda[i];
+        volatile float t5 = momentum * buf[i];
+        volatile float b = t5 + t4;
+        volatile float t6 = lr * b;
+        volatile float wn = w[i] - t6;
+        buf_out[i] = b;
+        w_out[i] = wn;
+    }
+}

@@ -134,3 +134,48 @@ def test_footprint_counts_nonzeros_and_reproduces_the_two_times_of_pq():
     nnz = oracle.count_nonzero(res["theta_f16"])
     assert nnz == res["select"]["k"] == 1000
     assert 4 * w.size / (2 * nnz) == 2 / 0.05                      # r_c = 2 / (1 - s)
+
+
+# ---- learning-step update with the penalty folded in ("L-C Optimizer Settings": SGD, momentum 0.9) ----
+
+def _sgd_case(n=3000, seed=20):
+    rng = np.random.default_rng(seed)
+    f = lambda s: (rng.standard_normal(n) * s).astype(np.float32)  # noqa: E731
+    return f(0.01), f(1e-3), f(0.01), f(0.01), f(1e-3)            # w, grad L, theta, lambda, momentum buffer
+
+
+def test_sgd_step_matches_numpy_float32():
+    w, g, th, lam, buf = _sgd_case()
+    mu, lr, m = np.float32(1e-3), np.float32(0.1), np.float32(0.9)
+    (wn,), (bn,) = oracle.lc_sgd_step([w], [g], [th], [lam], [buf], mu, lr, m)
+    grad = ((g + mu * (w - th)) - lam)
+    b = m * buf + grad
+    assert np.array_equal(bn.view(np.uint32), b.view(np.uint32))
+    assert np.array_equal(wn.view(np.uint32), (w - lr * b).view(np.uint32))
+
+
+def test_sgd_step_against_torch_sgd_with_the_penalty_gradient():
+    import torch
+    w, g, th, lam, buf = _sgd_case(seed=21)
+    mu, lr, m = 1e-3, 0.1, 0.9
+    (wn,), (bn,) = oracle.lc_sgd_step([w], [g], [th], [lam], [buf], mu, lr, m)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.SGD([p], lr=lr, momentum=m)
+    opt.state[p]["momentum_buffer"] = torch.from_numpy(buf.copy())
+    p.grad = torch.from_numpy(g) + np.float32(mu) * (p.detach() - torch.from_numpy(th)) - torch.from_numpy(lam)
+    opt.step()
+    assert np.allclose(p.detach().numpy(), wn, rtol=0, atol=2e-9)       # torch may fuse w + (-lr) * buf
+    assert np.allclose(opt.state[p]["momentum_buffer"].numpy(), bn, rtol=0, atol=2e-10)
+    # without the penalty terms the update would differ by ~ lr * |lambda| ~ 1e-3
+    (w_plain,), _ = oracle.lc_sgd_step([w], [g], [w], [np.zeros_like(w)], [buf], mu, lr, m)
+    assert np.abs(w_plain - wn).max() > 1e-4
+
+
+def test_penalty_vanishes_at_the_constraint_and_mu_schedule():
+    w, g, _, _, buf = _sgd_case(seed=22)
+    (wn,), (bn,) = oracle.lc_sgd_step([w], [g], [w], [np.zeros_like(w)], [buf], 1e-3, 0.1, 0.9)
+    b = np.float32(0.9) * buf + g
+    assert np.array_equal(bn, b) and np.array_equal(wn, w - np.float32(0.1) * b)
+    assert oracle.mu_schedule(1e-3, 1.1, 0) == float(np.float32(1e-3))
+    assert abs(oracle.mu_schedule(1e-3, 1.1, 49) - 1e-3 * 1.1 ** 49) < 1e-9
+    assert oracle.mu_schedule(1e-3, 1.1, 10) < oracle.mu_schedule(1e-3, 1.1, 11)
