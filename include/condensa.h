@@ -65,7 +65,8 @@ enum { CONDENSA_OP_PRUNE = 0,        /* condensa_prune                          
        CONDENSA_OP_BLOCK_PRUNE = 2,  /* condensa_block_prune, _block_prune_nd                         */
        CONDENSA_OP_QUANTIZE = 3,
        CONDENSA_OP_LC_STEP = 4,      /* condensa_lc_step, _lc_step_pq                                 */
-       CONDENSA_OP_COUNT_NONZERO = 5 };
+       CONDENSA_OP_COUNT_NONZERO = 5,
+       CONDENSA_OP_LC_SGD_STEP = 6 };
 
 #define CONDENSA_MAX_DENSITIES 16
 #define CONDENSA_MAX_TENSORS   65536
@@ -270,6 +271,26 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
 condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int is_f16,
                                        uint64_t* count_dev,
                                        void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/*
+ * One SGD-with-momentum update of the learning (L) step with the L-C penalty folded in (Section 3.3:
+ * the L step "trains the uncompressed model but with a quadratic regularization term"; "L-C Optimizer
+ * Settings": SGD, momentum 0.9).  The gradient of L(w) + mu/2 ||w - theta - lambda/mu||^2 is
+ * grad L + mu (w - theta) - lambda, so the separate penalty-gradient buffer of condensa_lc_step is not
+ * needed.  Per element, binary32, one rounding per operation, no fused multiply-add:
+ *      g = (grad_loss + mu * (w - theta)) - lambda;   buf = momentum * buf + g;   w = w - lr * buf.
+ * `w` of every tensor in the table and momentum_buf are UPDATED IN PLACE; grad_loss, theta, lambda are
+ * host tables [n_tensors] of device inputs shaped like the weights.  The five buffers of a tensor
+ * must be distinct.  Workspace: condensa_workspace_bytes(CONDENSA_OP_LC_SGD_STEP, ...).
+ */
+condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tensors,
+                                     const float* const* grad_loss, const float* const* theta,
+                                     const float* const* lambda, float* const* momentum_buf,
+                                     float mu, float lr, float momentum,
+                                     void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* mu_j = mu_0 * a^j ("L-C Optimizer Settings": mu_0 = 1e-3, a = 1.1), evaluated in binary64 (host). */
+float condensa_mu_schedule(double mu0, double a, int j);
 
 /*
  * Network thinning, final phase (Section 3.4): physically remove the zero structures that structure

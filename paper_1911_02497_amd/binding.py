@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libcondensa.so")
 
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
-OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP, OP_COUNT_NONZERO = range(6)
+OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP, OP_COUNT_NONZERO, OP_LC_SGD_STEP = range(7)
 OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE, OPT_APPLY_THREADS = range(6)
 PHASES = ("sample", "sweep", "resolve", "apply", "aggregate")
 MAX_DENSITIES = 16
@@ -73,6 +73,10 @@ _PROTOTYPES = {
                                              ctypes.c_size_t, ctypes.c_void_p]),
     "condensa_count_nonzero": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_lc_sgd_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "condensa_mu_schedule": (ctypes.c_float, [ctypes.c_double, ctypes.c_double, ctypes.c_int]),
     "condensa_thin": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_void_p,
                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                        ctypes.c_void_p, ctypes.c_void_p]),
@@ -406,3 +410,25 @@ def condensa_thin(w, keep_out=None, keep_in=None, keep_out_offset=0, keep_in_off
                              0 if keep_in is None else keep_in.numel(), int(keep_in_offset),
                              out.data_ptr() if out.numel() else None, _stream(stream)))
     return out
+
+
+def condensa_lc_sgd_step(tensors, grad_loss, theta, lambdas, momentum_buf, mu, lr, momentum, workspace=None, stream=None):
+    """Marshals condensa_lc_sgd_step: ``tensors`` (weights) and ``momentum_buf`` are updated in place."""
+    import torch
+    lib = library()
+    dev = tensors[0].device if tensors else torch.device("cuda")
+    nt = len(tensors)
+    tab = _tensor_table(tensors)
+    total = sum(t.numel() for t in tensors)
+    k1, p1 = _ptr_table(grad_loss)
+    k2, p2 = _ptr_table(theta)
+    k3, p3 = _ptr_table(lambdas)
+    k4, p4 = _ptr_table(momentum_buf)
+    ws, need = _workspace(OP_LC_SGD_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
+    _check(lib.condensa_lc_sgd_step(tab, nt, p1, p2, p3, p4, float(mu), float(lr), float(momentum), ws.data_ptr(),
+                                    ws.numel(), _stream(stream)))
+    return ws
+
+
+def condensa_mu_schedule(mu0: float, a: float, j: int) -> float:
+    return float(library().condensa_mu_schedule(float(mu0), float(a), int(j)))

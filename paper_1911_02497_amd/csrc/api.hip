@@ -142,13 +142,13 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (1 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
-    const u64 tie_chunks = structure ? L.max_schunks : (op == CONDENSA_OP_COUNT_NONZERO ? 0 : L.max_chunks);
+    const u64 tie_chunks = structure ? L.max_schunks : ((op == CONDENSA_OP_COUNT_NONZERO || op == CONDENSA_OP_LC_SGD_STEP) ? 0 : L.max_chunks);
     L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
     if (structure) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
         L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
-    } else if (!per_tensor && op != CONDENSA_OP_COUNT_NONZERO) {
+    } else if (!per_tensor && op != CONDENSA_OP_COUNT_NONZERO && op != CONDENSA_OP_LC_SGD_STEP) {
         L.sample_cap = window_sample_size(N);
         L.cand_cap = window_cand_capacity(N, J);
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
@@ -294,7 +294,7 @@ extern "C" {
 
 size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures, int n_tensors,
                                 int n_densities, int scope) {
-    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_COUNT_NONZERO) return 0;
+    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_LC_SGD_STEP) return 0;
     if (op == CONDENSA_OP_QUANTIZE) return 0;
     if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
     if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
@@ -863,6 +863,64 @@ condensa_status condensa_profile_reset(void) {
     for (int i = 0; i < CONDENSA_PHASE_COUNT; ++i) { g_phase_ms[i] = 0.0; g_phase_n[i] = 0; }
     return CONDENSA_OK;
 }
+
+condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tensors, const float* const* grad_loss,
+                                     const float* const* theta, const float* const* lambda,
+                                     float* const* momentum_buf, float mu, float lr, float momentum,
+                                     void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (n_tensors > 0 && (!grad_loss || !theta || !lambda || !momentum_buf)) return CONDENSA_ERR_NULL;
+    if (!(mu >= 0.0f) || !std::isfinite(mu) || !std::isfinite(lr) || !std::isfinite(momentum)) return CONDENSA_ERR_DENSITY;
+    Tables tb;
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_LC_SGD_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+    std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    bool vec = tb.vec;
+    for (int t = 0; t < n_tensors; ++t) {
+        TensorDesc& d = tb.td[t];
+        if (d.n == 0) continue;
+        if (!grad_loss[t] || !theta[t] || !lambda[t] || !momentum_buf[t]) return CONDENSA_ERR_NULL;
+        d.grad = const_cast<float*>(grad_loss[t]);
+        d.lam = lambda[t];
+        d.lam_out = momentum_buf[t];
+        out[t].theta = const_cast<float*>(theta[t]);
+        const void* ptrs[5] = {d.w, d.grad, d.lam, d.lam_out, out[t].theta};
+        for (int i = 0; i < 5; ++i) {
+            if (!aligned16(ptrs[i])) vec = false;
+            for (int j = i + 1; j < 5; ++j)
+                if (ptrs[i] == ptrs[j]) return CONDENSA_ERR_ARG;       // five distinct buffers
+        }
+    }
+    std::vector<char> up(L.upload_bytes, 0);
+    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    if (rc != CONDENSA_OK) return rc;
+    hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
+                       at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
+                       at<TensorDesc>(workspace_dev, L.td), n_tensors, at<u32>(workspace_dev, L.chunk_map), tb.n_chunks);
+    CONDENSA_LAUNCH_CHECK();
+    if (tb.n_chunks == 0) return CONDENSA_OK;
+    DataArgs a{};
+    a.td = at<TensorDesc>(workspace_dev, L.td);
+    a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
+    a.n_chunks = tb.n_chunks;
+    a.N = tb.N;
+    a.n_tensors = n_tensors;
+    a.mu = mu;
+    PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+    const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+    const unsigned grid = static_cast<unsigned>(tb.n_chunks * (kChunk / 256));
+    if (vec) hipLaunchKernelGGL((k_lc_sgd<true>), dim3(grid), dim3(64), 0, st, a, od, lr, momentum);
+    else     hipLaunchKernelGGL((k_lc_sgd<false>), dim3(grid), dim3(64), 0, st, a, od, lr, momentum);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+float condensa_mu_schedule(double mu0, double a, int j) { return static_cast<float>(mu0 * std::pow(a, static_cast<double>(j))); }
 
 condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim, const int32_t* keep_out_dev,
                               int64_t n_keep_out, int64_t keep_out_offset, const int32_t* keep_in_dev,

@@ -120,6 +120,41 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
     if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
 }
 
+// ---- learning-step update with the penalty gradient folded in -----------------------------------------
+// g = grad L + mu (w - theta) - lambda;  buf' = m buf + g;  w' = w - lr buf'   (binary32, one rounding per
+// operation).  Table roles: td.w = weights (updated in place), td.grad = grad L, td.lam = lambda,
+// td.lam_out = momentum buffer (updated in place), out[t].theta = theta.
+template <bool VEC>
+__global__ __launch_bounds__(64) void k_lc_sgd(DataArgs a, const OutDesc* __restrict__ out, float lr, float momentum) {
+    constexpr u32 kSub = kChunk / 256;
+    const u64 c = blockIdx.x / kSub;
+    const u32 sub = blockIdx.x % kSub;
+    if (c >= a.n_chunks) return;
+    const int t = static_cast<int>(a.chunk_map[c]);
+    const TensorDesc& td = a.td[t];
+    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * 256 + threadIdx.x * 4;
+    if (e0 >= td.n) return;
+    float w[4], g[4], th[4], l[4], b[4];
+    load4<VEC>(td.w, e0, td.n, w);
+    load4<VEC>(td.grad, e0, td.n, g);
+    load4<VEC>(out[t].theta, e0, td.n, th);
+    load4<VEC>(td.lam, e0, td.n, l);
+    load4<VEC>(td.lam_out, e0, td.n, b);
+    float wn[4], bn[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float t1 = __fsub_rn(w[k], th[k]);
+        const float t2 = __fmul_rn(a.mu, t1);
+        const float t3 = __fadd_rn(g[k], t2);
+        const float t4 = __fsub_rn(t3, l[k]);
+        const float t5 = __fmul_rn(momentum, b[k]);
+        bn[k] = __fadd_rn(t5, t4);
+        wn[k] = __fsub_rn(w[k], __fmul_rn(lr, bn[k]));
+    }
+    store4<VEC>(td.lam_out, e0, td.n, bn);
+    store4<VEC>(const_cast<float*>(td.w), e0, td.n, wn);
+}
+
 // ---- footprint objective: number of non-zero parameters (Evaluation, Objective 1) ---------------------
 // Per-workgroup counts go to `partial`; k_sum_partials adds them up, so the result needs no atomics
 // and no cleared memory.

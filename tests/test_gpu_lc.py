@@ -121,3 +121,36 @@ def test_count_nonzero_edge_cases():
     assert int(P.condensa_count_nonzero([big, x, torch.zeros(0, device=DEV)]).item()) == want + 4
     assert int(P.condensa_count_nonzero([big[1:]]).item()) == int((big[1:] != 0).sum().item())   # misaligned view
     assert int(P.condensa_count_nonzero([]).item()) == 0
+
+
+# ---- learning-step update with the penalty folded in ----------------------------------------------------
+
+def test_sgd_step_with_penalty_against_the_oracle():
+    shapes = [(8192 + 77,), (64, 32, 3, 3), (0,), (10, 512)]
+    rng = np.random.default_rng(60)
+    mk = lambda s: [(rng.standard_normal(sh) * s).astype(np.float32) for sh in shapes]  # noqa: E731
+    ws, gs, ths, ls, bs = mk(0.01), mk(1e-3), mk(0.01), mk(0.01), mk(1e-3)
+    for j in (0, 7):
+        mu = P.condensa_mu_schedule(1e-3, 1.1, j)
+        assert mu == oracle.mu_schedule(1e-3, 1.1, j)
+        dw, db = up(ws), up(bs)
+        P.condensa_lc_sgd_step(dw, up(gs), up(ths), up(ls), db, mu, 0.1, 0.9)
+        torch.cuda.synchronize()
+        w_ora, b_ora = oracle.lc_sgd_step(ws, gs, ths, ls, bs, mu, 0.1, 0.9)
+        for t in range(len(ws)):
+            assert_bits_equal(dw[t], w_ora[t], f"w {t}")
+            assert_bits_equal(db[t], b_ora[t], f"buf {t}")
+    # the fused update equals the unfused one: penalty gradient from condensa_lc_step, then a plain momentum step
+    res = P.condensa_lc_step(up(ws), up(ls), 1e-3, 0.2)
+    torch.cuda.synchronize()
+    theta = [t.cpu().numpy() for t in res["theta"]]
+    lam2 = [t.cpu().numpy() for t in res["lambda"]]
+    w_f, b_f = oracle.lc_sgd_step(ws, gs, theta, lam2, bs, 1e-3, 0.1, 0.9)
+    for t in range(len(ws)):
+        g_pen = res["grad"][t].cpu().numpy()                       # mu (w - theta) - lambda'
+        b = np.float32(0.9) * bs[t] + (gs[t] + g_pen)
+        assert np.allclose(b, b_f[t], rtol=0, atol=2e-8) and np.allclose(ws[t] - np.float32(0.1) * b, w_f[t], rtol=0, atol=2e-8)
+    w = torch.ones(8, device=DEV)
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_lc_sgd_step([w], [w], [torch.zeros(8, device=DEV)], [torch.zeros(8, device=DEV)], [torch.zeros(8, device=DEV)], 1e-3, 0.1, 0.9)
+    assert e.value.code == -6
