@@ -137,9 +137,9 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
     L.ctl = off;    off += align_up(sizeof(Control));
     L.hist0 = off;  off += align_up(static_cast<size_t>(L.n_groups) * kBins * sizeof(u64));
     // later-level histograms: one per ranking, and room for the 2J window-boundary rankings
-    const size_t n_hx = static_cast<size_t>(L.n_slots) + 2u * kMaxJ;
+    const size_t n_hx = static_cast<size_t>(L.n_slots) + 2u * kMaxJ + 1u;    // + the shared level-0 histogram of the sample
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
-    if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (1 + kMaxJ) * sizeof(u64)); }
+    if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (2 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
     const u64 tie_chunks = structure ? L.max_schunks : ((op == CONDENSA_OP_COUNT_NONZERO || op == CONDENSA_OP_LC_SGD_STEP) ? 0 : L.max_chunks);
@@ -238,7 +238,9 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
         const u64 cpb = (a.n_chunks + blocks - 1) / blocks;
         blocks = (a.n_chunks + cpb - 1) / cpb;
         for (int level = 0; level < n_levels(31); ++level) {
-            hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
+            const int nj = a.J < kSlotBatch ? a.J : kSlotBatch;
+            const size_t lds = static_cast<size_t>(level == 0 ? kBins : nj * (1 << level_of(31, level).bits)) * sizeof(u32);
+            hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_scan_level, dim3(n_slots), dim3(kBlock), 0, st, a.slots, a.hist0, a.histx, a.J, 31,
                                level, a.ctl, a.only_failed, &a.ctl->need_tie);
@@ -276,12 +278,15 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
     return launch_ties_and_results<LC, VEC>(a, n_slots, n_groups, results, st);
 }
 
-static bool want_window(u64 N, bool per_tensor) {
+// Sampled window or radix levels?  Measured crossover (one MI355X): the radix levels cost one sweep per
+// level but little fixed work; the window path costs ~0.1-0.3 ms of small kernels and one sweep.  The
+// break-even sits near N x densities x input streams = 2^27.
+static bool want_window(u64 N, bool per_tensor, int J, bool lc) {
     if (per_tensor) return false;
     const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;
-    return N >= (static_cast<u64>(1) << 25);   // measured crossover against the radix levels: 2^25 .. 2^26 weights
+    return N * static_cast<u64>(J) * (lc ? 2u : 1u) >= (static_cast<u64>(1) << 27);
 }
 
 }  // namespace condensa
@@ -342,7 +347,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
             if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
         }
 
-    const bool window = want_window(tb.N, per_tensor);
+    const bool window = want_window(tb.N, per_tensor, J, false);
     std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
     for (int g = 0; g < L.n_groups; ++g)
         for (int j = 0; j < J; ++j) {
@@ -439,7 +444,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
         if (o.theta16 && (reinterpret_cast<uintptr_t>(o.theta16) & 7u)) vec = false;
     }
-    const bool window = want_window(tb.N, false);
+    const bool window = want_window(tb.N, false, 1, true);
     Slot slot;
     init_slot(&slot, tb.N, kept_count(density, tb.N), window ? 2u : 1u);
 

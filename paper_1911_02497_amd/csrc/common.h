@@ -20,7 +20,7 @@ constexpr int kQuadsPerThread = kChunk / (kBlock * 4);   // 8 float4 per thread 
 constexpr int kMaxJ = CONDENSA_MAX_DENSITIES;
 constexpr int kBins = 2048;            // bins of one radix level (digits are at most 11 bits)
 constexpr u64 kMaxElems = static_cast<u64>(1) << 36;   // elements per call (keeps every grid below 2^31 workgroups)
-constexpr int kSlotBatch = 8;          // rankings that share one sweep's LDS histograms
+constexpr int kSlotBatch = 15;         // rankings that share one sweep's LDS histograms (15 x 1024 bins x 4 B < 64 KB)
 
 // One weight tensor as the kernels see it (device table, one entry per tensor plus a sentinel).
 struct TensorDesc {

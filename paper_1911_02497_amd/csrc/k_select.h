@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kBlock) void k_prepare(u64* zero, u64 n_words, cons
 // keep one histogram per ranking, kSlotBatch rankings per sweep of the range.
 template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64 chunks_per_block) {
-    __shared__ u32 s_hist[kSlotBatch * 1024 > kBins ? kSlotBatch * 1024 : kBins];
+    extern __shared__ u32 s_hist[];       // level 0: kBins words; later levels: min(J, kSlotBatch) x 1024 words
     __shared__ u32 s_prefix[kSlotBatch];
     __shared__ u32 s_active[kSlotBatch];
     __shared__ u32 s_any;

@@ -16,7 +16,8 @@
 namespace condensa {
 
 constexpr int kSampleUnit = 4;         // consecutive elements read at one sample position
-constexpr int kArrayBatch = 4;         // rankings per pass over a key array (LDS histograms)
+constexpr int kArrayWords = 4 * kBins;  // LDS histogram words of the array kernels (32 KB)
+constexpr int kArrayBatchMax = 8;      // at most this many rankings per pass over a key array
 constexpr u32 kNoKey = 0xFFFFFFFFu;    // marks sample entries that fell past the end of a tensor
 constexpr int kSegs = 1024;            // candidate list segments / counter sets (see k_window_sweep)
 
@@ -26,7 +27,7 @@ struct WindowArgs {
     u64* cand_idx;         // [cand_cap]
     Slot* wslots;          // [2J] boundary rankings, later [J] index rankings
     u64* seg_cnt;          // [kSegs] candidates appended to each segment (may exceed seg_cap)
-    u64* seg_above;        // [kMaxJ][kSegs] keys above each window's upper bound
+    u64* seg_region;       // [kMaxJ + 1][kSegs] keys per region (region i: i windows have an upper bound >= key)
     u64 seg_cap;           // entries per segment
     u32 n_segs;            // segments in use
     u64 n_units;
@@ -45,6 +46,7 @@ struct ArrayArgs {
     u64 N;                 // index ranking: the ranked key is N - 1 - idx
     Slot* slots;
     u64* hist;             // [n_slots][kBins]
+    u64* shared0;          // NULL, or: all rankings have the same filter and no prefix at level 0, count once here
     const u32* gate;       // NULL, or skip the kernel when *gate == 0
     int n_slots;
     int key_bits;
@@ -131,20 +133,33 @@ __global__ __launch_bounds__(kBlock) void k_window_ranks(DataArgs a, WindowArgs 
 // itself, or N - 1 - idx for the index ranking) matches the ranking's prefix.
 template <bool IDX>
 __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
-    __shared__ u32 s_hist[kArrayBatch * kBins];
-    __shared__ u64 s_prefix[kArrayBatch];
-    __shared__ u32 s_lo[kArrayBatch], s_hi[kArrayBatch], s_active[kArrayBatch];
+    __shared__ u32 s_hist[kArrayWords];
+    __shared__ u64 s_prefix[kArrayBatchMax];
+    __shared__ u32 s_lo[kArrayBatchMax], s_hi[kArrayBatchMax], s_active[kArrayBatchMax];
     __shared__ u32 s_any;
     if (a.gate && *a.gate == 0) return;
     const Level L = level_of(a.key_bits, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
-    for (int j0 = 0; j0 < a.n_slots; j0 += kArrayBatch) {
-        const int nj = (a.n_slots - j0 < kArrayBatch) ? a.n_slots - j0 : kArrayBatch;
+    const bool share = (level == 0 && a.shared0 != nullptr);
+    int batch = kArrayWords / nb;
+    if (batch > kArrayBatchMax) batch = kArrayBatchMax;
+    const int n_slots = share ? 1 : a.n_slots;
+    for (int j0 = 0; j0 < n_slots; j0 += batch) {
+        const int nj = (n_slots - j0 < batch) ? n_slots - j0 : batch;
         __syncthreads();
         if (tid == 0) s_any = 0;
         __syncthreads();
-        if (tid < nj) {
+        if (share) {
+            // one count serves every ranking: active when any of them still selects
+            if (tid < a.n_slots && a.slots[tid].state == kSelecting && a.slots[tid].level_begin == 0) s_any = 1;
+            if (tid == 0) {
+                s_prefix[0] = 0;
+                s_lo[0] = static_cast<u32>(a.slots[0].lo);
+                s_hi[0] = static_cast<u32>(a.slots[0].hi);
+                s_active[0] = 1;
+            }
+        } else if (tid < nj) {
             const Slot& s = a.slots[j0 + tid];
             s_prefix[tid] = s.prefix;
             s_lo[tid] = static_cast<u32>(s.lo);
@@ -177,9 +192,10 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
             for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < a.n_host; i += stride) take(i);
         }
         __syncthreads();
+        u64* dst = share ? a.shared0 : a.hist + static_cast<u64>(j0) * kBins;
         for (int i = tid; i < nj * nb; i += kBlock) {
             const u32 v = s_hist[i];
-            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.hist + static_cast<u64>(j0 + i / nb) * kBins + (i % nb)),
+            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + static_cast<u64>(i / nb) * kBins + (i % nb)),
                              static_cast<unsigned long long>(v));
         }
     }
@@ -188,35 +204,66 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
 // ---- the one sweep over the weights -----------------------------------------------------------------
 // Counters and the candidate list are split into segments chosen by the workgroup id: one global
 // atomic address shared by ~10^5 workgroups serialises the whole sweep, a thousand addresses do not.
-template <bool LC, bool VEC, bool MULTI>
+//
+// Several densities: the windows of the active rankings are put in descending order of their upper
+// bound.  For a key, i = number of windows whose upper bound is >= key places it in region i; the keys
+// above the window at sorted position p are the regions 0..p, and the key is a candidate iff it is
+// >= the smallest lower bound among the first i windows.  Region counts of a thread (at most 32 keys)
+// are packed in 6-bit fields.
+
+struct SortedWindows {
+    u32 hi[kMaxJ];         // upper bounds, descending
+    u32 minlo[kMaxJ];      // minlo[p] = smallest lower bound among sorted positions 0..p
+    u32 slot[kMaxJ];       // ranking at each sorted position
+    u32 n;                 // active rankings
+};
+
+// Deterministic order (upper bound descending, then lower bound descending, then ranking id); run by
+// one thread -- at most kMaxJ entries.
+__device__ inline void sort_windows(const Slot* slots, const Slot* wslots, int J, SortedWindows* out) {
+    u32 hi[kMaxJ], lo[kMaxJ], id[kMaxJ];
+    u32 n = 0;
+    for (int j = 0; j < J; ++j) {
+        if (slots[j].state != kSelecting) continue;
+        const u32 h = static_cast<u32>(wslots[2 * j].prefix), l = static_cast<u32>(wslots[2 * j + 1].prefix);
+        u32 p = n;
+        while (p > 0 && (hi[p - 1] < h || (hi[p - 1] == h && lo[p - 1] < l))) {
+            hi[p] = hi[p - 1]; lo[p] = lo[p - 1]; id[p] = id[p - 1];
+            --p;
+        }
+        hi[p] = h; lo[p] = l; id[p] = static_cast<u32>(j);
+        ++n;
+    }
+    u32 m = 0xFFFFFFFFu;
+    for (u32 p = 0; p < n; ++p) {
+        m = lo[p] < m ? lo[p] : m;
+        out->hi[p] = hi[p];
+        out->minlo[p] = m;
+        out->slot[p] = id[p];
+    }
+    out->n = n;
+}
+
+template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs w) {
-    constexpr int JM = MULTI ? kMaxJ : 1;
-    __shared__ u32 s_lo[kMaxJ], s_hi[kMaxJ];
-    __shared__ u32 s_above[kMaxJ];
+    __shared__ SortedWindows s_win;
+    __shared__ u32 s_region[kMaxJ + 1];
     __shared__ u64 s_wave[kBlock / 64];
     __shared__ u64 s_base;
     const u64 c = blockIdx.x;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    const int J = MULTI ? a.J : 1;
-    if (tid < J) {
-        const bool act = (a.slots[tid].state == kSelecting);
-        s_hi[tid] = act ? static_cast<u32>(w.wslots[2 * tid].prefix) : 0u;       // inactive: empty window
-        s_lo[tid] = act ? static_cast<u32>(w.wslots[2 * tid + 1].prefix) : 1u;
-        s_above[tid] = 0;
-    }
+    if (tid == 0) sort_windows(a.slots, w.wslots, a.J, &s_win);
+    if (tid <= kMaxJ) s_region[tid] = 0;
     __syncthreads();
+    const int n = static_cast<int>(s_win.n);
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
     const u64 base = (c - td.chunk_start) * kChunk;
 
     u32 key[kQuadsPerThread][4];
     u32 cmask = 0;
-    u32 above[JM];
-#pragma unroll
-    for (int j = 0; j < JM; ++j) above[j] = 0;
-    u32 lo0 = s_lo[0], hi0 = s_hi[0];
-
+    u64 pk0 = 0, pk1 = 0;                 // 6-bit counts of regions 0..9 and 10..16
 #pragma unroll
     for (int q = 0; q < kQuadsPerThread; ++q) {
         const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
@@ -232,45 +279,31 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            key[q][k] = mag_key(v[k]);
+            const u32 x = mag_key(v[k]);
+            key[q][k] = x;
             if (e0 + k < td.n) {
-                const u32 x = key[q][k];
-                bool cand;
-                if (MULTI) {
-                    cand = false;
-#pragma unroll
-                    for (int j = 0; j < JM; ++j) {
-                        if (j < J) {
-                            above[j] += (x > s_hi[j]) ? 1u : 0u;
-                            cand = cand || (x >= s_lo[j] && x <= s_hi[j]);
-                        }
-                    }
-                } else {
-                    above[0] += (x > hi0) ? 1u : 0u;
-                    cand = (x >= lo0 && x <= hi0);
-                }
-                if (cand) cmask |= 1u << (q * 4 + k);
+                int i = 0;
+                for (int p = 0; p < n; ++p) i += (s_win.hi[p] >= x) ? 1 : 0;
+                if (i < 10) pk0 += static_cast<u64>(1) << (6 * i);
+                else        pk1 += static_cast<u64>(1) << (6 * (i - 10));
+                if (i > 0 && x >= s_win.minlo[i - 1]) cmask |= 1u << (q * 4 + k);
             }
         }
     }
-
-    // keys above each window: wavefront sums, then one LDS and one global atomic per workgroup
+    // region counts: wavefront sums, then one LDS and one global atomic per workgroup and region
+    for (int r = 0; r <= n; ++r) {
+        u32 sum = static_cast<u32>(r < 10 ? (pk0 >> (6 * r)) : (pk1 >> (6 * (r - 10)))) & 63u;
 #pragma unroll
-    for (int j = 0; j < JM; ++j) {
-        if (j < J) {
-            u32 s = above[j];
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
-            if ((tid & 63) == 0 && s) atomicAdd(&s_above[j], s);
-        }
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_down(sum, d, 64);
+        if ((tid & 63) == 0 && sum) atomicAdd(&s_region[r], sum);
     }
     // candidates: one reservation per workgroup, then every thread writes its own in order
     u64 total;
     const u64 off = block_excl_scan_u64(__popc(cmask), s_wave, &total);    // syncs the workgroup
     const u32 seg = static_cast<u32>(c % w.n_segs);
-    if (tid < J && s_above[tid])
-        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[static_cast<u64>(tid) * kSegs + seg]),
-                  static_cast<unsigned long long>(s_above[tid]));
+    if (tid <= n && s_region[tid])
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_region[static_cast<u64>(tid) * kSegs + seg]),
+                  static_cast<unsigned long long>(s_region[tid]));
     if (total == 0) return;
     if (tid == 0)
         s_base = atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_cnt[seg]), static_cast<unsigned long long>(total));
@@ -342,7 +375,7 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
     if (lane == 0 && s)
-        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_above[seg]), static_cast<unsigned long long>(s));
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_region[seg]), static_cast<unsigned long long>(s));   // region 0
     const u32 cnt = __popc(cmask);
     u32 incl = cnt;
 #pragma unroll
@@ -376,10 +409,11 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
     __shared__ u64 s_wave[kBlock / 64];
-    __shared__ u64 s_above[kMaxJ];
+    __shared__ u64 s_region[kMaxJ + 1];
+    __shared__ SortedWindows s_win;
     __shared__ u32 s_overflow;
     const int tid = threadIdx.x;
-    if (tid == 0) s_overflow = 0;
+    if (tid == 0) { s_overflow = 0; sort_windows(a.slots, w.wslots, a.J, &s_win); }
     __syncthreads();
     // every thread sums a strided share of the segments, then the workgroup adds the shares up
     u64 cnt_sum = 0;
@@ -393,27 +427,30 @@ __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs 
     u64 total;
     block_excl_scan_u64(cnt_sum, s_wave, &total);
     if (tid == 0) a.ctl->cand_count = total;
-    for (int j = 0; j < a.J; ++j) {
+    const int n = static_cast<int>(s_win.n);
+    for (int r = 0; r < n; ++r) {                        // region n (below every window) is not needed
         u64 part = 0;
-        for (u32 seg = tid; seg < w.n_segs; seg += kBlock) part += w.seg_above[static_cast<u64>(j) * kSegs + seg];
+        for (u32 seg = tid; seg < w.n_segs; seg += kBlock) part += w.seg_region[static_cast<u64>(r) * kSegs + seg];
         u64 sum;
         block_excl_scan_u64(part, s_wave, &sum);
-        if (tid == 0) s_above[j] = sum;
+        if (tid == 0) s_region[r] = sum;
     }
     __syncthreads();
-    if (tid >= a.J) return;
-    Slot& s = a.slots[tid];
-    if (s.state != kSelecting) return;
-    const u64 above = s_above[tid];
-    a.ctl->above[tid] = above;
+    if (tid >= n) return;
+    // keys above the window at sorted position p: regions 0..p
+    u64 above = 0;
+    for (int r = 0; r <= tid; ++r) above += s_region[r];
+    const u32 j = s_win.slot[tid];
+    Slot& s = a.slots[j];
+    a.ctl->above[j] = above;
     if (s_overflow || above >= s.k) {
         s.state = kFailed;
         atomicOr(&a.ctl->window_failed, 1u);
         return;
     }
     s.remaining = s.k - above;
-    const u32 hi = static_cast<u32>(w.wslots[2 * tid].prefix);
-    const u32 lo = static_cast<u32>(w.wslots[2 * tid + 1].prefix);
+    const u32 hi = static_cast<u32>(w.wslots[2 * j].prefix);
+    const u32 lo = static_cast<u32>(w.wslots[2 * j + 1].prefix);
     s.hi = hi;
     s.lo = lo;
     // leading digits shared by lo and hi are shared by every candidate: those levels need no counting
@@ -493,8 +530,10 @@ static condensa_status rank_array(const ArrayArgs& ar, Control* ctl, u32* tie_fl
     for (int level = 0; level < n_levels(ar.key_bits); ++level) {
         hipLaunchKernelGGL((k_hist_array<IDX>), dim3(array_grid(ar.n_host)), dim3(kBlock), 0, st, ar, level);
         CONDENSA_LAUNCH_CHECK();
+        // with a shared level-0 histogram every ranking reads group 0 of `shared0` (J = n_slots)
         hipLaunchKernelGGL(k_scan_level, dim3(ar.n_slots), dim3(kBlock), 0, st, ar.slots,
-                           static_cast<const u64*>(nullptr), ar.hist, 1, ar.key_bits, level, ctl, 0, tie_flag);
+                           static_cast<const u64*>(ar.shared0), ar.hist, ar.shared0 ? ar.n_slots : 1, ar.key_bits,
+                           level, ctl, 0, tie_flag);
         CONDENSA_LAUNCH_CHECK();
     }
     return CONDENSA_OK;
@@ -514,7 +553,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.stride = quads / w.n_units;
     w.cand_cap = L.cand_cap;
     w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
-    w.seg_above = w.seg_cnt + kSegs;
+    w.seg_region = w.seg_cnt + kSegs;
     const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / kWaveElems) : a.n_chunks;
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
@@ -532,13 +571,14 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         ArrayArgs ar{};
         ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J;
         ar.hist = hist_aux; ar.key_bits = 31;
+        ar.shared0 = a.histx + static_cast<u64>(a.J + 2 * kMaxJ) * kBins;     // boundary rankings share level 0
         rc = rank_array<false>(ar, a.ctl, &a.ctl->unused_flag, st);
         if (rc != CONDENSA_OK) return rc;
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
         if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
-        else          hipLaunchKernelGGL((k_window_sweep<LC, VEC, true>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        else          hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
     }
     PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
