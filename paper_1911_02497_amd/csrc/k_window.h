@@ -170,31 +170,51 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
         }
         __syncthreads();
         if (!s_any) continue;                            // uniform: nothing to count in this batch
-        for (int i = tid; i < nj * nb; i += kBlock) s_hist[i] = 0;
+        // Keys of a sample or of a narrow window crowd into a few bins; spare LDS holds private copies
+        // of the histograms, chosen by lane, so that fewer lanes of a wavefront hit one address.
+        int copies = 1;
+        while (copies < 8 && 2 * copies * nj * nb <= kArrayWords) copies *= 2;
+        const int words = nj * nb;
+        for (int i = tid; i < copies * words; i += kBlock) s_hist[i] = 0;
         __syncthreads();
-        auto take = [&](u64 i) {
-            const u32 ck = a.keys[i];
-            const u64 rk = IDX ? (a.N - 1 - a.idx[i]) : static_cast<u64>(ck);
-            const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
-            for (int j = 0; j < nj; ++j)
-                if (s_active[j] && ck >= s_lo[j] && ck <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
-                    atomicAdd(&s_hist[j * nb + digit], 1u);
+        u32* my_hist = s_hist + (tid & (copies - 1)) * words;
+        // entries are fetched eight at a time so that their loads overlap (the loop is latency bound)
+        auto take_range = [&](u64 first, u64 count, u64 start, u64 step) {
+            constexpr int kUnroll = 8;
+            for (u64 i0 = start; i0 < count; i0 += step * kUnroll) {
+                u32 ck[kUnroll];
+                u64 ix[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const u64 i = i0 + step * u;
+                    ck[u] = (i < count) ? a.keys[first + i] : kNoKey;
+                    ix[u] = (IDX && i < count) ? a.idx[first + i] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    if (i0 + step * u >= count) break;
+                    const u64 rk = IDX ? (a.N - 1 - ix[u]) : static_cast<u64>(ck[u]);
+                    const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
+                    for (int j = 0; j < nj; ++j)
+                        if (s_active[j] && ck[u] >= s_lo[j] && ck[u] <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
+                            atomicAdd(&my_hist[j * nb + digit], 1u);
+                }
+            }
         };
         if (a.seg_cnt) {
             for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
                 u64 cnt = a.seg_cnt[seg];
                 if (cnt > a.seg_cap) cnt = a.seg_cap;
-                const u64 first = static_cast<u64>(seg) * a.seg_cap;
-                for (u64 i = tid; i < cnt; i += kBlock) take(first + i);
+                take_range(static_cast<u64>(seg) * a.seg_cap, cnt, tid, kBlock);
             }
         } else {
-            const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
-            for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < a.n_host; i += stride) take(i);
+            take_range(0, a.n_host, static_cast<u64>(blockIdx.x) * kBlock + tid, static_cast<u64>(gridDim.x) * kBlock);
         }
         __syncthreads();
         u64* dst = share ? a.shared0 : a.hist + static_cast<u64>(j0) * kBins;
-        for (int i = tid; i < nj * nb; i += kBlock) {
-            const u32 v = s_hist[i];
+        for (int i = tid; i < words; i += kBlock) {
+            u32 v = 0;
+            for (int cpy = 0; cpy < copies; ++cpy) v += s_hist[cpy * words + i];
             if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + static_cast<u64>(i / nb) * kBins + (i % nb)),
                              static_cast<unsigned long long>(v));
         }
@@ -514,7 +534,7 @@ __global__ __launch_bounds__(kBlock) void k_window_finish(DataArgs a, WindowArgs
 
 static inline unsigned array_grid(u64 n) {
     u64 b = (n + kBlock * 8 - 1) / (kBlock * 8);
-    if (b > 1024) b = 1024;
+    if (b > 1024) b = 1024;     // measured: 512 and 1024 workgroups are about equal, fewer are slower
     if (b == 0) b = 1;
     return static_cast<unsigned>(b);
 }
