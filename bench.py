@@ -56,7 +56,7 @@ def parse():
     ap.add_argument("--all-phases", action="store_true",
                     help="time every phase with events (adds ~10 us of idle gap per event); default: the apply sweep only")
     ap.add_argument("--workload", default="lc_stress",
-                    choices=["lc_stress", "single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
+                    choices=["lc_stress", "prune_stress", "single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
                              "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
                     help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
@@ -69,7 +69,17 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     name = args.workload
     up = lambda arrs: [torch.from_numpy(a).to(dev) for a in arrs]  # noqa: E731
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
-    if name == "single_prune_fp16":
+    if name == "prune_stress":
+        # global magnitude pruning of the large-model weights (no multipliers): theta + mask at density 0.1
+        host, _ = workloads.lc_stress(indices=range(args.tensors), threads=16)
+        d = up(host)
+        outs = {}
+        def call():
+            r = P.condensa_prune(d, [0.1], workspace=ws, outputs=outs)
+            outs.update({"theta": r["theta"], "mask": r["mask"], "results": r["results"]})
+        op, F, J, bytes_per_elem, desc = P.binding.OP_PRUNE, 0, 1, 13, "global prune d=0.1, theta + mask"
+        cpu = lambda: oracle.prune(host[:2], [0.1])  # noqa: E731
+    elif name == "single_prune_fp16":
         host = workloads.single_matrix()
         d = up(host)
         call = lambda: P.condensa_prune(d, [0.02], theta=False, theta_f16=True, mask=True, workspace=ws)  # noqa: E731
@@ -120,8 +130,10 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         t0 = time.perf_counter()
         cpu()
         dt = time.perf_counter() - t0
-        cpu_rec = {"value": round(N / dt, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
-                   "sample": f"the whole workload once, {dt:.2f} s", "host_cpus": os.cpu_count()}
+        n_cpu = sum(t.size for t in host[:2]) if name == "prune_stress" else N
+        cpu_rec = {"value": round(n_cpu / dt, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
+                   "sample": ("the first 2 tensors" if name == "prune_stress" else "the whole workload") + f" once, {dt:.2f} s",
+                   "host_cpus": os.cpu_count()}
     print(json.dumps({
         "metric": "weights pruned/sec and achieved HBM GB/s (% of peak) per compression step",
         "value": round(N / (ms * 1e-3), 1), "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -199,7 +199,7 @@ def select_records(results) -> List[Dict[str, int]]:
 
 
 def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16=False, mask=True,
-                   in_place=False, workspace=None, stream=None):
+                   in_place=False, workspace=None, stream=None, outputs=None):
     """Marshals a call of the C entry point condensa_prune.  ``theta`` / ``theta_f16`` / ``mask`` choose
     which outputs are allocated ([density][tensor] lists of device tensors); ``in_place`` passes the
     weights themselves as theta (one density only).  Returns the outputs and the record tensor."""
@@ -211,20 +211,26 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     dens = (ctypes.c_double * max(J, 1))(*[float(d) for d in densities])
     total = sum(t.numel() for t in tensors)
 
-    def outs(flag, dtype):
+    outputs = outputs or {}                      # preallocated [density][tensor] lists / record tensor to reuse
+
+    def outs(flag, dtype, name):
         if not flag:
             return None
+        if outputs.get(name) is not None:
+            return outputs[name]
         return [[torch.empty(t.shape, dtype=dtype, device=dev) for t in tensors] for _ in range(J)]
 
-    th = [list(tensors)] if (theta and in_place) else outs(theta, torch.float32)
-    th16 = outs(theta_f16, torch.int16)
-    mk = outs(mask, torch.uint8)
+    th = [list(tensors)] if (theta and in_place) else outs(theta, torch.float32, "theta")
+    th16 = outs(theta_f16, torch.int16, "theta_f16")
+    mk = outs(mask, torch.uint8, "mask")
     flat = lambda x: None if x is None else [t for row in x for t in row]  # noqa: E731
     k1, p1 = _ptr_table(flat(th))
     k2, p2 = _ptr_table(flat(th16))
     k3, p3 = _ptr_table(flat(mk))
     n_rec = J * (nt if scope == SCOPE_PER_TENSOR else 1)
-    results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
+    results = outputs.get("results")
+    if results is None:
+        results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace)
     _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
                               _stream(stream)))

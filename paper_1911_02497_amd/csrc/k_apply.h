@@ -15,6 +15,9 @@ __device__ inline bool keep_rule(u32 key, u32 T, u64 idx, u64 tie_end) {
     return key > T || (key == T && idx < tie_end);
 }
 
+// Workgroups that lie wholly inside their tensor (all but a tensor's last) take the unguarded 128-bit
+// accesses; the selection record and the output table are read before the data so that their latency
+// overlaps the data loads.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDesc* __restrict__ out) {
     __shared__ u32 s_T[kMaxJ];
@@ -26,48 +29,60 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
     const u64 g = a.per_tensor ? t : 0;
-    {
-        const TensorDesc& td0 = a.td[t];
-        if ((c - td0.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4) >= td0.n) return;   // uniform
-    }
+    const TensorDesc& td = a.td[t];
+    const u64 n = td.n;
+    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4);
+    if (wg0 >= n) return;                                                // uniform
     if (tid < a.J) {
         const Slot& s = a.slots[g * a.J + tid];
         s_T[tid] = static_cast<u32>(s.prefix);
         s_end[tid] = s.tie_end;
         s_out[tid] = out[static_cast<u64>(tid) * a.n_tensors + t];
     }
-    __syncthreads();
-    const TensorDesc& td = a.td[t];
-    const u64 base = (c - td.chunk_start) * kChunk;
     const u64 idx0 = a.per_tensor ? 0 : td.flat_start;
-    {
-        const u64 e0 = base + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
-        if (e0 >= td.n) return;
-        float v[4];
-        load4<VEC>(td.w, e0, td.n, v);
-        u32 key[4];
+    const u64 e0 = wg0 + tid * 4;
+    const bool full = VEC && wg0 + kBlock * 4 <= n;                      // uniform
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (full) {
+        const float4 x = *reinterpret_cast<const float4*>(td.w + e0);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    } else if (e0 < n) {
+        load4<VEC>(td.w, e0, n, v);
+    }
+    __syncthreads();
+    if (e0 >= n) return;
+    u32 key[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) key[k] = mag_key(v[k]);
-        for (int j = 0; j < a.J; ++j) {
-            const u32 T = s_T[j];
-            const u64 end = s_end[j];
-            float th[4];
-            u8 m[4];
+    for (int k = 0; k < 4; ++k) key[k] = mag_key(v[k]);
+    for (int j = 0; j < a.J; ++j) {
+        const u32 T = s_T[j];
+        const u64 end = s_end[j];
+        float th[4];
+        u8 m[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bool keep = keep_rule(key[k], T, idx0 + e0 + k, end);
-                m[k] = keep ? 1 : 0;
-                th[k] = keep ? v[k] : 0.0f;
+        for (int k = 0; k < 4; ++k) {
+            const bool keep = keep_rule(key[k], T, idx0 + e0 + k, end);
+            m[k] = keep ? 1 : 0;
+            th[k] = keep ? v[k] : 0.0f;
+        }
+        const OutDesc& o = s_out[j];
+        if (full) {
+            if (o.theta) *reinterpret_cast<float4*>(o.theta + e0) = make_float4(th[0], th[1], th[2], th[3]);
+            if (o.theta16) {
+                ushort4 h;
+                h.x = f32_to_f16_rne(th[0]); h.y = f32_to_f16_rne(th[1]); h.z = f32_to_f16_rne(th[2]); h.w = f32_to_f16_rne(th[3]);
+                *reinterpret_cast<ushort4*>(o.theta16 + e0) = h;
             }
-            const OutDesc& o = s_out[j];
-            if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
+            if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+        } else {
+            if (o.theta) store4<VEC>(o.theta, e0, n, th);
             if (o.theta16) {
                 u16 h[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) h[k] = f32_to_f16_rne(th[k]);
-                store4_u16<VEC>(o.theta16, e0, td.n, h);
+                store4_u16<VEC>(o.theta16, e0, n, h);
             }
-            if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+            if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
         }
     }
 }
@@ -85,16 +100,27 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
-    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (THREADS * 4) + tid * 4;
-    if (e0 >= td.n) return;
-    float w[4], l[4];
-    load4<VEC>(td.w, e0, td.n, w);
-    load4<VEC>(td.lam, e0, td.n, l);
+    const u64 n = td.n;
+    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (THREADS * 4);
+    if (wg0 >= n) return;                                                // uniform
     const Slot& s = a.slots[0];
     const u32 T = static_cast<u32>(s.prefix);
     const u64 end = s.tie_end;
     const OutDesc o = out[t];
     const float mu = a.mu;
+    const u64 e0 = wg0 + tid * 4;
+    const bool full = VEC && wg0 + THREADS * 4 <= n;                     // uniform
+    float w[4], l[4];
+    if (full) {
+        const float4 x = *reinterpret_cast<const float4*>(td.w + e0);
+        const float4 y = *reinterpret_cast<const float4*>(td.lam + e0);
+        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+        l[0] = y.x; l[1] = y.y; l[2] = y.z; l[3] = y.w;
+    } else {
+        if (e0 >= n) return;
+        load4<VEC>(td.w, e0, n, w);
+        load4<VEC>(td.lam, e0, n, l);
+    }
     float th[4], ln[4], gr[4];
     u8 m[4];
     u16 h[4] = {0, 0, 0, 0};
@@ -113,11 +139,23 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
         ln[k] = __fsub_rn(l[k], p);
         gr[k] = __fsub_rn(p, ln[k]);
     }
-    if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
-    if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, td.n, h);
-    store4<VEC>(td.lam_out, e0, td.n, ln);
-    if (td.grad) store4<VEC>(td.grad, e0, td.n, gr);
-    if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    if (full) {
+        if (o.theta) *reinterpret_cast<float4*>(o.theta + e0) = make_float4(th[0], th[1], th[2], th[3]);
+        if (PQ && o.theta16) {
+            ushort4 hv;
+            hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
+            *reinterpret_cast<ushort4*>(o.theta16 + e0) = hv;
+        }
+        *reinterpret_cast<float4*>(td.lam_out + e0) = make_float4(ln[0], ln[1], ln[2], ln[3]);
+        if (td.grad) *reinterpret_cast<float4*>(td.grad + e0) = make_float4(gr[0], gr[1], gr[2], gr[3]);
+        if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+    } else {
+        if (o.theta) store4<VEC>(o.theta, e0, n, th);
+        if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, n, h);
+        store4<VEC>(td.lam_out, e0, n, ln);
+        if (td.grad) store4<VEC>(td.grad, e0, n, gr);
+        if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
+    }
 }
 
 // ---- learning-step update with the penalty gradient folded in -----------------------------------------

@@ -346,12 +346,14 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     }
 }
 
-// Single-density form of the sweep: one wavefront per workgroup and 1024 elements each, so there is
-// no workgroup barrier; the wavefront reserves its candidate slots with one atomic on its segment.
-constexpr int kWaveQuads = 4;                               // float4 per thread
-constexpr int kWaveElems = 64 * 4 * kWaveQuads;             // 1024 elements per workgroup
-template <bool LC, bool VEC>
+// Single-density form of the sweep: one wavefront per workgroup, 8 KB of input each (1024 elements
+// with multipliers, 2048 without), so there is no workgroup barrier; the wavefront reserves its
+// candidate slots with one atomic on its segment.  Workgroups that lie wholly inside their tensor (all
+// but the last one of a tensor) issue every load before the first use, which keeps 4-8 loads per lane in
+// flight; the ragged last workgroup takes the guarded path.
+template <bool LC, bool VEC, int QUADS>
 __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs w) {
+    constexpr int kWaveElems = 64 * 4 * QUADS;
     constexpr u32 kSub = kChunk / kWaveElems;
     const u64 c = blockIdx.x / kSub;
     const u32 sub = blockIdx.x % kSub;
@@ -360,33 +362,62 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
     const u64 base = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * kWaveElems;
-    if (base >= td.n) return;
-    const bool act = (a.slots[0].state == kSelecting);
-    const u32 hi = act ? static_cast<u32>(w.wslots[0].prefix) : 0u;      // inactive: empty window
-    const u32 lo = act ? static_cast<u32>(w.wslots[1].prefix) : 1u;
+    const u64 n = td.n;
+    if (base >= n) return;
+    if (a.slots[0].state != kSelecting) return;                         // nothing to count (k == 0)
+    const u32 hi = static_cast<u32>(w.wslots[0].prefix);
+    const u32 lo = static_cast<u32>(w.wslots[1].prefix);
+    const u32 span = hi - lo;                                           // lo <= hi: x in [lo, hi] <=> x - lo <= span
+    const float* __restrict__ wp = td.w;
+    const float* __restrict__ lp = td.lam;
 
-    u32 key[kWaveQuads][4];
+    u32 key[QUADS][4];
     u32 cmask = 0, above = 0;
+    if (VEC && base + kWaveElems <= n) {                                // uniform over the wavefront
+        float4 wv[QUADS], lv[QUADS];
 #pragma unroll
-    for (int q = 0; q < kWaveQuads; ++q) {
-        const u64 e0 = base + static_cast<u64>(q) * 256 + lane * 4;
-        float v[4] = {0.f, 0.f, 0.f, 0.f};
-        if (e0 < td.n) {
-            load4<VEC>(td.w, e0, td.n, v);
+        for (int q = 0; q < QUADS; ++q) {
+            wv[q] = *reinterpret_cast<const float4*>(wp + base + q * 256 + lane * 4);
+            if (LC) lv[q] = *reinterpret_cast<const float4*>(lp + base + q * 256 + lane * 4);
+        }
+#pragma unroll
+        for (int q = 0; q < QUADS; ++q) {
+            float v[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
             if (LC) {
-                float l[4];
-                load4<VEC>(td.lam, e0, td.n, l);
+                const float l[4] = {lv[q].x, lv[q].y, lv[q].z, lv[q].w};
 #pragma unroll
                 for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
             }
-        }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const u32 x = mag_key(v[k]);
-            key[q][k] = x;
-            if (e0 + k < td.n) {
+            for (int k = 0; k < 4; ++k) {
+                const u32 x = mag_key(v[k]);
+                key[q][k] = x;
                 above += (x > hi) ? 1u : 0u;
-                if (x >= lo && x <= hi) cmask |= 1u << (q * 4 + k);
+                cmask |= ((x - lo <= span) ? 1u : 0u) << (q * 4 + k);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < QUADS; ++q) {
+            const u64 e0 = base + static_cast<u64>(q) * 256 + lane * 4;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (e0 < n) {
+                load4<VEC>(wp, e0, n, v);
+                if (LC) {
+                    float l[4];
+                    load4<VEC>(lp, e0, n, l);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 x = mag_key(v[k]);
+                key[q][k] = x;
+                if (e0 + k < n) {
+                    above += (x > hi) ? 1u : 0u;
+                    if (x - lo <= span) cmask |= 1u << (q * 4 + k);
+                }
             }
         }
     }
@@ -412,7 +443,7 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
     u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + incl - cnt;
     const u64 first = static_cast<u64>(seg) * w.seg_cap;
 #pragma unroll
-    for (int q = 0; q < kWaveQuads; ++q) {
+    for (int q = 0; q < QUADS; ++q) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (cmask & (1u << (q * 4 + k))) {
@@ -574,7 +605,8 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.cand_cap = L.cand_cap;
     w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
     w.seg_region = w.seg_cnt + kSegs;
-    const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / kWaveElems) : a.n_chunks;
+    constexpr int kWaveQuads = LC ? 4 : 8;                       // 8 KB of input per wavefront either way
+    const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
@@ -597,7 +629,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
-        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
         else          hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
     }
