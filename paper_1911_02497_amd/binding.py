@@ -11,7 +11,8 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libcondensa.so")
+# CONDENSA_LIBRARY names another build of the same library (same C ABI), e.g. one compiled elsewhere.
+_LIB_PATH = os.environ.get("CONDENSA_LIBRARY") or os.path.join(_HERE, "libcondensa.so")
 
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
 OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP, OP_COUNT_NONZERO, OP_LC_SGD_STEP = range(7)

@@ -234,13 +234,21 @@ template <bool LC, bool VEC>
 static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st) {
     if (a.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
-        u64 blocks = a.n_chunks < 2048 ? a.n_chunks : 2048;
-        const u64 cpb = (a.n_chunks + blocks - 1) / blocks;
-        blocks = (a.n_chunks + cpb - 1) / cpb;
         for (int level = 0; level < n_levels(31); ++level) {
+            // Past level 0 every workgroup holds J histograms and flushes their non-zero bins with global
+            // atomics: with several densities, few wide workgroups keep that flush small.
+            const bool wide = level > 0 && !a.per_tensor;
+            const unsigned threads = wide ? 1024 : kBlock;
+            const u64 cap = wide ? 256 : 2048;                 // measured best of 128..1024
+            const u64 per_iter = threads / kBlock;
+            u64 blocks = (a.n_chunks + per_iter - 1) / per_iter;
+            if (blocks > cap) blocks = cap;
+            u64 cpb = (a.n_chunks + blocks - 1) / blocks;
+            cpb = (cpb + per_iter - 1) / per_iter * per_iter;
+            blocks = (a.n_chunks + cpb - 1) / cpb;
             const int nj = a.J < kSlotBatch ? a.J : kSlotBatch;
             const size_t lds = static_cast<size_t>(level == 0 ? kBins : nj * (1 << level_of(31, level).bits)) * sizeof(u32);
-            hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), lds, st, a, level, cpb);
+            hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(threads), lds, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_scan_level, dim3(n_slots), dim3(kBlock), 0, st, a.slots, a.hist0, a.histx, a.J, 31,
                                level, a.ctl, a.only_failed, &a.ctl->need_tie);
@@ -278,15 +286,16 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
     return launch_ties_and_results<LC, VEC>(a, n_slots, n_groups, results, st);
 }
 
-// Sampled window or radix levels?  Measured crossover (one MI355X): the radix levels cost one sweep per
-// level but little fixed work; the window path costs ~0.1-0.3 ms of small kernels and one sweep.  The
-// break-even sits near N x densities x input streams = 2^27.
+// Sampled window or radix levels?  Measured (one MI355X, 2^24..2^30 weights, 1/4/10 densities): the radix
+// levels cost three sweeps whatever the number of densities and ~50 us of fixed work; the window path
+// costs one sweep, ~0.25 ms of small kernels, and candidate lists and a sweep that grow with the number
+// of densities.  One density breaks even near 2^26 element reads, four near 2^30, ten never.
 static bool want_window(u64 N, bool per_tensor, int J, bool lc) {
     if (per_tensor) return false;
     const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;
-    return N * static_cast<u64>(J) * (lc ? 2u : 1u) >= (static_cast<u64>(1) << 27);
+    return N * (lc ? 2u : 1u) >= (static_cast<u64>(J) * static_cast<u64>(J)) << 26;
 }
 
 }  // namespace condensa

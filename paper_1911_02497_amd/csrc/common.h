@@ -20,7 +20,7 @@ constexpr int kQuadsPerThread = kChunk / (kBlock * 4);   // 8 float4 per thread 
 constexpr int kMaxJ = CONDENSA_MAX_DENSITIES;
 constexpr int kBins = 2048;            // bins of one radix level (digits are at most 11 bits)
 constexpr u64 kMaxElems = static_cast<u64>(1) << 36;   // elements per call (keeps every grid below 2^31 workgroups)
-constexpr int kSlotBatch = 15;         // rankings that share one sweep's LDS histograms (15 x 1024 bins x 4 B < 64 KB)
+constexpr int kSlotBatch = 14;         // rankings that share one sweep's LDS histograms (14 x 1024 bins x 4 B + digit table < 64 KB)
 
 // One weight tensor as the kernels see it (device table, one entry per tensor plus a sentinel).
 struct TensorDesc {
@@ -93,6 +93,19 @@ __device__ inline u32 mag_key(float x) { return __float_as_uint(x) & 0x7FFFFFFFu
 __device__ inline float lc_shift(float w, float lam, float mu) {
     const float t = __fdiv_rn(lam, mu);
     return __fsub_rn(w, t);
+}
+
+// 128-bit accesses with the streaming (non-temporal) hint, for data that this call touches for the last
+// time: results that nothing re-reads before they leave the caches anyway, inputs on their final pass.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ inline float4 ld4_stream(const float* p) {
+    const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ inline void st4_stream(float* p, float a, float b, float c, float d) {
+    f32x4 t;
+    t.x = a; t.y = b; t.z = c; t.w = d;
+    __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
 }
 
 // Loads up to four consecutive elements e0 .. e0+3 of an n-element array; missing ones read 0.

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
     const bool full = VEC && wg0 + kBlock * 4 <= n;                      // uniform
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (full) {
-        const float4 x = *reinterpret_cast<const float4*>(td.w + e0);
+        const float4 x = ld4_stream(td.w + e0);
         v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
     } else if (e0 < n) {
         load4<VEC>(td.w, e0, n, v);
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
         }
         const OutDesc& o = s_out[j];
         if (full) {
-            if (o.theta) *reinterpret_cast<float4*>(o.theta + e0) = make_float4(th[0], th[1], th[2], th[3]);
+            if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
             if (o.theta16) {
                 ushort4 h;
                 h.x = f32_to_f16_rne(th[0]); h.y = f32_to_f16_rne(th[1]); h.z = f32_to_f16_rne(th[2]); h.w = f32_to_f16_rne(th[3]);
@@ -90,46 +90,18 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
 // theta = C(w - lambda/mu) entries, lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
 // each operation rounded once in binary32.  THREADS threads per workgroup, one float4 each.
 // PQ: the composed scheme Compose([Prune(), Quantize(float16)]) -- theta is rounded to binary16 and the
-// update sees its exact widening D(theta).
-template <bool VEC, int THREADS, bool PQ>
-__global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
-    constexpr u32 kSub = kChunk / (THREADS * 4);
-    const u64 c = blockIdx.x / kSub;
-    const u32 sub = blockIdx.x % kSub;
-    if (c >= a.n_chunks) return;
-    const int tid = threadIdx.x;
-    const int t = static_cast<int>(a.chunk_map[c]);
-    const TensorDesc& td = a.td[t];
-    const u64 n = td.n;
-    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (THREADS * 4);
-    if (wg0 >= n) return;                                                // uniform
-    const Slot& s = a.slots[0];
-    const u32 T = static_cast<u32>(s.prefix);
-    const u64 end = s.tie_end;
-    const OutDesc o = out[t];
-    const float mu = a.mu;
-    const u64 e0 = wg0 + tid * 4;
-    const bool full = VEC && wg0 + THREADS * 4 <= n;                     // uniform
-    float w[4], l[4];
-    if (full) {
-        const float4 x = *reinterpret_cast<const float4*>(td.w + e0);
-        const float4 y = *reinterpret_cast<const float4*>(td.lam + e0);
-        w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
-        l[0] = y.x; l[1] = y.y; l[2] = y.z; l[3] = y.w;
-    } else {
-        if (e0 >= n) return;
-        load4<VEC>(td.w, e0, n, w);
-        load4<VEC>(td.lam, e0, n, l);
-    }
-    float th[4], ln[4], gr[4];
-    u8 m[4];
-    u16 h[4] = {0, 0, 0, 0};
+// update sees its exact widening D(theta).  One float4 per thread in 64-thread workgroups measured best
+// for this 2-read 3-write kernel (more per thread or wider workgroups lose 10-15%).
+template <bool PQ>
+__device__ inline void lc_update4(const float w[4], const float l[4], float mu, u32 T, u64 idx, u64 end,
+                                  float th[4], float ln[4], float gr[4], u8 m[4], u16 h[4]) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const float v = lc_shift(w[k], l[k], mu);
-        const bool keep = keep_rule(mag_key(v), T, td.flat_start + e0 + k, end);
+        const bool keep = keep_rule(mag_key(v), T, idx + k, end);
         m[k] = keep ? 1 : 0;
         th[k] = keep ? v : 0.0f;
+        h[k] = 0;
         if (PQ) {
             h[k] = f32_to_f16_rne(th[k]);
             th[k] = f16_bits_to_f32(h[k]);
@@ -139,22 +111,68 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
         ln[k] = __fsub_rn(l[k], p);
         gr[k] = __fsub_rn(p, ln[k]);
     }
-    if (full) {
-        if (o.theta) *reinterpret_cast<float4*>(o.theta + e0) = make_float4(th[0], th[1], th[2], th[3]);
-        if (PQ && o.theta16) {
-            ushort4 hv;
-            hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
-            *reinterpret_cast<ushort4*>(o.theta16 + e0) = hv;
+}
+
+template <bool VEC, int THREADS, bool PQ, int QUADS = 1>
+__global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    constexpr u32 kTile = THREADS * 4 * QUADS;
+    constexpr u32 kSub = kChunk / kTile;
+    const u64 c = blockIdx.x / kSub;
+    const u32 sub = blockIdx.x % kSub;
+    if (c >= a.n_chunks) return;
+    const int tid = threadIdx.x;
+    const int t = static_cast<int>(a.chunk_map[c]);
+    const TensorDesc& td = a.td[t];
+    const u64 n = td.n;
+    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * kTile;
+    if (wg0 >= n) return;                                                // uniform
+    const Slot& s = a.slots[0];
+    const u32 T = static_cast<u32>(s.prefix);
+    const u64 end = s.tie_end;
+    const OutDesc o = out[t];
+    const float mu = a.mu;
+    if (VEC && wg0 + kTile <= n) {                                       // uniform
+        float4 x[QUADS], y[QUADS];
+#pragma unroll
+        for (int q = 0; q < QUADS; ++q) {
+            x[q] = ld4_stream(td.w + wg0 + q * (THREADS * 4) + tid * 4);
+            y[q] = ld4_stream(td.lam + wg0 + q * (THREADS * 4) + tid * 4);
         }
-        *reinterpret_cast<float4*>(td.lam_out + e0) = make_float4(ln[0], ln[1], ln[2], ln[3]);
-        if (td.grad) *reinterpret_cast<float4*>(td.grad + e0) = make_float4(gr[0], gr[1], gr[2], gr[3]);
-        if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+#pragma unroll
+        for (int q = 0; q < QUADS; ++q) {
+            const u64 e0 = wg0 + q * (THREADS * 4) + tid * 4;
+            const float w[4] = {x[q].x, x[q].y, x[q].z, x[q].w};
+            const float l[4] = {y[q].x, y[q].y, y[q].z, y[q].w};
+            float th[4], ln[4], gr[4];
+            u8 m[4];
+            u16 h[4];
+            lc_update4<PQ>(w, l, mu, T, td.flat_start + e0, end, th, ln, gr, m, h);
+            if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
+            if (PQ && o.theta16) {
+                ushort4 hv;
+                hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
+                *reinterpret_cast<ushort4*>(o.theta16 + e0) = hv;
+            }
+            st4_stream(td.lam_out + e0, ln[0], ln[1], ln[2], ln[3]);
+            if (td.grad) st4_stream(td.grad + e0, gr[0], gr[1], gr[2], gr[3]);
+            if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+        }
     } else {
-        if (o.theta) store4<VEC>(o.theta, e0, n, th);
-        if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, n, h);
-        store4<VEC>(td.lam_out, e0, n, ln);
-        if (td.grad) store4<VEC>(td.grad, e0, n, gr);
-        if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
+        for (int q = 0; q < QUADS; ++q) {
+            const u64 e0 = wg0 + q * (THREADS * 4) + tid * 4;
+            if (e0 >= n) return;
+            float w[4], l[4], th[4], ln[4], gr[4];
+            u8 m[4];
+            u16 h[4];
+            load4<VEC>(td.w, e0, n, w);
+            load4<VEC>(td.lam, e0, n, l);
+            lc_update4<PQ>(w, l, mu, T, td.flat_start + e0, end, th, ln, gr, m, h);
+            if (o.theta) store4<VEC>(o.theta, e0, n, th);
+            if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, n, h);
+            store4<VEC>(td.lam_out, e0, n, ln);
+            if (td.grad) store4<VEC>(td.grad, e0, n, gr);
+            if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
+        }
     }
 }
 

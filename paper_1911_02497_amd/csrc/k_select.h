@@ -87,10 +87,27 @@ __global__ __launch_bounds__(kBlock) void k_prepare(u64* zero, u64 n_words, cons
 // Every workgroup sweeps a contiguous range of chunks and keeps its counts in LDS; they are added
 // to the global histogram when the group (tensor under PER_TENSOR scope) changes and at the end.
 // Level 0 has no prefix to match, so the densities of a group share one histogram; later levels
-// keep one histogram per ranking, kSlotBatch rankings per sweep of the range.
+// keep one histogram per ranking, kSlotBatch rankings per sweep of the range.  At those levels a table
+// over the leading digit says which rankings of the batch a key can belong to (a bit per ranking), so
+// a key costs one LDS read unless it shares its leading digit with a threshold.
+
+// Rankings of a batch whose prefix starts with each leading digit; built by one thread (<= 14 entries).
+__device__ inline void build_digit_table(u16* tab, const u32* prefix, const u32* active, int nj, int tid) {
+    const Level L0 = level_of(31, 0);
+    for (int i = tid; i < kBins; i += kBlock) tab[i] = 0;
+    __syncthreads();
+    if (tid == 0)
+        for (int j = 0; j < nj; ++j)
+            if (active[j]) tab[prefix[j] >> L0.shift] |= static_cast<u16>(1u << j);
+}
+
+// The workgroup is 256 threads, or 1024 (GLOBAL scope, several densities, past level 0): the J
+// histograms of 4 KB each allow few workgroups per compute unit, so wide ones keep enough wavefronts
+// resident; each quarter of a wide workgroup takes a chunk of its own.
 template <bool LC, bool VEC>
-__global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64 chunks_per_block) {
+__global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 chunks_per_block) {
     extern __shared__ u32 s_hist[];       // level 0: kBins words; later levels: min(J, kSlotBatch) x 1024 words
+    __shared__ u16 s_tab[kBins];
     __shared__ u32 s_prefix[kSlotBatch];
     __shared__ u32 s_active[kSlotBatch];
     __shared__ u32 s_any;
@@ -101,85 +118,125 @@ __global__ __launch_bounds__(kBlock) void k_hist_data(DataArgs a, int level, u64
     const u64 c1 = (c0 + chunks_per_block < a.n_chunks) ? c0 + chunks_per_block : a.n_chunks;
 
     const Level L = level_of(31, level);
+    const Level L0 = level_of(31, 0);
     const int nb = 1 << L.bits;
-    const int tid = threadIdx.x;
+    const int wide = static_cast<int>(blockDim.x);
+    const int n_sub = wide / kBlock;                      // quarters (1 in a 256-thread workgroup)
+    const int sub = static_cast<int>(threadIdx.x) / kBlock;
+    const int tid = static_cast<int>(threadIdx.x) % kBlock;
+    const int wtid = static_cast<int>(threadIdx.x);
     const int n_batches = (level == 0) ? 1 : (a.J + kSlotBatch - 1) / kSlotBatch;
+
+    auto count_key = [&](u32 key) {
+        if (level == 0) {
+            atomicAdd(&s_hist[key >> L.shift], 1u);
+        } else {
+            u32 m = s_tab[key >> L0.shift];
+            const u32 digit = (key >> L.shift) & (nb - 1);
+            while (m) {
+                const int j = __ffs(m) - 1;
+                m &= m - 1;
+                if (((key ^ s_prefix[j]) >> L.hi_shift) == 0) atomicAdd(&s_hist[j * nb + digit], 1u);
+            }
+        }
+    };
+    auto flush = [&](long long group, int j0, int n_hist) {
+        for (int i = wtid; i < n_hist * nb; i += wide) {
+            const u32 v = s_hist[i];
+            if (v) {
+                u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(group) * kBins + i
+                                        : a.histx + (static_cast<u64>(group) * a.J + j0 + i / nb) * kBins + (i % nb);
+                atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
+            }
+        }
+    };
 
     for (int batch = 0; batch < n_batches; ++batch) {
         const int j0 = batch * kSlotBatch;
         const int nj = (level == 0) ? a.J : ((a.J - j0 < kSlotBatch) ? a.J - j0 : kSlotBatch);
         const int n_hist = (level == 0) ? 1 : nj;
         long long cur_group = -1;
-        for (u64 c = c0; c < c1; ++c) {
-            const int t = static_cast<int>(a.chunk_map[c]);
-            const long long g = a.per_tensor ? t : 0;
+        for (u64 cb = c0; cb < c1; cb += n_sub) {         // uniform over the workgroup
+            // wide workgroups run under GLOBAL scope only, where every chunk belongs to group 0
+            const long long g = a.per_tensor ? static_cast<long long>(a.chunk_map[cb]) : 0;
             if (g != cur_group) {
                 if (cur_group >= 0) {                     // flush the previous group's counts
                     __syncthreads();
-                    for (int i = tid; i < n_hist * nb; i += kBlock) {
-                        const u32 v = s_hist[i];
-                        if (v) {
-                            u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(cur_group) * kBins + i
-                                                    : a.histx + (static_cast<u64>(cur_group) * a.J + j0 + i / nb) * kBins + (i % nb);
-                            atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
-                        }
-                    }
+                    flush(cur_group, j0, n_hist);
                 }
                 __syncthreads();
-                if (tid == 0) s_any = 0;
+                if (wtid == 0) s_any = 0;
                 __syncthreads();
                 if (level == 0) {
-                    if (tid < a.J && a.slots[g * a.J + tid].state == kSelecting) s_any = 1;
-                } else if (tid < nj) {
-                    const Slot& s = a.slots[g * a.J + j0 + tid];
-                    s_prefix[tid] = static_cast<u32>(s.prefix);
-                    s_active[tid] = (s.state == kSelecting) ? 1u : 0u;
+                    if (wtid < a.J && a.slots[g * a.J + wtid].state == kSelecting) s_any = 1;
+                } else if (wtid < nj) {
+                    const Slot& s = a.slots[g * a.J + j0 + wtid];
+                    s_prefix[wtid] = static_cast<u32>(s.prefix);
+                    s_active[wtid] = (s.state == kSelecting) ? 1u : 0u;
                     if (s.state == kSelecting) s_any = 1;
                 }
-                for (int i = tid; i < n_hist * nb; i += kBlock) s_hist[i] = 0;
+                for (int i = wtid; i < n_hist * nb; i += wide) s_hist[i] = 0;
+                if (level != 0) for (int i = wtid; i < kBins; i += wide) s_tab[i] = 0;
+                __syncthreads();
+                if (level != 0 && wtid == 0)
+                    for (int j = 0; j < nj; ++j)
+                        if (s_active[j]) s_tab[s_prefix[j] >> L0.shift] |= static_cast<u16>(1u << j);
                 __syncthreads();
                 cur_group = g;
             }
             if (!s_any) continue;
+            const u64 c = cb + sub;
+            if (c >= c1) continue;                        // no barrier below this point in the iteration
+            const int t = static_cast<int>(a.chunk_map[c]);
             const TensorDesc& td = a.td[t];
             const u64 base = (c - td.chunk_start) * kChunk;
-#pragma unroll 2
-            for (int q = 0; q < kQuadsPerThread; ++q) {
-                const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-                if (e0 >= td.n) break;
-                float v[4];
-                load4<VEC>(td.w, e0, td.n, v);
-                if (LC) {
-                    float l[4];
-                    load4<VEC>(td.lam, e0, td.n, l);
+            const u64 n = td.n;
+            if (VEC && base + kChunk <= n) {              // whole chunk inside the tensor: loads first
+                constexpr int kHalf = LC ? kQuadsPerThread / 2 : kQuadsPerThread;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                for (int h = 0; h < kQuadsPerThread / kHalf; ++h) {
+                    float4 wv[kHalf], lv[kHalf];
+#pragma unroll
+                    for (int q = 0; q < kHalf; ++q) {
+                        const u64 e0 = base + static_cast<u64>(h * kHalf + q) * (kBlock * 4) + tid * 4;
+                        wv[q] = *reinterpret_cast<const float4*>(td.w + e0);
+                        if (LC) lv[q] = *reinterpret_cast<const float4*>(td.lam + e0);
+                    }
+#pragma unroll
+                    for (int q = 0; q < kHalf; ++q) {
+                        float v[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
+                        if (LC) {
+                            const float l[4] = {lv[q].x, lv[q].y, lv[q].z, lv[q].w};
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                        }
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) count_key(mag_key(v[k]));
+                    }
                 }
+            } else {
+                for (int q = 0; q < kQuadsPerThread; ++q) {
+                    const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+                    if (e0 >= n) break;
+                    float v[4];
+                    load4<VEC>(td.w, e0, n, v);
+                    if (LC) {
+                        float l[4];
+                        load4<VEC>(td.lam, e0, n, l);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if (e0 + k >= td.n) break;
-                    const u32 key = mag_key(v[k]);
-                    if (level == 0) {
-                        atomicAdd(&s_hist[key >> L.shift], 1u);
-                    } else {
-                        const u32 digit = (key >> L.shift) & (nb - 1);
-                        for (int j = 0; j < nj; ++j)
-                            if (s_active[j] && ((key ^ s_prefix[j]) >> L.hi_shift) == 0)
-                                atomicAdd(&s_hist[j * nb + digit], 1u);
+                        for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (e0 + k >= n) break;
+                        count_key(mag_key(v[k]));
                     }
                 }
             }
         }
         if (cur_group >= 0) {
             __syncthreads();
-            for (int i = tid; i < n_hist * nb; i += kBlock) {
-                const u32 v = s_hist[i];
-                if (v) {
-                    u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(cur_group) * kBins + i
-                                            : a.histx + (static_cast<u64>(cur_group) * a.J + j0 + i / nb) * kBins + (i % nb);
-                    atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
-                }
-            }
+            flush(cur_group, j0, n_hist);
             __syncthreads();
         }
     }
@@ -253,54 +310,92 @@ __global__ __launch_bounds__(kBlock) void k_scan_level(Slot* slots, const u64* h
 
 template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
+    __shared__ u16 s_tab[kBins];
     __shared__ u32 s_T[kMaxJ];
     __shared__ u32 s_need[kMaxJ];
     __shared__ u32 s_cnt[kMaxJ];
     __shared__ u32 s_any;
     if (a.ctl->need_tie == 0) return;
+    const Level L0 = level_of(31, 0);
     const int tid = threadIdx.x;
+    long long cur_group = -1;
+    auto count_key = [&](u32 key) {
+        u32 m = s_tab[key >> L0.shift];
+        while (m) {
+            const int j = __ffs(m) - 1;
+            m &= m - 1;
+            if (key == s_T[j]) atomicAdd(&s_cnt[j], 1u);
+        }
+    };
     for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
         const int t = static_cast<int>(a.chunk_map[c]);
-        const u64 g = a.per_tensor ? t : 0;
+        const long long g = a.per_tensor ? t : 0;
         __syncthreads();
-        if (tid == 0) s_any = 0;
-        __syncthreads();
-        if (tid < a.J) {
-            const Slot& s = a.slots[g * a.J + tid];
-            s_T[tid] = static_cast<u32>(s.prefix);
-            s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
-            s_cnt[tid] = 0;
-            if (s_need[tid]) s_any = 1;
+        if (g != cur_group) {
+            if (tid == 0) s_any = 0;
+            __syncthreads();
+            if (tid < a.J) {
+                const Slot& s = a.slots[static_cast<u64>(g) * a.J + tid];
+                s_T[tid] = static_cast<u32>(s.prefix);
+                s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
+                if (s_need[tid]) s_any = 1;
+            }
+            __syncthreads();
+            build_digit_table(s_tab, s_T, s_need, a.J, tid);
+            cur_group = g;
         }
+        if (tid < a.J) s_cnt[tid] = 0;
         __syncthreads();
         if (!s_any) continue;
         const TensorDesc& td = a.td[t];
         const u64 base = (c - td.chunk_start) * kChunk;
-        for (int q = 0; q < kQuadsPerThread; ++q) {
-            const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
-            if (e0 >= td.n) break;
-            float v[4];
-            load4<VEC>(td.w, e0, td.n, v);
-            if (LC) {
-                float l[4];
-                load4<VEC>(td.lam, e0, td.n, l);
+        const u64 n = td.n;
+        if (VEC && base + kChunk <= n) {
+            constexpr int kHalf = LC ? kQuadsPerThread / 2 : kQuadsPerThread;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+            for (int h = 0; h < kQuadsPerThread / kHalf; ++h) {
+                float4 wv[kHalf], lv[kHalf];
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    const u64 e0 = base + static_cast<u64>(h * kHalf + q) * (kBlock * 4) + tid * 4;
+                    wv[q] = *reinterpret_cast<const float4*>(td.w + e0);
+                    if (LC) lv[q] = *reinterpret_cast<const float4*>(td.lam + e0);
+                }
+#pragma unroll
+                for (int q = 0; q < kHalf; ++q) {
+                    float v[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
+                    if (LC) {
+                        const float l[4] = {lv[q].x, lv[q].y, lv[q].z, lv[q].w};
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) count_key(mag_key(v[k]));
+                }
             }
+        } else {
+            for (int q = 0; q < kQuadsPerThread; ++q) {
+                const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
+                if (e0 >= n) break;
+                float v[4];
+                load4<VEC>(td.w, e0, n, v);
+                if (LC) {
+                    float l[4];
+                    load4<VEC>(td.lam, e0, n, l);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (e0 + k >= td.n) break;
-                const u32 key = mag_key(v[k]);
-                for (int j = 0; j < a.J; ++j)
-                    if (s_need[j] && key == s_T[j]) atomicAdd(&s_cnt[j], 1u);
+                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (e0 + k >= n) break;
+                    count_key(mag_key(v[k]));
+                }
             }
         }
         __syncthreads();
         if (tid < a.J && s_need[tid]) a.tiecnt[static_cast<u64>(tid) * a.n_chunks + c] = s_cnt[tid];
     }
 }
-
-// One workgroup per ranking: finishes the tie search (if any) and writes the public record.
 template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_select* results, int n_groups) {
     __shared__ u64 s_wave[kBlock / 64];

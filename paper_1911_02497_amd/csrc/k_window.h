@@ -377,8 +377,8 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
         float4 wv[QUADS], lv[QUADS];
 #pragma unroll
         for (int q = 0; q < QUADS; ++q) {
-            wv[q] = *reinterpret_cast<const float4*>(wp + base + q * 256 + lane * 4);
-            if (LC) lv[q] = *reinterpret_cast<const float4*>(lp + base + q * 256 + lane * 4);
+            wv[q] = ld4_stream(wp + base + q * 256 + lane * 4);
+            if (LC) lv[q] = ld4_stream(lp + base + q * 256 + lane * 4);
         }
 #pragma unroll
         for (int q = 0; q < QUADS; ++q) {
@@ -605,7 +605,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.cand_cap = L.cand_cap;
     w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
     w.seg_region = w.seg_cnt + kSegs;
-    constexpr int kWaveQuads = LC ? 4 : 8;                       // 8 KB of input per wavefront either way
+    constexpr int kWaveQuads = LC ? 4 : 8;                       // 8 KB of input per wavefront: measured best of 4, 8, 16 KB
     const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
