@@ -212,7 +212,7 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     dens = (ctypes.c_double * max(J, 1))(*[float(d) for d in densities])
     total = sum(t.numel() for t in tensors)
 
-    outputs = outputs or {}                      # preallocated [density][tensor] lists / record tensor to reuse
+    outputs = (outputs or {}).get("_buffers", {})    # ``outputs``: an earlier call's result, whose tensors are reused
 
     def outs(flag, dtype, name):
         if not flag:
@@ -236,27 +236,35 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
                               _stream(stream)))
     return {"theta": th, "theta_f16": th16, "mask": mk, "results": results[:n_rec], "workspace": ws,
-            "_keep": (k1, k2, k3)}
+            "_keep": (k1, k2, k3),
+            "_buffers": {"theta": None if in_place else th, "theta_f16": th16, "mask": mk, "results": results}}
 
 
-def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask, extra_args, workspace, stream):
+def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask, extra_args, workspace, stream,
+                    outputs=None):
     import torch
     lib = library()
     dev = tensors[0].device if tensors else torch.device("cuda")
     nt = len(tensors)
     tab = _tensor_table(tensors)
     total = sum(t.numel() for t in tensors)
-    th = [torch.empty_like(t) for t in tensors] if theta else None
-    mk = [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors] if mask else None
+    o = (outputs or {}).get("_buffers", {})      # ``outputs``: an earlier call's result, whose tensors are reused
+    F = max(n_struct, 1)
+    n_rec = nt if scope == SCOPE_PER_TENSOR else 1
+
+    def reuse(name, make):
+        return o[name] if o.get(name) is not None else make()
+
+    th = reuse("theta", lambda: [torch.empty_like(t) for t in tensors]) if theta else None
+    mk = reuse("mask", lambda: [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors]) if mask else None
     k1, p1 = _ptr_table(th)
     k2, p2 = _ptr_table(mk)
-    F = max(n_struct, 1)
-    sumsq = torch.empty(F, dtype=torch.float64, device=dev)
-    norms = torch.empty(F, dtype=torch.float32, device=dev)
-    keep_idx = torch.full((F,), -1, dtype=torch.int32, device=dev)
-    smask = torch.empty(F, dtype=torch.uint8, device=dev)
-    n_rec = nt if scope == SCOPE_PER_TENSOR else 1
-    results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
+    sumsq = reuse("sumsq", lambda: torch.empty(F, dtype=torch.float64, device=dev))
+    norms = reuse("norms", lambda: torch.empty(F, dtype=torch.float32, device=dev))
+    keep_idx = reuse("keep_idx", lambda: torch.empty(F, dtype=torch.int32, device=dev))
+    keep_idx.fill_(-1)
+    smask = reuse("structure_mask", lambda: torch.empty(F, dtype=torch.uint8, device=dev))
+    results = reuse("results", lambda: torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev))
     ws, need = _workspace(op, total, n_struct, nt, 1, scope, dev, workspace)
     args = [tab, nt] + extra_args + [float(density), scope, p1, p2, sumsq.data_ptr(), norms.data_ptr(),
                                      keep_idx.data_ptr(), smask.data_ptr(), results.data_ptr(), ws.data_ptr(),
@@ -264,36 +272,41 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
     _check(getattr(lib, fn_name)(*args))
     return {"theta": th, "mask": mk, "sumsq": sumsq[:n_struct], "norms": norms[:n_struct],
             "keep_idx": keep_idx[:n_struct], "structure_mask": smask[:n_struct], "results": results[:n_rec],
-            "workspace": ws, "_keep": (k1, k2)}
+            "workspace": ws, "_keep": (k1, k2),
+            "_buffers": {"theta": th, "mask": mk, "sumsq": sumsq, "norms": norms, "keep_idx": keep_idx,
+                         "structure_mask": smask, "results": results}}
 
 
-def condensa_filter_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+def condensa_filter_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
+                          outputs=None):
     n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
     return _structure_call("condensa_filter_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream)
+                           [], workspace, stream, outputs)
 
 
 def condensa_block_prune(tensors, block_h, block_w, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
-                         workspace=None, stream=None):
+                         workspace=None, stream=None, outputs=None):
     n_struct = sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2)
     return _structure_call("condensa_block_prune", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [int(block_h), int(block_w)], workspace, stream)
+                           [int(block_h), int(block_w)], workspace, stream, outputs)
 
 
-def condensa_neuron_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+def condensa_neuron_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
+                          outputs=None):
     n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
     return _structure_call("condensa_neuron_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream)
+                           [], workspace, stream, outputs)
 
 
-def condensa_structure_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None):
+def condensa_structure_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
+                             outputs=None):
     n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
     return _structure_call("condensa_structure_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream)
+                           [], workspace, stream, outputs)
 
 
 def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
-                            workspace=None, stream=None):
+                            workspace=None, stream=None, outputs=None):
     nd = len(block_shape)
     blk = (ctypes.c_int32 * max(nd, 1))(*[int(b) for b in block_shape])
     n_struct = 0
@@ -304,7 +317,7 @@ def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, t
                 c *= -(-d // max(int(b), 1))
             n_struct += c
     return _structure_call("condensa_block_prune_nd", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [blk, nd], workspace, stream)
+                           [blk, nd], workspace, stream, outputs)
 
 
 def condensa_quantize(x, want_q=True, want_dq=True, stream=None):

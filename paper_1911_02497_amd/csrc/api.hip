@@ -644,7 +644,14 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     if (tb.F > 0) {
         {
             PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st);
-            hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            // every structure one contiguous row (filters, neurons) of some length: staged, coalesced reads
+            bool rows = tb.N / tb.F >= 16;
+            for (int t = 0; t < n_tensors && rows; ++t) {
+                const TensorDesc& d = tb.td[t];
+                if (d.n > 0 && !(d.d[1] == 1 && d.d[2] == 1 && d.b[0] == 1 && d.b[3] == d.d[3])) rows = false;
+            }
+            if (rows) hipLaunchKernelGGL(k_struct_sumsq_rows, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else      hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             CONDENSA_LAUNCH_CHECK();
         }
         PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
@@ -721,6 +728,9 @@ static condensa_status add_structure_geometry(const condensa_tensor* tensors, in
                 }
             }
         }
+        d.fd[kDivD1] = make_fastdiv(d.d[1]); d.fd[kDivD2] = make_fastdiv(d.d[2]); d.fd[kDivD3] = make_fastdiv(d.d[3]);
+        d.fd[kDivB0] = make_fastdiv(d.b[0]); d.fd[kDivB1] = make_fastdiv(d.b[1]);
+        d.fd[kDivB2] = make_fastdiv(d.b[2]); d.fd[kDivB3] = make_fastdiv(d.b[3]);
         d.n_struct = f;
         F += f;
         sc += (f + kChunk - 1) / kChunk;

@@ -22,6 +22,32 @@ constexpr int kBins = 2048;            // bins of one radix level (digits are at
 constexpr u64 kMaxElems = static_cast<u64>(1) << 36;   // elements per call (keeps every grid below 2^31 workgroups)
 constexpr int kSlotBatch = 14;         // rankings that share one sweep's LDS histograms (14 x 1024 bins x 4 B + digit table < 64 KB)
 
+// Division of a 32-bit unsigned x by a divisor fixed on the host, by multiplication with a rounded-up
+// reciprocal (Granlund & Montgomery 1994, unsigned case): with l = ceil(log2 d) and
+// m = floor(2^32 (2^l - d) / d) + 1,  t = hi32(m x)  gives  x / d = (t + ((x - t) >> min(l, 1))) >> max(l - 1, 0).
+struct FastDiv {
+    u32 mul;
+    u32 sh;                // first shift | second shift << 8
+};
+
+__host__ __device__ inline FastDiv make_fastdiv(u32 d) {   // d >= 1
+    int l = 0;
+    while (l < 32 && (static_cast<u64>(1) << l) < d) ++l;
+    FastDiv f;
+    f.mul = static_cast<u32>(((static_cast<u64>(1) << 32) * ((static_cast<u64>(1) << l) - d)) / d + 1);
+    f.sh = static_cast<u32>(l < 1 ? l : 1) | (static_cast<u32>(l > 1 ? l - 1 : 0) << 8);
+    return f;
+}
+
+__host__ __device__ inline u32 fast_div(u32 x, FastDiv f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const u32 t = __umulhi(x, f.mul);
+#else
+    const u32 t = static_cast<u32>((static_cast<u64>(x) * f.mul) >> 32);
+#endif
+    return (t + ((x - t) >> (f.sh & 0xFFu))) >> (f.sh >> 8);
+}
+
 // One weight tensor as the kernels see it (device table, one entry per tensor plus a sentinel).
 struct TensorDesc {
     const float* w;
@@ -37,8 +63,11 @@ struct TensorDesc {
     u64 n_struct;          // structures in this tensor: product of ceil(d/b)
     u64 pad;               // id of this tensor's first structure chunk
     u64 reserved[2];
+    FastDiv fd[7];         // reciprocals of d[1], d[2], d[3], b[0], b[1], b[2], b[3] (structure pruning)
+    u64 reserved2;
 };
-static_assert(sizeof(TensorDesc) == 128, "TensorDesc layout");
+static_assert(sizeof(TensorDesc) == 192, "TensorDesc layout");
+enum { kDivD1 = 0, kDivD2, kDivD3, kDivB0, kDivB1, kDivB2, kDivB3 };
 
 struct OutDesc {           // outputs of tensor t for density j, entry j * n_tensors + t
     float* theta;

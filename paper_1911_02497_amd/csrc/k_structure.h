@@ -91,6 +91,89 @@ __global__ __launch_bounds__(kBlock) void k_struct_sumsq(StructArgs a, double* s
     if (norms) norms[u] = static_cast<float>(sqrt(acc));
 }
 
+// Row structures (filters, neurons: structure s of a tensor is the contiguous run [s L, (s+1) L) of its
+// memory): thread-per-structure loads would touch one cache line per lane, so the workgroup stages
+// 32-element pieces of its 256 rows through LDS with coalesced 128-bit loads (8 lanes per row piece) and
+// every thread then adds its own row's piece in memory order -- the same additions in the same order as
+// k_struct_sumsq.  Rows are padded to 33 words so that the per-thread reads hit distinct banks.
+constexpr int kRowTile = 32;
+
+__global__ __launch_bounds__(kBlock) void k_struct_sumsq_rows(StructArgs a, double* sumsq, float* norms) {
+    __shared__ float s_tile[kBlock][kRowTile + 1];
+    __shared__ const float* s_row[kBlock];
+    __shared__ u32 s_len[kBlock];
+    __shared__ u32 s_maxlen, s_minlen, s_aligned;
+    const int tid = threadIdx.x;
+    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + tid;
+    if (tid == 0) { s_maxlen = 0; s_minlen = 0xFFFFFFFFu; s_aligned = 1; }
+    __syncthreads();
+    u32 len = 0;
+    const float* row = nullptr;
+    if (u < a.F) {
+        const int t = tensor_of_struct(a.td, a.n_tensors, u);
+        const TensorDesc& td = a.td[t];
+        len = td.d[3];
+        row = td.w + (u - td.struct_start) * len;
+    }
+    s_row[tid] = row;
+    s_len[tid] = len;
+    atomicMax(&s_maxlen, len);
+    atomicMin(&s_minlen, len);                            // 0 when the last workgroup is ragged
+    if (row && (reinterpret_cast<uintptr_t>(row) & 15u)) atomicAnd(&s_aligned, 0u);
+    __syncthreads();
+    const u32 maxlen = s_maxlen;
+    const u32 fast_end = s_aligned ? (s_minlen / kRowTile) * kRowTile : 0;   // pieces below it: unguarded loads
+    const int seg = tid & 7, sub = tid >> 3;              // 8 lanes per row piece, 32 rows per pass
+    double acc = 0.0;
+    for (u32 cb = 0; cb < maxlen; cb += kRowTile) {
+        if (cb < fast_end) {
+            float4 v[8];
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass)
+                v[pass] = *reinterpret_cast<const float4*>(s_row[pass * 32 + sub] + cb + seg * 4);
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                float* dst = &s_tile[pass * 32 + sub][seg * 4];
+                dst[0] = v[pass].x; dst[1] = v[pass].y; dst[2] = v[pass].z; dst[3] = v[pass].w;
+            }
+        } else {
+            for (int pass = 0; pass < 8; ++pass) {
+                const int st = pass * 32 + sub;
+                const u32 L = s_len[st];
+                const float* p = s_row[st];
+                float* dst = &s_tile[st][seg * 4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const u32 x = cb + seg * 4 + k;
+                    dst[k] = (x < L) ? p[x] : 0.0f;
+                }
+            }
+        }
+        __syncthreads();
+        if (len > cb) {
+            const u32 m = (len - cb < static_cast<u32>(kRowTile)) ? len - cb : static_cast<u32>(kRowTile);
+            if (m == kRowTile) {
+#pragma unroll
+                for (int j = 0; j < kRowTile; ++j) {
+                    const double x = static_cast<double>(s_tile[tid][j]);
+                    acc = acc + x * x;
+                }
+            } else {
+                for (u32 j = 0; j < m; ++j) {
+                    const double x = static_cast<double>(s_tile[tid][j]);
+                    acc = acc + x * x;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (u < a.F) {
+        a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
+        if (sumsq) sumsq[u] = acc;
+        if (norms) norms[u] = static_cast<float>(sqrt(acc));
+    }
+}
+
 // Histogram of one radix level over the aggregate keys (one ranking per group).
 __global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u64 chunks_per_block) {
     __shared__ u32 s_hist[kBins];
@@ -307,56 +390,78 @@ __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const Out
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
-    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4) + tid * 4;
-    if (e0 >= td.n) return;
+    const u64 n = td.n;
+    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * (kBlock * 4);
+    if (wg0 >= n) return;                                                // uniform
+    const u64 e0 = wg0 + tid * 4;
+    const bool full = VEC && wg0 + kBlock * 4 <= n;                      // uniform: unguarded 128-bit accesses
+    if (!full && e0 >= n) return;
     const OutDesc o = out[t];
     const u8* __restrict__ sm = a.smask + td.struct_start;
     const u32 d1 = td.d[1], d2 = td.d[2], d3 = td.d[3];
     const u32 b0 = td.b[0], b1 = td.b[1], b2 = td.b[2], b3 = td.b[3];
-    const u32 G1 = (d1 + b1 - 1) / b1, G2 = (d2 + b2 - 1) / b2, G3 = (d3 + b3 - 1) / b3;
+    const u32 G1 = fast_div(d1 + b1 - 1, td.fd[kDivB1]), G2 = fast_div(d2 + b2 - 1, td.fd[kDivB2]),
+              G3 = fast_div(d3 + b3 - 1, td.fd[kDivB3]);
     float v[4];
-    load4<VEC>(td.w, e0, td.n, v);
-    // coordinates of the first element; the others follow by carrying along the last dimension
+    if (full) {
+        const float4 x = ld4_stream(td.w + e0);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    } else {
+        load4<VEC>(td.w, e0, n, v);
+    }
+    // Coordinates of the first element; the others follow by carrying along the last dimension.  Below
+    // 2^32 elements every quotient comes from the host's reciprocals (a hardware-free u32 division costs
+    // ~30 instructions, and a dozen of them per thread made this sweep ALU-bound).
+    const bool small = n <= 0xFFFFFFFFull;
     u64 r;
     u32 x3;
-    if (td.n <= 0xFFFFFFFFull) {
+    if (small) {
         const u32 e32 = static_cast<u32>(e0);
-        r = e32 / d3;
-        x3 = e32 % d3;
+        const u32 q = fast_div(e32, td.fd[kDivD3]);
+        r = q;
+        x3 = e32 - q * d3;
     } else {
         r = e0 / d3;
         x3 = static_cast<u32>(e0 % d3);
     }
     auto row_base = [&](u64 row) -> u64 {               // structure id of column block 0 in this row
-        u64 x2, x1, x0;
-        if (row <= 0xFFFFFFFFull) {
+        if (small) {
             const u32 r32 = static_cast<u32>(row);
-            x2 = r32 % d2;
-            const u32 q = r32 / d2;
-            x1 = q % d1;
-            x0 = q / d1;
-        } else {
-            x2 = row % d2;
-            const u64 q = row / d2;
-            x1 = q % d1;
-            x0 = q / d1;
+            const u32 q = fast_div(r32, td.fd[kDivD2]);
+            const u32 x2 = r32 - q * d2;
+            const u32 x0 = fast_div(q, td.fd[kDivD1]);
+            const u32 x1 = q - x0 * d1;
+            return ((static_cast<u64>(fast_div(x0, td.fd[kDivB0])) * G1 + fast_div(x1, td.fd[kDivB1])) * G2 +
+                    fast_div(x2, td.fd[kDivB2])) * G3;
         }
+        const u64 x2 = row % d2;
+        const u64 q = row / d2;
+        const u64 x1 = q % d1;
+        const u64 x0 = q / d1;
         return (((x0 / b0) * G1 + x1 / b1) * G2 + x2 / b2) * G3;
     };
     u64 gbase = row_base(r);
+    u32 cb = fast_div(x3, td.fd[kDivB3]);               // column block and position inside it
+    u32 xin = x3 - cb * b3;
     float th[4];
     u8 m[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        while (x3 >= d3) { x3 -= d3; ++r; gbase = row_base(r); }
+        if (x3 >= d3) { x3 = 0; cb = 0; xin = 0; ++r; gbase = row_base(r); }
         u8 keep = 0;
-        if (e0 + k < td.n) keep = sm[gbase + x3 / b3];
+        if (full || e0 + k < n) keep = sm[gbase + cb];
         m[k] = keep;
         th[k] = keep ? v[k] : 0.0f;
         ++x3;
+        if (++xin == b3) { xin = 0; ++cb; }
     }
-    if (o.theta) store4<VEC>(o.theta, e0, td.n, th);
-    if (o.mask) store4_u8<VEC>(o.mask, e0, td.n, m);
+    if (full) {
+        if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
+        if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+    } else {
+        if (o.theta) store4<VEC>(o.theta, e0, n, th);
+        if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
+    }
 }
 
 // Thinning gather: out[o', i', r] = w[keep_out[o'] - off_out, keep_in[i'] - off_in, r]; NULL list = identity.
