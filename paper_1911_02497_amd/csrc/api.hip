@@ -546,7 +546,7 @@ condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_ten
     if (rc != CONDENSA_OK) return rc;
     bool vec = true;
     for (int t = 0; t < n_tensors; ++t)
-        if (tb.td[t].n > 0 && (reinterpret_cast<uintptr_t>(tb.td[t].w) & (is_f16 ? 7u : 15u))) vec = false;
+        if (tb.td[t].n > 0 && (reinterpret_cast<uintptr_t>(tb.td[t].w) & 15u)) vec = false;
     std::vector<char> up(L.upload_bytes, 0);
     std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -834,11 +834,13 @@ condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_de
     if (x_dev == nullptr) return CONDENSA_ERR_NULL;
     const bool vec = aligned16(x_dev) && (!dq_dev || aligned16(dq_dev)) &&
                      (!q_dev || (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0);
-    u64 blocks = ((n + 3) / 4 + kBlock - 1) / kBlock;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    constexpr int QT = kQuantThreads;
+    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);           // <= 2^28 for n <= 2^36
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (vec) hipLaunchKernelGGL((k_quantize<true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, x_dev, n, q_dev, dq_dev);
-    else     hipLaunchKernelGGL((k_quantize<false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, x_dev, n, q_dev, dq_dev);
+    if (!dq_dev && aligned16(x_dev) && aligned16(q_dev))
+        hipLaunchKernelGGL((k_quantize_codes<QT>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, x_dev, n, q_dev);
+    else if (vec) hipLaunchKernelGGL((k_quantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
+    else     hipLaunchKernelGGL((k_quantize<false, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
 }
@@ -848,11 +850,11 @@ condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq
     if (n == 0) return CONDENSA_OK;
     if (dq_dev == nullptr || q_dev == nullptr) return CONDENSA_ERR_NULL;
     const bool vec = aligned16(dq_dev) && (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0;
-    u64 blocks = ((n + 3) / 4 + kBlock - 1) / kBlock;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    constexpr int QT = kQuantThreads;
+    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (vec) hipLaunchKernelGGL((k_dequantize<true>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, q_dev, n, dq_dev);
-    else     hipLaunchKernelGGL((k_dequantize<false>), dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, q_dev, n, dq_dev);
+    if (vec) hipLaunchKernelGGL((k_dequantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else     hipLaunchKernelGGL((k_dequantize<false, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
 }

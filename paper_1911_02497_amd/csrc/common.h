@@ -127,6 +127,7 @@ __device__ inline float lc_shift(float w, float lam, float mu) {
 // 128-bit accesses with the streaming (non-temporal) hint, for data that this call touches for the last
 // time: results that nothing re-reads before they leave the caches anyway, inputs on their final pass.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 __device__ inline float4 ld4_stream(const float* p) {
     const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     return make_float4(t.x, t.y, t.z, t.w);

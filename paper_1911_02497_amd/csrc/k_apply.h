@@ -188,14 +188,29 @@ __global__ __launch_bounds__(64) void k_lc_sgd(DataArgs a, const OutDesc* __rest
     if (c >= a.n_chunks) return;
     const int t = static_cast<int>(a.chunk_map[c]);
     const TensorDesc& td = a.td[t];
-    const u64 e0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * 256 + threadIdx.x * 4;
-    if (e0 >= td.n) return;
+    const u64 n = td.n;
+    const u64 wg0 = (c - td.chunk_start) * kChunk + static_cast<u64>(sub) * 256;
+    if (wg0 >= n) return;                                                // uniform
+    const u64 e0 = wg0 + threadIdx.x * 4;
+    const float* theta = out[t].theta;
+    const bool full = VEC && wg0 + 256 <= n;                             // uniform
     float w[4], g[4], th[4], l[4], b[4];
-    load4<VEC>(td.w, e0, td.n, w);
-    load4<VEC>(td.grad, e0, td.n, g);
-    load4<VEC>(out[t].theta, e0, td.n, th);
-    load4<VEC>(td.lam, e0, td.n, l);
-    load4<VEC>(td.lam_out, e0, td.n, b);
+    if (full) {
+        const float4 x0 = ld4_stream(td.w + e0), x1 = ld4_stream(td.grad + e0), x2 = ld4_stream(theta + e0),
+                     x3 = ld4_stream(td.lam + e0), x4 = ld4_stream(td.lam_out + e0);
+        w[0] = x0.x; w[1] = x0.y; w[2] = x0.z; w[3] = x0.w;
+        g[0] = x1.x; g[1] = x1.y; g[2] = x1.z; g[3] = x1.w;
+        th[0] = x2.x; th[1] = x2.y; th[2] = x2.z; th[3] = x2.w;
+        l[0] = x3.x; l[1] = x3.y; l[2] = x3.z; l[3] = x3.w;
+        b[0] = x4.x; b[1] = x4.y; b[2] = x4.z; b[3] = x4.w;
+    } else {
+        if (e0 >= n) return;
+        load4<VEC>(td.w, e0, n, w);
+        load4<VEC>(td.grad, e0, n, g);
+        load4<VEC>(theta, e0, n, th);
+        load4<VEC>(td.lam, e0, n, l);
+        load4<VEC>(td.lam_out, e0, n, b);
+    }
     float wn[4], bn[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -207,8 +222,13 @@ __global__ __launch_bounds__(64) void k_lc_sgd(DataArgs a, const OutDesc* __rest
         bn[k] = __fadd_rn(t5, t4);
         wn[k] = __fsub_rn(w[k], __fmul_rn(lr, bn[k]));
     }
-    store4<VEC>(td.lam_out, e0, td.n, bn);
-    store4<VEC>(const_cast<float*>(td.w), e0, td.n, wn);
+    if (full) {
+        st4_stream(td.lam_out + e0, bn[0], bn[1], bn[2], bn[3]);
+        st4_stream(const_cast<float*>(td.w) + e0, wn[0], wn[1], wn[2], wn[3]);
+    } else {
+        store4<VEC>(td.lam_out, e0, n, bn);
+        store4<VEC>(const_cast<float*>(td.w), e0, n, wn);
+    }
 }
 
 // ---- footprint objective: number of non-zero parameters (Evaluation, Objective 1) ---------------------
@@ -223,6 +243,27 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
         const int t = static_cast<int>(a.chunk_map[c]);
         const TensorDesc& td = a.td[t];
         const u64 base = (c - td.chunk_start) * kChunk;
+        if (!F16 && VEC && base + kChunk <= td.n) {       // whole chunk inside the tensor: loads first
+            float4 v[kQuadsPerThread];
+#pragma unroll
+            for (int q = 0; q < kQuadsPerThread; ++q) v[q] = ld4_stream(td.w + base + q * (kBlock * 4) + tid * 4);
+#pragma unroll
+            for (int q = 0; q < kQuadsPerThread; ++q)
+                cnt += (mag_key(v[q].x) != 0) + (mag_key(v[q].y) != 0) + (mag_key(v[q].z) != 0) + (mag_key(v[q].w) != 0);
+            continue;
+        }
+        if (F16 && VEC && base + kChunk <= td.n) {        // binary16: 8 codes per 128-bit load
+            const u16* p = reinterpret_cast<const u16*>(td.w);
+            u16x8 v[kQuadsPerThread / 2];
+#pragma unroll
+            for (int q = 0; q < kQuadsPerThread / 2; ++q)
+                v[q] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(p + base + q * (kBlock * 8) + tid * 8));
+#pragma unroll
+            for (int q = 0; q < kQuadsPerThread / 2; ++q)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) cnt += (v[q][k] & 0x7FFFu) != 0;
+            continue;
+        }
         for (int q = 0; q < kQuadsPerThread; ++q) {
             const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
             if (e0 >= td.n) break;

@@ -5,45 +5,83 @@
 
 namespace condensa {
 
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_quantize(const float* x, u64 n, u16* q, float* dq) {
-    const u64 n_quads = (n + 3) / 4;
-    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
-    for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x; i < n_quads; i += stride) {
-        const u64 e0 = i * 4;
-        float v[4];
+constexpr int kQuantThreads = 64;       // wavefront-sized workgroups measured best for these sweeps (64 vs 256)
+
+// One float4 per thread; workgroups that lie wholly inside the array use unguarded 128-bit accesses with
+// the streaming hint (nothing here is read twice).
+template <bool VEC, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_quantize(const float* x, u64 n, u16* q, float* dq) {   // dq may be x
+    const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 4);
+    const u64 e0 = wg0 + threadIdx.x * 4;
+    const bool full = VEC && wg0 + THREADS * 4 <= n;                     // uniform
+    float v[4];
+    if (full) {
+        const float4 t = ld4_stream(x + e0);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        if (e0 >= n) return;
         load4<VEC>(x, e0, n, v);
-        u16 h[4];
-        float d[4];
+    }
+    u16 h[4];
+    float d[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            h[k] = f32_to_f16_rne(v[k]);
-            d[k] = f16_bits_to_f32(h[k]);
+    for (int k = 0; k < 4; ++k) {
+        h[k] = f32_to_f16_rne(v[k]);
+        d[k] = f16_bits_to_f32(h[k]);
+    }
+    if (full) {
+        if (q) {
+            ushort4 hv;
+            hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
+            *reinterpret_cast<ushort4*>(q + e0) = hv;
         }
+        if (dq) st4_stream(dq + e0, d[0], d[1], d[2], d[3]);
+    } else {
         if (q) store4_u16<VEC>(q, e0, n, h);
         if (dq) store4<VEC>(dq, e0, n, d);
     }
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_dequantize(const u16* q, u64 n, float* dq) {
-    const u64 n_quads = (n + 3) / 4;
-    const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
-    for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x; i < n_quads; i += stride) {
-        const u64 e0 = i * 4;
-        u16 h[4];
-        if (VEC && e0 + 4 <= n) {
-            const ushort4 t = *reinterpret_cast<const ushort4*>(q + e0);
-            h[0] = t.x; h[1] = t.y; h[2] = t.z; h[3] = t.w;
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) h[k] = (e0 + k < n) ? q[e0 + k] : static_cast<u16>(0);
-        }
-        float d[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) d[k] = f16_bits_to_f32(h[k]);
-        store4<VEC>(dq, e0, n, d);
+// Codes only: eight elements per thread -- two loads in flight per lane and a full 128-bit store of the
+// codes (measured 76% of peak against 58% with four per thread; the reverse layout, two strided 128-bit
+// stores per lane, halves the rate, so the other kernels keep one float4 per thread).  Requires 16-byte
+// aligned x and q.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_quantize_codes(const float* __restrict__ x, u64 n, u16* __restrict__ q) {
+    const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 8);
+    const u64 e0 = wg0 + threadIdx.x * 8;
+    if (wg0 + THREADS * 8 <= n) {                                        // uniform
+        const float4 a = ld4_stream(x + e0);
+        const float4 b = ld4_stream(x + e0 + 4);
+        u16x8 h;
+        h[0] = f32_to_f16_rne(a.x); h[1] = f32_to_f16_rne(a.y); h[2] = f32_to_f16_rne(a.z); h[3] = f32_to_f16_rne(a.w);
+        h[4] = f32_to_f16_rne(b.x); h[5] = f32_to_f16_rne(b.y); h[6] = f32_to_f16_rne(b.z); h[7] = f32_to_f16_rne(b.w);
+        __builtin_nontemporal_store(h, reinterpret_cast<u16x8*>(q + e0));
+    } else {
+        for (int k = 0; k < 8; ++k)
+            if (e0 + k < n) q[e0 + k] = f32_to_f16_rne(x[e0 + k]);
     }
+}
+
+template <bool VEC, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_dequantize(const u16* __restrict__ q, u64 n, float* __restrict__ dq) {
+    const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 4);
+    const u64 e0 = wg0 + threadIdx.x * 4;
+    const bool full = VEC && wg0 + THREADS * 4 <= n;                     // uniform
+    u16 h[4];
+    if (full) {
+        const ushort4 t = *reinterpret_cast<const ushort4*>(q + e0);
+        h[0] = t.x; h[1] = t.y; h[2] = t.z; h[3] = t.w;
+    } else {
+        if (e0 >= n) return;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h[k] = (e0 + k < n) ? q[e0 + k] : static_cast<u16>(0);
+    }
+    float d[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) d[k] = f16_bits_to_f32(h[k]);
+    if (full) st4_stream(dq + e0, d[0], d[1], d[2], d[3]);
+    else      store4<VEC>(dq, e0, n, d);
 }
 
 }  // namespace condensa
