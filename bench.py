@@ -67,7 +67,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     """The small workloads (launch- and cache-bound): same JSON shape, step = one call of the entry point."""
     import oracle
     name = args.workload
-    up = lambda arrs: [torch.from_numpy(a).to(dev) for a in arrs]  # noqa: E731
+    up = lambda arrs: P.tensor_table([torch.from_numpy(a).to(dev) for a in arrs])  # noqa: E731  (marshalled once)
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
     prev = [None]                                # the first call allocates the outputs, later ones reuse them
     if name == "prune_stress":

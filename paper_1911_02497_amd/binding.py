@@ -133,7 +133,29 @@ def _stream(stream) -> int:
     return int(s.cuda_stream)
 
 
-def _tensor_table(tensors):
+class TensorTable(list):
+    """A list of weight tensors together with its marshalled ``condensa_tensor`` array.  Passing one
+    instead of a plain list to the calls below skips the per-call marshalling (it matters for models with
+    many small tensors, where the Python loop costs more than the GPU work).  The tensors must keep their
+    storage: a tensor that is reallocated needs a new table."""
+
+    def __init__(self, tensors):
+        super().__init__(tensors)
+        self._arr = _marshal_tensors(self)
+        self._total = sum(t.numel() for t in self)
+        self._cache = {}
+
+    def cached(self, key, make):
+        if key not in self._cache:
+            self._cache[key] = make()
+        return self._cache[key]
+
+
+def tensor_table(tensors) -> TensorTable:
+    return tensors if isinstance(tensors, TensorTable) else TensorTable(tensors)
+
+
+def _marshal_tensors(tensors):
     import torch
     arr = (Tensor * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
@@ -147,6 +169,18 @@ def _tensor_table(tensors):
         arr[i].ndim = t.dim()
         arr[i].reserved = 0
     return arr
+
+
+def _tensor_table(tensors):
+    return tensors._arr if isinstance(tensors, TensorTable) else _marshal_tensors(tensors)
+
+
+def _total(tensors) -> int:
+    return tensors._total if isinstance(tensors, TensorTable) else sum(t.numel() for t in tensors)
+
+
+def _cached(tensors, key, make):
+    return tensors.cached(key, make) if isinstance(tensors, TensorTable) else make()
 
 
 def _ptr_table(tensors: Optional[Sequence]):
@@ -210,7 +244,7 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     nt, J = len(tensors), len(densities)
     tab = _tensor_table(tensors)
     dens = (ctypes.c_double * max(J, 1))(*[float(d) for d in densities])
-    total = sum(t.numel() for t in tensors)
+    total = _total(tensors)
 
     outputs = (outputs or {}).get("_buffers", {})    # ``outputs``: an earlier call's result, whose tensors are reused
 
@@ -247,7 +281,7 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
     dev = tensors[0].device if tensors else torch.device("cuda")
     nt = len(tensors)
     tab = _tensor_table(tensors)
-    total = sum(t.numel() for t in tensors)
+    total = _total(tensors)
     o = (outputs or {}).get("_buffers", {})      # ``outputs``: an earlier call's result, whose tensors are reused
     F = max(n_struct, 1)
     n_rec = nt if scope == SCOPE_PER_TENSOR else 1
@@ -257,8 +291,7 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
 
     th = reuse("theta", lambda: [torch.empty_like(t) for t in tensors]) if theta else None
     mk = reuse("mask", lambda: [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors]) if mask else None
-    k1, p1 = _ptr_table(th)
-    k2, p2 = _ptr_table(mk)
+    k1, p1, k2, p2 = reuse("_tables", lambda: _ptr_table(th) + _ptr_table(mk))
     sumsq = reuse("sumsq", lambda: torch.empty(F, dtype=torch.float64, device=dev))
     norms = reuse("norms", lambda: torch.empty(F, dtype=torch.float32, device=dev))
     keep_idx = reuse("keep_idx", lambda: torch.empty(F, dtype=torch.int32, device=dev))
@@ -274,33 +307,34 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
             "keep_idx": keep_idx[:n_struct], "structure_mask": smask[:n_struct], "results": results[:n_rec],
             "workspace": ws, "_keep": (k1, k2),
             "_buffers": {"theta": th, "mask": mk, "sumsq": sumsq, "norms": norms, "keep_idx": keep_idx,
-                         "structure_mask": smask, "results": results}}
+                         "structure_mask": smask, "results": results, "_tables": (k1, p1, k2, p2)}}
 
 
 def condensa_filter_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
                           outputs=None):
-    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_filter_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
                            [], workspace, stream, outputs)
 
 
 def condensa_block_prune(tensors, block_h, block_w, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
                          workspace=None, stream=None, outputs=None):
-    n_struct = sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2)
+    n_struct = _cached(tensors, ("blocks", block_h, block_w),
+                       lambda: sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2))
     return _structure_call("condensa_block_prune", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
                            [int(block_h), int(block_w)], workspace, stream, outputs)
 
 
 def condensa_neuron_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
                           outputs=None):
-    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_neuron_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
                            [], workspace, stream, outputs)
 
 
 def condensa_structure_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
                              outputs=None):
-    n_struct = sum(t.shape[0] if t.numel() else 0 for t in tensors)
+    n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_structure_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
                            [], workspace, stream, outputs)
 
@@ -349,7 +383,7 @@ def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=Fa
     dev = tensors[0].device if tensors else torch.device("cuda")
     nt = len(tensors)
     tab = _tensor_table(tensors)
-    total = sum(t.numel() for t in tensors)
+    total = _total(tensors)
     outputs = outputs or {}
     th = outputs.get("theta") or ([torch.empty_like(t) for t in tensors] if theta else None)
     gr = outputs.get("grad") or ([torch.empty_like(t) for t in tensors] if grad else None)
@@ -401,7 +435,7 @@ def condensa_count_nonzero(tensors, workspace=None, stream=None):
         for d in range(t.dim()):
             arr[i].shape[d] = t.shape[d]
         arr[i].ndim = t.dim()
-    total = sum(t.numel() for t in tensors)
+    total = _total(tensors)
     count = torch.zeros(1, dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_COUNT_NONZERO, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
     _check(lib.condensa_count_nonzero(arr, nt, is_f16, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
@@ -439,7 +473,7 @@ def condensa_lc_sgd_step(tensors, grad_loss, theta, lambdas, momentum_buf, mu, l
     dev = tensors[0].device if tensors else torch.device("cuda")
     nt = len(tensors)
     tab = _tensor_table(tensors)
-    total = sum(t.numel() for t in tensors)
+    total = _total(tensors)
     k1, p1 = _ptr_table(grad_loss)
     k2, p2 = _ptr_table(theta)
     k3, p3 = _ptr_table(lambdas)

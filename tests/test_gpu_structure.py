@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_1911_02497_amd as P
 import workloads
-from gpu_util import DEV, assert_bits_equal, assert_select_equal, up
+from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
 
 pytestmark = pytest.mark.gpu
 
@@ -160,3 +160,23 @@ def test_new_structure_entry_points_reject_bad_shapes():
         with pytest.raises(P.CondensaError) as e:
             call()
         assert e.value.code == -4
+
+
+def test_marshalled_table_and_reused_outputs_give_the_same_results():
+    """A TensorTable (tensors marshalled once) and an earlier result's tensors passed as ``outputs`` must
+    not change anything: second and third calls against the oracle, buffers identical to the first's."""
+    arrs = workloads.resnet56_cifar_convs()
+    table = P.tensor_table(up(arrs))
+    ora = oracle.filter_prune(arrs, 0.3, P.SCOPE_GLOBAL)
+    first = P.condensa_filter_prune(table, 0.3, P.SCOPE_GLOBAL)
+    for density in (0.7, 0.3):                    # a different density in between overwrites every buffer
+        res = P.condensa_filter_prune(table, density, P.SCOPE_GLOBAL, outputs=first)
+    torch.cuda.synchronize()
+    assert res["theta"][0].data_ptr() == first["theta"][0].data_ptr()
+    _compare(res, ora, P.SCOPE_GLOBAL, arrs, "reused outputs")
+
+    pr = P.condensa_prune(table, [0.1, 0.5])
+    pr2 = P.condensa_prune(table, [0.1, 0.5], outputs=pr)
+    torch.cuda.synchronize()
+    assert pr2["mask"][1][0].data_ptr() == pr["mask"][1][0].data_ptr()
+    check_prune_against_oracle(pr2, oracle.prune(arrs, [0.1, 0.5], P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, len(arrs), "reused outputs")
