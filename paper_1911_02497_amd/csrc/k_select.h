@@ -15,8 +15,10 @@ struct Control {
     u64 cand_count;        // candidates written by the window sweep (may exceed the capacity)
     u64 sample_count;      // valid sample elements
     u64 above[kMaxJ];      // window sweep: keys above each window's upper bound
-    u64 pad[4];
+    u64 tie_count;         // candidates equal to the threshold (the tie list holds the first tie_cap)
+    u64 pad[3];
 };
+static_assert(sizeof(Control) == 32 + 8 * kMaxJ + 32, "Control layout");
 
 struct DataArgs {
     const TensorDesc* td;

@@ -34,6 +34,8 @@ struct WindowArgs {
     u64 stride;            // sample positions are one per stride of quads
     u64 cand_cap;
     int margin16;
+    u64* tie_list;         // [tie_cap] flat indices of the candidates equal to the threshold (one density)
+    u64 tie_cap;
 };
 
 struct ArrayArgs {
@@ -48,6 +50,9 @@ struct ArrayArgs {
     u64* hist;             // [n_slots][kBins]
     u64* shared0;          // NULL, or: all rankings have the same filter and no prefix at level 0, count once here
     const u32* gate;       // NULL, or skip the kernel when *gate == 0
+    const u64* alt_idx;    // index ranking: NULL, or a short list holding exactly the entries that take part,
+    const u64* alt_cnt;    //   used instead of the array when it is complete (*alt_cnt <= alt_cap)
+    u64 alt_cap;
     int n_slots;
     int key_bits;
 };
@@ -138,6 +143,9 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
     __shared__ u32 s_lo[kArrayBatchMax], s_hi[kArrayBatchMax], s_active[kArrayBatchMax];
     __shared__ u32 s_any;
     if (a.gate && *a.gate == 0) return;
+    const bool use_alt = IDX && a.alt_cnt != nullptr && *a.alt_cnt <= a.alt_cap;
+    const u64 alt_n = use_alt ? *a.alt_cnt : 0;
+    if (use_alt && static_cast<u64>(blockIdx.x) * kBlock >= alt_n) return;      // nothing for this workgroup
     const Level L = level_of(a.key_bits, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
@@ -201,7 +209,14 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
                 }
             }
         };
-        if (a.seg_cnt) {
+        if (use_alt) {                                   // every listed entry passes the key filter
+            for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < alt_n; i += static_cast<u64>(gridDim.x) * kBlock) {
+                const u64 rk = a.N - 1 - a.alt_idx[i];
+                const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
+                for (int j = 0; j < nj; ++j)
+                    if (s_active[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0) atomicAdd(&my_hist[j * nb + digit], 1u);
+            }
+        } else if (a.seg_cnt) {
             for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
                 u64 cnt = a.seg_cnt[seg];
                 if (cnt > a.seg_cap) cnt = a.seg_cap;
@@ -457,6 +472,37 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
     }
 }
 
+// Flat indices of the candidates equal to the threshold, for the index ranking; one reservation per
+// wavefront.  The count keeps running past the capacity so that an incomplete list is recognised.
+__global__ __launch_bounds__(kBlock) void k_window_collect(DataArgs a, WindowArgs w) {
+    if (a.ctl->need_tie_w == 0) return;
+    const Slot& slot = a.slots[0];
+    if (!(slot.state == kDone && slot.need_tie)) return;
+    const u32 T = static_cast<u32>(slot.prefix);
+    const int lane = threadIdx.x & 63;
+    for (u32 seg = blockIdx.x; seg < w.n_segs; seg += gridDim.x) {
+        u64 cnt = w.seg_cnt[seg];
+        if (cnt > w.seg_cap) cnt = w.seg_cap;
+        const u64 first = static_cast<u64>(seg) * w.seg_cap;
+        const u64 rounds = (cnt + kBlock - 1) / kBlock;    // uniform over the workgroup
+        for (u64 r = 0; r < rounds; ++r) {
+            const u64 i = r * kBlock + threadIdx.x;
+            const bool hit = (i < cnt) && w.cand_key[first + i] == T;
+            const u64 ballot = __ballot(hit);
+            if (ballot == 0) continue;                     // uniform over the wavefront
+            const u32 n_hit = static_cast<u32>(__popcll(ballot));
+            const int leader = __ffsll(static_cast<long long>(ballot)) - 1;
+            u64 b = 0;
+            if (lane == leader) b = atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->tie_count), static_cast<unsigned long long>(n_hit));
+            const u32 blo = __shfl(static_cast<u32>(b), leader, 64), bhi = __shfl(static_cast<u32>(b >> 32), leader, 64);
+            if (hit) {
+                const u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + __popcll(ballot & ((static_cast<u64>(1) << lane) - 1));
+                if (pos < w.tie_cap) w.tie_list[pos] = w.cand_idx[first + i];
+            }
+        }
+    }
+}
+
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
     __shared__ u64 s_wave[kBlock / 64];
@@ -611,6 +657,8 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
     w.margin16 = static_cast<int>(m);
+    w.tie_list = reinterpret_cast<u64*>(base + L.sample);        // the sample is dead once its ranking is done
+    w.tie_cap = L.sample_cap / 2;
     u64* hist_main = a.histx;                                    // [J]
     u64* hist_aux = a.histx + static_cast<u64>(a.J) * kBins;     // [2J]
     condensa_status rc;
@@ -646,12 +694,18 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     hipLaunchKernelGGL(k_window_tie_setup, dim3(1), dim3(kBlock), 0, st, a, w);
     CONDENSA_LAUNCH_CHECK();
+    if (a.J == 1) {
+        // the index search then runs on the short list of ties instead of the whole candidate list
+        hipLaunchKernelGGL(k_window_collect, dim3(array_grid(static_cast<u64>(w.n_segs) * kBlock * 8)), dim3(kBlock), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+    }
     {
         ArrayArgs ar{};
         ar.keys = w.cand_key; ar.idx = w.cand_idx; ar.seg_cnt = w.seg_cnt; ar.seg_cap = w.seg_cap; ar.n_segs = w.n_segs;
         ar.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; ar.N = a.N;
         ar.slots = w.wslots; ar.n_slots = a.J; ar.hist = hist_aux; ar.key_bits = bits_for(a.N - 1);
         ar.gate = &a.ctl->need_tie_w;
+        if (a.J == 1) { ar.alt_idx = w.tie_list; ar.alt_cnt = &a.ctl->tie_count; ar.alt_cap = w.tie_cap; }
         rc = rank_array<true>(ar, a.ctl, &a.ctl->unused_flag, st);
         if (rc != CONDENSA_OK) return rc;
     }

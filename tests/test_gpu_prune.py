@@ -128,3 +128,18 @@ def test_argument_errors_have_no_side_effects():
         P.condensa_prune([w], [0.5], scope=7)
     assert e.value.code == -6
     assert torch.all(w == 1)
+
+
+@pytest.mark.parametrize("levels,n", [(8, (1 << 22) + 12345), (256, (1 << 24) + 77), (3, 300001)])
+def test_few_distinct_values_far_apart(levels, n, select_path):
+    """Quantised-looking weights: few distinct magnitudes, far apart in key space, each with a huge number
+    of ties.  With 256 levels (16M weights) the sampled window spans a few levels whose keys are ~2^19
+    apart and the ~65000 ties at the threshold are only partly kept (index search on the tie list); with
+    8 or 3 levels one level alone overflows the candidate list and the radix levels take over."""
+    rng = np.random.default_rng(levels)
+    table = (0.37 * (1.9 if levels <= 8 else 1.05) ** np.arange(levels)).astype(np.float32)
+    w = (table[rng.integers(0, levels, n)] * rng.choice(np.array([-1.0, 1.0], np.float32), n)).astype(np.float32)
+    for density in ((0.5, 0.123) if levels == 256 else (0.5, 1.0 / levels, 0.123, 0.999)):
+        res, _ = _prune_both([w[: n // 3], w[n // 3:]], [density], what=f"{levels} levels d={density}")
+        if select_path == "window" and levels == 256:
+            assert P.select_records(res["results"])[0]["path"] == 2, "expected to resolve inside the window"
