@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 # kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
 MEASURED_TRAFFIC = {"bytes": 24166108438, "tensors": 64,
                     "sources_sha256": "8319c434fe5e0baf187196e70359a1b73b7c0adb806a601553dadbccbe996430"}
-KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_apply.h")
+KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 
 
 def kernel_sources_hash():
@@ -60,6 +60,8 @@ def parse():
                              "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
                     help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
+    ap.add_argument("--two-sweeps", action="store_true",
+                    help="window path: separate selection and apply sweeps (default: one sweep does both)")
     return ap.parse_args()
 
 
@@ -69,6 +71,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     name = args.workload
     up = lambda arrs: P.tensor_table([torch.from_numpy(a).to(dev) for a in arrs])  # noqa: E731  (marshalled once)
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
     prev = [None]                                # the first call allocates the outputs, later ones reuse them
     if name == "prune_stress":
         # global magnitude pruning of the large-model weights (no multipliers): theta + mask at density 0.1
@@ -201,6 +204,7 @@ def main():
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
     P.condensa_set_option(P.OPT_APPLY_THREADS, args.apply_threads)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
 
     def step():
         return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,
@@ -216,7 +220,7 @@ def main():
         torch.cuda.synchronize()
 
     P.condensa_profile_reset()
-    P.condensa_set_option(P.OPT_PROFILE, 0x1F if args.all_phases else (1 << 3))
+    P.condensa_set_option(P.OPT_PROFILE, 0x1F if args.all_phases else ((1 << 3) | (1 << 1)))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -230,20 +234,24 @@ def main():
     rec = P.select_records(outputs["results"])[0]
     assert rec["k"] == int(np.floor(density * N + 0.5)) and rec["n"] == N, rec
 
-    # ---- roofline of the dominant kernel: the fused apply/update sweep -------------------------------
-    # algorithmic bytes per element of that launch: read w, lambda (8) + write theta, lambda', g (12) [+1 mask]
-    apply_bytes_per_elem = 20 + (1 if args.mask else 0)
-    step_bytes_per_elem = 28 + (1 if args.mask else 0)      # plus the one selection read of w, lambda
-    apply = phases["apply"]
-    apply_ms = apply["ms"] / max(apply["intervals"], 1)
-    achieved = apply_bytes_per_elem * N / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0
+    # ---- roofline of the dominant kernel --------------------------------------------------------------
+    # One-sweep window path (default): k_window_fused reads w, lambda (8 B) and writes theta, lambda', g
+    # (12 B) [+1 mask] per weight, and that is also all the step needs.  Two sweeps (radix path, or
+    # --two-sweeps): k_lc_apply moves the same 20 B and the selection reads w, lambda once more (28 B a step).
+    one_sweep = rec["path"] == 2 and not args.two_sweeps
+    kernel_bytes_per_elem = 20 + (1 if args.mask else 0)
+    step_bytes_per_elem = kernel_bytes_per_elem + (0 if one_sweep else 8)
+    kernel_name, phase = ("k_window_fused", "sweep") if one_sweep else ("k_lc_apply", "apply")
+    kp = phases[phase]
+    kernel_ms = kp["ms"] / max(kp["intervals"], 1)
+    achieved = kernel_bytes_per_elem * N / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     traffic = None
-    if (T == MEASURED_TRAFFIC["tensors"] and not args.mask
+    if (T == MEASURED_TRAFFIC["tensors"] and not args.mask and one_sweep
             and kernel_sources_hash() == MEASURED_TRAFFIC["sources_sha256"]):
         traffic = MEASURED_TRAFFIC["bytes"]
-    roofline = {"bound": "hbm", "kernel": "k_lc_apply", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "avg_launch_ms": round(apply_ms, 4), "algorithmic_bytes_per_launch": apply_bytes_per_elem * N}
+                "avg_launch_ms": round(kernel_ms, 4), "algorithmic_bytes_per_launch": kernel_bytes_per_elem * N}
     step_gbps = step_bytes_per_elem * N / (ms_per_step * 1e-3) / 1e9
     phase_ms = {k: round(v["ms"] / args.steps, 4) for k, v in phases.items() if v["intervals"]}
 
@@ -275,6 +283,7 @@ def main():
         "config": {"workload": f"L-C compression step, {T} fp32 tensors of {rows}x{cols} ({N} weights) + multipliers, "
                                f"mu={mu}, density={density}, outputs theta/lambda'/grad" + ("/mask" if args.mask else ""),
                    "select_path": {1: "radix", 2: "window"}.get(rec["path"], str(rec["path"])),
+                   "sweeps_over_the_weights": 1 if one_sweep else (2 if rec["path"] == 2 else 4),
                    "threshold_key": rec["threshold_key"], "n_tie": rec["n_tie"]},
         "step_algorithmic_GBps": round(step_gbps, 1),
         "step_frac_of_hbm_peak": round(step_gbps / HBM_PEAK_GBPS, 4),

@@ -318,7 +318,9 @@ enum {
     CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
     CONDENSA_OPT_PROFILE       = 4, /* bit p set: bracket phase p of every call with HIP events on the call's stream */
     CONDENSA_OPT_APPLY_THREADS = 5, /* workgroup size of the L-C apply sweep: 0 (default = 64), 64, 128 or 256 */
-    CONDENSA_OPT_COUNT         = 6
+    CONDENSA_OPT_FUSED_SWEEP   = 6, /* window path with one density: 0 = selection and apply share one sweep
+                                       when the outputs do not alias the inputs, 1 = always two sweeps   */
+    CONDENSA_OPT_COUNT         = 7
 };
 condensa_status condensa_set_option(int option, int64_t value);
 int64_t         condensa_get_option(int option);

@@ -3,6 +3,7 @@
 #include "host.h"
 #include "k_apply.h"
 #include "k_quantize.h"
+#include "k_fused.h"
 #include "k_select.h"
 #include "k_structure.h"
 #include "k_window.h"
@@ -10,7 +11,7 @@
 namespace condensa {
 
 std::atomic<int> g_last_hip_error{0};
-std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {112}, {0}, {0}, {0}};
+std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {112}, {0}, {0}, {0}, {0}};
 
 // ---- pinned staging ring -------------------------------------------------------------------------
 
@@ -154,6 +155,10 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
         L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
         L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));
+        if (J == 1) {
+            L.cand_w = off;   off += align_up(L.cand_cap * sizeof(float));
+            L.cand_lam = off; off += align_up(L.cand_cap * sizeof(float));
+        }
     }
     L.total = off;
     return L;
@@ -233,7 +238,8 @@ static unsigned fill_grid(u64 words) {
 template <bool LC, bool VEC>
 static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st) {
     if (a.n_chunks > 0) {
-        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
+        // as the gated fallback of the window path these launches are (normally empty) resolve work
+        PhaseTimer timer(a.only_failed ? CONDENSA_PHASE_RESOLVE : CONDENSA_PHASE_SWEEP, st);
         for (int level = 0; level < n_levels(31); ++level) {
             // Past level 0 every workgroup holds J histograms and flushes their non-zero bins with global
             // atomics: with several densities, few wide workgroups keep that flush small.
@@ -274,10 +280,11 @@ static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, i
 
 template <bool LC, bool VEC>
 static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool use_window, int n_slots,
-                                     int n_groups, condensa_select* results, hipStream_t st) {
+                                     int n_groups, condensa_select* results, hipStream_t st,
+                                     const FusedRequest* fused = nullptr) {
     condensa_status rc;
     if (use_window) {
-        rc = launch_window_path<LC, VEC>(a, L, ws, st);
+        rc = launch_window_path<LC, VEC>(a, L, ws, st, fused);
         if (rc != CONDENSA_OK) return rc;
         a.only_failed = 1;
     }
@@ -393,11 +400,28 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     a.only_failed = 0;
     a.mu = 0.0f;
 
-    rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st)
-                : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st);
+    // One density on the window path: selection and apply share one sweep unless theta overwrites the weights.
+    bool fuse = window && J == 1 && any_out && tb.n_chunks > 0 && slots[0].k > 0 &&
+                g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
+    for (int t = 0; t < n_tensors && fuse; ++t)
+        if (out[t].theta == tb.td[t].w && tb.td[t].n > 0) fuse = false;
+    WindowArgs wargs{};
+    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, &wargs};
+    rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr)
+                : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
 
-    if (any_out && tb.n_chunks > 0) {
+    if (fuse) {
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+        hipLaunchKernelGGL((k_window_fixup<false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
+        CONDENSA_LAUNCH_CHECK();
+        const u64 n_tiles = tb.n_chunks * kSubPerChunk;
+        const unsigned grid = static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096);
+        if (vec) hipLaunchKernelGGL((k_prune_apply_gated<true>), dim3(grid), dim3(kBlock), 0, st, a, od, n_tiles);
+        else     hipLaunchKernelGGL((k_prune_apply_gated<false>), dim3(grid), dim3(kBlock), 0, st, a, od, n_tiles);
+        CONDENSA_LAUNCH_CHECK();
+    } else if (any_out && tb.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
@@ -489,11 +513,28 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     bool vec_in = tb.vec;
     for (int t = 0; t < n_tensors; ++t)
         if (tb.td[t].n > 0 && !aligned16(tb.td[t].lam)) vec_in = false;
-    rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st)
-                : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st);
+    // Window path: selection and apply share one sweep unless lambda is updated in place (a failed window
+    // needs the inputs again) or theta is also wanted in binary16.
+    bool fuse = window && !pq && tb.n_chunks > 0 && slot.k > 0 && g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
+    for (int t = 0; t < n_tensors && fuse; ++t)
+        if (tb.td[t].n > 0 && tb.td[t].lam_out == tb.td[t].lam) fuse = false;
+    WindowArgs wargs{};
+    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, &wargs};
+    rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr)
+                : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
 
-    if (tb.n_chunks > 0) {
+    if (fuse) {
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+        hipLaunchKernelGGL((k_window_fixup<true>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
+        CONDENSA_LAUNCH_CHECK();
+        const u64 n_tiles = tb.n_chunks * (kChunk / 256);
+        const unsigned grid = static_cast<unsigned>(n_tiles < 16384 ? n_tiles : 16384);
+        if (vec) hipLaunchKernelGGL((k_lc_apply_gated<true>), dim3(grid), dim3(64), 0, st, a, od, n_tiles);
+        else     hipLaunchKernelGGL((k_lc_apply_gated<false>), dim3(grid), dim3(64), 0, st, a, od, n_tiles);
+        CONDENSA_LAUNCH_CHECK();
+    } else if (tb.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         const int64_t at_opt = g_options[CONDENSA_OPT_APPLY_THREADS].load();

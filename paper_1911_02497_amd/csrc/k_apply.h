@@ -19,12 +19,12 @@ __device__ inline bool keep_rule(u32 key, u32 T, u64 idx, u64 tie_end) {
 // accesses; the selection record and the output table are read before the data so that their latency
 // overlaps the data loads.
 template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDesc* __restrict__ out) {
+__device__ inline void prune_apply_tile(const DataArgs& a, const OutDesc* __restrict__ out, u64 tile) {
     __shared__ u32 s_T[kMaxJ];
     __shared__ u64 s_end[kMaxJ];
     __shared__ OutDesc s_out[kMaxJ];
-    const u64 c = blockIdx.x / kSubPerChunk;
-    const u32 sub = blockIdx.x % kSubPerChunk;
+    const u64 c = tile / kSubPerChunk;
+    const u32 sub = static_cast<u32>(tile % kSubPerChunk);
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
@@ -87,6 +87,11 @@ __global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDes
     }
 }
 
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_prune_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    prune_apply_tile<VEC>(a, out, blockIdx.x);
+}
+
 // theta = C(w - lambda/mu) entries, lambda' = lambda - mu (w - theta), g = mu (w - theta) - lambda',
 // each operation rounded once in binary32.  THREADS threads per workgroup, one float4 each.
 // PQ: the composed scheme Compose([Prune(), Quantize(float16)]) -- theta is rounded to binary16 and the
@@ -113,12 +118,12 @@ __device__ inline void lc_update4(const float w[4], const float l[4], float mu, 
     }
 }
 
-template <bool VEC, int THREADS, bool PQ, int QUADS = 1>
-__global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
+template <bool VEC, int THREADS, bool PQ, int QUADS>
+__device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restrict__ out, u64 tile) {
     constexpr u32 kTile = THREADS * 4 * QUADS;
     constexpr u32 kSub = kChunk / kTile;
-    const u64 c = blockIdx.x / kSub;
-    const u32 sub = blockIdx.x % kSub;
+    const u64 c = tile / kSub;
+    const u32 sub = static_cast<u32>(tile % kSub);
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
@@ -174,6 +179,11 @@ __global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc*
             if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
         }
     }
+}
+
+template <bool VEC, int THREADS, bool PQ, int QUADS = 1>
+__global__ __launch_bounds__(THREADS) void k_lc_apply(DataArgs a, const OutDesc* __restrict__ out) {
+    lc_apply_tile<VEC, THREADS, PQ, QUADS>(a, out, blockIdx.x);
 }
 
 // ---- learning-step update with the penalty gradient folded in -----------------------------------------

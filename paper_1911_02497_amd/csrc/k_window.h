@@ -19,6 +19,8 @@ constexpr int kSampleUnit = 4;         // consecutive elements read at one sampl
 constexpr int kArrayWords = 4 * kBins;  // LDS histogram words of the array kernels (32 KB)
 constexpr int kArrayBatchMax = 8;      // at most this many rankings per pass over a key array
 constexpr u32 kNoKey = 0xFFFFFFFFu;    // marks sample entries that fell past the end of a tensor
+constexpr int kArrayThreads = 1024;     // workgroup of the array kernels: wide, so that few workgroups flush their
+                                       // LDS histograms with (slow, memory-side) global atomics
 constexpr int kSegs = 1024;            // candidate list segments / counter sets (see k_window_sweep)
 
 struct WindowArgs {
@@ -36,6 +38,10 @@ struct WindowArgs {
     int margin16;
     u64* tie_list;         // [tie_cap] flat indices of the candidates equal to the threshold (one density)
     u64 tie_cap;
+    float* cand_w;         // [cand_cap] fused sweep: weight of each candidate
+    float* cand_lam;       // [cand_cap] fused sweep: multiplier of each candidate (L-C step)
+    const OutDesc* out;    // fused sweep: output table
+    int want_mid;          // fused sweep: also rank the sample key at the expected position of the threshold
 };
 
 struct ArrayArgs {
@@ -131,13 +137,27 @@ __global__ __launch_bounds__(kBlock) void k_window_ranks(DataArgs a, WindowArgs 
     }
     w.wslots[2 * j] = hi;
     w.wslots[2 * j + 1] = lo;
+    if (w.want_mid && j == 0) {                          // one density: the estimate of the threshold itself
+        Slot mid{};
+        mid.n = S;
+        mid.hi = 0x7FFFFFFFu;
+        mid.state = kDone;
+        if (main.state == kSelecting && S > 0) {
+            double r = floor(static_cast<double>(main.k) / static_cast<double>(main.n) * static_cast<double>(S) + 0.5);
+            if (r < 1.0) r = 1.0;
+            if (r > static_cast<double>(S)) r = static_cast<double>(S);
+            mid.state = kSelecting;
+            mid.remaining = static_cast<u64>(r);
+        }
+        w.wslots[2 * a.J] = mid;
+    }
 }
 
 // ---- histogram of one radix level over a key array -------------------------------------------------
 // Entry i takes part in ranking j when its key lies in [slot.lo, slot.hi] and the ranked key (the key
 // itself, or N - 1 - idx for the index ranking) matches the ranking's prefix.
 template <bool IDX>
-__global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
+__global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int level) {
     __shared__ u32 s_hist[kArrayWords];
     __shared__ u64 s_prefix[kArrayBatchMax];
     __shared__ u32 s_lo[kArrayBatchMax], s_hi[kArrayBatchMax], s_active[kArrayBatchMax];
@@ -145,7 +165,8 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
     if (a.gate && *a.gate == 0) return;
     const bool use_alt = IDX && a.alt_cnt != nullptr && *a.alt_cnt <= a.alt_cap;
     const u64 alt_n = use_alt ? *a.alt_cnt : 0;
-    if (use_alt && static_cast<u64>(blockIdx.x) * kBlock >= alt_n) return;      // nothing for this workgroup
+    const int nt = static_cast<int>(blockDim.x);
+    if (use_alt && static_cast<u64>(blockIdx.x) * nt >= alt_n) return;          // nothing for this workgroup
     const Level L = level_of(a.key_bits, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
@@ -183,7 +204,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
         int copies = 1;
         while (copies < 8 && 2 * copies * nj * nb <= kArrayWords) copies *= 2;
         const int words = nj * nb;
-        for (int i = tid; i < copies * words; i += kBlock) s_hist[i] = 0;
+        for (int i = tid; i < copies * words; i += nt) s_hist[i] = 0;
         __syncthreads();
         u32* my_hist = s_hist + (tid & (copies - 1)) * words;
         // entries are fetched eight at a time so that their loads overlap (the loop is latency bound)
@@ -210,7 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
             }
         };
         if (use_alt) {                                   // every listed entry passes the key filter
-            for (u64 i = static_cast<u64>(blockIdx.x) * kBlock + tid; i < alt_n; i += static_cast<u64>(gridDim.x) * kBlock) {
+            for (u64 i = static_cast<u64>(blockIdx.x) * nt + tid; i < alt_n; i += static_cast<u64>(gridDim.x) * nt) {
                 const u64 rk = a.N - 1 - a.alt_idx[i];
                 const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
                 for (int j = 0; j < nj; ++j)
@@ -220,14 +241,14 @@ __global__ __launch_bounds__(kBlock) void k_hist_array(ArrayArgs a, int level) {
             for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
                 u64 cnt = a.seg_cnt[seg];
                 if (cnt > a.seg_cap) cnt = a.seg_cap;
-                take_range(static_cast<u64>(seg) * a.seg_cap, cnt, tid, kBlock);
+                take_range(static_cast<u64>(seg) * a.seg_cap, cnt, tid, nt);
             }
         } else {
-            take_range(0, a.n_host, static_cast<u64>(blockIdx.x) * kBlock + tid, static_cast<u64>(gridDim.x) * kBlock);
+            take_range(0, a.n_host, static_cast<u64>(blockIdx.x) * nt + tid, static_cast<u64>(gridDim.x) * nt);
         }
         __syncthreads();
         u64* dst = share ? a.shared0 : a.hist + static_cast<u64>(j0) * kBins;
-        for (int i = tid; i < words; i += kBlock) {
+        for (int i = tid; i < words; i += nt) {
             u32 v = 0;
             for (int cpy = 0; cpy < copies; ++cpy) v += s_hist[cpy * words + i];
             if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + static_cast<u64>(i / nb) * kBins + (i % nb)),
@@ -609,9 +630,19 @@ __global__ __launch_bounds__(kBlock) void k_window_finish(DataArgs a, WindowArgs
     }
 }
 
+// Workgroups of 256 threads for the candidate-segment kernels (one per 2048 entries, at most 1024).
 static inline unsigned array_grid(u64 n) {
     u64 b = (n + kBlock * 8 - 1) / (kBlock * 8);
-    if (b > 1024) b = 1024;     // measured: 512 and 1024 workgroups are about equal, fewer are slower
+    if (b > 1024) b = 1024;     // measured: time falls with the workgroup count up to here
+    if (b == 0) b = 1;
+    return static_cast<unsigned>(b);
+}
+
+// Workgroups of kArrayThreads threads for k_hist_array: the same number of threads in a quarter of the
+// workgroups.
+static inline unsigned hist_array_grid(u64 n) {
+    u64 b = (n + kArrayThreads * 8 - 1) / (kArrayThreads * 8);
+    if (b > 256) b = 256;       // measured: 256 and 512 equal, 128 slower
     if (b == 0) b = 1;
     return static_cast<unsigned>(b);
 }
@@ -625,7 +656,7 @@ static inline int bits_for(u64 max_value) {
 template <bool IDX>
 static condensa_status rank_array(const ArrayArgs& ar, Control* ctl, u32* tie_flag, hipStream_t st) {
     for (int level = 0; level < n_levels(ar.key_bits); ++level) {
-        hipLaunchKernelGGL((k_hist_array<IDX>), dim3(array_grid(ar.n_host)), dim3(kBlock), 0, st, ar, level);
+        hipLaunchKernelGGL((k_hist_array<IDX>), dim3(hist_array_grid(ar.n_host)), dim3(kArrayThreads), 0, st, ar, level);
         CONDENSA_LAUNCH_CHECK();
         // with a shared level-0 histogram every ranking reads group 0 of `shared0` (J = n_slots)
         hipLaunchKernelGGL(k_scan_level, dim3(ar.n_slots), dim3(kBlock), 0, st, ar.slots,
@@ -636,8 +667,24 @@ static condensa_status rank_array(const ArrayArgs& ar, Control* ctl, u32* tie_fl
     return CONDENSA_OK;
 }
 
+// Selection and apply in one sweep (defined with its fix-up kernels in k_fused.h).
+template <bool LC, bool VEC, int QUADS>
+__global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w);
+
+struct FusedRequest {
+    const OutDesc* out;    // device output table
+    bool vec_out;          // every output pointer allows 128-bit accesses
+    WindowArgs* w_out;     // receives the window arguments for the fix-up pass
+};
+
+// float4 per thread of the one-sweep kernel, measured on 1.2 G weights: the L-C form (2 reads, 3 writes)
+// is fastest with 1 (3.96 ms; 2: 4.16, 4: 4.13), the pruning form (1 read, theta + mask) with 4
+// (1.79 ms; 2: 1.91, 1: 2.37).
+constexpr int kFusedQuadsLC = 1, kFusedQuadsPrune = 4;
+
 template <bool LC, bool VEC>
-static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st) {
+static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st,
+                                          const FusedRequest* fused) {
     if (a.n_chunks == 0) return CONDENSA_OK;
     char* base = static_cast<char*>(ws);
     WindowArgs w{};
@@ -652,7 +699,14 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.seg_cnt = reinterpret_cast<u64*>(base + L.seg);
     w.seg_region = w.seg_cnt + kSegs;
     constexpr int kWaveQuads = LC ? 4 : 8;                       // 8 KB of input per wavefront: measured best of 4, 8, 16 KB
-    const u64 sweep_groups = (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
+    constexpr int kFusedQuads = LC ? kFusedQuadsLC : kFusedQuadsPrune;
+    const bool fuse = fused != nullptr && a.J == 1;
+    const u64 sweep_groups = fuse ? a.n_chunks * (kChunk / (256 * kFusedQuads))
+                                  : (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
+    w.cand_w = reinterpret_cast<float*>(base + L.cand_w);
+    w.cand_lam = reinterpret_cast<float*>(base + L.cand_lam);
+    w.out = fuse ? fused->out : nullptr;
+    w.want_mid = fuse ? 1 : 0;
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
@@ -669,7 +723,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         hipLaunchKernelGGL(k_window_ranks, dim3(1), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
         ArrayArgs ar{};
-        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J;
+        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J + (fuse ? 1 : 0);
         ar.hist = hist_aux; ar.key_bits = 31;
         ar.shared0 = a.histx + static_cast<u64>(a.J + 2 * kMaxJ) * kBins;     // boundary rankings share level 0
         rc = rank_array<false>(ar, a.ctl, &a.ctl->unused_flag, st);
@@ -677,7 +731,11 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
-        if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+        if (fuse && VEC && fused->vec_out)
+            hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+        else if (fuse)
+            hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+        else if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
         else          hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
     }
@@ -711,6 +769,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     hipLaunchKernelGGL(k_window_finish, dim3(1), dim3(kBlock), 0, st, a, w);
     CONDENSA_LAUNCH_CHECK();
+    if (fuse && fused->w_out) *fused->w_out = w;
     return CONDENSA_OK;
 }
 

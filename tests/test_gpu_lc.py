@@ -10,15 +10,18 @@ from gpu_util import DEV, assert_bits_equal, assert_select_equal, up
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["radix", "window", "window_narrow"], autouse=True)
+@pytest.fixture(params=["radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
 def select_path(request):
-    """Every case runs through the radix levels, the sampled window, and a window whose margin is
-    cut to a couple of sample ranks so that it regularly misses and falls back."""
+    """Every case runs through the radix levels, the sampled window (selection and apply in one sweep
+    where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
+    regularly misses and falls back, and the window with separate selection and apply sweeps."""
     P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
     P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else 112)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if request.param == "window_two_sweeps" else 0)
     yield request.param
     P.condensa_set_option(P.OPT_SELECT_PATH, 0)
     P.condensa_set_option(P.OPT_WINDOW_MARGIN, 112)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
 
 
 def _check(ws, ls, mu, d, what="", **kw):

@@ -11,15 +11,18 @@ from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_ag
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["radix", "window", "window_narrow"], autouse=True)
+@pytest.fixture(params=["radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
 def select_path(request):
-    """Every case runs through the radix levels, the sampled window, and a window whose margin is
-    cut to a couple of sample ranks so that it regularly misses and falls back."""
+    """Every case runs through the radix levels, the sampled window (selection and apply in one sweep
+    where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
+    regularly misses and falls back, and the window with separate selection and apply sweeps."""
     P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
     P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else 112)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if request.param == "window_two_sweeps" else 0)
     yield request.param
     P.condensa_set_option(P.OPT_SELECT_PATH, 0)
     P.condensa_set_option(P.OPT_WINDOW_MARGIN, 112)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
 
 
 def _prune_both(arrs, densities, scope=P.SCOPE_GLOBAL, what="", **kw):
@@ -141,5 +144,5 @@ def test_few_distinct_values_far_apart(levels, n, select_path):
     w = (table[rng.integers(0, levels, n)] * rng.choice(np.array([-1.0, 1.0], np.float32), n)).astype(np.float32)
     for density in ((0.5, 0.123) if levels == 256 else (0.5, 1.0 / levels, 0.123, 0.999)):
         res, _ = _prune_both([w[: n // 3], w[n // 3:]], [density], what=f"{levels} levels d={density}")
-        if select_path == "window" and levels == 256:
+        if select_path in ("window", "window_two_sweeps") and levels == 256:
             assert P.select_records(res["results"])[0]["path"] == 2, "expected to resolve inside the window"
