@@ -406,7 +406,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     for (int t = 0; t < n_tensors && fuse; ++t)
         if (out[t].theta == tb.td[t].w && tb.td[t].n > 0) fuse = false;
     WindowArgs wargs{};
-    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, &wargs};
+    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, false, &wargs};
     rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr)
                 : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
@@ -414,7 +414,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     if (fuse) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-        hipLaunchKernelGGL((k_window_fixup<false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
+        hipLaunchKernelGGL((k_window_fixup<false, false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
         CONDENSA_LAUNCH_CHECK();
         const u64 n_tiles = tb.n_chunks * kSubPerChunk;
         const unsigned grid = static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096);
@@ -514,12 +514,12 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     for (int t = 0; t < n_tensors; ++t)
         if (tb.td[t].n > 0 && !aligned16(tb.td[t].lam)) vec_in = false;
     // Window path: selection and apply share one sweep unless lambda is updated in place (a failed window
-    // needs the inputs again) or theta is also wanted in binary16.
-    bool fuse = window && !pq && tb.n_chunks > 0 && slot.k > 0 && g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
+    // needs the inputs again).
+    bool fuse = window && tb.n_chunks > 0 && slot.k > 0 && g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
     for (int t = 0; t < n_tensors && fuse; ++t)
         if (tb.td[t].n > 0 && tb.td[t].lam_out == tb.td[t].lam) fuse = false;
     WindowArgs wargs{};
-    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, &wargs};
+    FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, pq, &wargs};
     rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr)
                 : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
@@ -527,12 +527,15 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     if (fuse) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-        hipLaunchKernelGGL((k_window_fixup<true>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
+        if (pq) hipLaunchKernelGGL((k_window_fixup<true, true>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
+        else    hipLaunchKernelGGL((k_window_fixup<true, false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
         CONDENSA_LAUNCH_CHECK();
         const u64 n_tiles = tb.n_chunks * (kChunk / 256);
-        const unsigned grid = static_cast<unsigned>(n_tiles < 16384 ? n_tiles : 16384);
-        if (vec) hipLaunchKernelGGL((k_lc_apply_gated<true>), dim3(grid), dim3(64), 0, st, a, od, n_tiles);
-        else     hipLaunchKernelGGL((k_lc_apply_gated<false>), dim3(grid), dim3(64), 0, st, a, od, n_tiles);
+        const dim3 grid(static_cast<unsigned>(n_tiles < 16384 ? n_tiles : 16384));
+        if (pq && vec)  hipLaunchKernelGGL((k_lc_apply_gated<true, true>), grid, dim3(64), 0, st, a, od, n_tiles);
+        else if (pq)    hipLaunchKernelGGL((k_lc_apply_gated<false, true>), grid, dim3(64), 0, st, a, od, n_tiles);
+        else if (vec)   hipLaunchKernelGGL((k_lc_apply_gated<true, false>), grid, dim3(64), 0, st, a, od, n_tiles);
+        else            hipLaunchKernelGGL((k_lc_apply_gated<false, false>), grid, dim3(64), 0, st, a, od, n_tiles);
         CONDENSA_LAUNCH_CHECK();
     } else if (tb.n_chunks > 0) {
         PhaseTimer timer(CONDENSA_PHASE_APPLY, st);

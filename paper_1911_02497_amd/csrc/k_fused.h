@@ -24,7 +24,8 @@ __device__ inline u32 window_mid(u32 ranked, u32 lo, u32 hi) {
     return ranked < lo ? lo : (ranked > hi ? hi : ranked);
 }
 
-template <bool LC, bool VEC, int QUADS>
+// PQ (with LC): theta is rounded to binary16 and the update sees its exact widening, as in k_lc_apply.
+template <bool LC, bool VEC, int QUADS, bool PQ>
 __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
     constexpr int kWaveElems = 256 * QUADS;
     constexpr u32 kSub = kChunk / kWaveElems;
@@ -72,6 +73,7 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
         }
         float th[4], ln[4], gr[4];
         u8 m[4];
+        u16 h16[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const float v = LC ? lc_shift(wk[q][k], lk[q][k], mu) : wk[q][k];
@@ -84,6 +86,10 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
             }
             m[k] = keep ? 1 : 0;
             th[k] = keep ? v : 0.0f;
+            if (PQ) {
+                h16[k] = f32_to_f16_rne(th[k]);
+                th[k] = f16_bits_to_f32(h16[k]);
+            }
             if (LC) {
                 const float e = __fsub_rn(wk[q][k], th[k]);
                 const float p = __fmul_rn(mu, e);
@@ -96,6 +102,11 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
             if (!LC && o.theta16) {
                 ushort4 h;
                 h.x = f32_to_f16_rne(th[0]); h.y = f32_to_f16_rne(th[1]); h.z = f32_to_f16_rne(th[2]); h.w = f32_to_f16_rne(th[3]);
+                *reinterpret_cast<ushort4*>(o.theta16 + e0) = h;
+            }
+            if (PQ && o.theta16) {
+                ushort4 h;
+                h.x = h16[0]; h.y = h16[1]; h.z = h16[2]; h.w = h16[3];
                 *reinterpret_cast<ushort4*>(o.theta16 + e0) = h;
             }
             if (LC) {
@@ -111,6 +122,7 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
                 for (int k = 0; k < 4; ++k) h[k] = f32_to_f16_rne(th[k]);
                 store4_u16<VEC>(o.theta16, e0, n, h);
             }
+            if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, n, h16);
             if (LC) {
                 store4<VEC>(td.lam_out, e0, n, ln);
                 if (td.grad) store4<VEC>(td.grad, e0, n, gr);
@@ -172,7 +184,7 @@ constexpr unsigned kFixupParts = 4;   // workgroups per candidate segment in the
                                       // the pass is bound by its scattered 4-byte writes)
 
 // Outputs of the candidates whose final decision differs from the provisional one of the fused sweep.
-template <bool LC>
+template <bool LC, bool PQ>
 __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs w) {
     if (a.ctl->window_failed != 0) return;                 // the gated apply sweep rewrites everything
     const Slot& s = a.slots[0];
@@ -205,7 +217,12 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
             const float wv = w.cand_w[first + i];
             if (LC) {
                 const float lv = w.cand_lam[first + i];
-                const float th = keep ? lc_shift(wv, lv, mu) : 0.0f;
+                float th = keep ? lc_shift(wv, lv, mu) : 0.0f;
+                if (PQ) {
+                    const u16 h = f32_to_f16_rne(th);
+                    th = f16_bits_to_f32(h);
+                    if (o.theta16) o.theta16[e] = h;
+                }
                 const float d = __fsub_rn(wv, th);
                 const float p = __fmul_rn(mu, d);
                 const float ln = __fsub_rn(lv, p);
@@ -224,10 +241,10 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
 
 // Full apply sweeps that run only when the window failed: a fixed, modest grid walks the tiles, so that
 // the usual case costs one empty launch.
-template <bool VEC>
+template <bool VEC, bool PQ>
 __global__ __launch_bounds__(64) void k_lc_apply_gated(DataArgs a, const OutDesc* __restrict__ out, u64 n_tiles) {
     if (a.ctl->window_failed == 0) return;
-    for (u64 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) lc_apply_tile<VEC, 64, false, 1>(a, out, tile);
+    for (u64 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) lc_apply_tile<VEC, 64, PQ, 1>(a, out, tile);
 }
 
 template <bool VEC>

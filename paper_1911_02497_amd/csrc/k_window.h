@@ -668,12 +668,13 @@ static condensa_status rank_array(const ArrayArgs& ar, Control* ctl, u32* tie_fl
 }
 
 // Selection and apply in one sweep (defined with its fix-up kernels in k_fused.h).
-template <bool LC, bool VEC, int QUADS>
+template <bool LC, bool VEC, int QUADS, bool PQ>
 __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w);
 
 struct FusedRequest {
     const OutDesc* out;    // device output table
     bool vec_out;          // every output pointer allows 128-bit accesses
+    bool pq;               // L-C step whose theta is also rounded to binary16
     WindowArgs* w_out;     // receives the window arguments for the fix-up pass
 };
 
@@ -731,10 +732,14 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
-        if (fuse && VEC && fused->vec_out)
-            hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+        const dim3 fg(static_cast<unsigned>(sweep_groups));
+        if (fuse && LC && fused->pq) {
+            if (VEC && fused->vec_out) hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
+            else                       hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
+        } else if (fuse && VEC && fused->vec_out)
+            hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
         else if (fuse)
-            hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
+            hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
         else if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
         else          hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
