@@ -24,11 +24,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 
-# HBM traffic of one k_lc_apply launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# HBM traffic of one k_window_fused launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # calibrated with a plain copy (profiles/lc_step_large_model_hbm_counters.md).  Reported only while the
 # kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
-MEASURED_TRAFFIC = {"bytes": 24166108438, "tensors": 64,
-                    "sources_sha256": "8319c434fe5e0baf187196e70359a1b73b7c0adb806a601553dadbccbe996430"}
+MEASURED_TRAFFIC = {"bytes": 24661339585, "tensors": 64,
+                    "sources_sha256": "9bf8f7c1105b190889aed6d8525172681db2a470f4e6bd7d603b812a36a943b1"}
 KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 
 
@@ -126,6 +126,12 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         call()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    if name == "prune_stress":
+        # one sweep (window path, default) reads the weights once: 4 + 4 theta + 1 mask; two sweeps read them twice
+        path = P.select_records(prev[0]["results"])[0]["path"]
+        one_sweep = path == 2 and not args.two_sweeps
+        bytes_per_elem = 9 if one_sweep else (13 if path == 2 else 21)
+        desc += f" ({'1 sweep' if one_sweep else '2 sweeps' if path == 2 else 'radix levels'} over the weights)"
     gbps = bytes_per_elem * N / (ms * 1e-3) / 1e9
     cpu_rec = None
     if not args.no_cpu_baseline:
