@@ -94,7 +94,8 @@ typedef struct {
     uint64_t n_tie;         /* keys equal to the threshold                                         */
     uint64_t threshold_key; /* the k-th largest key; UINT64_MAX when k == 0                        */
     uint64_t tie_end;       /* n when all ties are kept, else 1 + index of the last kept tie; 0 if k == 0 */
-    uint64_t path;          /* diagnostic: 1 = radix levels over the data, 2 = sampled window      */
+    uint64_t path;          /* diagnostic: 1 = radix levels over the data, 2 = sampled window,
+                               3 = sampled window missed, radix levels as fallback                 */
 } condensa_select;
 
 /*
@@ -124,6 +125,8 @@ size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structu
  *                         PER_TENSOR (entry j*n_tensors + t)
  *  workspace_dev/bytes    see condensa_workspace_bytes(CONDENSA_OP_PRUNE, ...)
  * With theta, theta_f16 and mask all NULL only the thresholds are computed.
+ * One density, GLOBAL scope, large tensors and theta not aliasing w: the selection and the outputs come
+ * from ONE sweep over the weights (see CONDENSA_OPT_FUSED_SWEEP); results are the same either way.
  */
 condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors,
                                const double* densities, int n_densities, int scope,
@@ -232,7 +235,9 @@ condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq
  * the gradient of the penalty that the next learning step adds to the loss gradient.
  *
  *  lambda      host table [n_tensors] of device fp32 multipliers shaped like the weights
- *  lambda_out  NULL (update lambda in place) or host table of device outputs
+ *  lambda_out  NULL (update lambda in place) or host table of device outputs; with separate outputs and
+ *              large tensors the whole step reads w and lambda once (CONDENSA_OPT_FUSED_SWEEP), in place
+ *              it reads them twice
  *  theta, grad, mask  NULL or host tables [n_tensors]; entries may be NULL (skipped).  None of
  *              them may alias w or lambda.
  *  result_dev  device, one record
@@ -333,9 +338,11 @@ int64_t         condensa_get_option(int option);
  */
 enum {
     CONDENSA_PHASE_SAMPLE    = 0,  /* sampling and the ranking of the sample                        */
-    CONDENSA_PHASE_SWEEP     = 1,  /* full sweeps over the weights that feed the selection          */
+    CONDENSA_PHASE_SWEEP     = 1,  /* full sweeps over the weights that feed the selection (the one-sweep
+                                      form also writes the outputs here)                          */
     CONDENSA_PHASE_RESOLVE   = 2,  /* ranking of candidates / aggregates, tie search, records       */
-    CONDENSA_PHASE_APPLY     = 3,  /* the mask / theta / L-C update kernel                          */
+    CONDENSA_PHASE_APPLY     = 3,  /* the mask / theta / L-C update kernel, or the fix-up pass after the
+                                      one-sweep form                                              */
     CONDENSA_PHASE_AGGREGATE = 4,  /* per-structure sums of squares                                 */
     CONDENSA_PHASE_COUNT     = 5
 };
