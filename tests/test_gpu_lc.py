@@ -157,3 +157,31 @@ def test_sgd_step_with_penalty_against_the_oracle():
     with pytest.raises(P.CondensaError) as e:
         P.condensa_lc_sgd_step([w], [w], [torch.zeros(8, device=DEV)], [torch.zeros(8, device=DEV)], [torch.zeros(8, device=DEV)], 1e-3, 0.1, 0.9)
     assert e.value.code == -6
+
+
+def test_misaligned_tensors_and_partial_outputs():
+    """Pointers that are not 16-byte aligned take the scalar path of every sweep (also of the one-sweep
+    form); outputs that are not asked for are skipped."""
+    n = 8192 * 3 + 77
+    ws, ls = _gauss([(n,), (1001,)], 21, 0.01), _gauss([(n,), (1001,)], 22, 0.01)
+    ora = oracle.lc_step(ws, ls, 1e-3, 0.25)
+
+    def shifted(a):                                     # same values, storage offset by one element
+        big = torch.empty(a.size + 1, dtype=torch.float32, device=DEV)
+        big[1:] = torch.from_numpy(a.reshape(-1)).to(DEV)
+        return big[1:].view(a.shape)
+
+    dw, dl = [shifted(a) for a in ws], [shifted(a) for a in ls]
+    out_l = [shifted(np.zeros_like(a)) for a in ls]
+    res = P.condensa_lc_step(dw, dl, 1e-3, 0.25, lambda_out=out_l, grad=False)
+    torch.cuda.synchronize()
+    assert res["grad"] is None
+    for t in range(2):
+        assert_bits_equal(res["theta"][t], ora["theta"][t], f"theta {t}")
+        assert_bits_equal(out_l[t], ora["lambda"][t], f"lambda {t}")
+        assert np.array_equal(res["mask"][t].cpu().numpy(), ora["mask"][t])
+    res = P.condensa_lc_step(up(ws), up(ls), 1e-3, 0.25, theta=False, mask=False)
+    torch.cuda.synchronize()
+    for t in range(2):
+        assert_bits_equal(res["lambda"][t], ora["lambda"][t], f"lambda only {t}")
+        assert_bits_equal(res["grad"][t], ora["grad"][t], f"grad only {t}")
