@@ -685,6 +685,10 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     a.per_tensor = per_tensor ? 1 : 0;
 
     const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
+    // groups of at most kSmallGroup structures: one workgroup per group ranks, masks and lists them
+    bool small = tb.F > 0 && g_options[CONDENSA_OPT_SELECT_PATH].load() != 1;
+    if (per_tensor) { for (int t = 0; t < n_tensors && small; ++t) if (tb.td[t].n_struct > kSmallGroup) small = false; }
+    else if (tb.F > kSmallGroup) small = false;
     if (tb.F > 0) {
         {
             PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st);
@@ -699,25 +703,36 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             CONDENSA_LAUNCH_CHECK();
         }
         PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
+        if (small) {
+            hipLaunchKernelGGL(k_struct_small, dim3(L.n_slots), dim3(kSmallThreads), 0, st, a, structure_mask_dev,
+                               keep_idx_dev, results_dev);
+            CONDENSA_LAUNCH_CHECK();
+        }
         u64 blocks = tb.n_schunks < 1024 ? tb.n_schunks : 1024;
         const u64 cpb = (tb.n_schunks + blocks - 1) / blocks;
         blocks = (tb.n_schunks + cpb - 1) / cpb;
-        for (int level = 0; level < n_levels(63); ++level) {
+        for (int level = 0; level < n_levels(63) && !small; ++level) {
             hipLaunchKernelGGL(k_hist_keys, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_scan_level, dim3(L.n_slots), dim3(kBlock), 0, st, a.slots,
                                static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();
         }
-        hipLaunchKernelGGL(k_tie_count_keys, dim3(static_cast<unsigned>(tb.n_schunks)), dim3(kBlock), 0, st, a);
+        if (!small) {
+            hipLaunchKernelGGL(k_tie_count_keys, dim3(static_cast<unsigned>(tb.n_schunks)), dim3(kBlock), 0, st, a);
+            CONDENSA_LAUNCH_CHECK();
+        }
+    }
+    if (!small) {
+        hipLaunchKernelGGL(k_tie_locate_keys, dim3(L.n_slots), dim3(kBlock), 0, st, a, results_dev);
         CONDENSA_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(k_tie_locate_keys, dim3(L.n_slots), dim3(kBlock), 0, st, a, results_dev);
-    CONDENSA_LAUNCH_CHECK();
     if (tb.F > 0) {
-        hipLaunchKernelGGL(k_struct_mask, dim3(sblocks), dim3(kBlock), 0, st, a, structure_mask_dev);
-        CONDENSA_LAUNCH_CHECK();
-        if (keep_idx_dev) {
+        if (!small) {
+            hipLaunchKernelGGL(k_struct_mask, dim3(sblocks), dim3(kBlock), 0, st, a, structure_mask_dev);
+            CONDENSA_LAUNCH_CHECK();
+        }
+        if (keep_idx_dev && !small) {
             hipLaunchKernelGGL(k_struct_scan_blocks, dim3(1), dim3(kBlock), 0, st, a.sblock, static_cast<u64>(sblocks));
             CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_struct_keep_idx, dim3(sblocks), dim3(kBlock), 0, st, a, keep_idx_dev);

@@ -334,6 +334,154 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate_keys(StructArgs a, conden
     }
 }
 
+// ---- small groups: ranking, tie rule, structure mask and kept-id list in one workgroup ----------------
+//
+// A CIFAR ResNet has 2 032 filters, its layers 16 to 64 each: rankings of that size are
+// bound by launch latency (six histogram + scan launch pairs, tie kernels, mask, scan, compaction: 19
+// launches of ~4.5 us).  One workgroup of 1024 threads per group does the same steps back to back: six
+// radix levels with an LDS histogram, the index search among tied aggregates, keep flags and the ordered
+// list of kept ids (every thread owns a contiguous run of structures, so a workgroup scan orders them).
+// Used when no group has more than kSmallGroup structures.
+
+constexpr int kSmallThreads = 1024;
+constexpr u64 kSmallGroup = 4096;       // measured: 2 032 filters 0.141 -> 0.100 ms per call, 43 008 blocks 0.22 -> 0.30 ms
+
+// Exclusive scan over the 1024 threads of the workgroup in thread order; *total gets the sum.
+// s_part holds kSmallThreads / 64 entries.  All threads must call it.
+__device__ inline u64 small_excl_scan(u64 v, u64* s_part, u64* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u64 incl = wave_incl_scan_u64(v);
+    __syncthreads();                                       // s_part may still be read from a previous call
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    u64 before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kSmallThreads / 64; ++w) {
+        const u64 t = s_part[w];
+        if (w < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+__global__ __launch_bounds__(kSmallThreads) void k_struct_small(StructArgs a, u8* user_mask, int32_t* keep_idx,
+                                                                condensa_select* results) {
+    __shared__ u32 s_hist[kBins];
+    __shared__ u64 s_part[kSmallThreads / 64];
+    __shared__ u64 s_sel[3];                               // bin, rank inside it, entries in it
+    __shared__ u64 s_tie_end;
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x;
+    Slot& slot = a.slots[g];
+    const u64 first = a.per_tensor ? a.td[g].struct_start : 0;
+    const u64 n = a.per_tensor ? a.td[g + 1].struct_start - first : a.F;
+    const u64 k = slot.k;
+    const u64* __restrict__ keys = a.keys + first;
+
+    // kept structures of the groups before this one: their kept counts are fixed by the density
+    u64 kept_before = 0;
+    if (keep_idx && g > 0) {
+        u64 part = 0;
+        for (int i = tid; i < g; i += kSmallThreads) part += a.slots[i].k;
+        u64 tot;
+        small_excl_scan(part, s_part, &tot);
+        kept_before = tot;
+    }
+
+    u64 T = ~static_cast<u64>(0), keep_ties = 0, n_tie = 0, tie_end = 0;
+    if (k > 0) {                                           // uniform over the workgroup
+        u64 prefix = 0, remaining = k;
+        for (int level = 0; level < n_levels(63); ++level) {
+            const Level L = level_of(63, level);
+            const int nb = 1 << L.bits;
+            for (int i = tid; i < nb; i += kSmallThreads) s_hist[i] = 0;
+            __syncthreads();
+            for (u64 i = tid; i < n; i += kSmallThreads) {
+                const u64 key = keys[i];
+                if (((key ^ prefix) >> L.hi_shift) == 0) atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
+            }
+            __syncthreads();
+            // two bins per thread, from the top
+            u64 cnt[2], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int b = nb - 1 - (tid * 2 + j);
+                cnt[j] = (b >= 0) ? s_hist[b] : 0;
+                sum += cnt[j];
+            }
+            u64 total;
+            u64 cum = small_excl_scan(sum, s_part, &total);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int b = nb - 1 - (tid * 2 + j);
+                if (b >= 0 && cum < remaining && remaining <= cum + cnt[j]) {
+                    s_sel[0] = static_cast<u64>(b);
+                    s_sel[1] = remaining - cum;
+                    s_sel[2] = cnt[j];
+                }
+                cum += cnt[j];
+            }
+            __syncthreads();                               // k <= n, so exactly one thread wrote s_sel
+            prefix |= s_sel[0] << L.shift;
+            remaining = s_sel[1];
+            n_tie = s_sel[2];
+            __syncthreads();
+        }
+        T = prefix;
+        keep_ties = remaining;
+    }
+
+    // every thread owns the contiguous run [i0, i1) of the group
+    const u64 per = (n + kSmallThreads - 1) / kSmallThreads;
+    const u64 i0 = per * tid < n ? per * tid : n;
+    const u64 i1 = i0 + per < n ? i0 + per : n;
+    if (k > 0) {
+        tie_end = n;
+        if (keep_ties < n_tie) {                           // uniform: find the keep_ties-th tie in index order
+            u64 mine = 0;
+            for (u64 i = i0; i < i1; ++i) mine += (keys[i] == T) ? 1u : 0u;
+            u64 total;
+            const u64 before = small_excl_scan(mine, s_part, &total);
+            if (before < keep_ties && keep_ties <= before + mine) {
+                u64 seen = before;
+                for (u64 i = i0; i < i1; ++i) {
+                    if (keys[i] == T && ++seen == keep_ties) { s_tie_end = i + 1; break; }
+                }
+            }
+            __syncthreads();
+            tie_end = s_tie_end;
+        }
+    }
+    // keep flags and the ordered list of kept ids
+    u64 kept = 0;
+    for (u64 i = i0; i < i1; ++i) {
+        const u64 key = keys[i];
+        const u32 keep = (k > 0 && (key > T || (key == T && i < tie_end))) ? 1u : 0u;
+        a.smask[first + i] = static_cast<u8>(keep);
+        if (user_mask) user_mask[first + i] = static_cast<u8>(keep);
+        kept += keep;
+    }
+    if (keep_idx) {
+        u64 total;
+        u64 pos = kept_before + small_excl_scan(kept, s_part, &total);
+        for (u64 i = i0; i < i1; ++i)
+            if (a.smask[first + i]) keep_idx[pos++] = static_cast<int32_t>(first + i);
+    }
+    if (tid == 0) {
+        condensa_select out;
+        out.n = slot.n;
+        out.k = k;
+        out.n_gt = k > 0 ? k - keep_ties : 0;
+        out.n_tie_kept = keep_ties;
+        out.n_tie = n_tie;
+        out.threshold_key = T;
+        out.tie_end = tie_end;
+        out.path = slot.path;
+        results[g] = out;
+    }
+}
+
 // keep flag of every structure and the number of kept structures of every block of 256
 __global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask) {
     __shared__ u32 s_cnt;

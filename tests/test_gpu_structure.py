@@ -11,6 +11,15 @@ from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_ag
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["auto", "launch_per_level"], autouse=True)
+def ranking_form(request):
+    """Every case runs with the default choice (one workgroup per group ranks, masks and lists groups of up
+    to 4 096 structures) and with the general form (one histogram and one scan launch per radix level)."""
+    P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "launch_per_level" else 0)
+    yield request.param
+    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
+
+
 def _compare(res, ora, scope, arrs, what):
     recs = P.select_records(res["results"])
     if scope == P.SCOPE_GLOBAL:
