@@ -103,9 +103,10 @@ __device__ inline void build_digit_table(u16* tab, const u32* prefix, const u32*
             if (active[j]) tab[prefix[j] >> L0.shift] |= static_cast<u16>(1u << j);
 }
 
-// The workgroup is 256 threads, or 1024 (GLOBAL scope, several densities, past level 0): the J
-// histograms of 4 KB each allow few workgroups per compute unit, so wide ones keep enough wavefronts
-// resident; each quarter of a wide workgroup takes a chunk of its own.
+// The workgroup is 1024 threads under GLOBAL scope (few, wide workgroups: fewer flushes of the LDS
+// histograms through global atomics, and enough wavefronts per compute unit even when J histograms of
+// 4 KB each limit the workgroups per unit), 256 under PER_TENSOR scope, where the histograms change with
+// the tensor.  Each quarter of a wide workgroup takes a chunk of its own.
 template <bool LC, bool VEC>
 __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 chunks_per_block) {
     extern __shared__ u32 s_hist[];       // level 0: kBins words; later levels: min(J, kSlotBatch) x 1024 words
