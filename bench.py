@@ -49,7 +49,8 @@ def parse():
     ap.add_argument("--tensors", type=int, default=64, help="number of 4096x4608 matrices (64 = the full workload)")
     ap.add_argument("--mask", action="store_true", help="also write the byte mask (+N bytes per step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tensors", type=int, default=2)
+    ap.add_argument("--cpu-sample-tensors", type=int, default=6,
+                    help="the oracle is timed on the first this-many tensors (6: ~12 s of one host core)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch plain device copies of one tensor (known bytes) for counter calibration")
     ap.add_argument("--apply-threads", type=int, default=0, help="workgroup size of the apply sweep (0 = default)")
@@ -60,6 +61,8 @@ def parse():
                              "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
                     help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
+    ap.add_argument("--window-margin", type=int, default=112,
+                    help="half-width of the sampled window in 1/16 standard deviations (default 112 = 7 sigma)")
     ap.add_argument("--two-sweeps", action="store_true",
                     help="window path: separate selection and apply sweeps (default: one sweep does both)")
     return ap.parse_args()
@@ -72,6 +75,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     up = lambda arrs: P.tensor_table([torch.from_numpy(a).to(dev) for a in arrs])  # noqa: E731  (marshalled once)
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
     P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, args.window_margin)
     prev = [None]                                # the first call allocates the outputs, later ones reuse them
     if name == "prune_stress":
         # global magnitude pruning of the large-model weights (no multipliers): theta + mask at density 0.1
@@ -211,6 +215,7 @@ def main():
     P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
     P.condensa_set_option(P.OPT_APPLY_THREADS, args.apply_threads)
     P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, args.window_margin)
 
     def step():
         return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,
