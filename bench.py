@@ -61,8 +61,8 @@ def parse():
                              "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
                     help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
-    ap.add_argument("--window-margin", type=int, default=112,
-                    help="half-width of the sampled window in 1/16 standard deviations (default 112 = 7 sigma)")
+    ap.add_argument("--window-margin", type=int, default=80,
+                    help="half-width of the sampled window in 1/16 standard deviations (default 80 = 5 sigma)")
     ap.add_argument("--two-sweeps", action="store_true",
                     help="window path: separate selection and apply sweeps (default: one sweep does both)")
     return ap.parse_args()

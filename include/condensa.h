@@ -319,7 +319,9 @@ enum {
     CONDENSA_OPT_SELECT_PATH   = 0, /* 0 auto, 1 radix levels over the data only, 2 sampled window even for small N */
     CONDENSA_OPT_SAMPLE_LOG2   = 1, /* log2 of the sample size of the window path; 0 = auto             */
     CONDENSA_OPT_WINDOW_MARGIN = 2, /* half-width of the sampled window in 1/16 standard deviations of
-                                       the sample rank; default 112 (= 7 sigma); 0 makes windows miss    */
+                                       the sample rank; default 80 (= 5 sigma of a sample whose units of
+                                       4 neighbours are fully correlated, i.e. 10 sigma of independent
+                                       draws); 0 makes windows miss                                  */
     CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
     CONDENSA_OPT_PROFILE       = 4, /* bit p set: bracket phase p of every call with HIP events on the call's stream */
     CONDENSA_OPT_APPLY_THREADS = 5, /* workgroup size of the L-C apply sweep: 0 (default = 64), 64, 128 or 256 */

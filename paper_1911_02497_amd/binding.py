@@ -17,6 +17,7 @@ _LIB_PATH = os.environ.get("CONDENSA_LIBRARY") or os.path.join(_HERE, "libconden
 SCOPE_GLOBAL, SCOPE_PER_TENSOR = 0, 1
 OP_PRUNE, OP_FILTER_PRUNE, OP_BLOCK_PRUNE, OP_QUANTIZE, OP_LC_STEP, OP_COUNT_NONZERO, OP_LC_SGD_STEP = range(7)
 OPT_SELECT_PATH, OPT_SAMPLE_LOG2, OPT_WINDOW_MARGIN, OPT_CAND_SHIFT, OPT_PROFILE, OPT_APPLY_THREADS, OPT_FUSED_SWEEP = range(7)
+WINDOW_MARGIN_DEFAULT = 80          # CONDENSA_OPT_WINDOW_MARGIN as the library starts with
 PHASES = ("sample", "sweep", "resolve", "apply", "aggregate")
 MAX_DENSITIES = 16
 

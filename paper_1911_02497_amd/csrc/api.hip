@@ -11,7 +11,7 @@
 namespace condensa {
 
 std::atomic<int> g_last_hip_error{0};
-std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {112}, {0}, {0}, {0}, {0}};
+std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {80}, {0}, {0}, {0}, {0}};
 
 // ---- pinned staging ring -------------------------------------------------------------------------
 

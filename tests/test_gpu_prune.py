@@ -17,11 +17,11 @@ def select_path(request):
     where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
     regularly misses and falls back, and the window with separate selection and apply sweeps."""
     P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else 112)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else P.WINDOW_MARGIN_DEFAULT)
     P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if request.param == "window_two_sweeps" else 0)
     yield request.param
     P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 112)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
     P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
 
 
