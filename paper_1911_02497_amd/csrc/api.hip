@@ -912,7 +912,9 @@ condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq
     constexpr int QT = kQuantThreads;
     const u64 blocks = (n + QT * 4 - 1) / (QT * 4);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (vec) hipLaunchKernelGGL((k_dequantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+    if (aligned16(q_dev) && aligned16(dq_dev))
+        hipLaunchKernelGGL((k_dequantize_wide<QT>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else if (vec) hipLaunchKernelGGL((k_dequantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
     else     hipLaunchKernelGGL((k_dequantize<false, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;

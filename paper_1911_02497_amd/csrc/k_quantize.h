@@ -84,4 +84,35 @@ __global__ __launch_bounds__(THREADS) void k_dequantize(const u16* __restrict__ 
     else      store4<VEC>(dq, e0, n, d);
 }
 
+// Wide form: a wavefront takes 512 codes.  Every lane loads eight codes with one 128-bit access, the
+// lanes then trade halves so that lane L holds codes 4L..4L+3 and 256+4L..256+4L+3, and writes them with
+// two 128-bit stores that are contiguous across the wavefront (storing each lane's own eight values
+// instead, 32 bytes apart per lane, runs at half the rate).  Requires 16-byte aligned q and dq.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_dequantize_wide(const u16* __restrict__ q, u64 n, float* __restrict__ dq) {
+    constexpr int kPerWave = 512;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u64 wave0 = (static_cast<u64>(blockIdx.x) * (THREADS / 64) + wave) * kPerWave;
+    if (wave0 >= n) return;
+    if (wave0 + kPerWave <= n) {                                         // uniform over the wavefront
+        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + wave0 + lane * 8));
+        // lane L needs the codes 4L..4L+3: dwords (L & 1) * 2, +1 of lane L / 2; and the same of lane 32 + L / 2
+        const int src = lane >> 1;
+        const bool odd = lane & 1;
+        const u32 lo0 = __shfl(v[0], src, 64), lo1 = __shfl(v[1], src, 64), lo2 = __shfl(v[2], src, 64), lo3 = __shfl(v[3], src, 64);
+        const u32 hi0 = __shfl(v[0], src + 32, 64), hi1 = __shfl(v[1], src + 32, 64), hi2 = __shfl(v[2], src + 32, 64), hi3 = __shfl(v[3], src + 32, 64);
+        const u32 c0 = odd ? lo2 : lo0, c1 = odd ? lo3 : lo1, d0 = odd ? hi2 : hi0, d1 = odd ? hi3 : hi1;
+        st4_stream(dq + wave0 + lane * 4, f16_bits_to_f32(static_cast<u16>(c0)), f16_bits_to_f32(static_cast<u16>(c0 >> 16)),
+                   f16_bits_to_f32(static_cast<u16>(c1)), f16_bits_to_f32(static_cast<u16>(c1 >> 16)));
+        st4_stream(dq + wave0 + 256 + lane * 4, f16_bits_to_f32(static_cast<u16>(d0)), f16_bits_to_f32(static_cast<u16>(d0 >> 16)),
+                   f16_bits_to_f32(static_cast<u16>(d1)), f16_bits_to_f32(static_cast<u16>(d1 >> 16)));
+    } else {
+        for (int k = 0; k < 8; ++k) {
+            const u64 e = wave0 + static_cast<u64>(k) * 64 + lane;
+            if (e < n) dq[e] = f16_bits_to_f32(q[e]);
+        }
+    }
+}
+
 }  // namespace condensa

@@ -68,6 +68,21 @@ def test_empty_and_dequantize_all_patterns():
     assert_bits_equal(got, want, "dequantize")
 
 
+@pytest.mark.parametrize("n", [1, 7, 511, 512, 513, 1000, 64 * 512 + 3, (1 << 20) + 255])
+def test_dequantize_and_codes_only_ragged_sizes(n):
+    """Sizes around the 512-code wavefront tile of the wide dequantize and the 8-element thread tile of the
+    codes-only quantize, aligned and misaligned storage."""
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * rng.choice(np.array([1e-6, 1.0, 300.0], np.float32), n)).astype(np.float32)
+    oq, odq = oracle.quantize_f16(x)
+    q, _ = P.condensa_quantize(torch.from_numpy(x).to(DEV), want_dq=False)
+    assert np.array_equal(q.cpu().numpy().view(np.uint16), oq)
+    assert_bits_equal(P.condensa_dequantize(q), odq, "dequantize aligned")
+    big = torch.empty(n + 1, dtype=torch.int16, device=DEV)
+    big[1:] = q
+    assert_bits_equal(P.condensa_dequantize(big[1:]), odq, "dequantize misaligned")
+
+
 def test_errors():
     with pytest.raises(P.CondensaError) as e:
         P.condensa_quantize(torch.zeros(4, device=DEV), want_q=False, want_dq=False)
