@@ -298,6 +298,9 @@ def main():
                    "threshold_key": rec["threshold_key"], "n_tie": rec["n_tie"]},
         "step_algorithmic_GBps": round(step_gbps, 1),
         "step_frac_of_hbm_peak": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "step_bytes_per_weight": step_bytes_per_elem,
+        # the same time against the 28 B/weight of a select-then-apply step (weights and multipliers read twice)
+        "step_GBps_at_two_read_accounting": round((28 + (1 if args.mask else 0)) * N / (ms_per_step * 1e-3) / 1e9, 1),
         "phase_ms_per_step": phase_ms,
         "input_generation_s": round(gen_s, 1),
         "roofline": roofline,
