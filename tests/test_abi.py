@@ -46,3 +46,26 @@ def test_host_only_calls():
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(P.binding.Tensor) == 48
     assert len(P.binding.SELECT_FIELDS) * 8 == 64
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Only the one-GPU path exists: asking for more must end with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_workspace_sizes_are_monotone_and_cover_the_documented_cases():
+    from paper_1911_02497_amd import binding as B
+    lib = B.library()
+    n = 1207959552
+    big = lib.condensa_workspace_bytes(B.OP_LC_STEP, n, 0, 64, 1, B.SCOPE_GLOBAL)
+    assert 0.5e9 < big < 1.0e9                         # candidate capacity N/32 x 28 B dominates
+    assert lib.condensa_workspace_bytes(B.OP_LC_STEP, n // 2, 0, 64, 1, B.SCOPE_GLOBAL) < big
+    assert lib.condensa_workspace_bytes(B.OP_PRUNE, n, 0, 64, 16, B.SCOPE_GLOBAL) > 0
+    assert lib.condensa_workspace_bytes(B.OP_PRUNE, n, 0, 64, 17, B.SCOPE_GLOBAL) == 0      # too many densities
+    assert lib.condensa_workspace_bytes(B.OP_QUANTIZE, n, 0, 1, 1, B.SCOPE_GLOBAL) == 0      # needs none
+    assert lib.condensa_workspace_bytes(99, n, 0, 1, 1, B.SCOPE_GLOBAL) == 0
