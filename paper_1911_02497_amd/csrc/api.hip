@@ -155,6 +155,7 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
         L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
         L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));
+        L.sorted_windows = off; off += align_up(256);             // SortedWindows (196 B)
         if (J == 1) {
             L.cand_w = off;   off += align_up(L.cand_cap * sizeof(float));
             L.cand_lam = off; off += align_up(L.cand_cap * sizeof(float));
@@ -295,14 +296,16 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
 
 // Sampled window or radix levels?  Measured (one MI355X, 2^24..2^30 weights, 1/4/10 densities): the radix
 // levels cost three sweeps whatever the number of densities and ~50 us of fixed work; the window path
-// costs one sweep, ~0.25 ms of small kernels, and candidate lists and a sweep that grow with the number
-// of densities.  One density breaks even near 2^26 element reads, four near 2^30, ten never.
+// costs one sweep, ~0.2 ms of small kernels, and candidate lists and a sweep that grow with the number
+// of densities.  One density breaks even near 2^26 element reads, four near 2^27.5, ten near 2^30.
 static bool want_window(u64 N, bool per_tensor, int J, bool lc) {
     if (per_tensor) return false;
     const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;
-    return N * (lc ? 2u : 1u) >= (static_cast<u64>(J) * static_cast<u64>(J)) << 26;
+    u64 need = static_cast<u64>(J) << 26;
+    if (J > 4) need = need * static_cast<u64>(J) / 4;
+    return N * (lc ? 2u : 1u) >= need;
 }
 
 }  // namespace condensa

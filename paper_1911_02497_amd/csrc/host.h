@@ -81,6 +81,7 @@ struct Layout {
     size_t skeys = 0, sblock = 0, smask = 0;                // structure keys, per-block kept counts, keep flags
     size_t sample = 0, cand_key = 0, cand_idx = 0;          // window path
     size_t cand_w = 0, cand_lam = 0;                        // inputs of the candidates (fused sweep)
+    size_t sorted_windows = 0;                              // several densities: the windows in sweep order
     u64 sample_cap = 0, cand_cap = 0;
     size_t total = 0;
     u64 max_chunks = 0, max_schunks = 0;

@@ -23,6 +23,8 @@ constexpr int kArrayThreads = 1024;     // workgroup of the array kernels: wide,
                                        // LDS histograms with (slow, memory-side) global atomics
 constexpr int kSegs = 1024;            // candidate list segments / counter sets (see k_window_sweep)
 
+struct SortedWindows;
+
 struct WindowArgs {
     u32* sample;           // [n_units * kSampleUnit]
     u32* cand_key;         // [cand_cap]
@@ -42,6 +44,7 @@ struct WindowArgs {
     float* cand_lam;       // [cand_cap] fused sweep: multiplier of each candidate (L-C step)
     const OutDesc* out;    // fused sweep: output table
     int want_mid;          // fused sweep: also rank the sample key at the expected position of the threshold
+    struct SortedWindows* sorted;   // several densities: the windows in sweep order, written by k_window_sort
 };
 
 struct ArrayArgs {
@@ -300,6 +303,13 @@ __device__ inline void sort_windows(const Slot* slots, const Slot* wslots, int J
     out->n = n;
 }
 
+// Runs once between the sample ranking and the sweep (one thread): ordering the windows inside every
+// workgroup of the sweep, a chain of ~2J dependent global loads in one thread, cost the sweep more than
+// its memory traffic.
+__global__ void k_window_sort(DataArgs a, WindowArgs w) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) sort_windows(a.slots, w.wslots, a.J, w.sorted);
+}
+
 template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs w) {
     __shared__ SortedWindows s_win;
@@ -309,7 +319,8 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     const u64 c = blockIdx.x;
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
-    if (tid == 0) sort_windows(a.slots, w.wslots, a.J, &s_win);
+    if (tid < static_cast<int>(sizeof(SortedWindows) / sizeof(u32)))
+        reinterpret_cast<u32*>(&s_win)[tid] = reinterpret_cast<const u32*>(w.sorted)[tid];
     if (tid <= kMaxJ) s_region[tid] = 0;
     __syncthreads();
     const int n = static_cast<int>(s_win.n);
@@ -320,11 +331,19 @@ __global__ __launch_bounds__(kBlock) void k_window_sweep(DataArgs a, WindowArgs 
     u32 key[kQuadsPerThread][4];
     u32 cmask = 0;
     u64 pk0 = 0, pk1 = 0;                 // 6-bit counts of regions 0..9 and 10..16
+    const bool full = VEC && !LC && base + kChunk <= td.n;               // uniform: all loads first
+    float4 wv[kQuadsPerThread];
+    if (full) {
+#pragma unroll
+        for (int q = 0; q < kQuadsPerThread; ++q) wv[q] = ld4_stream(td.w + base + q * (kBlock * 4) + tid * 4);
+    }
 #pragma unroll
     for (int q = 0; q < kQuadsPerThread; ++q) {
         const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
         float v[4] = {0.f, 0.f, 0.f, 0.f};
-        if (e0 < td.n) {
+        if (full) {
+            v[0] = wv[q].x; v[1] = wv[q].y; v[2] = wv[q].z; v[3] = wv[q].w;
+        } else if (e0 < td.n) {
             load4<VEC>(td.w, e0, td.n, v);
             if (LC) {
                 float l[4];
@@ -708,6 +727,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.cand_lam = reinterpret_cast<float*>(base + L.cand_lam);
     w.out = fuse ? fused->out : nullptr;
     w.want_mid = fuse ? 1 : 0;
+    w.sorted = reinterpret_cast<SortedWindows*>(base + L.sorted_windows);
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
     const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
@@ -741,7 +761,11 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         else if (fuse)
             hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
         else if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
-        else          hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        else {
+            hipLaunchKernelGGL(k_window_sort, dim3(1), dim3(64), 0, st, a, w);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
+        }
         CONDENSA_LAUNCH_CHECK();
     }
     PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
