@@ -1,0 +1,95 @@
+"""GPU parity on seeded random cases: tensor lists of random shapes (empty and one-element tensors included),
+value distributions with few or many ties, random densities; every case through the four selection forms."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1911_02497_amd as P
+from gpu_util import assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
+
+pytestmark = pytest.mark.gpu
+
+FORMS = {"radix": (1, None, 0), "window": (2, None, 0), "window_narrow": (2, 0, 0), "window_two_sweeps": (2, None, 1)}
+
+
+@pytest.fixture(params=sorted(FORMS), autouse=True)
+def form(request):
+    path, margin, two = FORMS[request.param]
+    P.condensa_set_option(P.OPT_SELECT_PATH, path)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT if margin is None else margin)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
+    yield request.param
+    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
+    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+
+
+def _random_tensors(rng, big=False):
+    n_t = int(rng.integers(1, 7))
+    shapes = [(int(rng.integers(2_000_000, 5_000_000)),)] if big else []      # large enough for a sampled window to hold
+    for _ in range(n_t):
+        kind = int(rng.integers(0, 6))
+        if kind == 0:
+            shapes.append((int(rng.integers(0, 3)),))                       # empty or tiny
+        elif kind == 1:
+            shapes.append((int(rng.integers(1, 40)), int(rng.integers(1, 40)), 3, 3))
+        elif kind == 2:
+            shapes.append((int(rng.integers(1, 300)), int(rng.integers(1, 300))))
+        else:
+            shapes.append((int(rng.integers(1, 120000)),))
+    style = int(rng.integers(0, 4))
+    out = []
+    for s in shapes:
+        if style == 0:
+            a = rng.standard_normal(s) * 0.02
+        elif style == 1:
+            a = rng.integers(-4, 5, s) * 0.25                               # nine values: huge tie classes
+        elif style == 2:
+            a = rng.standard_normal(s) * (rng.random(s) < 0.3)              # 70 % exact zeros
+        else:
+            a = np.exp(rng.standard_normal(s) * 6) * rng.choice([-1.0, 1.0], s)   # many octaves
+        out.append(np.asarray(a, dtype=np.float32).reshape(s))
+    return out
+
+
+@pytest.mark.parametrize("seed", list(range(12)) + [100, 101, 102, 103])
+def test_prune_random(seed):
+    rng = np.random.default_rng(1000 + seed)
+    ws = _random_tensors(rng, big=seed >= 100)
+    n = sum(w.size for w in ws)
+    dens = [float(rng.choice([0.0, 1.0, rng.random(), rng.random() ** 3, 1.0 / max(n, 1)]))
+            for _ in range(int(rng.integers(1, 4)))]
+    scope = P.SCOPE_PER_TENSOR if rng.random() < 0.3 else P.SCOPE_GLOBAL
+    f16 = bool(rng.random() < 0.5)
+    res = P.condensa_prune(up(ws), dens, scope=scope, theta_f16=f16)
+    torch.cuda.synchronize()
+    ora = oracle.prune(ws, dens, scope)
+    check_prune_against_oracle(res, ora, scope, len(ws), f"seed {seed} dens {dens}")
+    if f16:
+        for j in range(len(dens)):
+            for t in range(len(ws)):
+                q, _ = oracle.quantize_f16(ora[j]["theta"][t])
+                assert np.array_equal(res["theta_f16"][j][t].cpu().numpy().view(np.uint16), q), f"seed {seed} f16 d{j} t{t}"
+
+
+@pytest.mark.parametrize("seed", list(range(12)) + [100, 101, 102, 103])
+def test_lc_step_random(seed):
+    rng = np.random.default_rng(2000 + seed)
+    ws = _random_tensors(rng, big=seed >= 100)
+    ls = [np.asarray(rng.standard_normal(w.shape) * 0.01 * (rng.random() < 0.8), dtype=np.float32) for w in ws]
+    mu = float(rng.choice([1e-3, 1.0, 37.5]))
+    d = float(rng.choice([0.0, 1.0, rng.random(), rng.random() ** 3]))
+    # the composed scheme only where theta stays finite in binary16 (inf - inf would compare NaN payloads)
+    pq = bool(rng.random() < 0.4) and max((float(np.abs(w).max()) if w.size else 0.0) for w in ws) < 1e4
+    res = (P.condensa_lc_step_pq if pq else P.condensa_lc_step)(up(ws), up(ls), mu, d)
+    torch.cuda.synchronize()
+    ora = (oracle.lc_step_pq if pq else oracle.lc_step)(ws, ls, mu, d)
+    what = f"seed {seed} mu {mu} d {d} pq {pq}"
+    assert_select_equal(P.select_records(res["results"])[0], ora["select"], what)
+    for t in range(len(ws)):
+        assert np.array_equal(res["mask"][t].cpu().numpy(), ora["mask"][t]), f"{what} mask {t}"
+        for name in ("theta", "lambda", "grad"):
+            assert_bits_equal(res[name][t], ora[name][t], f"{what} {name} {t}")
+        if pq:
+            assert np.array_equal(res["theta_f16"][t].cpu().numpy().view(np.uint16), ora["theta_f16"][t]), f"{what} f16 {t}"
