@@ -189,3 +189,38 @@ def test_marshalled_table_and_reused_outputs_give_the_same_results():
     torch.cuda.synchronize()
     assert pr2["mask"][1][0].data_ptr() == pr["mask"][1][0].data_ptr()
     check_prune_against_oracle(pr2, oracle.prune(arrs, [0.1, 0.5], P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, len(arrs), "reused outputs")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_structure_cases(seed):
+    """Seeded random cases: n-D blocks of random shapes over tensors of random shapes (ragged edges, blocks
+    larger than a dimension, duplicated and zero structures), and mixed neuron / filter lists; both scopes."""
+    rng = np.random.default_rng(3000 + seed)
+    density = float(rng.choice([0.0, 1.0, rng.random(), rng.random() ** 2]))
+    scope = P.SCOPE_PER_TENSOR if rng.random() < 0.5 else P.SCOPE_GLOBAL
+    if seed % 2 == 0:
+        nd = int(rng.integers(1, 5))
+        block = [int(rng.integers(1, 9)) for _ in range(nd)]
+        arrs = []
+        for _ in range(int(rng.integers(1, 5))):
+            shape = tuple(int(rng.integers(1, 70 if nd <= 2 else 14)) for _ in range(nd))
+            a = rng.integers(-2, 3, shape).astype(np.float32) if rng.random() < 0.4 else rng.standard_normal(shape).astype(np.float32)
+            arrs.append(a)
+        res = P.condensa_block_prune_nd(up(arrs), block, density, scope)
+        torch.cuda.synchronize()
+        _compare(res, oracle.block_prune_nd(arrs, block, density, scope), scope, arrs, f"seed {seed} block {block}")
+    else:
+        arrs = []
+        for _ in range(int(rng.integers(1, 6))):
+            if rng.random() < 0.5:
+                shape = (int(rng.integers(1, 200)), int(rng.integers(1, 100)))
+            else:
+                shape = (int(rng.integers(1, 60)), int(rng.integers(1, 20)), 3, 3)
+            a = rng.standard_normal(shape).astype(np.float32)
+            if shape[0] > 3:
+                a[1] = a[0]
+                a[2] = 0
+            arrs.append(a)
+        res = P.condensa_structure_prune(up(arrs), density, scope)
+        torch.cuda.synchronize()
+        _compare(res, oracle.structure_prune(arrs, density, scope), scope, arrs, f"seed {seed} structures")
