@@ -212,10 +212,20 @@ __global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u
         const TensorDesc& td = a.td[t];
         const u64 base = (c - td.pad) * kChunk;
         const u64 prefix = s_prefix;
-        for (u64 i = base + tid; i < base + kChunk && i < td.n_struct; i += kBlock) {
-            const u64 key = a.keys[td.struct_start + i];
-            if (((key ^ prefix) >> L.hi_shift) == 0)
-                atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
+        const u64 end = (base + kChunk < td.n_struct) ? base + kChunk : td.n_struct;
+        const u64* __restrict__ kp = a.keys + td.struct_start;
+        // eight keys per step so that their loads overlap (a chunk is 32 keys per thread)
+        for (u64 i0 = base + tid; i0 < end; i0 += 8 * kBlock) {
+            u64 key[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const u64 i = i0 + static_cast<u64>(u) * kBlock;
+                key[u] = (i < end) ? kp[i] : ~prefix;      // a filler that fails the prefix test at every level
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + static_cast<u64>(u) * kBlock < end && ((key[u] ^ prefix) >> L.hi_shift) == 0)
+                    atomicAdd(&s_hist[(key[u] >> L.shift) & (nb - 1)], 1u);
         }
     }
     if (cur_group >= 0) {
