@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
             "oracle_select_keep": [vp, vp, u64, u64, ctypes.POINTER(Select), vp],
             "oracle_apply_keep": [vp, vp, u64, vp],
             "oracle_quantize_f16": [vp, u64, vp, vp],
+            "oracle_quantize_bf16": [vp, u64, vp, vp],
+            "oracle_dequantize_bf16": [vp, u64, vp],
             "oracle_dequantize_f16": [vp, u64, vp],
             "oracle_filter_sumsq": [vp, u64, u64, vp],
             "oracle_block_sumsq": [vp, u64, u64, u64, u64, vp],
@@ -169,6 +171,22 @@ def dequantize_f16(q: np.ndarray) -> np.ndarray:
     qf = np.ascontiguousarray(q, dtype=np.uint16).reshape(-1)
     dq = np.empty(qf.size, np.float32)
     lib().oracle_dequantize_f16(_p(qf), qf.size, _p(dq))
+    return dq.reshape(np.shape(q))
+
+
+def quantize_bf16(x: np.ndarray):
+    """binary32 -> bfloat16 bits (round to nearest even) and the exact widening back."""
+    xf = _f32(x).reshape(-1)
+    q = np.empty(xf.size, np.uint16)
+    dq = np.empty(xf.size, np.float32)
+    lib().oracle_quantize_bf16(_p(xf), xf.size, _p(q), _p(dq))
+    return q.reshape(np.shape(x)), dq.reshape(np.shape(x))
+
+
+def dequantize_bf16(q: np.ndarray) -> np.ndarray:
+    qf = np.ascontiguousarray(q, dtype=np.uint16).reshape(-1)
+    dq = np.empty(qf.size, np.float32)
+    lib().oracle_dequantize_bf16(_p(qf), qf.size, _p(dq))
     return dq.reshape(np.shape(q))
 
 

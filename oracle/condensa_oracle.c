@@ -194,6 +194,34 @@ void oracle_dequantize_f16(const uint16_t* q, uint64_t n, float* dq)
     for (uint64_t i = 0; i < n; ++i) dq[i] = bits_f32(f16_to_f32_bits(q[i]));
 }
 
+/* ---- bfloat16: Quantize(dtype) with the other common 16-bit floating-point type (Table 1; "data types for
+ * quantization" are named as an extension in the Conclusions).  bfloat16 is the upper half of binary32:
+ * 1 sign, 8 exponent, 7 fraction bits.  Round to nearest, ties to even, decided on the 16 dropped bits;
+ * a carry out of the fraction moves into the exponent (the largest finite values round to infinity);
+ * NaN stays NaN: sign and upper payload bits kept, quiet bit set. */
+static uint16_t f32_to_bf16_bits(uint32_t u)
+{
+    const uint32_t upper = u >> 16, dropped = u & 0xFFFFu;
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)(upper | 0x0040u);
+    if (dropped > 0x8000u) return (uint16_t)(upper + 1u);
+    if (dropped == 0x8000u) return (uint16_t)(upper + (upper & 1u));
+    return (uint16_t)upper;
+}
+
+void oracle_quantize_bf16(const float* x, uint64_t n, uint16_t* q, float* dq /* nullable */)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint16_t h = f32_to_bf16_bits(f32_bits(x[i]));
+        q[i] = h;
+        if (dq) dq[i] = bits_f32((uint32_t)h << 16);
+    }
+}
+
+void oracle_dequantize_bf16(const uint16_t* q, uint64_t n, float* dq)
+{
+    for (uint64_t i = 0; i < n; ++i) dq[i] = bits_f32((uint32_t)q[i] << 16);
+}
+
 /* ---- structure aggregates --------------------------------------------- */
 
 /* filters of one tensor [n_filters, len]: S_f = sum of squares, binary64, memory order */
