@@ -225,6 +225,18 @@ condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_de
 condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream);
 
 /*
+ * Quantize(dtype) for the other common 16-bit floating-point type, bfloat16 (Table 1: Quantize(dtype);
+ * Conclusions: data types for quantization as an extension).  q = upper half of the binary32 pattern
+ * after rounding to nearest even on the 16 dropped bits (a carry runs into the exponent: values above the
+ * largest finite bfloat16 become infinity; subnormals are kept); NaN -> quiet NaN keeping the sign and
+ * the upper payload bits.  dq = exact widening.  Arguments and aliasing as for condensa_quantize /
+ * condensa_dequantize.
+ */
+condensa_status condensa_quantize_bf16(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev,
+                                       void* stream);
+condensa_status condensa_dequantize_bf16(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream);
+
+/*
  * One compression step of the L-C algorithm with the augmented-Lagrangian updates (Section 3.3;
  * mu_j = mu_0 a^j is the caller's schedule, "L-C Optimizer Settings").  Per element, in binary32
  * with one rounding per operation and no fused multiply-add:

@@ -65,6 +65,9 @@ _PROTOTYPES = {
     "condensa_quantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
     "condensa_dequantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "condensa_quantize_bf16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p]),
+    "condensa_dequantize_bf16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
     "condensa_lc_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -355,23 +358,39 @@ def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, t
                            [blk, nd], workspace, stream, outputs)
 
 
-def condensa_quantize(x, want_q=True, want_dq=True, stream=None):
+def _quantize(fn_name, x, want_q, want_dq, stream):
     import torch
-    lib = library()
     q = torch.empty(x.shape, dtype=torch.int16, device=x.device) if want_q else None
     dq = torch.empty_like(x) if want_dq else None
-    _check(lib.condensa_quantize(x.data_ptr() if x.numel() else None, x.numel(),
-                                 q.data_ptr() if q is not None else None,
-                                 dq.data_ptr() if dq is not None else None, _stream(stream)))
+    _check(getattr(library(), fn_name)(x.data_ptr() if x.numel() else None, x.numel(),
+                                       q.data_ptr() if q is not None else None,
+                                       dq.data_ptr() if dq is not None else None, _stream(stream)))
     return q, dq
 
 
-def condensa_dequantize(q, stream=None):
+def _dequantize(fn_name, q, stream):
     import torch
-    lib = library()
     dq = torch.empty(q.shape, dtype=torch.float32, device=q.device)
-    _check(lib.condensa_dequantize(q.data_ptr() if q.numel() else None, q.numel(), dq.data_ptr(), _stream(stream)))
+    _check(getattr(library(), fn_name)(q.data_ptr() if q.numel() else None, q.numel(), dq.data_ptr(), _stream(stream)))
     return dq
+
+
+def condensa_quantize(x, want_q=True, want_dq=True, stream=None):
+    """binary16 codes (int16 views of the bits) and / or their exact widening."""
+    return _quantize("condensa_quantize", x, want_q, want_dq, stream)
+
+
+def condensa_dequantize(q, stream=None):
+    return _dequantize("condensa_dequantize", q, stream)
+
+
+def condensa_quantize_bf16(x, want_q=True, want_dq=True, stream=None):
+    """bfloat16 codes (int16 views of the bits) and / or their exact widening."""
+    return _quantize("condensa_quantize_bf16", x, want_q, want_dq, stream)
+
+
+def condensa_dequantize_bf16(q, stream=None):
+    return _dequantize("condensa_dequantize_bf16", q, stream)
 
 
 def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,

@@ -887,9 +887,9 @@ condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_te
 
 }  // extern "C"
 
-extern "C" {
-
-condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
+namespace condensa {
+template <typename C>
+static condensa_status quantize_impl(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
     if (n > kMaxElems) return CONDENSA_ERR_SIZE;
     if (n == 0) return CONDENSA_OK;
     if (q_dev == nullptr && dq_dev == nullptr) return CONDENSA_ERR_NULL;
@@ -900,14 +900,15 @@ condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_de
     const u64 blocks = (n + QT * 4 - 1) / (QT * 4);           // <= 2^28 for n <= 2^36
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (!dq_dev && aligned16(x_dev) && aligned16(q_dev))
-        hipLaunchKernelGGL((k_quantize_codes<QT>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, x_dev, n, q_dev);
-    else if (vec) hipLaunchKernelGGL((k_quantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
-    else     hipLaunchKernelGGL((k_quantize<false, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
+        hipLaunchKernelGGL((k_quantize_codes<QT, C>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, x_dev, n, q_dev);
+    else if (vec) hipLaunchKernelGGL((k_quantize<true, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
+    else     hipLaunchKernelGGL((k_quantize<false, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
 }
 
-condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
+template <typename C>
+static condensa_status dequantize_impl(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
     if (n > kMaxElems) return CONDENSA_ERR_SIZE;
     if (n == 0) return CONDENSA_OK;
     if (dq_dev == nullptr || q_dev == nullptr) return CONDENSA_ERR_NULL;
@@ -916,11 +917,30 @@ condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq
     const u64 blocks = (n + QT * 4 - 1) / (QT * 4);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (aligned16(q_dev) && aligned16(dq_dev))
-        hipLaunchKernelGGL((k_dequantize_wide<QT>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, q_dev, n, dq_dev);
-    else if (vec) hipLaunchKernelGGL((k_dequantize<true, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
-    else     hipLaunchKernelGGL((k_dequantize<false, QT>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+        hipLaunchKernelGGL((k_dequantize_wide<QT, C>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else if (vec) hipLaunchKernelGGL((k_dequantize<true, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else     hipLaunchKernelGGL((k_dequantize<false, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
+}
+}  // namespace condensa
+
+extern "C" {
+
+condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
+    return quantize_impl<CodecF16>(x_dev, n, q_dev, dq_dev, stream);
+}
+
+condensa_status condensa_dequantize(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
+    return dequantize_impl<CodecF16>(q_dev, n, dq_dev, stream);
+}
+
+condensa_status condensa_quantize_bf16(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
+    return quantize_impl<CodecBF16>(x_dev, n, q_dev, dq_dev, stream);
+}
+
+condensa_status condensa_dequantize_bf16(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
+    return dequantize_impl<CodecBF16>(q_dev, n, dq_dev, stream);
 }
 
 condensa_status condensa_profile_read(int phase, double* total_ms, uint64_t* intervals) {

@@ -240,4 +240,25 @@ __device__ inline float f16_bits_to_f32(u16 hb) {
     return __uint_as_float(out);
 }
 
+// bfloat16 (upper half of binary32), round to nearest even: add half of the dropped range, less one when the
+// kept part is even (so that an exact tie does not carry); a carry runs into the exponent and the largest
+// finite values become infinity.  NaN keeps sign and upper payload, quiet bit set.
+__device__ inline u16 f32_to_bf16_rne(float x) {
+    const u32 u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<u16>((u >> 16) | 0x0040u);
+    return static_cast<u16>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+__device__ inline float bf16_bits_to_f32(u16 hb) { return __uint_as_float(static_cast<u32>(hb) << 16); }
+
+// The 16-bit codecs of the quantize kernels.
+struct CodecF16 {
+    static __device__ inline u16 enc(float x) { return f32_to_f16_rne(x); }
+    static __device__ inline float dec(u16 h) { return f16_bits_to_f32(h); }
+};
+struct CodecBF16 {
+    static __device__ inline u16 enc(float x) { return f32_to_bf16_rne(x); }
+    static __device__ inline float dec(u16 h) { return bf16_bits_to_f32(h); }
+};
+
 }  // namespace condensa

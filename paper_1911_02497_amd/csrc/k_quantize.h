@@ -9,7 +9,7 @@ constexpr int kQuantThreads = 64;       // wavefront-sized workgroups measured b
 
 // One float4 per thread; workgroups that lie wholly inside the array use unguarded 128-bit accesses with
 // the streaming hint (nothing here is read twice).
-template <bool VEC, int THREADS>
+template <bool VEC, int THREADS, typename C>
 __global__ __launch_bounds__(THREADS) void k_quantize(const float* x, u64 n, u16* q, float* dq) {   // dq may be x
     const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 4);
     const u64 e0 = wg0 + threadIdx.x * 4;
@@ -26,8 +26,8 @@ __global__ __launch_bounds__(THREADS) void k_quantize(const float* x, u64 n, u16
     float d[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        h[k] = f32_to_f16_rne(v[k]);
-        d[k] = f16_bits_to_f32(h[k]);
+        h[k] = C::enc(v[k]);
+        d[k] = C::dec(h[k]);
     }
     if (full) {
         if (q) {
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(THREADS) void k_quantize(const float* x, u64 n, u16
 // codes (measured 76% of peak against 58% with four per thread; the reverse layout, two strided 128-bit
 // stores per lane, halves the rate, so the other kernels keep one float4 per thread).  Requires 16-byte
 // aligned x and q.
-template <int THREADS>
+template <int THREADS, typename C>
 __global__ __launch_bounds__(THREADS) void k_quantize_codes(const float* __restrict__ x, u64 n, u16* __restrict__ q) {
     const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 8);
     const u64 e0 = wg0 + threadIdx.x * 8;
@@ -54,16 +54,16 @@ __global__ __launch_bounds__(THREADS) void k_quantize_codes(const float* __restr
         const float4 a = ld4_stream(x + e0);
         const float4 b = ld4_stream(x + e0 + 4);
         u16x8 h;
-        h[0] = f32_to_f16_rne(a.x); h[1] = f32_to_f16_rne(a.y); h[2] = f32_to_f16_rne(a.z); h[3] = f32_to_f16_rne(a.w);
-        h[4] = f32_to_f16_rne(b.x); h[5] = f32_to_f16_rne(b.y); h[6] = f32_to_f16_rne(b.z); h[7] = f32_to_f16_rne(b.w);
+        h[0] = C::enc(a.x); h[1] = C::enc(a.y); h[2] = C::enc(a.z); h[3] = C::enc(a.w);
+        h[4] = C::enc(b.x); h[5] = C::enc(b.y); h[6] = C::enc(b.z); h[7] = C::enc(b.w);
         __builtin_nontemporal_store(h, reinterpret_cast<u16x8*>(q + e0));
     } else {
         for (int k = 0; k < 8; ++k)
-            if (e0 + k < n) q[e0 + k] = f32_to_f16_rne(x[e0 + k]);
+            if (e0 + k < n) q[e0 + k] = C::enc(x[e0 + k]);
     }
 }
 
-template <bool VEC, int THREADS>
+template <bool VEC, int THREADS, typename C>
 __global__ __launch_bounds__(THREADS) void k_dequantize(const u16* __restrict__ q, u64 n, float* __restrict__ dq) {
     const u64 wg0 = static_cast<u64>(blockIdx.x) * (THREADS * 4);
     const u64 e0 = wg0 + threadIdx.x * 4;
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(THREADS) void k_dequantize(const u16* __restrict__ 
     }
     float d[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) d[k] = f16_bits_to_f32(h[k]);
+    for (int k = 0; k < 4; ++k) d[k] = C::dec(h[k]);
     if (full) st4_stream(dq + e0, d[0], d[1], d[2], d[3]);
     else      store4<VEC>(dq, e0, n, d);
 }
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(THREADS) void k_dequantize(const u16* __restrict__ 
 // lanes then trade halves so that lane L holds codes 4L..4L+3 and 256+4L..256+4L+3, and writes them with
 // two 128-bit stores that are contiguous across the wavefront (storing each lane's own eight values
 // instead, 32 bytes apart per lane, runs at half the rate).  Requires 16-byte aligned q and dq.
-template <int THREADS>
+template <int THREADS, typename C>
 __global__ __launch_bounds__(THREADS) void k_dequantize_wide(const u16* __restrict__ q, u64 n, float* __restrict__ dq) {
     constexpr int kPerWave = 512;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -103,14 +103,14 @@ __global__ __launch_bounds__(THREADS) void k_dequantize_wide(const u16* __restri
         const u32 lo0 = __shfl(v[0], src, 64), lo1 = __shfl(v[1], src, 64), lo2 = __shfl(v[2], src, 64), lo3 = __shfl(v[3], src, 64);
         const u32 hi0 = __shfl(v[0], src + 32, 64), hi1 = __shfl(v[1], src + 32, 64), hi2 = __shfl(v[2], src + 32, 64), hi3 = __shfl(v[3], src + 32, 64);
         const u32 c0 = odd ? lo2 : lo0, c1 = odd ? lo3 : lo1, d0 = odd ? hi2 : hi0, d1 = odd ? hi3 : hi1;
-        st4_stream(dq + wave0 + lane * 4, f16_bits_to_f32(static_cast<u16>(c0)), f16_bits_to_f32(static_cast<u16>(c0 >> 16)),
-                   f16_bits_to_f32(static_cast<u16>(c1)), f16_bits_to_f32(static_cast<u16>(c1 >> 16)));
-        st4_stream(dq + wave0 + 256 + lane * 4, f16_bits_to_f32(static_cast<u16>(d0)), f16_bits_to_f32(static_cast<u16>(d0 >> 16)),
-                   f16_bits_to_f32(static_cast<u16>(d1)), f16_bits_to_f32(static_cast<u16>(d1 >> 16)));
+        st4_stream(dq + wave0 + lane * 4, C::dec(static_cast<u16>(c0)), C::dec(static_cast<u16>(c0 >> 16)),
+                   C::dec(static_cast<u16>(c1)), C::dec(static_cast<u16>(c1 >> 16)));
+        st4_stream(dq + wave0 + 256 + lane * 4, C::dec(static_cast<u16>(d0)), C::dec(static_cast<u16>(d0 >> 16)),
+                   C::dec(static_cast<u16>(d1)), C::dec(static_cast<u16>(d1 >> 16)));
     } else {
         for (int k = 0; k < 8; ++k) {
             const u64 e = wave0 + static_cast<u64>(k) * 64 + lane;
-            if (e < n) dq[e] = f16_bits_to_f32(q[e]);
+            if (e < n) dq[e] = C::dec(q[e]);
         }
     }
 }

@@ -87,3 +87,34 @@ def test_errors():
     with pytest.raises(P.CondensaError) as e:
         P.condensa_quantize(torch.zeros(4, device=DEV), want_q=False, want_dq=False)
     assert e.value.code == -1
+
+
+@pytest.mark.parametrize("n", [1, 511, 513, 4097, (1 << 20) + 255])
+def test_bfloat16_against_the_oracle(n):
+    """bfloat16 quantize / dequantize: random magnitudes over many octaves plus every special class, ragged
+    sizes, codes-only and misaligned forms."""
+    rng = np.random.default_rng(n + 5)
+    with np.errstate(over="ignore"):                   # some magnitudes overflow binary32 on purpose
+        x = (rng.standard_normal(n) * np.exp(rng.standard_normal(n) * 25)).astype(np.float32)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 3.3895314e38, -3.4e38, 1e-40, -2e-45, 1.00390625, 1.01171875],
+                       np.float32)
+    x[: min(n, special.size)] = special[: min(n, special.size)]
+    oq, odq = oracle.quantize_bf16(x)
+    dx = torch.from_numpy(x).to(DEV)
+    q, dq = P.condensa_quantize_bf16(dx)
+    assert np.array_equal(q.cpu().numpy().view(np.uint16), oq)
+    assert_bits_equal(dq, odq, "bf16 dq")
+    q2, _ = P.condensa_quantize_bf16(dx, want_dq=False)
+    assert np.array_equal(q2.cpu().numpy().view(np.uint16), oq)
+    assert_bits_equal(P.condensa_dequantize_bf16(q), odq, "bf16 dequantize")
+    big = torch.empty(n + 1, dtype=torch.float32, device=DEV)
+    big[1:] = dx
+    q3, dq3 = P.condensa_quantize_bf16(big[1:])
+    assert np.array_equal(q3.cpu().numpy().view(np.uint16), oq)
+    assert_bits_equal(dq3, odq, "bf16 misaligned")
+
+
+def test_bfloat16_all_codes_round_trip():
+    allh = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    got = P.condensa_dequantize_bf16(torch.from_numpy(allh.view(np.int16)).to(DEV))
+    assert_bits_equal(got, oracle.dequantize_bf16(allh), "bf16 all codes")
