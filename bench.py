@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 # HBM traffic of one k_window_fused launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # calibrated with a plain copy (profiles/lc_step_large_model_hbm_counters.md).  Reported only while the
 # kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
-MEASURED_TRAFFIC = {"bytes": 24607917699, "tensors": 64,
-                    "sources_sha256": "9bf8f7c1105b190889aed6d8525172681db2a470f4e6bd7d603b812a36a943b1"}
+MEASURED_TRAFFIC = {"bytes": 24596180612, "tensors": 64,
+                    "sources_sha256": "daa05200ddb78e03ab7b709251f748dfd047a998e2357f72cb50e7fca41cb53e"}
 KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 
 
