@@ -69,3 +69,46 @@ def test_workspace_sizes_are_monotone_and_cover_the_documented_cases():
     assert lib.condensa_workspace_bytes(B.OP_PRUNE, n, 0, 64, 17, B.SCOPE_GLOBAL) == 0      # too many densities
     assert lib.condensa_workspace_bytes(B.OP_QUANTIZE, n, 0, 1, 1, B.SCOPE_GLOBAL) == 0      # needs none
     assert lib.condensa_workspace_bytes(99, n, 0, 1, 1, B.SCOPE_GLOBAL) == 0
+
+
+def test_argument_errors_are_found_on_the_host_before_any_launch():
+    """Bad arguments must come back as a status before anything touches a GPU (so these run without one)."""
+    from paper_1911_02497_amd import binding as B
+    lib = B.library()
+    null = None
+    fake = ctypes.c_void_p(256)                          # never dereferenced: the calls fail first
+    for fn in (lib.condensa_quantize, lib.condensa_quantize_bf16):
+        assert fn(null, 4, fake, fake, null) == -1                       # x missing
+        assert fn(fake, 4, null, null, null) == -1                       # no output wanted
+        assert fn(fake, (1 << 36) + 1, fake, null, null) == -2           # too many elements
+        assert fn(null, 0, null, null, null) == 0                        # nothing to do
+    for fn in (lib.condensa_dequantize, lib.condensa_dequantize_bf16):
+        assert fn(null, 4, fake, null) == -1
+        assert fn(fake, 4, null, null) == -1
+        assert fn(null, 0, null, null) == 0
+    t = (B.Tensor * 1)()
+    t[0].w = 256
+    t[0].shape[0] = 16
+    t[0].ndim = 1
+    dens = (ctypes.c_double * 1)(0.5)
+    res = ctypes.c_void_p(512)
+    ws = ctypes.c_void_p(4096)
+    # density out of range, too many densities, bad scope, workspace too small / misaligned / missing
+    bad = (ctypes.c_double * 1)(1.5)
+    assert lib.condensa_prune(t, 1, bad, 1, 0, null, null, null, res, ws, 1 << 30, null) == -3
+    assert lib.condensa_prune(t, 1, dens, 17, 0, null, null, null, res, ws, 1 << 30, null) == -2
+    assert lib.condensa_prune(t, 1, dens, 1, 7, null, null, null, res, ws, 1 << 30, null) == -6
+    assert lib.condensa_prune(t, 1, dens, 1, 0, null, null, null, res, ws, 16, null) == -5
+    assert lib.condensa_prune(t, 1, dens, 1, 0, null, null, null, res, ctypes.c_void_p(4100), 1 << 30, null) == -5
+    assert lib.condensa_prune(t, 1, dens, 1, 0, null, null, null, res, null, 1 << 30, null) == -5
+    assert lib.condensa_prune(t, 1, dens, 1, 0, null, null, null, null, ws, 1 << 30, null) == -1
+    t[0].ndim = 5
+    assert lib.condensa_prune(t, 1, dens, 1, 0, null, null, null, res, ws, 1 << 30, null) == -4
+    t[0].ndim = 1
+    # filter pruning wants 4-D tensors, block pruning 2-D ones whose dimensions the block divides
+    assert lib.condensa_filter_prune(t, 1, 0.5, 0, null, null, null, null, null, null, res, ws, 1 << 30, null) == -4
+    t[0].shape[0], t[0].shape[1], t[0].ndim = 6, 8, 2
+    assert lib.condensa_block_prune(t, 1, 4, 4, 0.5, 0, null, null, null, null, null, null, res, ws, 1 << 30, null) == -4
+    assert lib.condensa_block_prune(t, 1, 0, 4, 0.5, 0, null, null, null, null, null, null, res, ws, 1 << 30, null) == -4
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
+        assert len(lib.condensa_status_string(code)) > 0
