@@ -73,8 +73,8 @@ __global__ __launch_bounds__(kBlock) void k_struct_sumsq(StructArgs a, double* s
                 const float* row = td.w + off;
                 if (aligned && ((off | len) & 3u) == 0) {
                     for (u32 x = 0; x < len; x += 4) {
-                        const float4 v = *reinterpret_cast<const float4*>(row + x);
-                        acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x);
+                        const float4 v = *reinterpret_cast<const float4*>(row + x);   // no streaming hint: the lanes of a
+                        acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x); // wavefront share cache lines here
                         acc = acc + static_cast<double>(v.y) * static_cast<double>(v.y);
                         acc = acc + static_cast<double>(v.z) * static_cast<double>(v.z);
                         acc = acc + static_cast<double>(v.w) * static_cast<double>(v.w);
@@ -125,16 +125,24 @@ __global__ __launch_bounds__(kBlock) void k_struct_sumsq_rows(StructArgs a, doub
     const u32 fast_end = s_aligned ? (s_minlen / kRowTile) * kRowTile : 0;   // pieces below it: unguarded loads
     const int seg = tid & 7, sub = tid >> 3;              // 8 lanes per row piece, 32 rows per pass
     double acc = 0.0;
+    // Pieces below fast_end are fetched one iteration ahead, so that the loads of piece i+1 are in flight
+    // while piece i is added up.
+    float4 v[8];
+    if (fast_end > 0) {
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) v[pass] = ld4_stream(s_row[pass * 32 + sub] + seg * 4);
+    }
     for (u32 cb = 0; cb < maxlen; cb += kRowTile) {
         if (cb < fast_end) {
-            float4 v[8];
-#pragma unroll
-            for (int pass = 0; pass < 8; ++pass)
-                v[pass] = *reinterpret_cast<const float4*>(s_row[pass * 32 + sub] + cb + seg * 4);
 #pragma unroll
             for (int pass = 0; pass < 8; ++pass) {
                 float* dst = &s_tile[pass * 32 + sub][seg * 4];
                 dst[0] = v[pass].x; dst[1] = v[pass].y; dst[2] = v[pass].z; dst[3] = v[pass].w;
+            }
+            if (cb + kRowTile < fast_end) {
+#pragma unroll
+                for (int pass = 0; pass < 8; ++pass)
+                    v[pass] = ld4_stream(s_row[pass * 32 + sub] + cb + kRowTile + seg * 4);
             }
         } else {
             for (int pass = 0; pass < 8; ++pass) {
