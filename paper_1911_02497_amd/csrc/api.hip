@@ -401,6 +401,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     a.J = J;
     a.per_tensor = per_tensor ? 1 : 0;
     a.only_failed = 0;
+    a.streaming = (tb.N * 4u >= (static_cast<u64>(512) << 20)) ? 1 : 0;            // well beyond the 256 MB last-level cache
     a.mu = 0.0f;
 
     // One density on the window path: selection and apply share one sweep unless theta overwrites the weights.
@@ -510,6 +511,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.J = 1;
     a.per_tensor = 0;
     a.only_failed = 0;
+    a.streaming = (tb.N * 8u >= (static_cast<u64>(512) << 20)) ? 1 : 0;            // w and lambda: well beyond the 256 MB last-level cache
     a.mu = mu;
 
     // the selection sweeps read w and lambda only, so their vector path depends on those alone

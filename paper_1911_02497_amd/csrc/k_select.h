@@ -34,6 +34,7 @@ struct DataArgs {
     int J;                 // rankings (densities) per group
     int per_tensor;        // 1: group = tensor, 0: one group
     int only_failed;       // 1: runs as the fallback of the window path (skip when nothing failed)
+    int streaming;         // 1: the inputs exceed the caches, so repeated sweeps gain nothing from keeping lines
     float mu;
 };
 
@@ -202,8 +203,8 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
 #pragma unroll
                     for (int q = 0; q < kHalf; ++q) {
                         const u64 e0 = base + static_cast<u64>(h * kHalf + q) * (kBlock * 4) + tid * 4;
-                        wv[q] = *reinterpret_cast<const float4*>(td.w + e0);
-                        if (LC) lv[q] = *reinterpret_cast<const float4*>(td.lam + e0);
+                        wv[q] = a.streaming ? ld4_stream(td.w + e0) : *reinterpret_cast<const float4*>(td.w + e0);
+                        if (LC) lv[q] = a.streaming ? ld4_stream(td.lam + e0) : *reinterpret_cast<const float4*>(td.lam + e0);
                     }
 #pragma unroll
                     for (int q = 0; q < kHalf; ++q) {
@@ -361,8 +362,8 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
 #pragma unroll
                 for (int q = 0; q < kHalf; ++q) {
                     const u64 e0 = base + static_cast<u64>(h * kHalf + q) * (kBlock * 4) + tid * 4;
-                    wv[q] = *reinterpret_cast<const float4*>(td.w + e0);
-                    if (LC) lv[q] = *reinterpret_cast<const float4*>(td.lam + e0);
+                    wv[q] = a.streaming ? ld4_stream(td.w + e0) : *reinterpret_cast<const float4*>(td.w + e0);
+                    if (LC) lv[q] = a.streaming ? ld4_stream(td.lam + e0) : *reinterpret_cast<const float4*>(td.lam + e0);
                 }
 #pragma unroll
                 for (int q = 0; q < kHalf; ++q) {
