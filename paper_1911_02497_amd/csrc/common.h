@@ -138,6 +138,19 @@ __device__ inline void st4_stream(float* p, float a, float b, float c, float d) 
     __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
 }
 
+// Four mask bytes / four 16-bit codes as one store with the streaming hint (p 4- / 8-byte aligned).
+__device__ inline void st_mask4_stream(u8* p, u8 a, u8 b, u8 c, u8 d) {
+    __builtin_nontemporal_store(static_cast<u32>(a) | (static_cast<u32>(b) << 8) | (static_cast<u32>(c) << 16) | (static_cast<u32>(d) << 24),
+                                reinterpret_cast<u32*>(p));
+}
+__device__ inline void st_code4_stream(u16* p, u16 a, u16 b, u16 c, u16 d) {
+    typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 t;
+    t.x = static_cast<u32>(a) | (static_cast<u32>(b) << 16);
+    t.y = static_cast<u32>(c) | (static_cast<u32>(d) << 16);
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+}
+
 // Loads up to four consecutive elements e0 .. e0+3 of an n-element array; missing ones read 0.
 template <bool VEC>
 __device__ inline void load4(const float* __restrict__ p, u64 e0, u64 n, float v[4]) {

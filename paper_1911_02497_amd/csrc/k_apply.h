@@ -69,11 +69,9 @@ __device__ inline void prune_apply_tile(const DataArgs& a, const OutDesc* __rest
         if (full) {
             if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
             if (o.theta16) {
-                ushort4 h;
-                h.x = f32_to_f16_rne(th[0]); h.y = f32_to_f16_rne(th[1]); h.z = f32_to_f16_rne(th[2]); h.w = f32_to_f16_rne(th[3]);
-                *reinterpret_cast<ushort4*>(o.theta16 + e0) = h;
+                st_code4_stream(o.theta16 + e0, f32_to_f16_rne(th[0]), f32_to_f16_rne(th[1]), f32_to_f16_rne(th[2]), f32_to_f16_rne(th[3]));
             }
-            if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+            if (o.mask) st_mask4_stream(o.mask + e0, m[0], m[1], m[2], m[3]);
         } else {
             if (o.theta) store4<VEC>(o.theta, e0, n, th);
             if (o.theta16) {
@@ -154,13 +152,11 @@ __device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restric
             lc_update4<PQ>(w, l, mu, T, td.flat_start + e0, end, th, ln, gr, m, h);
             if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
             if (PQ && o.theta16) {
-                ushort4 hv;
-                hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
-                *reinterpret_cast<ushort4*>(o.theta16 + e0) = hv;
+                st_code4_stream(o.theta16 + e0, h[0], h[1], h[2], h[3]);
             }
             st4_stream(td.lam_out + e0, ln[0], ln[1], ln[2], ln[3]);
             if (td.grad) st4_stream(td.grad + e0, gr[0], gr[1], gr[2], gr[3]);
-            if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+            if (o.mask) st_mask4_stream(o.mask + e0, m[0], m[1], m[2], m[3]);
         }
     } else {
         for (int q = 0; q < QUADS; ++q) {

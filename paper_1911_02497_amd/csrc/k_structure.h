@@ -623,7 +623,7 @@ __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const Out
     }
     if (full) {
         if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
-        if (o.mask) *reinterpret_cast<u32*>(o.mask + e0) = static_cast<u32>(m[0]) | (static_cast<u32>(m[1]) << 8) | (static_cast<u32>(m[2]) << 16) | (static_cast<u32>(m[3]) << 24);
+        if (o.mask) st_mask4_stream(o.mask + e0, m[0], m[1], m[2], m[3]);
     } else {
         if (o.theta) store4<VEC>(o.theta, e0, n, th);
         if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
