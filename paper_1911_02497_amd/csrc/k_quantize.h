@@ -31,9 +31,7 @@ __global__ __launch_bounds__(THREADS) void k_quantize(const float* x, u64 n, u16
     }
     if (full) {
         if (q) {
-            ushort4 hv;
-            hv.x = h[0]; hv.y = h[1]; hv.z = h[2]; hv.w = h[3];
-            *reinterpret_cast<ushort4*>(q + e0) = hv;
+            st_code4_stream(q + e0, h[0], h[1], h[2], h[3]);
         }
         if (dq) st4_stream(dq + e0, d[0], d[1], d[2], d[3]);
     } else {
