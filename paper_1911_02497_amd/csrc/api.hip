@@ -690,6 +690,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     a.per_tensor = per_tensor ? 1 : 0;
 
     const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
+    const unsigned mtiles = static_cast<unsigned>((tb.F + kMaskTile - 1) / kMaskTile);
     // groups of at most kSmallGroup structures: one workgroup per group ranks, masks and lists them
     bool small = tb.F > 0 && g_options[CONDENSA_OPT_SELECT_PATH].load() != 1;
     if (per_tensor) { for (int t = 0; t < n_tensors && small; ++t) if (tb.td[t].n_struct > kSmallGroup) small = false; }
@@ -703,7 +704,22 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
                 const TensorDesc& d = tb.td[t];
                 if (d.n > 0 && !(d.d[1] == 1 && d.d[2] == 1 && d.b[0] == 1 && d.b[3] == d.d[3])) rows = false;
             }
+            // every tensor a matrix tiled exactly by 2-D blocks of one width of 4, 8 or 16, rows 16-byte aligned
+            u32 tile_w = 0;
+            bool tiles = !rows;
+            for (int t = 0; t < n_tensors && tiles; ++t) {
+                const TensorDesc& d = tb.td[t];
+                if (d.n == 0) continue;
+                const bool ok = d.d[0] == 1 && d.d[1] == 1 && d.d[2] % d.b[2] == 0 && d.d[3] % d.b[3] == 0 &&
+                                (d.b[3] == 4 || d.b[3] == 8 || d.b[3] == 16) && (tile_w == 0 || tile_w == d.b[3]) &&
+                                aligned16(d.w) && d.d[3] % 4 == 0 && d.n <= 0xFFFFFFFFull;
+                if (!ok) tiles = false;
+                tile_w = d.b[3];
+            }
             if (rows) hipLaunchKernelGGL(k_struct_sumsq_rows, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else if (tiles && tile_w == 4)  hipLaunchKernelGGL((k_struct_sumsq_tiles<1>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else if (tiles && tile_w == 8)  hipLaunchKernelGGL((k_struct_sumsq_tiles<2>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else if (tiles && tile_w == 16) hipLaunchKernelGGL((k_struct_sumsq_tiles<4>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else      hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             CONDENSA_LAUNCH_CHECK();
         }
@@ -734,13 +750,13 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     }
     if (tb.F > 0) {
         if (!small) {
-            hipLaunchKernelGGL(k_struct_mask, dim3(sblocks), dim3(kBlock), 0, st, a, structure_mask_dev);
+            hipLaunchKernelGGL(k_struct_mask, dim3(mtiles), dim3(kBlock), 0, st, a, structure_mask_dev);
             CONDENSA_LAUNCH_CHECK();
         }
         if (keep_idx_dev && !small) {
-            hipLaunchKernelGGL(k_struct_scan_blocks, dim3(1), dim3(kBlock), 0, st, a.sblock, static_cast<u64>(sblocks));
+            hipLaunchKernelGGL(k_struct_scan_blocks, dim3(1), dim3(kScanThreads), 0, st, a.sblock, static_cast<u64>(mtiles));
             CONDENSA_LAUNCH_CHECK();
-            hipLaunchKernelGGL(k_struct_keep_idx, dim3(sblocks), dim3(kBlock), 0, st, a, keep_idx_dev);
+            hipLaunchKernelGGL(k_struct_keep_idx, dim3(mtiles), dim3(kBlock), 0, st, a, keep_idx_dev);
             CONDENSA_LAUNCH_CHECK();
         }
         if ((theta || mask) && tb.n_chunks > 0) {

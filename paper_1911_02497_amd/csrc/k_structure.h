@@ -16,7 +16,7 @@ struct StructArgs {
     Control* ctl;
     u64* keys;             // [F] sign-less binary64 patterns of the aggregates
     u8* smask;             // [F]
-    u32* sblock;           // [ceil(F / kBlock) + 1] kept structures per block of 256, then its scan
+    u32* sblock;           // kept structures per tile of kMaskTile structures, then its exclusive scan
     const u32* chunk_map;  // [n_chunks] tensor that owns each element chunk
     u64 F;
     u64 n_schunks;
@@ -86,6 +86,111 @@ __global__ __launch_bounds__(kBlock) void k_struct_sumsq(StructArgs a, double* s
                     }
                 }
             }
+    a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
+    if (sumsq) sumsq[u] = acc;
+    if (norms) norms[u] = static_cast<float>(sqrt(acc));
+}
+
+// Tensor that owns structure u: a proportional guess (exact when the tensors hold equal numbers of
+// structures) checked against the neighbouring starts, else the binary search.
+__device__ inline int tensor_of_struct_guess(const TensorDesc* __restrict__ td, int n_tensors, u64 F, u64 u) {
+    int g = static_cast<int>(static_cast<float>(u) * (static_cast<float>(n_tensors) / static_cast<float>(F)));
+    g = g < 0 ? 0 : (g > n_tensors - 1 ? n_tensors - 1 : g);
+    const u64 lo = td[g].struct_start;
+    const u64 hi = (g + 1 < n_tensors) ? td[g + 1].struct_start : F;
+    if (lo <= u && u < hi) return g;
+    return tensor_of_struct(td, n_tensors, u);
+}
+
+__device__ inline double add_squares(double acc, const float4& v) {
+    acc = acc + static_cast<double>(v.x) * static_cast<double>(v.x);
+    acc = acc + static_cast<double>(v.y) * static_cast<double>(v.y);
+    acc = acc + static_cast<double>(v.z) * static_cast<double>(v.z);
+    acc = acc + static_cast<double>(v.w) * static_cast<double>(v.w);
+    return acc;
+}
+
+// 2-D blocks of width 4 Q (Q = 1, 2, 4) that tile their matrices exactly, rows 16-byte aligned, fewer
+// than 2^32 elements per tensor.  One thread per block; the loads of 16 / Q block rows are issued
+// together before their squares are added in row-major order -- the same additions in the same order
+// as k_struct_sumsq.  Q = 2: where the 64 blocks of a wavefront lie in one block row, lane l fetches the
+// l-th and the (64 + l)-th float4 of the run (two fully used 1 KB loads per matrix row, so the streaming
+// hint is safe), even lanes own the run's blocks 0..31 and odd lanes blocks 32..63, and neighbouring
+// lanes trade the halves they fetched for each other.
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_struct_sumsq_tiles(StructArgs a, double* sumsq, float* norms) {
+    constexpr int G = 16 / Q;                                // block rows per group of loads
+    const u32 lane = threadIdx.x & 63u;
+    const u64 wb = static_cast<u64>(blockIdx.x) * kBlock + (threadIdx.x & ~63u);   // the wavefront's first block
+    if (wb >= a.F) return;
+    double acc = 0.0;
+    u64 u = wb + lane;
+    bool run = false;
+    if (Q == 2 && wb + 64 <= a.F) {                          // every lane computes the same values here
+        const int t = tensor_of_struct_guess(a.td, a.n_tensors, a.F, wb);
+        const TensorDesc& td = a.td[t];
+        const u64 s0 = wb - td.struct_start;
+        if (s0 + 64 <= td.n_struct) {
+            const u32 d3 = td.d[3], b2 = td.b[2];
+            const u32 G3 = fast_div(d3, td.fd[kDivB3]);
+            const u32 s32 = static_cast<u32>(s0);
+            const u32 g2 = s32 / G3, g3 = s32 - g2 * G3;
+            if (g3 + 64 <= G3) {
+                run = true;
+                const u32 half = lane & 1u;
+                u = wb + (lane >> 1) + (half ? 32u : 0u);
+                const float* p = td.w + static_cast<u64>(g2) * b2 * d3 + static_cast<u64>(g3) * 8u + lane * 4u;
+                for (u32 r0 = 0; r0 < b2; r0 += G) {
+                    float4 va[G], vb[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        if (r0 + g < b2) {
+                            const float* q = p + static_cast<u64>(r0 + g) * d3;
+                            va[g] = ld4_stream(q);
+                            vb[g] = ld4_stream(q + 256);
+                        }
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if (r0 + g < b2) {                   // the same for every lane: one tensor, one block height
+                            const float4 send = half ? va[g] : vb[g];
+                            float4 recv;
+                            recv.x = __shfl_xor(send.x, 1); recv.y = __shfl_xor(send.y, 1);
+                            recv.z = __shfl_xor(send.z, 1); recv.w = __shfl_xor(send.w, 1);
+                            acc = add_squares(acc, half ? recv : va[g]);
+                            acc = add_squares(acc, half ? vb[g] : recv);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (!run) {
+        if (u >= a.F) return;
+        const int t = tensor_of_struct_guess(a.td, a.n_tensors, a.F, u);
+        const TensorDesc& td = a.td[t];
+        const u32 d3 = td.d[3], b2 = td.b[2];
+        const u32 G3 = fast_div(d3, td.fd[kDivB3]);
+        const u32 s = static_cast<u32>(u - td.struct_start);
+        const u32 g2 = s / G3, g3 = s - g2 * G3;
+        const float* p = td.w + static_cast<u64>(g2) * b2 * d3 + static_cast<u64>(g3) * (4u * Q);
+        for (u32 r0 = 0; r0 < b2; r0 += G) {
+            float4 v[G][Q];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    if (r0 + g < b2) {
+                        const float* src = p + static_cast<u64>(r0 + g) * d3 + q * 4;
+                        v[g][q] = (Q == 1) ? ld4_stream(src) : *reinterpret_cast<const float4*>(src);
+                    }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (r0 + g < b2) {
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) acc = add_squares(acc, v[g][q]);
+                }
+        }
+    }
     a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
     if (sumsq) sumsq[u] = acc;
     if (norms) norms[u] = static_cast<float>(sqrt(acc));
@@ -500,51 +605,130 @@ __global__ __launch_bounds__(kSmallThreads) void k_struct_small(StructArgs a, u8
     }
 }
 
-// keep flag of every structure and the number of kept structures of every block of 256
-__global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask) {
-    __shared__ u32 s_cnt;
-    const int tid = threadIdx.x;
-    if (tid == 0) s_cnt = 0;
-    __syncthreads();
-    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + tid;
-    u32 keep = 0;
-    if (u < a.F) {
-        const int t = tensor_of_struct(a.td, a.n_tensors, u);
-        const Slot& s = a.slots[a.per_tensor ? t : 0];
-        const u64 idx = a.per_tensor ? u - a.td[t].struct_start : u;
-        const u64 key = a.keys[u];
-        keep = (key > s.prefix || (key == s.prefix && idx < s.tie_end)) ? 1u : 0u;
-        if (s.state == kInactive) keep = 0;
-        a.smask[u] = static_cast<u8>(keep);
-        if (user_mask) user_mask[u] = static_cast<u8>(keep);
+// Structures per thread and per workgroup of the mask / kept-index passes.
+constexpr int kMaskPer = 4;
+constexpr int kMaskTile = kBlock * kMaskPer;
+constexpr int kScanThreads = 1024;
+
+// inclusive scan of one u32 per thread over the workgroup; *total = workgroup sum.  Ends with a barrier.
+template <int THREADS>
+__device__ inline u32 wg_incl_scan_u32(u32 v, u32* s_wave, u32* total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    u32 inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const u32 o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
     }
-    if (keep) atomicAdd(&s_cnt, 1u);
+    if (lane == 63) s_wave[wv] = inc;
     __syncthreads();
-    if (tid == 0) a.sblock[blockIdx.x] = s_cnt;
+    u32 before = 0, tot = 0;
+#pragma unroll
+    for (int j = 0; j < THREADS / 64; ++j) {
+        const u32 x = s_wave[j];
+        if (j < wv) before += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return before + inc;
 }
 
-// exclusive scan of the per-block counts (single workgroup)
-__global__ __launch_bounds__(kBlock) void k_struct_scan_blocks(u32* sblock, u64 n_blocks) {
-    __shared__ u64 s_wave[kBlock / 64];
-    u64 running = 0;
-    for (u64 base = 0; base < n_blocks; base += kBlock) {
-        const u64 i = base + threadIdx.x;
-        const u64 v = (i < n_blocks) ? sblock[i] : 0;
-        u64 total;
-        const u64 ex = block_excl_scan_u64(v, s_wave, &total);
-        if (i < n_blocks) sblock[i] = static_cast<u32>(running + ex);
+// keep flag of every structure and the number of kept structures of every tile of kMaskTile
+__global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask) {
+    __shared__ u32 s_wave[kBlock / 64];
+    const int tid = threadIdx.x;
+    const u64 u0 = (static_cast<u64>(blockIdx.x) * kBlock + tid) * kMaskPer;
+    u32 keep[kMaskPer] = {0, 0, 0, 0};
+    if (u0 < a.F) {
+        const bool full = u0 + kMaskPer <= a.F;
+        u64 key[kMaskPer] = {0, 0, 0, 0};
+        if (full) {
+            const ulonglong2 k01 = *reinterpret_cast<const ulonglong2*>(a.keys + u0);
+            const ulonglong2 k23 = *reinterpret_cast<const ulonglong2*>(a.keys + u0 + 2);
+            key[0] = k01.x; key[1] = k01.y; key[2] = k23.x; key[3] = k23.y;
+        } else {
+            for (int k = 0; k < kMaskPer; ++k) if (u0 + k < a.F) key[k] = a.keys[u0 + k];
+        }
+        int t = a.per_tensor ? tensor_of_struct(a.td, a.n_tensors, u0) : 0;
+#pragma unroll
+        for (int k = 0; k < kMaskPer; ++k) {
+            const u64 u = u0 + k;
+            if (u >= a.F) break;
+            u64 idx = u;
+            if (a.per_tensor) {
+                while (t + 1 < a.n_tensors && a.td[t + 1].struct_start <= u) ++t;
+                idx = u - a.td[t].struct_start;
+            }
+            const Slot& s = a.slots[a.per_tensor ? t : 0];
+            keep[k] = (key[k] > s.prefix || (key[k] == s.prefix && idx < s.tie_end)) ? 1u : 0u;
+            if (s.state == kInactive) keep[k] = 0;
+        }
+        const uchar4 m4 = make_uchar4(static_cast<u8>(keep[0]), static_cast<u8>(keep[1]), static_cast<u8>(keep[2]),
+                                      static_cast<u8>(keep[3]));
+        if (full) {
+            *reinterpret_cast<uchar4*>(a.smask + u0) = m4;
+            if (user_mask) {
+                if ((reinterpret_cast<uintptr_t>(user_mask) & 3u) == 0) *reinterpret_cast<uchar4*>(user_mask + u0) = m4;
+                else for (int k = 0; k < kMaskPer; ++k) user_mask[u0 + k] = static_cast<u8>(keep[k]);
+            }
+        } else {
+            for (int k = 0; k < kMaskPer; ++k)
+                if (u0 + k < a.F) {
+                    a.smask[u0 + k] = static_cast<u8>(keep[k]);
+                    if (user_mask) user_mask[u0 + k] = static_cast<u8>(keep[k]);
+                }
+        }
+    }
+    u32 total;
+    wg_incl_scan_u32<kBlock>(keep[0] + keep[1] + keep[2] + keep[3], s_wave, &total);
+    if (tid == 0) a.sblock[blockIdx.x] = total;
+}
+
+// exclusive scan of the per-tile counts (single workgroup, 4 counts per thread and step)
+__global__ __launch_bounds__(kScanThreads) void k_struct_scan_blocks(u32* sblock, u64 n_blocks) {
+    __shared__ u32 s_wave[kScanThreads / 64];
+    u32 running = 0;
+    for (u64 base = 0; base < n_blocks; base += kScanThreads * 4) {
+        const u64 i = base + static_cast<u64>(threadIdx.x) * 4;
+        u32 v[4] = {0, 0, 0, 0};
+        const bool full = i + 4 <= n_blocks;
+        if (full) {
+            const uint4 x = *reinterpret_cast<const uint4*>(sblock + i);
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        } else {
+            for (int k = 0; k < 4; ++k) if (i + k < n_blocks) v[k] = sblock[i + k];
+        }
+        const u32 sum = v[0] + v[1] + v[2] + v[3];
+        u32 total;
+        const u32 ex = running + wg_incl_scan_u32<kScanThreads>(sum, s_wave, &total) - sum;
+        if (full) {
+            *reinterpret_cast<uint4*>(sblock + i) = make_uint4(ex, ex + v[0], ex + v[0] + v[1], ex + v[0] + v[1] + v[2]);
+        } else {
+            u32 e = ex;
+            for (int k = 0; k < 4; ++k) if (i + k < n_blocks) { sblock[i + k] = e; e += v[k]; }
+        }
         running += total;
     }
 }
 
 // ascending ids of the kept structures
 __global__ __launch_bounds__(kBlock) void k_struct_keep_idx(StructArgs a, int32_t* keep_idx) {
-    __shared__ u64 s_wave[kBlock / 64];
-    const u64 u = static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x;
-    const u32 keep = (u < a.F) ? a.smask[u] : 0u;
-    u64 total;
-    const u64 ex = block_excl_scan_u64(keep, s_wave, &total);
-    if (keep) keep_idx[a.sblock[blockIdx.x] + ex] = static_cast<int32_t>(u);
+    __shared__ u32 s_wave[kBlock / 64];
+    const u64 u0 = (static_cast<u64>(blockIdx.x) * kBlock + threadIdx.x) * kMaskPer;
+    u32 m[kMaskPer] = {0, 0, 0, 0};
+    if (u0 + kMaskPer <= a.F) {
+        const uchar4 x = *reinterpret_cast<const uchar4*>(a.smask + u0);
+        m[0] = x.x; m[1] = x.y; m[2] = x.z; m[3] = x.w;
+    } else {
+        for (int k = 0; k < kMaskPer; ++k) if (u0 + k < a.F) m[k] = a.smask[u0 + k];
+    }
+    const u32 sum = m[0] + m[1] + m[2] + m[3];
+    u32 total;
+    u64 pos = static_cast<u64>(a.sblock[blockIdx.x]) + wg_incl_scan_u32<kBlock>(sum, s_wave, &total) - sum;
+#pragma unroll
+    for (int k = 0; k < kMaskPer; ++k)
+        if (m[k]) keep_idx[pos++] = static_cast<int32_t>(u0 + k);
 }
 
 // theta = w on kept structures, +0 elsewhere; element mask = structure mask broadcast

@@ -99,6 +99,21 @@ def test_block_prune_small_shapes_scopes_and_ties():
         _compare(res, oracle.block_prune([m], bh, bw, 0.5, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, [m], f"{bh}x{bw}")
 
 
+@pytest.mark.parametrize("bh,bw", [(1, 4), (32, 4), (3, 8), (8, 8), (24, 8), (8, 16), (5, 16)])
+def test_exactly_tiled_blocks_of_width_4_8_16(bh, bw):
+    """Block widths with an aggregation kernel of their own: matrices whose block rows hold 130, 65, 9 and 1
+    blocks (wavefronts inside one block row, across two, across tensors), heights of less and more than one
+    group of loads, an empty tensor between them, tensors of unequal size, a ragged last wavefront."""
+    rng = np.random.default_rng(bh * 100 + bw)
+    shapes = [(bh * 3, bw * 130), (0, bw), (bh * 2, bw * 65), (bh * 5, bw * 9), (bh, bw), (bh * 7, bw * 130)]
+    ms = [rng.standard_normal(s).astype(np.float32) for s in shapes]
+    ms[2][0:bh, 0:bw] = ms[2][bh:2 * bh, bw:2 * bw]       # exact tie between two blocks
+    for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
+        res = P.condensa_block_prune(up(ms), bh, bw, 0.37, scope)
+        torch.cuda.synchronize()
+        _compare(res, oracle.block_prune(ms, bh, bw, 0.37, scope), scope, ms, f"{bh}x{bw} scope={scope}")
+
+
 def test_shape_errors():
     m = torch.ones((6, 10), device=DEV)
     with pytest.raises(P.CondensaError) as e:
