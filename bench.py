@@ -57,9 +57,9 @@ def parse():
     ap.add_argument("--all-phases", action="store_true",
                     help="time every phase with events (adds ~10 us of idle gap per event); default: the apply sweep only")
     ap.add_argument("--workload", default="lc_stress",
-                    choices=["lc_stress", "prune_stress", "single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
+                    choices=["lc_stress", "prune_stress", "filter_stress", "block_stress", "single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
                              "resnet_filter_per_tensor", "transformer_block8", "transformer_block32"],
-                    help="lc_stress is the benchmark; the others are the small parity workloads, timed for reference")
+                    help="lc_stress is the benchmark; *_stress run the other entry points on the same weights, the rest are the small parity workloads, timed for reference")
     ap.add_argument("--select-path", type=int, default=0, help="0 auto, 1 radix levels only, 2 sampled window")
     ap.add_argument("--window-margin", type=int, default=80,
                     help="half-width of the sampled window in 1/16 standard deviations (default 80 = 5 sigma)")
@@ -84,6 +84,22 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         call = lambda: P.condensa_prune(d, [0.1], workspace=ws, outputs=prev[0])  # noqa: E731
         op, F, J, bytes_per_elem, desc = P.binding.OP_PRUNE, 0, 1, 13, "global prune d=0.1, theta + mask"
         cpu = lambda: oracle.prune(host[:2], [0.1])  # noqa: E731
+    elif name in ("filter_stress", "block_stress"):
+        # structure pruning of the large-model weights: the matrices as 4096 filters of 512x3x3, or 8x8 blocks
+        host, _ = workloads.lc_stress(indices=range(args.tensors), threads=16)
+        if name == "filter_stress":
+            host = [h.reshape(h.shape[0], h.shape[1] // 9, 3, 3) for h in host]
+            d = up(host)
+            call = lambda: P.condensa_filter_prune(d, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0])  # noqa: E731
+            op, F, desc = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in host), "global filter prune d=0.5, theta + mask"
+            cpu = lambda: oracle.filter_prune(host[:8], 0.5, P.SCOPE_GLOBAL)  # noqa: E731
+        else:
+            d = up(host)
+            call = lambda: P.condensa_block_prune(d, 8, 8, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0])  # noqa: E731
+            op, F = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // 8) * (t.shape[1] // 8) for t in host)
+            desc = "global block prune 8x8 d=0.5, theta + mask"
+            cpu = lambda: oracle.block_prune(host[:8], 8, 8, 0.5, P.SCOPE_GLOBAL)  # noqa: E731
+        J, bytes_per_elem = 1, 13                 # the weights are read twice (aggregate, apply): 4 + 4 + 4 theta + 1 mask
     elif name == "single_prune_fp16":
         host = workloads.single_matrix()
         d = up(host)
@@ -142,9 +158,10 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         t0 = time.perf_counter()
         cpu()
         dt = time.perf_counter() - t0
-        n_cpu = sum(t.size for t in host[:2]) if name == "prune_stress" else N
+        n_sample = {"prune_stress": 2, "filter_stress": 8, "block_stress": 8}.get(name, len(host))
+        n_cpu = sum(t.size for t in host[:n_sample])
         cpu_rec = {"value": round(n_cpu / dt, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
-                   "sample": ("the first 2 tensors" if name == "prune_stress" else "the whole workload") + f" once, {dt:.2f} s",
+                   "sample": (f"the first {n_sample} tensors" if name.endswith("_stress") else "the whole workload") + f" once, {dt:.2f} s",
                    "host_cpus": os.cpu_count()}
     print(json.dumps({
         "metric": "weights pruned/sec and achieved HBM GB/s (% of peak) per compression step",

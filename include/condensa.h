@@ -25,7 +25,7 @@
  *    any other alignment is accepted and takes a scalar path.
  *  - The flat index of an element is its position in the concatenation of the call's tensors in
  *    table order.  Tensors with zero elements and calls with zero tensors are valid.  A call may
- *    carry at most 2^36 elements in total (CONDENSA_ERR_SIZE beyond that).
+ *    carry at most 3 * 2^32 (12 884 901 888) elements in total (CONDENSA_ERR_SIZE beyond that).
  *  - kept count  k = llround(density * N) (binary64 product, halves away from zero), clamped to
  *    [0, N]; density must lie in [0, 1].
  *  - Ordering key of a value x is the bit pattern of |x|: -0 equals +0, infinities rank above

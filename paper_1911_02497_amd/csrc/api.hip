@@ -915,7 +915,7 @@ static condensa_status quantize_impl(const float* x_dev, uint64_t n, uint16_t* q
     const bool vec = aligned16(x_dev) && (!dq_dev || aligned16(dq_dev)) &&
                      (!q_dev || (reinterpret_cast<uintptr_t>(q_dev) & 7u) == 0);
     constexpr int QT = kQuantThreads;
-    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);           // <= 2^28 for n <= 2^36
+    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);           // x QT threads stays below 2^32 for n <= kMaxElems
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (!dq_dev && aligned16(x_dev) && aligned16(q_dev))
         hipLaunchKernelGGL((k_quantize_codes<QT, C>), dim3(static_cast<unsigned>((n + QT * 8 - 1) / (QT * 8))), dim3(QT), 0, st, x_dev, n, q_dev);

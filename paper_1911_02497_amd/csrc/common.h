@@ -19,7 +19,11 @@ constexpr int kChunk = 8192;           // elements of one tensor handled as a un
 constexpr int kQuadsPerThread = kChunk / (kBlock * 4);   // 8 float4 per thread and chunk
 constexpr int kMaxJ = CONDENSA_MAX_DENSITIES;
 constexpr int kBins = 2048;            // bins of one radix level (digits are at most 11 bits)
-constexpr u64 kMaxElems = static_cast<u64>(1) << 36;   // elements per call (keeps every grid below 2^31 workgroups)
+// Elements per call.  The densest launches give one thread four elements (of tensors padded to whole
+// chunks, at most 65536 of them), and a launch must stay below 2^32 threads: the runtime rejects a
+// multiple of 2^32 and silently wraps anything else above it.  3 * 2^32 elements is also about what fits
+// the device: an L-C step moves 20 bytes per weight.
+constexpr u64 kMaxElems = static_cast<u64>(3) << 32;
 constexpr int kSlotBatch = 14;         // rankings that share one sweep's LDS histograms (14 x 1024 bins x 4 B + digit table < 64 KB)
 
 // Division of a 32-bit unsigned x by a divisor fixed on the host, by multiplication with a rounded-up

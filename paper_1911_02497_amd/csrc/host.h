@@ -65,7 +65,7 @@ inline bool tensor_elems(const condensa_tensor& t, u64* n) {
     for (int i = 0; i < t.ndim; ++i) {
         if (t.shape[i] < 0) return false;
         const u64 d = static_cast<u64>(t.shape[i]);
-        if (d != 0 && p > kMaxElems / d) return false;   // cap at 2^36 elements
+        if (d != 0 && p > kMaxElems / d) return false;   // cap at kMaxElems
         p *= d;
     }
     *n = p;

@@ -80,7 +80,7 @@ def test_argument_errors_are_found_on_the_host_before_any_launch():
     for fn in (lib.condensa_quantize, lib.condensa_quantize_bf16):
         assert fn(null, 4, fake, fake, null) == -1                       # x missing
         assert fn(fake, 4, null, null, null) == -1                       # no output wanted
-        assert fn(fake, (1 << 36) + 1, fake, null, null) == -2           # too many elements
+        assert fn(fake, (3 << 32) + 1, fake, null, null) == -2           # too many elements
         assert fn(null, 0, null, null, null) == 0                        # nothing to do
     for fn in (lib.condensa_dequantize, lib.condensa_dequantize_bf16):
         assert fn(null, 4, fake, null) == -1
