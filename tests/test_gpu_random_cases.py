@@ -93,3 +93,44 @@ def test_lc_step_random(seed):
             assert_bits_equal(res[name][t], ora[name][t], f"{what} {name} {t}")
         if pq:
             assert np.array_equal(res["theta_f16"][t].cpu().numpy().view(np.uint16), ora["theta_f16"][t]), f"{what} f16 {t}"
+
+
+@pytest.mark.parametrize("scope", [P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR])
+def test_three_thousand_small_tensors(scope):
+    """Long tensor tables: 3000 tensors of 0..200 elements (every chunk is ragged, many tensors are empty)
+    around two larger ones, under element pruning, the L-C step and filter pruning."""
+    rng = np.random.default_rng(77)
+    sizes = [int(s) for s in rng.integers(0, 201, 3000)]
+    sizes[1500], sizes[2999] = 70001, 8192 * 3
+    ws = [np.asarray(rng.standard_normal(s) * 0.05, dtype=np.float32) for s in sizes]
+    dev = up(ws)
+    dens = [0.25, 0.9]
+    res = P.condensa_prune(dev, dens, scope=scope)
+    torch.cuda.synchronize()
+    check_prune_against_oracle(res, oracle.prune(ws, dens, scope), scope, len(ws), f"3000 tensors scope {scope}")
+    if scope == P.SCOPE_GLOBAL:
+        ls = [np.asarray(rng.standard_normal(w.shape) * 0.01, dtype=np.float32) for w in ws]
+        got = P.condensa_lc_step(dev, up(ls), 0.5, 0.3)
+        torch.cuda.synchronize()
+        ora = oracle.lc_step(ws, ls, 0.5, 0.3)
+        assert_select_equal(P.select_records(got["results"])[0], ora["select"], "3000 tensors lc")
+        for t in range(len(ws)):
+            assert np.array_equal(got["mask"][t].cpu().numpy(), ora["mask"][t])
+            for name in ("theta", "lambda", "grad"):
+                assert_bits_equal(got[name][t], ora[name][t], f"3000 tensors lc {name} {t}")
+    # the same data as 4-D tensors of 1..4 filters each
+    fs = [w[: (w.size // 4) * 4].reshape(-1, 2, 2, 1)[:4].copy() for w in ws if w.size >= 4]
+    got = P.condensa_filter_prune(up(fs), 0.5, scope)
+    torch.cuda.synchronize()
+    ora = oracle.filter_prune(fs, 0.5, scope)
+    recs = P.select_records(got["results"])
+    if scope == P.SCOPE_GLOBAL:
+        assert_select_equal(recs[0], ora["select"], "3000 tensors filters")
+    else:
+        for t in range(len(fs)):
+            assert_select_equal(recs[t], ora["select"][t], f"3000 tensors filters {t}")
+    assert np.array_equal(got["sumsq"].cpu().numpy().view(np.uint64), ora["sumsq"].view(np.uint64))
+    assert np.array_equal(got["structure_mask"].cpu().numpy(), ora["structure_mask"])
+    for t in range(len(fs)):
+        assert np.array_equal(got["mask"][t].cpu().numpy(), ora["mask"][t])
+        assert_bits_equal(got["theta"][t], ora["theta"][t], f"3000 tensors filters theta {t}")
