@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 # HBM traffic of one k_window_fused launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # calibrated with a plain copy (profiles/lc_step_large_model_hbm_counters.md).  Reported only while the
 # kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
-MEASURED_TRAFFIC = {"bytes": 24598172696, "tensors": 64,
-                    "sources_sha256": "bd94dd595494f2f3f07980972e7a9f6fbf5b26ddcfcbbafe9ff52530dd7f9044"}
+MEASURED_TRAFFIC = {"bytes": 24598545169, "tensors": 64,
+                    "sources_sha256": "e65a5e5a2efa2f0048c3d6c36cace239eb0619d9551d012ea4feaca6beb9e513"}
 KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 
 

@@ -238,38 +238,56 @@ __global__ __launch_bounds__(64) void k_lc_sgd(DataArgs a, const OutDesc* __rest
 }
 
 // ---- footprint objective: number of non-zero parameters (Evaluation, Objective 1) ---------------------
-// Per-workgroup counts go to `partial`; k_sum_partials adds them up, so the result needs no atomics
-// and no cleared memory.
+// Persistent workgroups, one chunk per step; the loads of the next chunk are requested before the current
+// one is counted.  Per-workgroup counts go to `partial`; k_sum_partials adds them up, so the result needs
+// no atomics and no cleared memory.
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* partial) {
     __shared__ u64 s_wave[kBlock / 64];
+    constexpr int R = F16 ? kQuadsPerThread / 2 : kQuadsPerThread;     // 128-bit loads per thread and chunk
     const int tid = threadIdx.x;
     u64 cnt = 0;
-    for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
-        const int t = static_cast<int>(a.chunk_map[c]);
-        const TensorDesc& td = a.td[t];
+    f32x4 nxt[R];
+    bool nxt_full = false;
+    // requests chunk c's data when the whole chunk lies inside its tensor (the same for every thread)
+    auto request = [&](u64 c) {
+        nxt_full = false;
+        if (!VEC || c >= a.n_chunks) return;
+        const TensorDesc& td = a.td[a.chunk_map[c]];
         const u64 base = (c - td.chunk_start) * kChunk;
-        if (!F16 && VEC && base + kChunk <= td.n) {       // whole chunk inside the tensor: loads first
-            float4 v[kQuadsPerThread];
+        if (base + kChunk > td.n) return;
+        nxt_full = true;
+        if (F16) {
+            const u16* p = reinterpret_cast<const u16*>(td.w) + base;
 #pragma unroll
-            for (int q = 0; q < kQuadsPerThread; ++q) v[q] = ld4_stream(td.w + base + q * (kBlock * 4) + tid * 4);
+            for (int q = 0; q < R; ++q)
+                nxt[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + q * (kBlock * 8) + tid * 8));
+        } else {
 #pragma unroll
-            for (int q = 0; q < kQuadsPerThread; ++q)
-                cnt += (mag_key(v[q].x) != 0) + (mag_key(v[q].y) != 0) + (mag_key(v[q].z) != 0) + (mag_key(v[q].w) != 0);
+            for (int q = 0; q < R; ++q)
+                nxt[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(td.w + base + q * (kBlock * 4) + tid * 4));
+        }
+    };
+    request(blockIdx.x);
+    for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+        f32x4 cur[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q) cur[q] = nxt[q];
+        const bool full = nxt_full;
+        request(c + gridDim.x);
+        if (full) {
+#pragma unroll
+            for (int q = 0; q < R; ++q)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const u32 bits = __float_as_uint(cur[q][k]);
+                    if (F16) cnt += ((bits & 0x7FFFu) != 0) + ((bits & 0x7FFF0000u) != 0);
+                    else     cnt += (bits & 0x7FFFFFFFu) != 0;
+                }
             continue;
         }
-        if (F16 && VEC && base + kChunk <= td.n) {        // binary16: 8 codes per 128-bit load
-            const u16* p = reinterpret_cast<const u16*>(td.w);
-            u16x8 v[kQuadsPerThread / 2];
-#pragma unroll
-            for (int q = 0; q < kQuadsPerThread / 2; ++q)
-                v[q] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(p + base + q * (kBlock * 8) + tid * 8));
-#pragma unroll
-            for (int q = 0; q < kQuadsPerThread / 2; ++q)
-#pragma unroll
-                for (int k = 0; k < 8; ++k) cnt += (v[q][k] & 0x7FFFu) != 0;
-            continue;
-        }
+        const TensorDesc& td = a.td[a.chunk_map[c]];
+        const u64 base = (c - td.chunk_start) * kChunk;
         for (int q = 0; q < kQuadsPerThread; ++q) {
             const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
             if (e0 >= td.n) break;
