@@ -7,7 +7,7 @@
  * compression (C) step of the L-C algorithm with its multiplier update (Section 3.3).  A target
  * sparsity s (Introduction: proportion of zero-valued parameters) is passed as the density
  * d = 1 - s; the library turns it into an exact kept count and a magnitude threshold
- * (Section 3.1: "magnitude threshold computation from a sparsity").
+ * (Section 3.1: the schemes derive the magnitude threshold from the sparsity).
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -108,7 +108,7 @@ size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structu
 
 /*
  * Prune() scheme / prune operator: unstructured magnitude pruning (Background: magnitude
- * thresholding; Section 3.3: Theta has fewer non-zeros "by removing lower magnitude weights";
+ * thresholding; Section 3.3: Theta is made sparse by dropping the weights of lowest magnitude;
  * Table 1).  Serves n_densities target densities from one sweep over the weights, which is what a
  * sparsity search with up to 10 samples per search (Results) asks of the same reference weights.
  * Optionally fuses Quantize(float16) (Evaluation, Objective 1: Compose([Prune(), Quantize(float16)])).
@@ -171,7 +171,7 @@ condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tenso
                                      void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
- * NeuronPrune scheme / neuron_prune operator (Table 1: "aggregates and prunes neurons (1D blocks)").
+ * NeuronPrune scheme / neuron_prune operator (Table 1: neurons, seen as 1-D blocks, are aggregated and pruned).
  * Every tensor must have ndim == 2, [out, in]; neuron r is row r (the weights into output unit r).
  * Aggregate, ranking and arguments as for condensa_filter_prune.
  */
@@ -183,7 +183,7 @@ condensa_status condensa_neuron_prune(const condensa_tensor* tensors, int n_tens
                                       void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
- * StructurePrune scheme (Table 1: "combines neuron and filter pruning"): tensors with ndim == 2
+ * StructurePrune scheme (Table 1: neuron and filter pruning together): tensors with ndim == 2
  * contribute their neurons, tensors with ndim == 4 their filters, to one list of structures (ids in
  * table order) that is ranked globally or per tensor.  Arguments as for condensa_filter_prune.
  */
@@ -195,7 +195,7 @@ condensa_status condensa_structure_prune(const condensa_tensor* tensors, int n_t
                                          void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
- * BlockPrune with n-D blocks and ragged edges (Table 1: "n-D blocks of size bs"; the evaluation
+ * BlockPrune with n-D blocks and ragged edges (Table 1: blocks of any dimensionality and a given size; the evaluation
  * prunes blocks of size 5 in LSTM matrices).  block_shape has block_ndim (1..4) positive entries and
  * every tensor must have ndim == block_ndim.  The block grid has ceil(dim / block) cells per
  * dimension; cells on the far edge of a dimension that the block does not divide are smaller.
@@ -238,7 +238,7 @@ condensa_status condensa_dequantize_bf16(const uint16_t* q_dev, uint64_t n, floa
 
 /*
  * One compression step of the L-C algorithm with the augmented-Lagrangian updates (Section 3.3;
- * mu_j = mu_0 a^j is the caller's schedule, "L-C Optimizer Settings").  Per element, in binary32
+ * mu_j = mu_0 a^j is the caller's schedule, L-C Optimizer Settings).  Per element, in binary32
  * with one rounding per operation and no fused multiply-add:
  *      t = lambda / mu;  v = w - t;
  *      theta = prune(v) at `density`, one global ranking over all tensors of the call;
@@ -279,8 +279,8 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
                                     void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /*
- * Memory-footprint objective (Evaluation, Objective 1: "the number of bytes consumed by the model's
- * non-zero parameters"): writes to *count_dev the number of non-zero elements over all tensors; the
+ * Memory-footprint objective (Evaluation, Objective 1: the bytes taken by the model's non-zero
+ * parameters): writes to *count_dev the number of non-zero elements over all tensors; the
  * footprint is that count times the element size.  is_f16 = 0: tensors hold fp32 values; is_f16 = 1:
  * `w` of every tensor points to binary16 bit patterns (as written to theta_f16) and shape counts
  * those.  +0 and -0 are zeros.  Workspace: condensa_workspace_bytes(CONDENSA_OP_COUNT_NONZERO, ...).
@@ -291,8 +291,8 @@ condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_ten
 
 /*
  * One SGD-with-momentum update of the learning (L) step with the L-C penalty folded in (Section 3.3:
- * the L step "trains the uncompressed model but with a quadratic regularization term"; "L-C Optimizer
- * Settings": SGD, momentum 0.9).  The gradient of L(w) + mu/2 ||w - theta - lambda/mu||^2 is
+ * the L step trains the uncompressed model with an added quadratic penalty; L-C Optimizer Settings:
+ * SGD, momentum 0.9).  The gradient of L(w) + mu/2 ||w - theta - lambda/mu||^2 is
  * grad L + mu (w - theta) - lambda, so the separate penalty-gradient buffer of condensa_lc_step is not
  * needed.  Per element, binary32, one rounding per operation, no fused multiply-add:
  *      g = (grad_loss + mu * (w - theta)) - lambda;   buf = momentum * buf + g;   w = w - lr * buf.
@@ -306,7 +306,7 @@ condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tenso
                                      float mu, float lr, float momentum,
                                      void* workspace_dev, size_t workspace_bytes, void* stream);
 
-/* mu_j = mu_0 * a^j ("L-C Optimizer Settings": mu_0 = 1e-3, a = 1.1), evaluated in binary64 (host). */
+/* mu_j = mu_0 * a^j (L-C Optimizer Settings: mu_0 = 1e-3, a = 1.1), evaluated in binary64 (host). */
 float condensa_mu_schedule(double mu0, double a, int j);
 
 /*

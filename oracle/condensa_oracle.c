@@ -7,9 +7,9 @@
  *
  * What is written out here (paper passages in brackets):
  *   - unstructured magnitude pruning to an exact kept count: the weights of
- *     lower magnitude are set to zero [Background, "thresholding (magnitude
- *     based)"; Section 3.3, pruning as D(Theta) = Theta with fewer non-zeros;
- *     Section 3.1 "magnitude threshold computation from a sparsity"];
+ *     lower magnitude are set to zero [Background, magnitude-based
+ *     thresholding; Section 3.3, pruning as D(Theta) = Theta with fewer non-zeros;
+ *     Section 3.1, the magnitude threshold that realises a given sparsity];
  *     sparsity is the proportion of zero-valued parameters [Introduction];
  *   - low-precision approximation, binary32 -> binary16 and back [Background;
  *     Section 3.1 quantize/dequantize; Section 3.3 w_i = theta_i];
@@ -17,7 +17,7 @@
  *     selection [Table 1, FilterPrune / BlockPrune; Section 3.1];
  *   - the C step as C(w) = argmin ||w - D(Theta)||^2 inside one augmented
  *     Lagrangian iteration with multipliers lambda and penalty mu
- *     [Section 3.3; constants in "L-C Optimizer Settings"].
+ *     [Section 3.3; constants in L-C Optimizer Settings].
  *
  * Readings where the paper is silent (identical on the GPU side by
  * specification, not by shared code):
@@ -312,7 +312,7 @@ void oracle_lc_update(const float* w, const float* lambda, const float* v, const
     }
 }
 
-/* ---- n-D blocks with ragged edges (BlockPrune "n-D blocks of size bs", Table 1) ------------------
+/* ---- n-D blocks with ragged edges (BlockPrune over blocks of any dimensionality, Table 1) ------------------
  * The tensor is viewed as 4-D [d0,d1,d2,d3] (leading dims 1 for lower ranks), the block as
  * [b0,b1,b2,b3].  The block grid has ceil(d/b) cells per dim; cells at the far edges are smaller.
  * Block id is row-major over the grid; inside a block the squares are added in row-major order. */
@@ -390,7 +390,7 @@ uint64_t oracle_count_nonzero_f16(const uint16_t* x, uint64_t n)
     return c;
 }
 
-/* ---- thinning: physically remove zero structures (Section 3.4, "Network Thinning", final phase) ----
+/* ---- thinning: physically remove zero structures (Section 3.4, Network Thinning, final phase) ----
  * out[o', i', r] = w[keep_out[o'], keep_in[i'], r] for a tensor viewed as [Cout, Cin, kh*kw];
  * a NULL list keeps every index of that dimension. */
 void oracle_thin(const float* w, uint64_t c_out, uint64_t c_in, uint64_t ksize,
@@ -407,7 +407,7 @@ void oracle_thin(const float* w, uint64_t c_out, uint64_t c_in, uint64_t ksize,
 }
 
 /* ---- learning-step update with the L-C penalty folded in (Section 3.3: the L step trains w with a
- * quadratic regularisation term; "L-C Optimizer Settings": SGD with momentum 0.9) ------------------
+ * quadratic regularisation term; L-C Optimizer Settings: SGD with momentum 0.9) ------------------
  * gradient of  L(w) + mu/2 ||w - theta - lambda/mu||^2  is  grad L + mu (w - theta) - lambda;
  * momentum update  buf' = m buf + g;  w' = w - lr buf'.  binary32, one rounding per operation. */
 void oracle_lc_sgd_step(const float* w, const float* grad_loss, const float* theta, const float* lambda,

@@ -1,6 +1,6 @@
 // Exact k-th-largest selection by most-significant-digit radix levels with workgroup-private LDS
 // histograms, and the deterministic tie rule (lowest index first).
-// Section 3.1: "magnitude threshold computation from a sparsity"; Section 3.3: the C step.
+// Section 3.1: the magnitude threshold that realises a given sparsity; Section 3.3: the C step.
 #pragma once
 #include "common.h"
 

@@ -1,7 +1,7 @@
 // Structure pruning: per-filter / per-block sums of squares, ranking of the aggregates, structure
 // masks, kept-index lists and the element-wise apply.
-// Table 1: FilterPrune ("aggregates and prunes filters (3D blocks)"), BlockPrune ("n-D blocks of size
-// bs"); Section 3.1: "filter/neuron/block aggregation".
+// Table 1: FilterPrune (filters, seen as 3-D blocks, are aggregated and pruned), BlockPrune (blocks of any
+// dimensionality and a given size); Section 3.1: the schemes aggregate filters, neurons and blocks.
 #pragma once
 #include "k_apply.h"
 #include "k_select.h"

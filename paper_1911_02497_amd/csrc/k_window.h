@@ -7,7 +7,7 @@
 // resolved exactly on that short candidate list.  A window that turns out not to hold the wanted
 // rank (or a candidate list that overflows) is detected on the device and the ranking falls back to
 // the radix levels over the weights, so the result never depends on the sample.
-// Section 3.1: "magnitude threshold computation from a sparsity"; several target sparsities of one
+// Section 3.1: the magnitude threshold that realises a given sparsity; several target sparsities of one
 // search (Results: up to 10 samples per search) are served by the same sweep.
 #pragma once
 #include "host.h"

@@ -136,7 +136,7 @@ def test_footprint_counts_nonzeros_and_reproduces_the_two_times_of_pq():
     assert 4 * w.size / (2 * nnz) == 2 / 0.05                      # r_c = 2 / (1 - s)
 
 
-# ---- learning-step update with the penalty folded in ("L-C Optimizer Settings": SGD, momentum 0.9) ----
+# ---- learning-step update with the penalty folded in (L-C Optimizer Settings: SGD, momentum 0.9) ----
 
 def _sgd_case(n=3000, seed=20):
     rng = np.random.default_rng(seed)

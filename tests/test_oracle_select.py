@@ -4,8 +4,8 @@ The oracle is checked against things it does not compute itself: a brute-force
 O(N^2) rank written here from the definition, exhaustive optimality of the
 compression mapping C(w) = argmin ||w - D(Theta)||^2 (Section 3.3), numpy's
 partition, the closed-form Gaussian quantile, and the invariants that follow
-from "sparsity = proportion of zero-valued parameters" (Introduction) and
-"zeroing out lower magnitude weights" (Section 3.3).
+from sparsity being the proportion of zero-valued parameters (Introduction) and
+from pruning zeroing the weights of lowest magnitude (Section 3.3).
 """
 import itertools
 import math
