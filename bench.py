@@ -178,7 +178,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
+        print("bench.py: the path runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
