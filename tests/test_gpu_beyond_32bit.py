@@ -75,7 +75,9 @@ def _check_prune_properties(ws, theta, mask, rec, k, what):
     return T
 
 
-FORMS = {"one_sweep": (2, 0), "two_sweeps": (2, 1), "radix": (1, 0)}
+# (selection path, two sweeps, window margin); a margin of zero makes the sampled window miss, so that the
+# one-sweep call ends in the radix levels and the gated full apply
+FORMS = {"one_sweep": (2, 0, None), "two_sweeps": (2, 1, None), "radix": (1, 0, None), "window_missed": (2, 0, 0)}
 
 
 @pytest.mark.parametrize("form", sorted(FORMS))
@@ -83,15 +85,16 @@ def test_global_prune_of_more_than_2_32_weights(big_weights, form):
     ws = big_weights
     N = N_EACH * N_TENSORS
     assert N > (1 << 32)
-    path, two = FORMS[form]
+    path, two, margin = FORMS[form]
     P.condensa_set_option(P.OPT_SELECT_PATH, path)
     P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
+    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT if margin is None else margin)
     try:
         density = 0.1
         res = P.condensa_prune(ws, [density])
         torch.cuda.synchronize()
         rec = P.select_records(res["results"])[0]
-        assert rec["path"] == (1 if form == "radix" else 2), rec
+        assert rec["path"] in {"radix": (1,), "window_missed": (2, 3)}.get(form, (2,)), rec
         k = int(round(density * N))
         T = _check_prune_properties(ws, res["theta"][0], res["mask"][0], rec, k, form)
         del res
@@ -121,6 +124,7 @@ def test_global_prune_of_more_than_2_32_weights(big_weights, form):
     finally:
         P.condensa_set_option(P.OPT_SELECT_PATH, 0)
         P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+        P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
         _free()
 
 
