@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
             "oracle_quantize_f16": [vp, u64, vp, vp],
             "oracle_quantize_bf16": [vp, u64, vp, vp],
             "oracle_dequantize_bf16": [vp, u64, vp],
+            "oracle_quantize_fp8": [vp, u64, ctypes.c_int, vp, vp],
+            "oracle_dequantize_fp8": [vp, u64, ctypes.c_int, vp],
             "oracle_dequantize_f16": [vp, u64, vp],
             "oracle_filter_sumsq": [vp, u64, u64, vp],
             "oracle_block_sumsq": [vp, u64, u64, u64, u64, vp],
@@ -78,6 +80,8 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = None
             fn.argtypes = args
+        for name in ("oracle_quantize_fp8", "oracle_dequantize_fp8"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("oracle_count_nonzero_f32", "oracle_count_nonzero_f16"):
             fn = getattr(L, name)
             fn.restype = u64
@@ -187,6 +191,28 @@ def dequantize_bf16(q: np.ndarray) -> np.ndarray:
     qf = np.ascontiguousarray(q, dtype=np.uint16).reshape(-1)
     dq = np.empty(qf.size, np.float32)
     lib().oracle_dequantize_bf16(_p(qf), qf.size, _p(dq))
+    return dq.reshape(np.shape(q))
+
+
+FP8_E4M3, FP8_E5M2 = 0, 1
+
+
+def quantize_fp8(x: np.ndarray, fmt: int):
+    """binary32 -> 8-bit floating point codes (E4M3 or E5M2: nearest finite value, ties to even, saturating)
+    and the exact widening back."""
+    xf = _f32(x).reshape(-1)
+    q = np.empty(xf.size, np.uint8)
+    dq = np.empty(xf.size, np.float32)
+    if lib().oracle_quantize_fp8(_p(xf), xf.size, int(fmt), _p(q), _p(dq)) != 0:
+        raise ValueError("unknown 8-bit format")
+    return q.reshape(np.shape(x)), dq.reshape(np.shape(x))
+
+
+def dequantize_fp8(q: np.ndarray, fmt: int) -> np.ndarray:
+    qf = np.ascontiguousarray(q, dtype=np.uint8).reshape(-1)
+    dq = np.empty(qf.size, np.float32)
+    if lib().oracle_dequantize_fp8(_p(qf), qf.size, int(fmt), _p(dq)) != 0:
+        raise ValueError("unknown 8-bit format")
     return dq.reshape(np.shape(q))
 
 

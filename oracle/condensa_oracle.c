@@ -194,8 +194,8 @@ void oracle_dequantize_f16(const uint16_t* q, uint64_t n, float* dq)
     for (uint64_t i = 0; i < n; ++i) dq[i] = bits_f32(f16_to_f32_bits(q[i]));
 }
 
-/* ---- bfloat16: Quantize(dtype) with the other common 16-bit floating-point type (Table 1; "data types for
- * quantization" are named as an extension in the Conclusions).  bfloat16 is the upper half of binary32:
+/* ---- bfloat16: Quantize(dtype) with the other common 16-bit floating-point type (Table 1; the Conclusions
+ * name further quantization data types as an extension).  bfloat16 is the upper half of binary32:
  * 1 sign, 8 exponent, 7 fraction bits.  Round to nearest, ties to even, decided on the 16 dropped bits;
  * a carry out of the fraction moves into the exponent (the largest finite values round to infinity);
  * NaN stays NaN: sign and upper payload bits kept, quiet bit set. */
@@ -220,6 +220,83 @@ void oracle_quantize_bf16(const float* x, uint64_t n, uint16_t* q, float* dq /* 
 void oracle_dequantize_bf16(const uint16_t* q, uint64_t n, float* dq)
 {
     for (uint64_t i = 0; i < n; ++i) dq[i] = bits_f32((uint32_t)q[i] << 16);
+}
+
+/* ---- 8-bit floating point: Quantize(dtype) with the two 8-bit formats of the OCP 8-bit floating point
+ * specification (Table 1; low-precision approximation = a fixed codebook, Background).
+ *   format 0, E4M3: 1 sign, 4 exponent (bias 7), 3 fraction bits; no infinity; S.1111.111 is NaN;
+ *                   largest finite value 448, smallest subnormal 2^-9.
+ *   format 1, E5M2: 1 sign, 5 exponent (bias 15), 2 fraction bits; IEEE-like infinities and NaNs;
+ *                   largest finite value 57344, smallest subnormal 2^-16.
+ * A code's value is written out from the definition; quantization is the definition too: the nearest
+ * finite value of the format, found by search over all of them, ties to the code with the even fraction.
+ * Reading where the paper says nothing: finite inputs beyond the largest finite value saturate to it
+ * (the usual choice for weights); E5M2 keeps infinite inputs infinite, E4M3 (no infinity) saturates them;
+ * NaN gives the format's NaN with the sign kept (E5M2: quiet NaN S.11111.10) and widens to the
+ * binary32 quiet NaN S.0x7FC00000. */
+static int fp8_geometry(int format, int* mant_bits, int* bias, int* max_code, int* has_inf)
+{
+    if (format == 0) { *mant_bits = 3; *bias = 7;  *max_code = 0x7E; *has_inf = 0; return 1; }
+    if (format == 1) { *mant_bits = 2; *bias = 15; *max_code = 0x7B; *has_inf = 1; return 1; }
+    return 0;
+}
+
+/* value of the non-negative finite code c (0 <= c <= max_code) */
+static double fp8_code_value(int c, int mant_bits, int bias)
+{
+    const int e = c >> mant_bits, m = c & ((1 << mant_bits) - 1);
+    if (e == 0) return ldexp((double)m, 1 - bias - mant_bits);
+    return ldexp(1.0 + ldexp((double)m, -mant_bits), e - bias);
+}
+
+static uint8_t f32_to_fp8(float x, int mant_bits, int bias, int max_code, int has_inf)
+{
+    const uint32_t u = f32_bits(x);
+    const uint8_t sign = (uint8_t)((u >> 31) << 7);
+    const uint32_t a = u & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint8_t)(sign | (has_inf ? 0x7E : 0x7F));
+    if (a == 0x7F800000u) return (uint8_t)(sign | (has_inf ? 0x7C : max_code));
+    const double v = fabs((double)x);
+    if (v >= fp8_code_value(max_code, mant_bits, bias)) return (uint8_t)(sign | max_code);   /* saturation */
+    int best = 0;
+    double best_err = v;                                   /* distance to code 0 */
+    for (int c = 1; c <= max_code; ++c) {
+        const double err = fabs(v - fp8_code_value(c, mant_bits, bias));
+        if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
+    }
+    return (uint8_t)(sign | best);
+}
+
+static float fp8_to_f32(uint8_t c, int mant_bits, int bias, int max_code, int has_inf)
+{
+    const uint32_t sign = (uint32_t)(c & 0x80u) << 24;
+    const int mag = c & 0x7F;
+    if (mag > max_code) {
+        if (has_inf && mag == 0x7C) return bits_f32(sign | 0x7F800000u);
+        return bits_f32(sign | 0x7FC00000u);
+    }
+    const float v = (float)fp8_code_value(mag, mant_bits, bias);   /* exact: at most 4 significant bits */
+    return bits_f32(sign | f32_bits(v));
+}
+
+int oracle_quantize_fp8(const float* x, uint64_t n, int format, uint8_t* q, float* dq /* nullable */)
+{
+    int mb, bias, mc, inf;
+    if (!fp8_geometry(format, &mb, &bias, &mc, &inf)) return -1;
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint8_t c = f32_to_fp8(x[i], mb, bias, mc, inf);
+        q[i] = c;
+        if (dq) dq[i] = fp8_to_f32(c, mb, bias, mc, inf);
+    }
+    return 0;
+}
+
+int oracle_dequantize_fp8(const uint8_t* q, uint64_t n, int format, float* dq)
+{
+    int mb, bias, mc, inf;
+    if (!fp8_geometry(format, &mb, &bias, &mc, &inf)) return -1;
+    for (uint64_t i = 0; i < n; ++i) dq[i] = fp8_to_f32(q[i], mb, bias, mc, inf);
+    return 0;
 }
 
 /* ---- structure aggregates --------------------------------------------- */
