@@ -237,6 +237,24 @@ condensa_status condensa_quantize_bf16(const float* x_dev, uint64_t n, uint16_t*
 condensa_status condensa_dequantize_bf16(const uint16_t* q_dev, uint64_t n, float* dq_dev, void* stream);
 
 /*
+ * Quantize(dtype) for the two 8-bit floating-point formats of the OCP 8-bit floating point specification
+ * (Table 1: Quantize(dtype); Background: low-precision approximation is quantization with a fixed
+ * codebook).  format: CONDENSA_FP8_E4M3 (4 exponent bits, bias 7, 3 fraction bits, no infinity, S.1111.111
+ * is NaN, largest finite value 448) or CONDENSA_FP8_E5M2 (5 exponent bits, bias 15, 2 fraction bits,
+ * IEEE-like infinities and NaNs, largest finite value 57344); anything else is CONDENSA_ERR_ARG.
+ * q = the nearest finite value of the format, ties to the even fraction, subnormals kept.  Finite inputs
+ * beyond the largest finite value saturate to it; infinite inputs stay infinite in E5M2 and saturate in
+ * E4M3; NaN gives the format's NaN (E5M2: S.11111.10) with the sign kept.  dq = exact widening (NaN codes
+ * widen to the binary32 quiet NaN S.0x7FC00000).  q_dev holds one byte per element; q_dev or dq_dev may be
+ * NULL (not both); dq_dev may alias x_dev.  4-byte aligned q_dev and 16-byte aligned x_dev / dq_dev get
+ * vector accesses.
+ */
+enum { CONDENSA_FP8_E4M3 = 0, CONDENSA_FP8_E5M2 = 1 };
+condensa_status condensa_quantize_fp8(const float* x_dev, uint64_t n, int format, uint8_t* q_dev, float* dq_dev,
+                                      void* stream);
+condensa_status condensa_dequantize_fp8(const uint8_t* q_dev, uint64_t n, int format, float* dq_dev, void* stream);
+
+/*
  * One compression step of the L-C algorithm with the augmented-Lagrangian updates (Section 3.3;
  * mu_j = mu_0 a^j is the caller's schedule, L-C Optimizer Settings).  Per element, in binary32
  * with one rounding per operation and no fused multiply-add:

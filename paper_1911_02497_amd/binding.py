@@ -68,6 +68,10 @@ _PROTOTYPES = {
     "condensa_quantize_bf16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                                 ctypes.c_void_p]),
     "condensa_dequantize_bf16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
+    "condensa_quantize_fp8": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p]),
+    "condensa_dequantize_fp8": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p,
+                                                 ctypes.c_void_p]),
     "condensa_lc_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -391,6 +395,28 @@ def condensa_quantize_bf16(x, want_q=True, want_dq=True, stream=None):
 
 def condensa_dequantize_bf16(q, stream=None):
     return _dequantize("condensa_dequantize_bf16", q, stream)
+
+
+FP8_E4M3, FP8_E5M2 = 0, 1
+
+
+def condensa_quantize_fp8(x, fmt, want_q=True, want_dq=True, stream=None):
+    """8-bit floating-point codes (uint8; fmt = FP8_E4M3 or FP8_E5M2) and / or their exact widening."""
+    import torch
+    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if want_q else None
+    dq = torch.empty_like(x) if want_dq else None
+    _check(library().condensa_quantize_fp8(x.data_ptr() if x.numel() else None, x.numel(), int(fmt),
+                                           q.data_ptr() if q is not None else None,
+                                           dq.data_ptr() if dq is not None else None, _stream(stream)))
+    return q, dq
+
+
+def condensa_dequantize_fp8(q, fmt, stream=None):
+    import torch
+    dq = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(library().condensa_dequantize_fp8(q.data_ptr() if q.numel() else None, q.numel(), int(fmt), dq.data_ptr(),
+                                             _stream(stream)))
+    return dq
 
 
 def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,

@@ -941,9 +941,57 @@ static condensa_status dequantize_impl(const uint16_t* q_dev, uint64_t n, float*
     CONDENSA_LAUNCH_CHECK();
     return CONDENSA_OK;
 }
+template <typename C>
+static condensa_status quantize8_impl(const float* x_dev, uint64_t n, uint8_t* q_dev, float* dq_dev, void* stream) {
+    if (n > kMaxElems) return CONDENSA_ERR_SIZE;
+    if (n == 0) return CONDENSA_OK;
+    if (q_dev == nullptr && dq_dev == nullptr) return CONDENSA_ERR_NULL;
+    if (x_dev == nullptr) return CONDENSA_ERR_NULL;
+    const bool vec = aligned16(x_dev) && (!dq_dev || aligned16(dq_dev)) &&
+                     (!q_dev || (reinterpret_cast<uintptr_t>(q_dev) & 3u) == 0);
+    constexpr int QT = kQuantThreads;
+    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!dq_dev && aligned16(x_dev) && aligned16(q_dev))
+        hipLaunchKernelGGL((k_quantize8_codes<QT, C>), dim3(static_cast<unsigned>((n + QT * 16 - 1) / (QT * 16))), dim3(QT), 0, st, x_dev, n, q_dev);
+    else if (vec) hipLaunchKernelGGL((k_quantize8<true, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
+    else     hipLaunchKernelGGL((k_quantize8<false, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, x_dev, n, q_dev, dq_dev);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+template <typename C>
+static condensa_status dequantize8_impl(const uint8_t* q_dev, uint64_t n, float* dq_dev, void* stream) {
+    if (n > kMaxElems) return CONDENSA_ERR_SIZE;
+    if (n == 0) return CONDENSA_OK;
+    if (dq_dev == nullptr || q_dev == nullptr) return CONDENSA_ERR_NULL;
+    const bool vec = aligned16(dq_dev) && (reinterpret_cast<uintptr_t>(q_dev) & 3u) == 0;
+    constexpr int QT = kQuantThreads;
+    const u64 blocks = (n + QT * 4 - 1) / (QT * 4);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (aligned16(q_dev) && aligned16(dq_dev))
+        hipLaunchKernelGGL((k_dequantize8_wide<QT, C>), dim3(static_cast<unsigned>((n + QT * 16 - 1) / (QT * 16))), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else if (vec) hipLaunchKernelGGL((k_dequantize8<true, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+    else     hipLaunchKernelGGL((k_dequantize8<false, QT, C>), dim3(static_cast<unsigned>(blocks)), dim3(QT), 0, st, q_dev, n, dq_dev);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
 }  // namespace condensa
 
 extern "C" {
+
+condensa_status condensa_quantize_fp8(const float* x_dev, uint64_t n, int format, uint8_t* q_dev, float* dq_dev,
+                                      void* stream) {
+    if (format == CONDENSA_FP8_E4M3) return quantize8_impl<CodecE4M3>(x_dev, n, q_dev, dq_dev, stream);
+    if (format == CONDENSA_FP8_E5M2) return quantize8_impl<CodecE5M2>(x_dev, n, q_dev, dq_dev, stream);
+    return CONDENSA_ERR_ARG;
+}
+
+condensa_status condensa_dequantize_fp8(const uint8_t* q_dev, uint64_t n, int format, float* dq_dev, void* stream) {
+    if (format == CONDENSA_FP8_E4M3) return dequantize8_impl<CodecE4M3>(q_dev, n, dq_dev, stream);
+    if (format == CONDENSA_FP8_E5M2) return dequantize8_impl<CodecE5M2>(q_dev, n, dq_dev, stream);
+    return CONDENSA_ERR_ARG;
+}
 
 condensa_status condensa_quantize(const float* x_dev, uint64_t n, uint16_t* q_dev, float* dq_dev, void* stream) {
     return quantize_impl<CodecF16>(x_dev, n, q_dev, dq_dev, stream);

@@ -278,4 +278,48 @@ struct CodecBF16 {
     static __device__ inline float dec(u16 h) { return bf16_bits_to_f32(h); }
 };
 
+// 8-bit floating point with EXP exponent bits, MAN fraction bits and the given bias (OCP 8-bit floating
+// point formats: E4M3 has no infinity and one NaN pattern per sign, E5M2 is IEEE-like).  Round to nearest
+// even in integer arithmetic on the binary32 pattern (normal results) or by an exact power-of-two scaling
+// and the hardware's round-to-nearest-even integer conversion (subnormal results); finite values beyond the
+// largest finite code saturate to it; E5M2 keeps infinities, E4M3 saturates them; NaN keeps its sign.
+template <int EXP, int MAN, int BIAS, bool HAS_INF>
+struct CodecFP8 {
+    static constexpr u32 kMaxCode = HAS_INF ? ((((1u << EXP) - 1u) << MAN) - 1u) : 0x7Eu;
+    static constexpr u32 kInfCode = ((1u << EXP) - 1u) << MAN;
+    static constexpr int kEmin = 1 - BIAS;                            // exponent of the smallest normal value
+    static __device__ inline u8 enc(float x) {
+        const u32 u = __float_as_uint(x);
+        const u32 sign = (u >> 24) & 0x80u;
+        const u32 a = u & 0x7FFFFFFFu;
+        if (a > 0x7F800000u) return static_cast<u8>(sign | (HAS_INF ? (kInfCode | (1u << (MAN - 1))) : 0x7Fu));
+        if (a == 0x7F800000u) return static_cast<u8>(sign | (HAS_INF ? kInfCode : kMaxCode));
+        const int e = static_cast<int>(a >> 23) - 127;
+        u32 code;
+        if (e >= kEmin) {
+            constexpr int SH = 23 - MAN;
+            const u32 r = a + ((1u << (SH - 1)) - 1u) + ((a >> SH) & 1u);      // ties to even; a carry runs into the exponent
+            code = (r >> SH) - (static_cast<u32>(127 - BIAS) << MAN);
+        } else {
+            // below the smallest normal value the codes are multiples of 2^(kEmin - MAN): 0 .. 2^MAN
+            code = static_cast<u32>(__float2int_rn(__uint_as_float(a) * __uint_as_float(static_cast<u32>(127 + MAN - kEmin) << 23)));
+        }
+        if (code > kMaxCode) code = kMaxCode;
+        return static_cast<u8>(sign | code);
+    }
+    static __device__ inline float dec(u8 c) {
+        const u32 sign = static_cast<u32>(c & 0x80u) << 24;
+        const u32 mag = c & 0x7Fu;
+        const u32 ex = mag >> MAN, m = mag & ((1u << MAN) - 1u);
+        if (mag > kMaxCode) return __uint_as_float(sign | ((HAS_INF && mag == kInfCode) ? 0x7F800000u : 0x7FC00000u));
+        if (ex == 0) {
+            const float v = static_cast<float>(m) * __uint_as_float(static_cast<u32>(127 + kEmin - MAN) << 23);   // exact
+            return __uint_as_float(sign | __float_as_uint(v));
+        }
+        return __uint_as_float(sign | ((ex + static_cast<u32>(127 - BIAS)) << 23) | (m << (23 - MAN)));
+    }
+};
+typedef CodecFP8<4, 3, 7, false> CodecE4M3;
+typedef CodecFP8<5, 2, 15, true> CodecE5M2;
+
 }  // namespace condensa

@@ -82,6 +82,15 @@ def test_argument_errors_are_found_on_the_host_before_any_launch():
         assert fn(fake, 4, null, null, null) == -1                       # no output wanted
         assert fn(fake, (3 << 32) + 1, fake, null, null) == -2           # too many elements
         assert fn(null, 0, null, null, null) == 0                        # nothing to do
+    for fmt in (0, 1):
+        assert lib.condensa_quantize_fp8(null, 4, fmt, fake, fake, null) == -1
+        assert lib.condensa_quantize_fp8(fake, 4, fmt, null, null, null) == -1
+        assert lib.condensa_quantize_fp8(fake, (3 << 32) + 1, fmt, fake, null, null) == -2
+        assert lib.condensa_quantize_fp8(null, 0, fmt, null, null, null) == 0
+        assert lib.condensa_dequantize_fp8(null, 4, fmt, fake, null) == -1
+        assert lib.condensa_dequantize_fp8(null, 0, fmt, null, null) == 0
+    assert lib.condensa_quantize_fp8(fake, 4, 2, fake, fake, null) == -6          # unknown format
+    assert lib.condensa_dequantize_fp8(fake, 4, -1, fake, null) == -6
     for fn in (lib.condensa_dequantize, lib.condensa_dequantize_bf16):
         assert fn(null, 4, fake, null) == -1
         assert fn(fake, 4, null, null) == -1

@@ -118,3 +118,56 @@ def test_bfloat16_all_codes_round_trip():
     allh = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
     got = P.condensa_dequantize_bf16(torch.from_numpy(allh.view(np.int16)).to(DEV))
     assert_bits_equal(got, oracle.dequantize_bf16(allh), "bf16 all codes")
+
+
+# ---- 8-bit floating point ---------------------------------------------------------------------------------
+
+FP8 = {"e4m3": (P.FP8_E4M3, oracle.FP8_E4M3, 448.0), "e5m2": (P.FP8_E5M2, oracle.FP8_E5M2, 57344.0)}
+
+
+@pytest.mark.parametrize("name", sorted(FP8))
+@pytest.mark.parametrize("n", [0, 1, 3, 255, 256, 257, 1024, 1025, 64 * 16 * 7 + 5, 1_000_003])
+def test_fp8_matches_the_oracle(name, n):
+    """Codes and widened values bit for bit: several workgroups and a ragged tail, weights-like values, every
+    binade of the format and beyond (saturation), tie points, specials; all three kernel forms (codes and
+    values, codes only, scalar path on misaligned pointers) and the dequantize entry point."""
+    fmt, ofmt, vmax = FP8[name]
+    rng = np.random.default_rng(n + fmt)
+    x = np.where(rng.random(n) < 0.5, rng.standard_normal(n) * 0.02,
+                 np.exp(rng.uniform(np.log(vmax) - 45, np.log(vmax) + 3, n)) * rng.choice([-1.0, 1.0], n)).astype(np.float32)
+    codes = np.arange(0x7C, dtype=np.uint8)
+    vals = oracle.dequantize_fp8(codes, ofmt).astype(np.float64)
+    mids = ((vals[:-1] + vals[1:]) / 2).astype(np.float32)
+    special = np.concatenate([np.array([0.0, -0.0, np.inf, -np.inf, np.nan, -np.nan, 3.4e38, -3.4e38, 1e-45, -1e-40], np.float32),
+                              mids, np.nextafter(mids, np.float32(np.inf)), -np.nextafter(mids, np.float32(0))])
+    m = min(n, special.size)
+    x[:m] = special[:m]
+    oq, odq = oracle.quantize_fp8(x, ofmt)
+    dx = torch.from_numpy(x).to(DEV)
+    q, dq = P.condensa_quantize_fp8(dx, fmt)
+    assert np.array_equal(q.cpu().numpy(), oq)
+    assert_bits_equal(dq, odq, f"{name} dq")
+    q2, _ = P.condensa_quantize_fp8(dx, fmt, want_dq=False)
+    assert np.array_equal(q2.cpu().numpy(), oq)
+    _, dq2 = P.condensa_quantize_fp8(dx, fmt, want_q=False)
+    assert_bits_equal(dq2, odq, f"{name} dq only")
+    assert_bits_equal(P.condensa_dequantize_fp8(q, fmt), odq, f"{name} dequantize")
+    big = torch.empty(n + 1, dtype=torch.float32, device=DEV)
+    big[1:] = dx
+    q3, dq3 = P.condensa_quantize_fp8(big[1:], fmt)
+    assert np.array_equal(q3.cpu().numpy(), oq)
+    assert_bits_equal(dq3, odq, f"{name} misaligned")
+    qb = torch.empty(n + 1, dtype=torch.uint8, device=DEV)
+    qb[1:] = q
+    assert_bits_equal(P.condensa_dequantize_fp8(qb[1:], fmt), odq, f"{name} dequantize misaligned")
+
+
+@pytest.mark.parametrize("name", sorted(FP8))
+def test_fp8_all_codes_and_errors(name):
+    fmt, ofmt, _ = FP8[name]
+    codes = np.arange(256, dtype=np.uint8)
+    got = P.condensa_dequantize_fp8(torch.from_numpy(codes).to(DEV), fmt)
+    assert_bits_equal(got, oracle.dequantize_fp8(codes, ofmt), f"{name} all codes")
+    with pytest.raises(P.CondensaError) as e:
+        P.condensa_quantize_fp8(torch.ones(8, device=DEV), 2)
+    assert e.value.code == -6
