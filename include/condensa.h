@@ -299,11 +299,14 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
 /*
  * Memory-footprint objective (Evaluation, Objective 1: the bytes taken by the model's non-zero
  * parameters): writes to *count_dev the number of non-zero elements over all tensors; the
- * footprint is that count times the element size.  is_f16 = 0: tensors hold fp32 values; is_f16 = 1:
- * `w` of every tensor points to binary16 bit patterns (as written to theta_f16) and shape counts
- * those.  +0 and -0 are zeros.  Workspace: condensa_workspace_bytes(CONDENSA_OP_COUNT_NONZERO, ...).
+ * footprint is that count times the element size.  kind = CONDENSA_COUNT_F32: tensors hold fp32
+ * values; CONDENSA_COUNT_CODES16: `w` of every tensor points to 16-bit floating-point codes (binary16 as
+ * written to theta_f16, or bfloat16) and shape counts those; CONDENSA_COUNT_CODES8: to 8-bit
+ * floating-point codes (condensa_quantize_fp8).  +0 and -0 are zeros.  Workspace:
+ * condensa_workspace_bytes(CONDENSA_OP_COUNT_NONZERO, ...).
  */
-condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int is_f16,
+enum { CONDENSA_COUNT_F32 = 0, CONDENSA_COUNT_CODES16 = 1, CONDENSA_COUNT_CODES8 = 2 };
+condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int kind,
                                        uint64_t* count_dev,
                                        void* workspace_dev, size_t workspace_bytes, void* stream);
 

@@ -82,7 +82,7 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = args
         for name in ("oracle_quantize_fp8", "oracle_dequantize_fp8"):
             getattr(L, name).restype = ctypes.c_int
-        for name in ("oracle_count_nonzero_f32", "oracle_count_nonzero_f16"):
+        for name in ("oracle_count_nonzero_f32", "oracle_count_nonzero_f16", "oracle_count_nonzero_u8"):
             fn = getattr(L, name)
             fn.restype = u64
             fn.argtypes = [vp, u64]
@@ -411,7 +411,7 @@ def lc_step_pq(tensors: Sequence[np.ndarray], lambdas: Sequence[np.ndarray], mu:
 
 
 def count_nonzero(tensors: Sequence[np.ndarray]) -> int:
-    """Non-zero parameters of float32 tensors or of binary16 bit patterns (uint16); -0 is zero."""
+    """Non-zero parameters of float32 tensors or of 16-bit / 8-bit floating-point codes (uint16 / uint8); -0 is zero."""
     total = 0
     for t in tensors:
         t = np.ascontiguousarray(t)
@@ -419,8 +419,10 @@ def count_nonzero(tensors: Sequence[np.ndarray]) -> int:
             total += int(lib().oracle_count_nonzero_f32(_p(t), t.size))
         elif t.dtype == np.uint16:
             total += int(lib().oracle_count_nonzero_f16(_p(t), t.size))
+        elif t.dtype == np.uint8:
+            total += int(lib().oracle_count_nonzero_u8(_p(t), t.size))
         else:
-            raise TypeError("float32 values or uint16 binary16 patterns")
+            raise TypeError("float32 values, uint16 or uint8 floating-point codes")
     return total
 
 

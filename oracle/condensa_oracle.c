@@ -467,6 +467,13 @@ uint64_t oracle_count_nonzero_f16(const uint16_t* x, uint64_t n)
     return c;
 }
 
+uint64_t oracle_count_nonzero_u8(const uint8_t* x, uint64_t n)
+{
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n; ++i) c += (x[i] & 0x7Fu) != 0u;
+    return c;
+}
+
 /* ---- thinning: physically remove zero structures (Section 3.4, Network Thinning, final phase) ----
  * out[o', i', r] = w[keep_out[o'], keep_in[i'], r] for a tensor viewed as [Cout, Cin, kh*kw];
  * a NULL list keeps every index of that dimension. */

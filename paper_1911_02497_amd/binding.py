@@ -466,15 +466,17 @@ def condensa_lc_step_pq(tensors, lambdas, mu, density, **kw):
 
 
 def condensa_count_nonzero(tensors, workspace=None, stream=None):
-    """Non-zero count of float32 tensors, or of binary16 bit patterns when the tensors are int16 / float16."""
+    """Non-zero count of float32 tensors, of 16-bit floating-point codes when the tensors are int16 / float16 /
+    bfloat16, or of 8-bit floating-point codes when they are uint8."""
     import torch
     lib = library()
     dev = tensors[0].device if tensors else torch.device("cuda")
-    is_f16 = 1 if (tensors and tensors[0].dtype in (torch.int16, torch.float16)) else 0
+    kinds = [(torch.float32,), (torch.int16, torch.float16, torch.bfloat16), (torch.uint8,)]
+    is_f16 = next((k for k, ds in enumerate(kinds) if tensors and tensors[0].dtype in ds), 0)
     nt = len(tensors)
     arr = (Tensor * max(nt, 1))()
     for i, t in enumerate(tensors):
-        want = (torch.int16, torch.float16) if is_f16 else (torch.float32,)
+        want = kinds[is_f16]
         if not (t.is_cuda and t.is_contiguous() and t.dtype in want and 1 <= t.dim() <= 4):
             raise TypeError("contiguous device tensors of one element type, 1 to 4 dimensions")
         arr[i].w = t.data_ptr() if t.numel() else None

@@ -582,11 +582,11 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
                         result_dev, workspace_dev, workspace_bytes, stream);
 }
 
-condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int is_f16,
+condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int kind,
                                        uint64_t* count_dev, void* workspace_dev, size_t workspace_bytes,
                                        void* stream) {
     if (count_dev == nullptr) return CONDENSA_ERR_NULL;
-    if (is_f16 != 0 && is_f16 != 1) return CONDENSA_ERR_ARG;
+    if (kind < CONDENSA_COUNT_F32 || kind > CONDENSA_COUNT_CODES8) return CONDENSA_ERR_ARG;
     Tables tb;
     condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
     if (rc != CONDENSA_OK) return rc;
@@ -614,12 +614,15 @@ condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_ten
     u64* partial = at<u64>(workspace_dev, L.hist0);            // kBins words, cleared by k_prepare
     const unsigned blocks = static_cast<unsigned>(tb.n_chunks < static_cast<u64>(kBins) ? (tb.n_chunks ? tb.n_chunks : 1) : kBins);
     if (tb.n_chunks > 0) {
-        if (is_f16) {
-            if (vec) hipLaunchKernelGGL((k_count_nonzero<true, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
-            else     hipLaunchKernelGGL((k_count_nonzero<true, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+        if (kind == CONDENSA_COUNT_CODES8) {
+            if (vec) hipLaunchKernelGGL((k_count_nonzero<2, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            else     hipLaunchKernelGGL((k_count_nonzero<2, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+        } else if (kind == CONDENSA_COUNT_CODES16) {
+            if (vec) hipLaunchKernelGGL((k_count_nonzero<1, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            else     hipLaunchKernelGGL((k_count_nonzero<1, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
         } else {
-            if (vec) hipLaunchKernelGGL((k_count_nonzero<false, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
-            else     hipLaunchKernelGGL((k_count_nonzero<false, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            if (vec) hipLaunchKernelGGL((k_count_nonzero<0, true>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
+            else     hipLaunchKernelGGL((k_count_nonzero<0, false>), dim3(blocks), dim3(kBlock), 0, st, a, partial);
         }
         CONDENSA_LAUNCH_CHECK();
     }

@@ -241,10 +241,13 @@ __global__ __launch_bounds__(64) void k_lc_sgd(DataArgs a, const OutDesc* __rest
 // Persistent workgroups, one chunk per step; the loads of the next chunk are requested before the current
 // one is counted.  Per-workgroup counts go to `partial`; k_sum_partials adds them up, so the result needs
 // no atomics and no cleared memory.
-template <bool F16, bool VEC>
+// KIND: 0 = binary32 values, 1 = 16-bit floating-point codes, 2 = 8-bit floating-point codes (a chunk
+// is kChunk elements of that width); a zero is a code whose bits below the sign are all clear.
+template <int KIND, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* partial) {
     __shared__ u64 s_wave[kBlock / 64];
-    constexpr int R = F16 ? kQuadsPerThread / 2 : kQuadsPerThread;     // 128-bit loads per thread and chunk
+    constexpr int R = kQuadsPerThread >> KIND;              // 128-bit loads per thread and chunk: 8, 4, 2
+    constexpr int PER = 4 << KIND;                          // elements per 128-bit load: 4, 8, 16
     const int tid = threadIdx.x;
     u64 cnt = 0;
     f32x4 nxt[R];
@@ -257,16 +260,10 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
         const u64 base = (c - td.chunk_start) * kChunk;
         if (base + kChunk > td.n) return;
         nxt_full = true;
-        if (F16) {
-            const u16* p = reinterpret_cast<const u16*>(td.w) + base;
+        const char* p = reinterpret_cast<const char*>(td.w) + (base << (2 - KIND));      // 4, 2 or 1 byte per element
 #pragma unroll
-            for (int q = 0; q < R; ++q)
-                nxt[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + q * (kBlock * 8) + tid * 8));
-        } else {
-#pragma unroll
-            for (int q = 0; q < R; ++q)
-                nxt[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(td.w + base + q * (kBlock * 4) + tid * 4));
-        }
+        for (int q = 0; q < R; ++q)
+            nxt[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + q * kBlock + tid);
     };
     request(blockIdx.x);
     for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
@@ -281,8 +278,10 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const u32 bits = __float_as_uint(cur[q][k]);
-                    if (F16) cnt += ((bits & 0x7FFFu) != 0) + ((bits & 0x7FFF0000u) != 0);
-                    else     cnt += (bits & 0x7FFFFFFFu) != 0;
+                    if (KIND == 0) cnt += (bits & 0x7FFFFFFFu) != 0;
+                    if (KIND == 1) cnt += ((bits & 0x7FFFu) != 0) + ((bits & 0x7FFF0000u) != 0);
+                    if (KIND == 2) cnt += ((bits & 0x7Fu) != 0) + ((bits & 0x7F00u) != 0) + ((bits & 0x7F0000u) != 0) +
+                                          ((bits & 0x7F000000u) != 0);
                 }
             continue;
         }
@@ -291,7 +290,10 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
         for (int q = 0; q < kQuadsPerThread; ++q) {
             const u64 e0 = base + static_cast<u64>(q) * (kBlock * 4) + tid * 4;
             if (e0 >= td.n) break;
-            if (F16) {
+            if (KIND == 2) {
+                const u8* p = reinterpret_cast<const u8*>(td.w);
+                for (int k = 0; k < 4; ++k) if (e0 + k < td.n) cnt += (p[e0 + k] & 0x7Fu) != 0;
+            } else if (KIND == 1) {
                 const u16* p = reinterpret_cast<const u16*>(td.w);
                 if (VEC && e0 + 4 <= td.n) {
                     const ushort4 v = *reinterpret_cast<const ushort4*>(p + e0);
@@ -307,6 +309,7 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
             }
         }
     }
+    (void)PER;
     u64 total;
     block_excl_scan_u64(cnt, s_wave, &total);
     if (tid == 0) partial[blockIdx.x] = total;

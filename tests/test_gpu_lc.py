@@ -124,6 +124,18 @@ def test_count_nonzero_edge_cases():
     assert int(P.condensa_count_nonzero([big, x, torch.zeros(0, device=DEV)]).item()) == want + 4
     assert int(P.condensa_count_nonzero([big[1:]]).item()) == int((big[1:] != 0).sum().item())   # misaligned view
     assert int(P.condensa_count_nonzero([]).item()) == 0
+    # 16-bit and 8-bit floating-point codes: several chunks, a ragged tail, a misaligned view, empty tensors
+    rng = np.random.default_rng(12)
+    v = (rng.standard_normal(8192 * 9 + 1234) * (rng.random(8192 * 9 + 1234) < 0.4)).astype(np.float32)
+    v[5], v[6] = -0.0, 1e-30
+    for codes in (oracle.quantize_f16(v)[0], oracle.quantize_bf16(v)[0], oracle.quantize_fp8(v, oracle.FP8_E4M3)[0],
+                  oracle.quantize_fp8(v, oracle.FP8_E5M2)[0]):
+        as_torch = codes.view(np.int16) if codes.dtype == np.uint16 else codes
+        d = torch.from_numpy(as_torch.copy()).to(DEV)
+        assert int(P.condensa_count_nonzero([d, d[:0], d[:100]]).item()) == oracle.count_nonzero([codes, codes[:100]])
+        assert int(P.condensa_count_nonzero([d[1:]]).item()) == oracle.count_nonzero([codes[1:]])
+    q8, _ = P.condensa_quantize_fp8(x, P.FP8_E5M2)
+    assert int(P.condensa_count_nonzero([q8]).item()) == 3
 
 
 # ---- learning-step update with the penalty folded in ----------------------------------------------------

@@ -129,6 +129,8 @@ def test_footprint_counts_nonzeros_and_reproduces_the_two_times_of_pq():
     assert oracle.count_nonzero([x]) == 3
     q, _ = oracle.quantize_f16(x)
     assert oracle.count_nonzero([q]) == 2                          # 1e-30 underflows to zero in binary16
+    q8, _ = oracle.quantize_fp8(np.array([0.0, -0.0, 1e-30, -2.0, 3.0, 2.0 ** -10, 2.0 ** -9, np.nan], np.float32), oracle.FP8_E4M3)
+    assert oracle.count_nonzero([q8]) == 4 == int(np.count_nonzero(q8 & 0x7F))   # 1e-30 and 2^-10 round to zero
     w, lam = _case(n=20000, seed=10)
     res = oracle.lc_step_pq([w], [np.zeros_like(w)], 1e-3, 0.05)
     nnz = oracle.count_nonzero(res["theta_f16"])
