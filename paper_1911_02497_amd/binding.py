@@ -472,11 +472,11 @@ def condensa_count_nonzero(tensors, workspace=None, stream=None):
     lib = library()
     dev = tensors[0].device if tensors else torch.device("cuda")
     kinds = [(torch.float32,), (torch.int16, torch.float16, torch.bfloat16), (torch.uint8,)]
-    is_f16 = next((k for k, ds in enumerate(kinds) if tensors and tensors[0].dtype in ds), 0)
+    kind = next((k for k, ds in enumerate(kinds) if tensors and tensors[0].dtype in ds), 0)
     nt = len(tensors)
     arr = (Tensor * max(nt, 1))()
     for i, t in enumerate(tensors):
-        want = kinds[is_f16]
+        want = kinds[kind]
         if not (t.is_cuda and t.is_contiguous() and t.dtype in want and 1 <= t.dim() <= 4):
             raise TypeError("contiguous device tensors of one element type, 1 to 4 dimensions")
         arr[i].w = t.data_ptr() if t.numel() else None
@@ -486,7 +486,7 @@ def condensa_count_nonzero(tensors, workspace=None, stream=None):
     total = _total(tensors)
     count = torch.zeros(1, dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_COUNT_NONZERO, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
-    _check(lib.condensa_count_nonzero(arr, nt, is_f16, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+    _check(lib.condensa_count_nonzero(arr, nt, kind, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
     return count
 
 

@@ -247,7 +247,6 @@ template <int KIND, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* partial) {
     __shared__ u64 s_wave[kBlock / 64];
     constexpr int R = kQuadsPerThread >> KIND;              // 128-bit loads per thread and chunk: 8, 4, 2
-    constexpr int PER = 4 << KIND;                          // elements per 128-bit load: 4, 8, 16
     const int tid = threadIdx.x;
     u64 cnt = 0;
     f32x4 nxt[R];
@@ -309,7 +308,6 @@ __global__ __launch_bounds__(kBlock) void k_count_nonzero(DataArgs a, u64* parti
             }
         }
     }
-    (void)PER;
     u64 total;
     block_excl_scan_u64(cnt, s_wave, &total);
     if (tid == 0) partial[blockIdx.x] = total;
