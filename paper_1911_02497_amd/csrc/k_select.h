@@ -131,9 +131,13 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
     const int wtid = static_cast<int>(threadIdx.x);
     const int n_batches = (level == 0) ? 1 : (a.J + kSlotBatch - 1) / kSlotBatch;
 
+    u32 p0 = 0;                                           // the prefix when a batch holds a single ranking
+    bool single = false;
     auto count_key = [&](u32 key) {
         if (level == 0) {
             atomicAdd(&s_hist[key >> L.shift], 1u);
+        } else if (single) {                              // one ranking: compare with its prefix, no table look-up
+            if (((key ^ p0) >> L.hi_shift) == 0) atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
         } else {
             u32 m = s_tab[key >> L0.shift];
             const u32 digit = (key >> L.shift) & (nb - 1);
@@ -189,6 +193,8 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
                 cur_group = g;
             }
             if (!s_any) continue;
+            single = (level != 0 && nj == 1);             // its ranking is selecting, or s_any would be 0
+            p0 = single ? s_prefix[0] : 0u;
             const u64 c = cb + sub;
             if (c >= c1) continue;                        // no barrier below this point in the iteration
             const int t = static_cast<int>(a.chunk_map[c]);
@@ -404,6 +410,7 @@ template <bool LC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_select* results, int n_groups) {
     __shared__ u64 s_wave[kBlock / 64];
     __shared__ u64 s_found[3];                 // chunk, rank inside it, flag
+    __shared__ u64 s_run[3];                   // run of chunks that holds the wanted tie, ties before the run
     const int s = blockIdx.x;
     const int g = s / a.J, j = s % a.J;
     const int tid = threadIdx.x;
@@ -420,19 +427,35 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
         const u64 my0 = cb + per * tid < ce ? cb + per * tid : ce;
         const u64 my1 = my0 + per < ce ? my0 + per : ce;
         u64 mine = 0;
-        for (u64 c = my0; c < my1; ++c) mine += cnt[c];
+        for (u64 c = my0; c < my1; c += 8) {          // eight loads in flight: the loop waits on latency only
+            u32 x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = (c + u < my1) ? cnt[c + u] : 0u;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) mine += x[u];
+        }
         u64 total;
         u64 before = block_excl_scan_u64(mine, s_wave, &total);
         if (tid == 0) s_found[2] = 0;
         __syncthreads();
-        if (before < r && r <= before + mine) {
-            u64 cum = before;
-            for (u64 c = my0; c < my1; ++c) {
-                const u64 x = cnt[c];
-                if (r <= cum + x) { s_found[0] = c; s_found[1] = r - cum; s_found[2] = 1; break; }
-                cum += x;
+        // the thread whose run holds the r-th tie publishes the run; the workgroup then searches it together
+        if (before < r && r <= before + mine) { s_run[0] = my0; s_run[1] = my1; s_run[2] = before; s_found[2] = 2; }
+        __syncthreads();
+        if (s_found[2] == 2) {
+            const u64 run0 = s_run[0], run1 = s_run[1];
+            u64 cum = s_run[2];
+            __syncthreads();
+            for (u64 i0 = run0; i0 < run1; i0 += kBlock) {                 // uniform trip count
+                const u64 c = i0 + tid;
+                const u64 x = (c < run1) ? cnt[c] : 0;
+                u64 tot;
+                const u64 ex = block_excl_scan_u64(x, s_wave, &tot);
+                if (cum + ex < r && r <= cum + ex + x) { s_found[0] = c; s_found[1] = r - (cum + ex); s_found[2] = 1; }
+                cum += tot;
             }
         }
+        __syncthreads();
+        if (s_found[2] == 2) s_found[2] = 0;          // cannot happen: the run's counts add up to `mine`
         __syncthreads();
         if (s_found[2]) {
             const u64 c = s_found[0];
