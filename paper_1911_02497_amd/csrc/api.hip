@@ -702,27 +702,31 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         {
             PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st);
             // every structure one contiguous row (filters, neurons) of some length: staged, coalesced reads
+            constexpr u64 kFewRowsMax = 32768;           // up to 1024 workgroups of kFewRows rows
             bool rows = tb.N / tb.F >= 16;
             for (int t = 0; t < n_tensors && rows; ++t) {
                 const TensorDesc& d = tb.td[t];
                 if (d.n > 0 && !(d.d[1] == 1 && d.d[2] == 1 && d.b[0] == 1 && d.b[3] == d.d[3])) rows = false;
             }
-            // every tensor a matrix tiled exactly by 2-D blocks of one width of 4, 8 or 16, rows 16-byte aligned
+            // every tensor a matrix tiled exactly by 2-D blocks of one width of 4, 8, 16 or 32, rows 16-byte aligned
             u32 tile_w = 0;
             bool tiles = !rows;
             for (int t = 0; t < n_tensors && tiles; ++t) {
                 const TensorDesc& d = tb.td[t];
                 if (d.n == 0) continue;
                 const bool ok = d.d[0] == 1 && d.d[1] == 1 && d.d[2] % d.b[2] == 0 && d.d[3] % d.b[3] == 0 &&
-                                (d.b[3] == 4 || d.b[3] == 8 || d.b[3] == 16) && (tile_w == 0 || tile_w == d.b[3]) &&
+                                (d.b[3] == 4 || d.b[3] == 8 || d.b[3] == 16 || d.b[3] == 32) && (tile_w == 0 || tile_w == d.b[3]) &&
                                 aligned16(d.w) && d.d[3] % 4 == 0 && d.n <= 0xFFFFFFFFull;
                 if (!ok) tiles = false;
                 tile_w = d.b[3];
             }
-            if (rows) hipLaunchKernelGGL(k_struct_sumsq_rows, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            if (rows && tb.F <= kFewRowsMax)
+                hipLaunchKernelGGL(k_struct_sumsq_rows_few, dim3(static_cast<unsigned>((tb.F + kFewRows - 1) / kFewRows)), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else if (rows) hipLaunchKernelGGL(k_struct_sumsq_rows, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else if (tiles && tile_w == 4)  hipLaunchKernelGGL((k_struct_sumsq_tiles<1>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else if (tiles && tile_w == 8)  hipLaunchKernelGGL((k_struct_sumsq_tiles<2>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else if (tiles && tile_w == 16) hipLaunchKernelGGL((k_struct_sumsq_tiles<4>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
+            else if (tiles && tile_w == 32) hipLaunchKernelGGL((k_struct_sumsq_tiles<8>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else      hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             CONDENSA_LAUNCH_CHECK();
         }

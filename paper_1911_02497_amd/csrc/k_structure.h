@@ -110,7 +110,7 @@ __device__ inline double add_squares(double acc, const float4& v) {
     return acc;
 }
 
-// 2-D blocks of width 4 Q (Q = 1, 2, 4) that tile their matrices exactly, rows 16-byte aligned, fewer
+// 2-D blocks of width 4 Q (Q = 1, 2, 4, 8) that tile their matrices exactly, rows 16-byte aligned, fewer
 // than 2^32 elements per tensor.  One thread per block; the loads of 16 / Q block rows are issued
 // together before their squares are added in row-major order -- the same additions in the same order
 // as k_struct_sumsq.  Q = 2: where the 64 blocks of a wavefront lie in one block row, lane l fetches the
@@ -281,6 +281,100 @@ __global__ __launch_bounds__(kBlock) void k_struct_sumsq_rows(StructArgs a, doub
         __syncthreads();
     }
     if (u < a.F) {
+        a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
+        if (sumsq) sumsq[u] = acc;
+        if (norms) norms[u] = static_cast<float>(sqrt(acc));
+    }
+}
+
+// The same aggregation for calls with few row structures (a CIFAR ResNet's 2 032 filters, a VGG's 5 504):
+// 256 rows per workgroup would leave most of the chip idle and every 32-element piece costs a load
+// latency, so here a workgroup takes kFewRows rows and stages kFewTile elements of each per step: one
+// wavefront fetches one row's piece per load instruction (1 KB contiguous), eight loads per thread are in
+// flight, the next piece is requested before the current one is added up, and the first kFewRows threads
+// add their rows' pieces in memory order.  Rows of any length and alignment: a float4 that lies inside
+// an aligned row is one 128-bit load, anything else is fetched element by element.
+constexpr int kFewRows = 32;
+constexpr int kFewTile = 256;
+
+__global__ __launch_bounds__(kBlock) void k_struct_sumsq_rows_few(StructArgs a, double* sumsq, float* norms) {
+    __shared__ float s_tile[kFewRows][kFewTile + 1];
+    __shared__ const float* s_row[kFewRows];
+    __shared__ u32 s_len[kFewRows];
+    __shared__ u32 s_vec[kFewRows];
+    __shared__ u32 s_maxlen;
+    const int tid = threadIdx.x;
+    const u64 u = static_cast<u64>(blockIdx.x) * kFewRows + tid;          // the row of thread tid < kFewRows
+    if (tid == 0) s_maxlen = 0;
+    __syncthreads();
+    u32 len = 0;
+    if (tid < kFewRows) {
+        const float* row = nullptr;
+        if (u < a.F) {
+            const int t = tensor_of_struct(a.td, a.n_tensors, u);
+            const TensorDesc& td = a.td[t];
+            len = td.d[3];
+            row = td.w + (u - td.struct_start) * len;
+        }
+        s_row[tid] = row;
+        s_len[tid] = len;
+        s_vec[tid] = (row && (reinterpret_cast<uintptr_t>(row) & 15u) == 0) ? 1u : 0u;
+        atomicMax(&s_maxlen, len);
+    }
+    __syncthreads();
+    const u32 maxlen = s_maxlen;
+    const int col = (tid & 63) * 4, wave = tid >> 6;                      // wavefront `wave` fetches rows 4 p + wave
+    float4 v[8];
+    auto fetch = [&](u32 cb) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int st = p * 4 + wave;
+            const u32 L = s_len[st];
+            const u32 x = cb + col;
+            const float* src = s_row[st];
+            float4 t = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (x + 4 <= L && s_vec[st]) {
+                t = *reinterpret_cast<const float4*>(src + x);
+            } else if (x < L) {
+                t.x = src[x];
+                if (x + 1 < L) t.y = src[x + 1];
+                if (x + 2 < L) t.z = src[x + 2];
+                if (x + 3 < L) t.w = src[x + 3];
+            }
+            v[p] = t;
+        }
+    };
+    double acc = 0.0;
+    if (maxlen > 0) fetch(0);
+    for (u32 cb = 0; cb < maxlen; cb += kFewTile) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            float* dst = &s_tile[p * 4 + wave][col];
+            dst[0] = v[p].x; dst[1] = v[p].y; dst[2] = v[p].z; dst[3] = v[p].w;
+        }
+        if (cb + kFewTile < maxlen) fetch(cb + kFewTile);
+        __syncthreads();
+        if (tid < kFewRows && len > cb) {
+            const u32 m = (len - cb < static_cast<u32>(kFewTile)) ? len - cb : static_cast<u32>(kFewTile);
+            u32 j = 0;
+            for (; j + 16 <= m; j += 16) {                // sixteen LDS reads at a time ahead of the addition chain
+                float t[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) t[k] = s_tile[tid][j + k];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const double x = static_cast<double>(t[k]);
+                    acc = acc + x * x;
+                }
+            }
+            for (; j < m; ++j) {
+                const double x = static_cast<double>(s_tile[tid][j]);
+                acc = acc + x * x;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid < kFewRows && u < a.F) {
         a.keys[u] = static_cast<u64>(__double_as_longlong(acc)) & 0x7FFFFFFFFFFFFFFFull;
         if (sumsq) sumsq[u] = acc;
         if (norms) norms[u] = static_cast<float>(sqrt(acc));

@@ -99,8 +99,8 @@ def test_block_prune_small_shapes_scopes_and_ties():
         _compare(res, oracle.block_prune([m], bh, bw, 0.5, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, [m], f"{bh}x{bw}")
 
 
-@pytest.mark.parametrize("bh,bw", [(1, 4), (32, 4), (3, 8), (8, 8), (24, 8), (8, 16), (5, 16)])
-def test_exactly_tiled_blocks_of_width_4_8_16(bh, bw):
+@pytest.mark.parametrize("bh,bw", [(1, 4), (32, 4), (3, 8), (8, 8), (24, 8), (8, 16), (5, 16), (3, 32), (32, 32)])
+def test_exactly_tiled_blocks_of_width_4_8_16_32(bh, bw):
     """Block widths with an aggregation kernel of their own: matrices whose block rows hold 130, 65, 9 and 1
     blocks (wavefronts inside one block row, across two, across tensors), heights of less and more than one
     group of loads, an empty tensor between them, tensors of unequal size, a ragged last wavefront."""
