@@ -465,26 +465,41 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
             const u64 base = (c - td.chunk_start) * kChunk;
             constexpr int kRun = kChunk / kBlock;              // 32 consecutive elements per thread
             const u64 e_begin = base + static_cast<u64>(tid) * kRun;
-            u32 hits = 0;
-            for (int k = 0; k < kRun; ++k) {
-                const u64 e = e_begin + k;
-                if (e >= td.n) break;
-                const float x = LC ? lc_shift(td.w[e], td.lam[e], a.mu) : td.w[e];
-                hits += (mag_key(x) == T) ? 1u : 0u;
-            }
-            u64 tot2;
-            const u64 bef2 = block_excl_scan_u64(hits, s_wave, &tot2);
-            if (bef2 < rr && rr <= bef2 + hits) {
-                u64 seen = bef2;
+            // bit k of `eq`: element e_begin + k exists and its key equals T (all loads issued before the first use)
+            u32 eq = 0;
+            if (VEC && e_begin + kRun <= td.n) {
+                float4 wv[kRun / 4], lv[kRun / 4];
+#pragma unroll
+                for (int q = 0; q < kRun / 4; ++q) {
+                    wv[q] = *reinterpret_cast<const float4*>(td.w + e_begin + 4 * q);
+                    if (LC) lv[q] = *reinterpret_cast<const float4*>(td.lam + e_begin + 4 * q);
+                }
+#pragma unroll
+                for (int q = 0; q < kRun / 4; ++q) {
+                    float v[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
+                    if (LC) {
+                        const float l[4] = {lv[q].x, lv[q].y, lv[q].z, lv[q].w};
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) eq |= (mag_key(v[k]) == T ? 1u : 0u) << (4 * q + k);
+                }
+            } else {
                 for (int k = 0; k < kRun; ++k) {
                     const u64 e = e_begin + k;
                     if (e >= td.n) break;
                     const float x = LC ? lc_shift(td.w[e], td.lam[e], a.mu) : td.w[e];
-                    if (mag_key(x) == T) {
-                        ++seen;
-                        if (seen == rr) { slot.tie_end = (a.per_tensor ? 0 : td.flat_start) + e + 1; break; }
-                    }
+                    eq |= (mag_key(x) == T ? 1u : 0u) << k;
                 }
+            }
+            const u32 hits = __popc(eq);
+            u64 tot2;
+            const u64 bef2 = block_excl_scan_u64(hits, s_wave, &tot2);
+            if (bef2 < rr && rr <= bef2 + hits) {
+                u32 m = eq;
+                for (u64 skip = rr - bef2 - 1; skip > 0; --skip) m &= m - 1;      // drop the ties before the wanted one
+                slot.tie_end = (a.per_tensor ? 0 : td.flat_start) + e_begin + (__ffs(m) - 1) + 1;
             }
         }
         __syncthreads();
