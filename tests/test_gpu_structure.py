@@ -72,6 +72,19 @@ def test_filter_prune_all_equal_filters():
         _compare(res, oracle.filter_prune([a], d, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, [a], f"all equal d={d}")
 
 
+def test_filter_prune_with_many_filters():
+    """More than 32 768 row structures take the aggregation kernel that stages 256 rows per workgroup: rows of
+    40, 132 and 7 elements (the last tensor's rows are not 16-byte aligned), a ragged last workgroup."""
+    rng = np.random.default_rng(21)
+    ts = [rng.standard_normal((30000, 10, 2, 2)).astype(np.float32), rng.standard_normal((5001, 33, 2, 2)).astype(np.float32),
+          rng.standard_normal((4000, 7, 1, 1)).astype(np.float32)]
+    ts[1][77] = ts[1][4000]                              # equal aggregates far apart
+    for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
+        res = P.condensa_filter_prune(up(ts), 0.45, scope)
+        torch.cuda.synchronize()
+        _compare(res, oracle.filter_prune(ts, 0.45, scope), scope, ts, f"many filters scope={scope}")
+
+
 @pytest.mark.parametrize("bh,bw", [(8, 8), (32, 32)])
 def test_transformer_block_prune_global(bh, bw):
     ws = workloads.transformer_base()
