@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0           # MI355X published HBM3E peak
 # HBM traffic of one k_window_fused launch on the full workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # calibrated with a plain copy (profiles/lc_step_large_model_hbm_counters.md).  Reported only while the
 # kernel's sources still hash to what was measured, and only for the full 64-tensor workload without mask.
-MEASURED_TRAFFIC = {"bytes": 24601065663, "tensors": 64,
-                    "sources_sha256": "866f5609bdd62a7ea62cd61a8d629c106d7604f90f896c6476a7fdad30fd916f"}
+MEASURED_TRAFFIC = {"bytes": 24522131159, "tensors": 64,
+                    "sources_sha256": "210d2707da11f78d9cde1bc77bf679492131162df606c7cce6e9c2642ce7f5f6"}
 KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 
 

@@ -136,23 +136,35 @@ __device__ inline float4 ld4_stream(const float* p) {
     const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     return make_float4(t.x, t.y, t.z, t.w);
 }
+// The store carries the system-scope bits together with the non-temporal one (write straight through,
+// keep nothing): on the L-C mix of 2 streams read and 3 written this measured 1.5-2 % faster than the
+// non-temporal bit alone, which is all the compiler's builtin sets.  Nothing in a kernel reads these
+// locations again, so the statement needs no ordering against the kernel's other accesses.  The s_nop
+// covers the two wait states that gfx940-class hardware wants between a vector store of more than 64
+// bits and a vector write of its data registers: the compiler cannot see inside the statement and might
+// reuse those registers in the very next instruction.
 __device__ inline void st4_stream(float* p, float a, float b, float c, float d) {
     f32x4 t;
     t.x = a; t.y = b; t.z = c; t.w = d;
-    __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
 }
 
 // Four mask bytes / four 16-bit codes as one store with the streaming hint (p 4- / 8-byte aligned).
 __device__ inline void st_mask4_stream(u8* p, u8 a, u8 b, u8 c, u8 d) {
-    __builtin_nontemporal_store(static_cast<u32>(a) | (static_cast<u32>(b) << 8) | (static_cast<u32>(c) << 16) | (static_cast<u32>(d) << 24),
-                                reinterpret_cast<u32*>(p));
+    const u32 t = static_cast<u32>(a) | (static_cast<u32>(b) << 8) | (static_cast<u32>(c) << 16) | (static_cast<u32>(d) << 24);
+    asm volatile("global_store_dword %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
 }
 __device__ inline void st_code4_stream(u16* p, u16 a, u16 b, u16 c, u16 d) {
     typedef u32 u32x2 __attribute__((ext_vector_type(2)));
     u32x2 t;
     t.x = static_cast<u32>(a) | (static_cast<u32>(b) << 16);
     t.y = static_cast<u32>(c) | (static_cast<u32>(d) << 16);
-    __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
+}
+// sixteen bytes of packed codes
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void st_words4_stream(void* p, u32x4 t) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
 }
 
 // Loads up to four consecutive elements e0 .. e0+3 of an n-element array; missing ones read 0.

@@ -63,7 +63,6 @@ __global__ __launch_bounds__(THREADS) void k_quantize_codes(const float* __restr
         // 64-bit word j of the wavefront (elements 4 j .. 4 j + 3) sits in (lo, hi)[j / 64] of lane j % 64;
         // lane L wants words 2 L and 2 L + 1
         const int kk = lane >> 5, src = (lane * 2) & 63;
-        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
         u32x4 out;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -72,7 +71,7 @@ __global__ __launch_bounds__(THREADS) void k_quantize_codes(const float* __restr
             out[2 * i] = kk == 0 ? a0 : a1;
             out[2 * i + 1] = kk == 0 ? b0 : b1;
         }
-        __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(q + wave0 + lane * 8));
+        st_words4_stream(q + wave0 + lane * 8, out);
     } else {
         for (int k = 0; k < 8; ++k) {
             const u64 e = wave0 + static_cast<u64>(k) * 64 + lane;
@@ -113,7 +112,6 @@ __global__ __launch_bounds__(THREADS) void k_dequantize_wide(const u16* __restri
     const u64 wave0 = (static_cast<u64>(blockIdx.x) * (THREADS / 64) + wave) * kPerWave;
     if (wave0 >= n) return;
     if (wave0 + kPerWave <= n) {                                         // uniform over the wavefront
-        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
         const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + wave0 + lane * 8));
         // lane L needs the codes 4L..4L+3: dwords (L & 1) * 2, +1 of lane L / 2; and the same of lane 32 + L / 2
         const int src = lane >> 1;
@@ -185,7 +183,6 @@ __global__ __launch_bounds__(THREADS) void k_quantize8_codes(const float* __rest
         }
         // word j of the wavefront (elements 4 j .. 4 j + 3) sits in w[j / 64] of lane j % 64; lane L wants words 4 L .. 4 L + 3
         const int kk = lane >> 4, src = (lane * 4) & 63;
-        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
         u32x4 out;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -193,7 +190,7 @@ __global__ __launch_bounds__(THREADS) void k_quantize8_codes(const float* __rest
             const u32 t2 = __shfl(w[2], src + i, 64), t3 = __shfl(w[3], src + i, 64);
             out[i] = kk == 0 ? t0 : (kk == 1 ? t1 : (kk == 2 ? t2 : t3));
         }
-        __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(q + wave0 + lane * 16));
+        st_words4_stream(q + wave0 + lane * 16, out);
     } else {
         for (int k = 0; k < 16; ++k) {
             const u64 e = wave0 + static_cast<u64>(k) * 64 + lane;
@@ -235,7 +232,6 @@ __global__ __launch_bounds__(THREADS) void k_dequantize8_wide(const u8* __restri
     const u64 wave0 = (static_cast<u64>(blockIdx.x) * (THREADS / 64) + wave) * kPerWave;
     if (wave0 >= n) return;
     if (wave0 + kPerWave <= n) {                                         // uniform over the wavefront
-        typedef u32 u32x4 __attribute__((ext_vector_type(4)));
         const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + wave0 + lane * 16));
         const int d = lane & 3;
 #pragma unroll
