@@ -76,3 +76,44 @@ def test_lc_step_on_the_large_model_workload():
     assert n_tie_below == rec["n_tie_kept"]
     if rec["n_tie_kept"] == rec["n_tie"]:
         assert tie_end == N
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("density", [0.003, 0.1, 0.97])
+def test_every_selection_form_gives_the_same_bits_at_full_size(density):
+    """1.2 G weights of the benchmark's shape (seeded on the device): the one-sweep form, the two-sweep form
+    and the radix levels must agree bit for bit on every output of the L-C step and of global pruning, and
+    on every field of the selection record.  (The form that the test above checks against the oracle
+    anchors the three.)"""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    ws = [torch.randn(4096, 4608, device=dev, generator=g) * 0.01 for _ in range(64)]
+    ls = [torch.randn(4096, 4608, device=dev, generator=g) * 0.01 for _ in range(64)]
+    fields = ("n", "k", "n_gt", "n_tie_kept", "n_tie", "threshold_key", "tie_end")
+    as_bits = lambda t: t.view(torch.int32) if t.dtype == torch.float32 else t  # noqa: E731
+    ref = ref_rec = None
+    try:
+        for name, (path, two) in {"one_sweep": (2, 0), "two_sweeps": (2, 1), "radix": (1, 0)}.items():
+            P.condensa_set_option(P.OPT_SELECT_PATH, path)
+            P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
+            r = P.condensa_lc_step(ws, ls, 1e-3, density)
+            p = P.condensa_prune(ws, [density])
+            torch.cuda.synchronize()
+            cur = (r["theta"], r["lambda"], r["grad"], r["mask"], p["theta"][0], p["mask"][0])
+            rec = (P.select_records(r["results"])[0], P.select_records(p["results"])[0])
+            assert rec[0]["path"] == rec[1]["path"] == (1 if name == "radix" else 2), (name, rec)
+            if ref is None:
+                ref, ref_rec = cur, rec
+                continue
+            for k in fields:
+                assert rec[0][k] == ref_rec[0][k] and rec[1][k] == ref_rec[1][k], (name, k, rec, ref_rec)
+            for which, (a_list, b_list) in enumerate(zip(cur, ref)):
+                for t, (a, b) in enumerate(zip(a_list, b_list)):
+                    assert torch.equal(as_bits(a), as_bits(b)), f"{name}: output {which} of tensor {t} differs"
+            del r, p, cur
+    finally:
+        P.condensa_set_option(P.OPT_SELECT_PATH, 0)
+        P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+        del ref, ws, ls
+        torch.cuda.empty_cache()
