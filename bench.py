@@ -73,15 +73,14 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     import oracle
     name = args.workload
     up = lambda arrs: P.tensor_table([torch.from_numpy(a).to(dev) for a in arrs])  # noqa: E731  (marshalled once)
-    P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, args.window_margin)
+    cfg = P.condensa_config(select_path=args.select_path, fused_sweep=1 if args.two_sweeps else 0,
+                            window_margin=args.window_margin)
     prev = [None]                                # the first call allocates the outputs, later ones reuse them
     if name == "prune_stress":
         # global magnitude pruning of the large-model weights (no multipliers): theta + mask at density 0.1
         host, _ = workloads.lc_stress(indices=range(args.tensors), threads=16)
         d = up(host)
-        call = lambda: P.condensa_prune(d, [0.1], workspace=ws, outputs=prev[0])  # noqa: E731
+        call = lambda: P.condensa_prune(d, [0.1], workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
         op, F, J, bytes_per_elem, desc = P.binding.OP_PRUNE, 0, 1, 13, "global prune d=0.1, theta + mask"
         cpu = lambda: oracle.prune(host[:2], [0.1])  # noqa: E731
     elif name in ("filter_stress", "block_stress"):
@@ -90,12 +89,12 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         if name == "filter_stress":
             host = [h.reshape(h.shape[0], h.shape[1] // 9, 3, 3) for h in host]
             d = up(host)
-            call = lambda: P.condensa_filter_prune(d, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0])  # noqa: E731
+            call = lambda: P.condensa_filter_prune(d, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
             op, F, desc = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in host), "global filter prune d=0.5, theta + mask"
             cpu = lambda: oracle.filter_prune(host[:8], 0.5, P.SCOPE_GLOBAL)  # noqa: E731
         else:
             d = up(host)
-            call = lambda: P.condensa_block_prune(d, 8, 8, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0])  # noqa: E731
+            call = lambda: P.condensa_block_prune(d, 8, 8, 0.5, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
             op, F = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // 8) * (t.shape[1] // 8) for t in host)
             desc = "global block prune 8x8 d=0.5, theta + mask"
             cpu = lambda: oracle.block_prune(host[:8], 8, 8, 0.5, P.SCOPE_GLOBAL)  # noqa: E731
@@ -103,7 +102,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
     elif name == "single_prune_fp16":
         host = workloads.single_matrix()
         d = up(host)
-        call = lambda: P.condensa_prune(d, [0.02], theta=False, theta_f16=True, mask=True, workspace=ws, outputs=prev[0])  # noqa: E731
+        call = lambda: P.condensa_prune(d, [0.02], theta=False, theta_f16=True, mask=True, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
         op, F, J, bytes_per_elem, desc = P.binding.OP_PRUNE, 0, 1, 11, "prune d=0.02 fused with fp16 theta + mask"
         cpu = lambda: oracle.quantize_f16(oracle.prune(host, [0.02])[0]["theta"][0])  # noqa: E731
     elif name in ("vgg_thresholds", "vgg_masks"):
@@ -111,10 +110,10 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         d = up(host)
         ds = workloads.search_densities()
         if name == "vgg_thresholds":
-            call = lambda: P.condensa_prune(d, ds, theta=False, mask=False, workspace=ws, outputs=prev[0])  # noqa: E731
+            call = lambda: P.condensa_prune(d, ds, theta=False, mask=False, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
             bytes_per_elem, desc = 4, "thresholds of 10 densities from one sweep"
         else:
-            call = lambda: P.condensa_prune(d, ds, theta=False, mask=True, workspace=ws, outputs=prev[0])  # noqa: E731
+            call = lambda: P.condensa_prune(d, ds, theta=False, mask=True, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
             bytes_per_elem, desc = 4 + 4 + 10, "10 densities, one selection sweep + one apply sweep writing 10 masks"
         op, F, J = P.binding.OP_PRUNE, 0, len(ds)
         cpu = lambda: oracle.prune(host, ds)  # noqa: E731
@@ -122,7 +121,7 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         host = workloads.resnet56_cifar_convs()
         d = up(host)
         scope, dens = (P.SCOPE_GLOBAL, 0.3) if name.endswith("global") else (P.SCOPE_PER_TENSOR, 0.5)
-        call = lambda: P.condensa_filter_prune(d, dens, scope, workspace=ws, outputs=prev[0])  # noqa: E731
+        call = lambda: P.condensa_filter_prune(d, dens, scope, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
         op, F, J, bytes_per_elem = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in host), 1, 13
         desc = f"filter prune density {dens}, theta + mask"
         cpu = lambda: oracle.filter_prune(host, dens, scope)  # noqa: E731
@@ -130,13 +129,13 @@ def run_small_workload(args, P, workloads, torch, np, dev):
         host = workloads.transformer_base()
         d = up(host)
         b = 8 if name.endswith("block8") else 32
-        call = lambda: P.condensa_block_prune(d, b, b, 0.25, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0])  # noqa: E731
+        call = lambda: P.condensa_block_prune(d, b, b, 0.25, P.SCOPE_GLOBAL, workspace=ws, outputs=prev[0], config=cfg)  # noqa: E731
         op, F, J, bytes_per_elem = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // b) * (t.shape[1] // b) for t in host), 1, 13
         desc = f"block prune {b}x{b} density 0.25, theta + mask"
         cpu = lambda: oracle.block_prune(host, b, b, 0.25, P.SCOPE_GLOBAL)  # noqa: E731
     N = sum(t.size for t in host)
     scope_ws = P.SCOPE_PER_TENSOR if name == "resnet_filter_per_tensor" else P.SCOPE_GLOBAL
-    ws = torch.empty(max(P.condensa_workspace_bytes(op, N, F, len(host), J, scope_ws), 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(P.condensa_workspace_bytes(op, N, F, len(host), J, scope_ws, cfg), 256), dtype=torch.uint8, device=dev)
     prev[0] = call()
     for _ in range(args.warmup):
         call()
@@ -227,16 +226,14 @@ def main():
     }
     if args.mask:
         outputs["mask"] = [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in w_dev]
-    ws_bytes = P.condensa_workspace_bytes(P.binding.OP_LC_STEP, N, 0, T, 1, P.SCOPE_GLOBAL)
+    cfg = P.condensa_config(select_path=args.select_path, apply_threads=args.apply_threads,
+                            fused_sweep=1 if args.two_sweeps else 0, window_margin=args.window_margin)
+    ws_bytes = P.condensa_workspace_bytes(P.binding.OP_LC_STEP, N, 0, T, 1, P.SCOPE_GLOBAL, cfg)
     workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
-    P.condensa_set_option(P.OPT_SELECT_PATH, args.select_path)
-    P.condensa_set_option(P.OPT_APPLY_THREADS, args.apply_threads)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if args.two_sweeps else 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, args.window_margin)
 
     def step():
         return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,
-                                  workspace=workspace)
+                                  workspace=workspace, config=cfg)
 
     for _ in range(args.warmup):
         step()
@@ -248,14 +245,14 @@ def main():
         torch.cuda.synchronize()
 
     P.condensa_profile_reset()
-    P.condensa_set_option(P.OPT_PROFILE, 0x1F if args.all_phases else ((1 << 3) | (1 << 1)))
+    cfg.profile = 0x1F if args.all_phases else ((1 << 3) | (1 << 1))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    P.condensa_set_option(P.OPT_PROFILE, 0)
+    cfg.profile = 0
     phases = P.condensa_profile_read()
 
     ms_per_step = elapsed * 1e3 / args.steps

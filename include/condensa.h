@@ -33,6 +33,13 @@
  *    kept first.  Pruned positions are written as +0.0; kept values are copied bit for bit.
  *  - Masks are one byte per element, 1 = kept, 0 = pruned.
  *  - Calls that share a workspace must be ordered on one stream.
+ *  - Buffers of one call must not overlap in memory (byte ranges are compared, not just start
+ *    addresses): every output, the workspace included, against every input and against every other
+ *    output; CONDENSA_ERR_ARG otherwise.  The only exception is the exact in-place form that an entry
+ *    point documents (theta == w, lambda updated in place).
+ *  - Every entry point that takes a workspace also takes `config`, the tuning knobs of THIS call
+ *    (condensa_config below); NULL means the process-wide defaults.  Two callers with different
+ *    settings therefore never interfere.
  */
 #ifndef CONDENSA_H
 #define CONDENSA_H
@@ -99,12 +106,34 @@ typedef struct {
 } condensa_select;
 
 /*
+ * Tuning / test knobs of one call.  They choose between forms of the computation that give the same
+ * results; normal use passes NULL.  condensa_config_init fills a struct with the process-wide defaults
+ * (what NULL stands for), after which single fields can be changed.  Invalid values: CONDENSA_ERR_ARG.
+ */
+typedef struct {
+    int32_t select_path;    /* 0 auto, 1 radix levels over the data only (structure calls: one launch per
+                               level), 2 sampled window even for small N                              */
+    int32_t sample_log2;    /* log2 of the sample size of the window path (10..26); 0 = auto           */
+    int32_t window_margin;  /* half-width of the sampled window in 1/16 standard deviations of the sample
+                               rank; default 80 (= 5 sigma of a sample whose units of 4 neighbours are
+                               fully correlated, i.e. 10 sigma of independent draws); 0 makes windows miss */
+    int32_t cand_shift;     /* candidate capacity = N >> value (1..30); 0 = auto                        */
+    int32_t profile;        /* bit p set: bracket phase p of the call with HIP events on its stream     */
+    int32_t apply_threads;  /* workgroup size of the two-sweep L-C apply: 0 (default = 64), 64, 128, 256 */
+    int32_t fused_sweep;    /* window path with one density: 0 = selection and apply share one sweep when
+                               the outputs do not alias the inputs, 1 = always two sweeps               */
+    int32_t reserved;       /* must be 0                                                               */
+} condensa_config;
+condensa_status condensa_config_init(condensa_config* config);
+
+/*
  * Bytes of workspace (256-byte aligned device memory) the operator needs for the given problem:
  * total_elems = sum of tensor sizes, n_structures = number of filters/blocks (0 for element
- * operators).  Returns 0 for invalid arguments.  CONDENSA_OP_QUANTIZE needs none (returns 0).
+ * operators).  The size depends on sample_log2 and cand_shift of `config`: size the workspace with the
+ * config the call will get.  Returns 0 for invalid arguments.  CONDENSA_OP_QUANTIZE needs none (returns 0).
  */
 size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures,
-                                int n_tensors, int n_densities, int scope);
+                                int n_tensors, int n_densities, int scope, const condensa_config* config);
 
 /*
  * Prune() scheme / prune operator: unstructured magnitude pruning (Background: magnitude
@@ -126,17 +155,18 @@ size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structu
  *  workspace_dev/bytes    see condensa_workspace_bytes(CONDENSA_OP_PRUNE, ...)
  * With theta, theta_f16 and mask all NULL only the thresholds are computed.
  * One density, GLOBAL scope, large tensors and theta not aliasing w: the selection and the outputs come
- * from ONE sweep over the weights (see CONDENSA_OPT_FUSED_SWEEP); results are the same either way.
+ * from ONE sweep over the weights (see condensa_config.fused_sweep); results are the same either way.
  */
 condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors,
                                const double* densities, int n_densities, int scope,
                                float* const* theta, uint16_t* const* theta_f16, uint8_t* const* mask,
                                condensa_select* results_dev,
-                               void* workspace_dev, size_t workspace_bytes, void* stream);
+                               void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
- * FilterPrune scheme / filter_prune operator (Table 1: "aggregates and prunes filters (3D
- * blocks)"; Section 3.1: filter aggregation).  Every tensor must have ndim == 4; filter f of a
+ * FilterPrune scheme / filter_prune operator (Table 1, FilterPrune row: whole filters, i.e. the 3-D
+ * slices of a convolution weight, are scored and removed; Section 3.1: filter aggregation).  Every tensor must have ndim == 4; filter f of a
  * tensor is the contiguous run of Cin*kh*kw weights of output channel f.  Aggregate: sum of
  * squares in binary64, added in memory order (the ranking of L2 norms); `density` counts filters.
  * Structure ids run over all filters of the call in table order.
@@ -145,7 +175,7 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors,
  *  sumsq_dev          NULL or device double [F]: the aggregates (the ranking keys)
  *  norms_dev          NULL or device float  [F]: (float)sqrt(sumsq)
  *  keep_idx_dev       NULL or device int32  [F]: ids of kept filters, ascending; entries past the
- *                     kept count are left untouched
+ *                     kept count are not written
  *  structure_mask_dev NULL or device bytes  [F]
  *  results_dev        device: 1 record (GLOBAL) or n_tensors records (PER_TENSOR)
  */
@@ -154,11 +184,12 @@ condensa_status condensa_filter_prune(const condensa_tensor* tensors, int n_tens
                                       float* const* theta, uint8_t* const* mask,
                                       double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                       uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                      void* workspace_dev, size_t workspace_bytes, void* stream);
+                                      void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
- * BlockPrune scheme / blockprune operator for 2-D blocks (Table 1: "aggregates and prunes n-D
- * blocks of size bs").  Every tensor must have ndim == 2 with block_h | R and block_w | C
+ * BlockPrune scheme / blockprune operator for 2-D blocks (Table 1, BlockPrune row: blocks of a given
+ * size are scored and removed).  Every tensor must have ndim == 2 with block_h | R and block_w | C
  * (CONDENSA_ERR_SHAPE otherwise).  Block ids are row-major over the block grid of a matrix,
  * matrices in table order; inside a block the squares are added in row-major order.
  * Other arguments as for condensa_filter_prune.
@@ -168,7 +199,8 @@ condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tenso
                                      float* const* theta, uint8_t* const* mask,
                                      double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                      uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                     void* workspace_dev, size_t workspace_bytes, void* stream);
+                                     void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * NeuronPrune scheme / neuron_prune operator (Table 1: neurons, seen as 1-D blocks, are aggregated and pruned).
@@ -180,7 +212,8 @@ condensa_status condensa_neuron_prune(const condensa_tensor* tensors, int n_tens
                                       float* const* theta, uint8_t* const* mask,
                                       double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                       uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                      void* workspace_dev, size_t workspace_bytes, void* stream);
+                                      void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * StructurePrune scheme (Table 1: neuron and filter pruning together): tensors with ndim == 2
@@ -192,7 +225,8 @@ condensa_status condensa_structure_prune(const condensa_tensor* tensors, int n_t
                                          float* const* theta, uint8_t* const* mask,
                                          double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                          uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                         void* workspace_dev, size_t workspace_bytes, void* stream);
+                                         void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * BlockPrune with n-D blocks and ragged edges (Table 1: blocks of any dimensionality and a given size; the evaluation
@@ -209,7 +243,8 @@ condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_te
                                         float* const* theta, uint8_t* const* mask,
                                         double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                         uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                        void* workspace_dev, size_t workspace_bytes, void* stream);
+                                        void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * Quantize(float16) scheme / quantize + dequantize operators (Section 3.1; Background:
@@ -266,7 +301,7 @@ condensa_status condensa_dequantize_fp8(const uint8_t* q_dev, uint64_t n, int fo
  *
  *  lambda      host table [n_tensors] of device fp32 multipliers shaped like the weights
  *  lambda_out  NULL (update lambda in place) or host table of device outputs; with separate outputs and
- *              large tensors the whole step reads w and lambda once (CONDENSA_OPT_FUSED_SWEEP), in place
+ *              large tensors the whole step reads w and lambda once (condensa_config.fused_sweep), in place
  *              it reads them twice
  *  theta, grad, mask  NULL or host tables [n_tensors]; entries may be NULL (skipped).  None of
  *              them may alias w or lambda.
@@ -277,7 +312,8 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors,
                                  float mu, double density,
                                  float* const* theta, float* const* grad, uint8_t* const* mask,
                                  condensa_select* result_dev,
-                                 void* workspace_dev, size_t workspace_bytes, void* stream);
+                                 void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * The L-C compression step for the composed scheme Compose([Prune(), Quantize(float16)]) (Evaluation,
@@ -294,7 +330,8 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
                                     float* const* theta, uint16_t* const* theta_f16,
                                     float* const* grad, uint8_t* const* mask,
                                     condensa_select* result_dev,
-                                    void* workspace_dev, size_t workspace_bytes, void* stream);
+                                    void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * Memory-footprint objective (Evaluation, Objective 1: the bytes taken by the model's non-zero
@@ -308,7 +345,8 @@ condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensor
 enum { CONDENSA_COUNT_F32 = 0, CONDENSA_COUNT_CODES16 = 1, CONDENSA_COUNT_CODES8 = 2 };
 condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int kind,
                                        uint64_t* count_dev,
-                                       void* workspace_dev, size_t workspace_bytes, void* stream);
+                                       void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /*
  * One SGD-with-momentum update of the learning (L) step with the L-C penalty folded in (Section 3.3:
@@ -325,7 +363,8 @@ condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tenso
                                      const float* const* grad_loss, const float* const* theta,
                                      const float* const* lambda, float* const* momentum_buf,
                                      float mu, float lr, float momentum,
-                                     void* workspace_dev, size_t workspace_bytes, void* stream);
+                                     void* workspace_dev, size_t workspace_bytes, void* stream,
+    const condensa_config* config);
 
 /* mu_j = mu_0 * a^j (L-C Optimizer Settings: mu_0 = 1e-3, a = 1.1), evaluated in binary64 (host). */
 float condensa_mu_schedule(double mu0, double a, int j);
@@ -347,27 +386,23 @@ condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim
                               const int32_t* keep_in_dev, int64_t n_keep_in, int64_t keep_in_offset,
                               float* out_dev, void* stream);
 
-/* ---- tuning / test knobs (process wide; not needed for normal use) ---------------------------- */
+/* ---- process-wide DEFAULTS of the knobs above: what a NULL config stands for ---------------------- */
 enum {
-    CONDENSA_OPT_SELECT_PATH   = 0, /* 0 auto, 1 radix levels over the data only, 2 sampled window even for small N */
-    CONDENSA_OPT_SAMPLE_LOG2   = 1, /* log2 of the sample size of the window path; 0 = auto             */
-    CONDENSA_OPT_WINDOW_MARGIN = 2, /* half-width of the sampled window in 1/16 standard deviations of
-                                       the sample rank; default 80 (= 5 sigma of a sample whose units of
-                                       4 neighbours are fully correlated, i.e. 10 sigma of independent
-                                       draws); 0 makes windows miss                                  */
-    CONDENSA_OPT_CAND_SHIFT    = 3, /* candidate capacity = N >> value; 0 = auto                          */
-    CONDENSA_OPT_PROFILE       = 4, /* bit p set: bracket phase p of every call with HIP events on the call's stream */
-    CONDENSA_OPT_APPLY_THREADS = 5, /* workgroup size of the L-C apply sweep: 0 (default = 64), 64, 128 or 256 */
-    CONDENSA_OPT_FUSED_SWEEP   = 6, /* window path with one density: 0 = selection and apply share one sweep
-                                       when the outputs do not alias the inputs, 1 = always two sweeps   */
+    CONDENSA_OPT_SELECT_PATH   = 0, /* condensa_config.select_path   */
+    CONDENSA_OPT_SAMPLE_LOG2   = 1, /* condensa_config.sample_log2   */
+    CONDENSA_OPT_WINDOW_MARGIN = 2, /* condensa_config.window_margin */
+    CONDENSA_OPT_CAND_SHIFT    = 3, /* condensa_config.cand_shift    */
+    CONDENSA_OPT_PROFILE       = 4, /* condensa_config.profile       */
+    CONDENSA_OPT_APPLY_THREADS = 5, /* condensa_config.apply_threads */
+    CONDENSA_OPT_FUSED_SWEEP   = 6, /* condensa_config.fused_sweep   */
     CONDENSA_OPT_COUNT         = 7
 };
 condensa_status condensa_set_option(int option, int64_t value);
 int64_t         condensa_get_option(int option);
 
 /*
- * Phase timing (benchmarks).  For every phase whose bit (1 << phase) is set in CONDENSA_OPT_PROFILE,
- * every entry point records a pair of timing events on the caller's stream around that phase.  condensa_profile_read waits
+ * Phase timing (benchmarks).  For every phase whose bit (1 << phase) is set in the call's
+ * condensa_config.profile, the entry point records a pair of timing events on the caller's stream around that phase.  condensa_profile_read waits
  * for the recorded events, adds the elapsed milliseconds of all finished intervals of `phase` to
  * its running totals and returns those totals; condensa_profile_reset drops totals and events.
  */

@@ -30,6 +30,13 @@ class CondensaError(RuntimeError):
         self.code = code
 
 
+class Config(ctypes.Structure):
+    """condensa_config: the tuning / test knobs of one call."""
+    _fields_ = [("select_path", ctypes.c_int32), ("sample_log2", ctypes.c_int32), ("window_margin", ctypes.c_int32),
+                ("cand_shift", ctypes.c_int32), ("profile", ctypes.c_int32), ("apply_threads", ctypes.c_int32),
+                ("fused_sweep", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 class Tensor(ctypes.Structure):
     _fields_ = [("w", ctypes.c_void_p), ("shape", ctypes.c_int64 * 4), ("ndim", ctypes.c_int32),
                 ("reserved", ctypes.c_int32)]
@@ -37,31 +44,32 @@ class Tensor(ctypes.Structure):
 
 _PROTOTYPES = {
     "condensa_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
-                                                   ctypes.c_int, ctypes.c_int]),
+                                                   ctypes.c_int, ctypes.c_int, ctypes.POINTER(Config)]),
+    "condensa_config_init": (ctypes.c_int32, [ctypes.POINTER(Config)]),
     "condensa_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                         ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_filter_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                               ctypes.c_size_t, ctypes.c_void_p]),
+                                               ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_neuron_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                               ctypes.c_size_t, ctypes.c_void_p]),
+                                               ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_structure_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                                  ctypes.c_size_t, ctypes.c_void_p]),
+                                                  ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_block_prune_nd": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_int32),
                                                  ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_void_p,
                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
-                                                 ctypes.c_void_p]),
+                                                 ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_block_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_quantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
     "condensa_dequantize": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]),
@@ -75,16 +83,16 @@ _PROTOTYPES = {
     "condensa_lc_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
-                                          ctypes.c_void_p]),
+                                          ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_lc_step_pq": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                             ctypes.c_size_t, ctypes.c_void_p]),
+                                             ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_count_nonzero": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
-                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_lc_sgd_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
-                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_mu_schedule": (ctypes.c_float, [ctypes.c_double, ctypes.c_double, ctypes.c_int]),
     "condensa_thin": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_void_p,
                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
@@ -201,16 +209,38 @@ def _ptr_table(tensors: Optional[Sequence]):
     return arr, ctypes.cast(arr, ctypes.c_void_p)
 
 
-def _workspace(op, total, n_struct, n_tensors, n_dens, scope, device, workspace=None):
+def condensa_config(**fields) -> Config:
+    """A condensa_config holding the process-wide defaults, with the given fields changed
+    (select_path, sample_log2, window_margin, cand_shift, profile, apply_threads, fused_sweep)."""
+    c = Config()
+    _check(library().condensa_config_init(ctypes.byref(c)))
+    for k, v in fields.items():
+        if k not in {f for f, _ in Config._fields_} or k == "reserved":
+            raise KeyError(k)
+        setattr(c, k, int(v))
+    return c
+
+
+def _cfg(config):
+    """None -> NULL (process-wide defaults); a dict of fields or a Config -> pointer to the struct."""
+    if config is None:
+        return None
+    if isinstance(config, dict):
+        config = condensa_config(**config)
+    return ctypes.byref(config)
+
+
+def _workspace(op, total, n_struct, n_tensors, n_dens, scope, device, workspace=None, config=None):
     import torch
-    need = int(library().condensa_workspace_bytes(op, total, n_struct, n_tensors, n_dens, scope))
+    need = int(library().condensa_workspace_bytes(op, total, n_struct, n_tensors, n_dens, scope, _cfg(config)))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
     return workspace, need
 
 
-def condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope) -> int:
-    return int(library().condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope))
+def condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope, config=None) -> int:
+    return int(library().condensa_workspace_bytes(op, total_elems, n_structures, n_tensors, n_densities, scope,
+                                                  _cfg(config)))
 
 
 def condensa_set_option(option: int, value: int) -> None:
@@ -242,7 +272,7 @@ def select_records(results) -> List[Dict[str, int]]:
 
 
 def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16=False, mask=True,
-                   in_place=False, workspace=None, stream=None, outputs=None):
+                   in_place=False, workspace=None, stream=None, outputs=None, config=None):
     """Marshals a call of the C entry point condensa_prune.  ``theta`` / ``theta_f16`` / ``mask`` choose
     which outputs are allocated ([density][tensor] lists of device tensors); ``in_place`` passes the
     weights themselves as theta (one density only).  Returns the outputs and the record tensor."""
@@ -274,16 +304,16 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     results = outputs.get("results")
     if results is None:
         results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
-    ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace)
+    ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace, config)
     _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
-                              _stream(stream)))
+                              _stream(stream), _cfg(config)))
     return {"theta": th, "theta_f16": th16, "mask": mk, "results": results[:n_rec], "workspace": ws,
             "_keep": (k1, k2, k3),
             "_buffers": {"theta": None if in_place else th, "theta_f16": th16, "mask": mk, "results": results}}
 
 
 def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask, extra_args, workspace, stream,
-                    outputs=None):
+                    outputs=None, config=None, fill_keep_idx=False):
     import torch
     lib = library()
     dev = tensors[0].device if tensors else torch.device("cuda")
@@ -303,13 +333,15 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
     sumsq = reuse("sumsq", lambda: torch.empty(F, dtype=torch.float64, device=dev))
     norms = reuse("norms", lambda: torch.empty(F, dtype=torch.float32, device=dev))
     keep_idx = reuse("keep_idx", lambda: torch.empty(F, dtype=torch.int32, device=dev))
-    keep_idx.fill_(-1)
+    if fill_keep_idx:                       # the library writes the first k entries only; on request the rest reads -1
+        with torch.cuda.stream(torch.cuda.current_stream() if stream is None else stream):
+            keep_idx.fill_(-1)
     smask = reuse("structure_mask", lambda: torch.empty(F, dtype=torch.uint8, device=dev))
     results = reuse("results", lambda: torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev))
-    ws, need = _workspace(op, total, n_struct, nt, 1, scope, dev, workspace)
+    ws, need = _workspace(op, total, n_struct, nt, 1, scope, dev, workspace, config)
     args = [tab, nt] + extra_args + [float(density), scope, p1, p2, sumsq.data_ptr(), norms.data_ptr(),
                                      keep_idx.data_ptr(), smask.data_ptr(), results.data_ptr(), ws.data_ptr(),
-                                     ws.numel(), _stream(stream)]
+                                     ws.numel(), _stream(stream), _cfg(config)]
     _check(getattr(lib, fn_name)(*args))
     return {"theta": th, "mask": mk, "sumsq": sumsq[:n_struct], "norms": norms[:n_struct],
             "keep_idx": keep_idx[:n_struct], "structure_mask": smask[:n_struct], "results": results[:n_rec],
@@ -319,36 +351,36 @@ def _structure_call(fn_name, op, tensors, n_struct, density, scope, theta, mask,
 
 
 def condensa_filter_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
-                          outputs=None):
+                          outputs=None, **kw):
     n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_filter_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream, outputs)
+                           [], workspace, stream, outputs, **kw)
 
 
 def condensa_block_prune(tensors, block_h, block_w, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
-                         workspace=None, stream=None, outputs=None):
+                         workspace=None, stream=None, outputs=None, **kw):
     n_struct = _cached(tensors, ("blocks", block_h, block_w),
                        lambda: sum((t.shape[0] // block_h) * (t.shape[1] // block_w) for t in tensors if t.dim() == 2))
     return _structure_call("condensa_block_prune", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [int(block_h), int(block_w)], workspace, stream, outputs)
+                           [int(block_h), int(block_w)], workspace, stream, outputs, **kw)
 
 
 def condensa_neuron_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
-                          outputs=None):
+                          outputs=None, **kw):
     n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_neuron_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream, outputs)
+                           [], workspace, stream, outputs, **kw)
 
 
 def condensa_structure_prune(tensors, density, scope=SCOPE_GLOBAL, theta=True, mask=True, workspace=None, stream=None,
-                             outputs=None):
+                             outputs=None, **kw):
     n_struct = _cached(tensors, "rows", lambda: sum(t.shape[0] if t.numel() else 0 for t in tensors))
     return _structure_call("condensa_structure_prune", OP_FILTER_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [], workspace, stream, outputs)
+                           [], workspace, stream, outputs, **kw)
 
 
 def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, theta=True, mask=True,
-                            workspace=None, stream=None, outputs=None):
+                            workspace=None, stream=None, outputs=None, **kw):
     nd = len(block_shape)
     blk = (ctypes.c_int32 * max(nd, 1))(*[int(b) for b in block_shape])
     n_struct = 0
@@ -359,7 +391,7 @@ def condensa_block_prune_nd(tensors, block_shape, density, scope=SCOPE_GLOBAL, t
                 c *= -(-d // max(int(b), 1))
             n_struct += c
     return _structure_call("condensa_block_prune_nd", OP_BLOCK_PRUNE, tensors, n_struct, density, scope, theta, mask,
-                           [blk, nd], workspace, stream, outputs)
+                           [blk, nd], workspace, stream, outputs, **kw)
 
 
 def _quantize(fn_name, x, want_q, want_dq, stream):
@@ -420,7 +452,7 @@ def condensa_dequantize_fp8(q, fmt, stream=None):
 
 
 def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,
-                     mask=True, outputs=None, workspace=None, stream=None, pq=False):
+                     mask=True, outputs=None, workspace=None, stream=None, pq=False, config=None):
     """Marshals condensa_lc_step.  By default fresh lambda_out tensors are allocated (lambda is left
     untouched); ``in_place`` updates lambda itself.  ``outputs`` may carry preallocated
     theta / grad / mask / lambda_out lists to reuse."""
@@ -446,16 +478,16 @@ def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=Fa
     results = outputs.get("results")
     if results is None:
         results = torch.zeros((1, len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
-    ws, need = _workspace(OP_LC_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
+    ws, need = _workspace(OP_LC_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace, config)
     th16, k4 = None, None
     if pq:
         th16 = outputs.get("theta_f16") or [torch.empty(t.shape, dtype=torch.int16, device=dev) for t in tensors]
         k4, p4 = _ptr_table(th16)
         _check(lib.condensa_lc_step_pq(tab, nt, pl, plo, float(mu), float(density), p1, p4, p2, p3,
-                                       results.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+                                       results.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream), _cfg(config)))
     else:
         _check(lib.condensa_lc_step(tab, nt, pl, plo, float(mu), float(density), p1, p2, p3, results.data_ptr(),
-                                    ws.data_ptr(), ws.numel(), _stream(stream)))
+                                    ws.data_ptr(), ws.numel(), _stream(stream), _cfg(config)))
     return {"theta": th, "theta_f16": th16, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo,
             "results": results, "workspace": ws, "_keep": (kl, klo, k1, k2, k3, k4)}
 
@@ -486,7 +518,7 @@ def condensa_count_nonzero(tensors, workspace=None, stream=None):
     total = _total(tensors)
     count = torch.zeros(1, dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_COUNT_NONZERO, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
-    _check(lib.condensa_count_nonzero(arr, nt, kind, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+    _check(lib.condensa_count_nonzero(arr, nt, kind, count.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream), None))
     return count
 
 
@@ -528,7 +560,7 @@ def condensa_lc_sgd_step(tensors, grad_loss, theta, lambdas, momentum_buf, mu, l
     k4, p4 = _ptr_table(momentum_buf)
     ws, need = _workspace(OP_LC_SGD_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace)
     _check(lib.condensa_lc_sgd_step(tab, nt, p1, p2, p3, p4, float(mu), float(lr), float(momentum), ws.data_ptr(),
-                                    ws.numel(), _stream(stream)))
+                                    ws.numel(), _stream(stream), None))
     return ws
 
 

@@ -1,5 +1,7 @@
 // C-ABI entry points of the compression-step library (see include/condensa.h): argument checks,
 // table building, workspace carving and the kernel launch sequences.
+#include <memory>
+
 #include "host.h"
 #include "k_apply.h"
 #include "k_quantize.h"
@@ -11,7 +13,48 @@
 namespace condensa {
 
 std::atomic<int> g_last_hip_error{0};
+
+// ---- configuration ---------------------------------------------------------------------------------
+
+namespace {
+// process-wide defaults: what a NULL condensa_config stands for
 std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT] = {{0}, {0}, {80}, {0}, {0}, {0}, {0}};
+
+bool option_value_ok(int option, int64_t value) {
+    if (value < 0) return false;
+    switch (option) {
+        case CONDENSA_OPT_SELECT_PATH:   return value <= 2;
+        case CONDENSA_OPT_SAMPLE_LOG2:   return value == 0 || (value >= 10 && value <= 26);
+        case CONDENSA_OPT_WINDOW_MARGIN: return value <= 0x7FFFFFFF;
+        case CONDENSA_OPT_CAND_SHIFT:    return value <= 30;
+        case CONDENSA_OPT_PROFILE:       return value < (1 << CONDENSA_PHASE_COUNT);
+        case CONDENSA_OPT_APPLY_THREADS: return value == 0 || value == 64 || value == 128 || value == 256;
+        case CONDENSA_OPT_FUSED_SWEEP:   return value <= 1;
+        default: return false;
+    }
+}
+}  // namespace
+
+condensa_status set_default_option(int option, int64_t value) {
+    if (!option_value_ok(option, value)) return CONDENSA_ERR_ARG;
+    g_options[option].store(value);
+    return CONDENSA_OK;
+}
+
+condensa_status resolve_config(const condensa_config* c, Config* out) {
+    if (c == nullptr) {
+        for (int i = 0; i < CONDENSA_OPT_COUNT; ++i) out->v[i] = g_options[i].load();
+        return CONDENSA_OK;
+    }
+    if (c->reserved != 0) return CONDENSA_ERR_ARG;
+    const int64_t v[CONDENSA_OPT_COUNT] = {c->select_path, c->sample_log2, c->window_margin, c->cand_shift,
+                                           c->profile, c->apply_threads, c->fused_sweep};
+    for (int i = 0; i < CONDENSA_OPT_COUNT; ++i) {
+        if (!option_value_ok(i, v[i])) return CONDENSA_ERR_ARG;
+        out->v[i] = v[i];
+    }
+    return CONDENSA_OK;
+}
 
 // ---- pinned staging ring -------------------------------------------------------------------------
 
@@ -60,13 +103,13 @@ struct Interval {
     hipEvent_t a = nullptr, b = nullptr;
     int phase = 0;
 };
-std::vector<Interval> g_intervals;          // recorded, not yet read
+std::vector<Interval> g_intervals;          // both events recorded, not yet read
 std::vector<hipEvent_t> g_event_pool;
 double g_phase_ms[CONDENSA_PHASE_COUNT] = {};
 u64 g_phase_n[CONDENSA_PHASE_COUNT] = {};
 std::mutex g_prof_mu;
 
-hipEvent_t take_event() {
+hipEvent_t take_event() {                   // g_prof_mu held
     if (!g_event_pool.empty()) {
         hipEvent_t e = g_event_pool.back();
         g_event_pool.pop_back();
@@ -78,29 +121,42 @@ hipEvent_t take_event() {
 }
 }  // namespace
 
-PhaseTimer::PhaseTimer(int phase, hipStream_t stream) : stream_(stream) {
-    if (((g_options[CONDENSA_OPT_PROFILE].load() >> phase) & 1) == 0) return;
+PhaseTimer::PhaseTimer(int phase, hipStream_t stream, const Config& cfg) : phase_(phase), stream_(stream) {
+    if (((cfg[CONDENSA_OPT_PROFILE] >> phase) & 1) == 0) return;
+    hipEvent_t a, b;
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mu);
+        a = take_event();
+        b = take_event();
+    }
+    if (a && b && hipEventRecord(a, stream_) == hipSuccess) {
+        a_ = a;
+        b_ = b;
+        return;
+    }
     std::lock_guard<std::mutex> lock(g_prof_mu);
-    Interval iv;
-    iv.phase = phase;
-    iv.a = take_event();
-    iv.b = take_event();
-    if (!iv.a || !iv.b) return;
-    if (hipEventRecord(iv.a, stream_) != hipSuccess) return;
-    g_intervals.push_back(iv);
-    slot_ = static_cast<int>(g_intervals.size()) - 1;
+    if (a) g_event_pool.push_back(a);
+    if (b) g_event_pool.push_back(b);
 }
 
 PhaseTimer::~PhaseTimer() {
-    if (slot_ < 0) return;
+    if (!a_) return;
+    const bool ok = hipEventRecord(b_, stream_) == hipSuccess;
     std::lock_guard<std::mutex> lock(g_prof_mu);
-    if (slot_ < static_cast<int>(g_intervals.size())) (void)hipEventRecord(g_intervals[slot_].b, stream_);
+    if (ok) {
+        Interval iv;
+        iv.a = a_; iv.b = b_; iv.phase = phase_;
+        g_intervals.push_back(iv);
+    } else {
+        g_event_pool.push_back(a_);
+        g_event_pool.push_back(b_);
+    }
 }
 
 // ---- workspace layout ----------------------------------------------------------------------------
 
-static u64 window_sample_size(u64 N) {
-    const int64_t opt = g_options[CONDENSA_OPT_SAMPLE_LOG2].load();
+static u64 window_sample_size(u64 N, const Config& cfg) {
+    const int64_t opt = cfg[CONDENSA_OPT_SAMPLE_LOG2];
     u64 s;
     if (opt > 0) s = static_cast<u64>(1) << (opt > 26 ? 26 : opt);
     else {
@@ -112,15 +168,15 @@ static u64 window_sample_size(u64 N) {
     return s;
 }
 
-static u64 window_cand_capacity(u64 N, int J) {
-    const int64_t opt = g_options[CONDENSA_OPT_CAND_SHIFT].load();
+static u64 window_cand_capacity(u64 N, int J, const Config& cfg) {
+    const int64_t opt = cfg[CONDENSA_OPT_CAND_SHIFT];
     const int shift = (opt > 0 && opt < 40) ? static_cast<int>(opt) : (J > 1 ? 3 : 5);
     u64 c = N >> shift;
     if (c < 4096) c = 4096;
     return c;
 }
 
-Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
+Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const Config& cfg, bool no_window) {
     Layout L;
     const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
     const bool structure = (op == CONDENSA_OP_FILTER_PRUNE || op == CONDENSA_OP_BLOCK_PRUNE);
@@ -149,9 +205,9 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
         L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
-    } else if (!per_tensor && op != CONDENSA_OP_COUNT_NONZERO && op != CONDENSA_OP_LC_SGD_STEP) {
-        L.sample_cap = window_sample_size(N);
-        L.cand_cap = window_cand_capacity(N, J);
+    } else if (!per_tensor && !no_window && op != CONDENSA_OP_COUNT_NONZERO && op != CONDENSA_OP_LC_SGD_STEP) {
+        L.sample_cap = window_sample_size(N, cfg);
+        L.cand_cap = window_cand_capacity(N, J, cfg);
         L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
         L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
         L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));
@@ -167,16 +223,50 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope) {
 
 // ---- tables ---------------------------------------------------------------------------------------
 
+// Host memory of one call's tables.  The usual entry points take it from the heap; the entry point for
+// callers that cannot allocate hands out pieces of a fixed buffer on its own stack instead.
+class HostArena {
+public:
+    HostArena() = default;                                         // heap
+    HostArena(char* fixed, size_t bytes) : fixed_(fixed), left_(bytes) {}
+    HostArena(const HostArena&) = delete;
+    HostArena& operator=(const HostArena&) = delete;
+    // n zero-initialised objects of T (trivially copyable table types), or nullptr when a fixed buffer is used up
+    template <typename T>
+    T* array(size_t n) {
+        const size_t bytes = align_up((n ? n : 1) * sizeof(T), 64);
+        char* p;
+        if (fixed_) {
+            if (bytes > left_) return nullptr;
+            p = fixed_;
+            fixed_ += bytes;
+            left_ -= bytes;
+        } else {
+            heap_.emplace_back(new char[bytes]);
+            p = heap_.back().get();
+        }
+        std::memset(p, 0, bytes);
+        return reinterpret_cast<T*>(p);
+    }
+private:
+    char* fixed_ = nullptr;
+    size_t left_ = 0;
+    std::vector<std::unique_ptr<char[]>> heap_;
+};
+
 struct Tables {
-    std::vector<TensorDesc> td;      // n_tensors + 1 (sentinel)
+    TensorDesc* td = nullptr;        // n_tensors + 1 (sentinel)
+    int n_td = 0;
     u64 N = 0, n_chunks = 0, F = 0, n_schunks = 0;
     bool vec = true;
 };
 
-static condensa_status build_tensor_table(const condensa_tensor* tensors, int n_tensors, Tables* tb) {
+static condensa_status build_tensor_table(const condensa_tensor* tensors, int n_tensors, Tables* tb, HostArena& arena) {
     if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return CONDENSA_ERR_SIZE;
     if (n_tensors > 0 && tensors == nullptr) return CONDENSA_ERR_NULL;
-    tb->td.assign(static_cast<size_t>(n_tensors) + 1, TensorDesc{});
+    tb->td = arena.array<TensorDesc>(static_cast<size_t>(n_tensors) + 1);
+    if (tb->td == nullptr) return CONDENSA_ERR_SIZE;
+    tb->n_td = n_tensors + 1;
     u64 flat = 0, chunk = 0;
     for (int t = 0; t < n_tensors; ++t) {
         u64 n;
@@ -237,10 +327,10 @@ static unsigned fill_grid(u64 words) {
 
 // Radix levels over the weights: 3 x (histogram sweep + bin search).
 template <bool LC, bool VEC>
-static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st) {
+static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st, const Config& cfg) {
     if (a.n_chunks > 0) {
         // as the gated fallback of the window path these launches are (normally empty) resolve work
-        PhaseTimer timer(a.only_failed ? CONDENSA_PHASE_RESOLVE : CONDENSA_PHASE_SWEEP, st);
+        PhaseTimer timer(a.only_failed ? CONDENSA_PHASE_RESOLVE : CONDENSA_PHASE_SWEEP, st, cfg);
         for (int level = 0; level < n_levels(31); ++level) {
             // Every workgroup flushes the non-zero bins of its LDS histograms (J of them past level 0) with
             // global atomics: few wide workgroups keep that flush small (level 0 of 20 M weights: 36 -> 19 us).
@@ -267,8 +357,8 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
 
 template <bool LC, bool VEC>
 static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, int n_groups,
-                                               condensa_select* results, hipStream_t st) {
-    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
+                                               condensa_select* results, hipStream_t st, const Config& cfg) {
+    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
     if (a.n_chunks > 0) {
         const unsigned tie_blocks = static_cast<unsigned>(a.n_chunks < 4096 ? a.n_chunks : 4096);
         hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(tie_blocks), dim3(kBlock), 0, st, a);
@@ -281,26 +371,26 @@ static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, i
 
 template <bool LC, bool VEC>
 static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool use_window, int n_slots,
-                                     int n_groups, condensa_select* results, hipStream_t st,
+                                     int n_groups, condensa_select* results, hipStream_t st, const Config& cfg,
                                      const FusedRequest* fused = nullptr) {
     condensa_status rc;
     if (use_window) {
-        rc = launch_window_path<LC, VEC>(a, L, ws, st, fused);
+        rc = launch_window_path<LC, VEC>(a, L, ws, st, cfg, fused);
         if (rc != CONDENSA_OK) return rc;
         a.only_failed = 1;
     }
-    rc = launch_radix_levels<LC, VEC>(a, n_slots, st);
+    rc = launch_radix_levels<LC, VEC>(a, n_slots, st, cfg);
     if (rc != CONDENSA_OK) return rc;
-    return launch_ties_and_results<LC, VEC>(a, n_slots, n_groups, results, st);
+    return launch_ties_and_results<LC, VEC>(a, n_slots, n_groups, results, st, cfg);
 }
 
 // Sampled window or radix levels?  Measured (one MI355X, 2^24..2^30 weights, 1/4/10 densities): the radix
 // levels cost three sweeps whatever the number of densities and ~50 us of fixed work; the window path
 // costs one sweep, ~0.2 ms of small kernels, and candidate lists and a sweep that grow with the number
 // of densities.  One density breaks even near 2^26 element reads, four near 2^27.5, ten near 2^30.
-static bool want_window(u64 N, bool per_tensor, int J, bool lc) {
+static bool want_window(u64 N, bool per_tensor, int J, bool lc, const Config& cfg) {
     if (per_tensor) return false;
-    const int64_t mode = g_options[CONDENSA_OPT_SELECT_PATH].load();
+    const int64_t mode = cfg[CONDENSA_OPT_SELECT_PATH];
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;
     u64 need = static_cast<u64>(J) << 26;
@@ -310,64 +400,70 @@ static bool want_window(u64 N, bool per_tensor, int J, bool lc) {
 
 }  // namespace condensa
 
-using namespace condensa;
+namespace condensa {
 
-// =====================================================================================================
-
-extern "C" {
-
-size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures, int n_tensors,
-                                int n_densities, int scope) {
-    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_LC_SGD_STEP) return 0;
-    if (op == CONDENSA_OP_QUANTIZE) return 0;
-    if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
-    if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
-    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return 0;
-    if (total_elems > kMaxElems || n_structures > total_elems) return 0;
-    return make_layout(op, total_elems, n_structures, n_tensors, n_densities, scope).total;
-}
-
-condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, const double* densities,
-                               int n_densities, int scope, float* const* theta, uint16_t* const* theta_f16,
-                               uint8_t* const* mask, condensa_select* results_dev, void* workspace_dev,
-                               size_t workspace_bytes, void* stream) {
+static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors, const double* densities,
+                                  int n_densities, int scope, float* const* theta, uint16_t* const* theta_f16,
+                                  uint8_t* const* mask, condensa_select* results_dev, void* workspace_dev,
+                                  size_t workspace_bytes, void* stream, const Config& cfg, HostArena& arena,
+                                  bool no_alloc) {
     if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return CONDENSA_ERR_SIZE;
     if (densities == nullptr || results_dev == nullptr) return CONDENSA_ERR_NULL;
     if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
     for (int j = 0; j < n_densities; ++j)
         if (!density_ok(densities[j])) return CONDENSA_ERR_DENSITY;
     Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb, arena);
     if (rc != CONDENSA_OK) return rc;
     const int J = n_densities;
     const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
     if (per_tensor && n_tensors == 0) return CONDENSA_OK;
-    const Layout L = make_layout(CONDENSA_OP_PRUNE, tb.N, 0, n_tensors, J, scope);
-    rc = check_workspace(workspace_dev, workspace_bytes, L);
-    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_PRUNE, tb.N, 0, n_tensors, J, scope, cfg, no_alloc);
 
-    // output table and aliasing / alignment checks
+    // output table, overlap and alignment checks
     const bool any_out = theta || theta_f16 || mask;
-    std::vector<OutDesc> out(static_cast<size_t>(J) * (n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    const size_t n_out = static_cast<size_t>(J) * (n_tensors > 0 ? n_tensors : 1);
+    OutDesc* out = arena.array<OutDesc>(n_out);
+    ByteRange* ranges = arena.array<ByteRange>(static_cast<size_t>(n_tensors) * (1 + 3 * J) + 2);
+    if (!out || !ranges) return CONDENSA_ERR_SIZE;
+    size_t n_ranges = 0;
     bool vec = tb.vec;
-    for (int j = 0; j < J; ++j)
-        for (int t = 0; t < n_tensors; ++t) {
-            OutDesc& o = out[static_cast<size_t>(j) * n_tensors + t];
+    bool in_place_any = false;
+    for (int t = 0; t < n_tensors; ++t) {
+        const u64 n = tb.td[t].n;
+        if (n == 0) continue;
+        bool in_place = false;
+        for (int j = 0; j < J; ++j) {
             const size_t i = static_cast<size_t>(j) * n_tensors + t;
-            if (tb.td[t].n == 0) continue;
+            OutDesc& o = out[i];
             o.theta = theta ? theta[i] : nullptr;
             o.theta16 = theta_f16 ? theta_f16[i] : nullptr;
             o.mask = mask ? mask[i] : nullptr;
-            if (o.theta == tb.td[t].w && J > 1) return CONDENSA_ERR_ARG;
-            if (static_cast<const void*>(o.theta16) == tb.td[t].w || static_cast<const void*>(o.mask) == tb.td[t].w)
-                return CONDENSA_ERR_ARG;
+            if (o.theta == tb.td[t].w) {                    // in place: one density only
+                if (J > 1) return CONDENSA_ERR_ARG;
+                in_place = true;
+            } else {
+                ranges[n_ranges++] = byte_range(o.theta, n * 4, true);
+            }
+            ranges[n_ranges++] = byte_range(o.theta16, n * 2, true);
+            ranges[n_ranges++] = byte_range(o.mask, n, true);
             if (o.theta && !aligned16(o.theta)) vec = false;
             if (o.theta16 && (reinterpret_cast<uintptr_t>(o.theta16) & 7u)) vec = false;
             if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
         }
+        ranges[n_ranges++] = byte_range(tb.td[t].w, n * 4, in_place);
+        in_place_any = in_place_any || in_place;
+    }
+    ranges[n_ranges++] = byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true);
+    ranges[n_ranges++] = byte_range(results_dev, static_cast<u64>(L.n_slots) * sizeof(condensa_select), true);
+    if (ranges_conflict(ranges, n_ranges)) return CONDENSA_ERR_ARG;
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return no_alloc ? CONDENSA_ERR_SIZE : rc;
 
-    const bool window = want_window(tb.N, per_tensor, J, false);
-    std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
+    const bool window = !no_alloc && want_window(tb.N, per_tensor, J, false, cfg);
+    Slot* slots = arena.array<Slot>(static_cast<size_t>(L.n_slots));
+    char* up = arena.array<char>(L.upload_bytes);
+    if (!slots || !up) return CONDENSA_ERR_SIZE;
     for (int g = 0; g < L.n_groups; ++g)
         for (int j = 0; j < J; ++j) {
             const u64 n = per_tensor ? tb.td[g].n : tb.N;
@@ -375,12 +471,11 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
         }
 
     // one upload: [tensor table | output table | rankings]
-    std::vector<char> up(L.upload_bytes, 0);
-    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
-    std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
-    std::memcpy(up.data() + L.slots, slots.data(), slots.size() * sizeof(Slot));
+    std::memcpy(up + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
+    std::memcpy(up + L.out, out, n_out * sizeof(OutDesc));
+    std::memcpy(up + L.slots, slots, static_cast<size_t>(L.n_slots) * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
+    rc = stage_upload(workspace_dev, up, L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
     hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
                        at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
@@ -405,18 +500,16 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     a.mu = 0.0f;
 
     // One density on the window path: selection and apply share one sweep unless theta overwrites the weights.
-    bool fuse = window && J == 1 && any_out && tb.n_chunks > 0 && slots[0].k > 0 &&
-                g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
-    for (int t = 0; t < n_tensors && fuse; ++t)
-        if (out[t].theta == tb.td[t].w && tb.td[t].n > 0) fuse = false;
+    const bool fuse = window && J == 1 && any_out && tb.n_chunks > 0 && slots[0].k > 0 && !in_place_any &&
+                      cfg[CONDENSA_OPT_FUSED_SWEEP] == 0;
     WindowArgs wargs{};
     FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, false, &wargs};
-    rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr)
-                : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, fuse ? &fr : nullptr);
+    rc = tb.vec ? run_selection<false, true>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, cfg, fuse ? &fr : nullptr)
+                : run_selection<false, false>(a, L, workspace_dev, window, L.n_slots, L.n_groups, results_dev, st, cfg, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
 
     if (fuse) {
-        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         hipLaunchKernelGGL((k_window_fixup<false, false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
         CONDENSA_LAUNCH_CHECK();
@@ -426,13 +519,61 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
         else     hipLaunchKernelGGL((k_prune_apply_gated<false>), dim3(grid), dim3(kBlock), 0, st, a, od, n_tiles);
         CONDENSA_LAUNCH_CHECK();
     } else if (any_out && tb.n_chunks > 0) {
-        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         if (vec) hipLaunchKernelGGL((k_prune_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
         else     hipLaunchKernelGGL((k_prune_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
         CONDENSA_LAUNCH_CHECK();
     }
     return CONDENSA_OK;
+}
+
+}  // namespace condensa
+
+using namespace condensa;
+
+// =====================================================================================================
+
+extern "C" {
+
+condensa_status condensa_config_init(condensa_config* config) {
+    if (config == nullptr) return CONDENSA_ERR_NULL;
+    Config c;
+    resolve_config(nullptr, &c);
+    config->select_path = static_cast<int32_t>(c[CONDENSA_OPT_SELECT_PATH]);
+    config->sample_log2 = static_cast<int32_t>(c[CONDENSA_OPT_SAMPLE_LOG2]);
+    config->window_margin = static_cast<int32_t>(c[CONDENSA_OPT_WINDOW_MARGIN]);
+    config->cand_shift = static_cast<int32_t>(c[CONDENSA_OPT_CAND_SHIFT]);
+    config->profile = static_cast<int32_t>(c[CONDENSA_OPT_PROFILE]);
+    config->apply_threads = static_cast<int32_t>(c[CONDENSA_OPT_APPLY_THREADS]);
+    config->fused_sweep = static_cast<int32_t>(c[CONDENSA_OPT_FUSED_SWEEP]);
+    config->reserved = 0;
+    return CONDENSA_OK;
+}
+
+size_t condensa_workspace_bytes(int op, uint64_t total_elems, uint64_t n_structures, int n_tensors,
+                                int n_densities, int scope, const condensa_config* config) {
+    if (op < CONDENSA_OP_PRUNE || op > CONDENSA_OP_LC_SGD_STEP) return 0;
+    if (op == CONDENSA_OP_QUANTIZE) return 0;
+    if (n_tensors < 0 || n_tensors > CONDENSA_MAX_TENSORS) return 0;
+    if (n_densities < 1 || n_densities > CONDENSA_MAX_DENSITIES) return 0;
+    if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return 0;
+    if (total_elems > kMaxElems || n_structures > total_elems) return 0;
+    Config cfg;
+    if (resolve_config(config, &cfg) != CONDENSA_OK) return 0;
+    return make_layout(op, total_elems, n_structures, n_tensors, n_densities, scope, cfg).total;
+}
+
+condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, const double* densities,
+                               int n_densities, int scope, float* const* theta, uint16_t* const* theta_f16,
+                               uint8_t* const* mask, condensa_select* results_dev, void* workspace_dev,
+                               size_t workspace_bytes, void* stream, const condensa_config* config) {
+    Config cfg;
+    const condensa_status rc = resolve_config(config, &cfg);
+    if (rc != CONDENSA_OK) return rc;
+    HostArena arena;
+    return prune_impl(tensors, n_tensors, densities, n_densities, scope, theta, theta_f16, mask, results_dev,
+                      workspace_dev, workspace_bytes, stream, cfg, arena, false);
 }
 
 }  // extern "C" (reopened below)
@@ -443,20 +584,25 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
                                     float* const* lambda_out, float mu, double density, float* const* theta,
                                     uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
                                     condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
-                                    void* stream) {
+                                    void* stream, const condensa_config* config) {
+    Config cfg;
+    condensa_status rc = resolve_config(config, &cfg);
+    if (rc != CONDENSA_OK) return rc;
     if (result_dev == nullptr) return CONDENSA_ERR_NULL;
     if (n_tensors > 0 && lambda == nullptr) return CONDENSA_ERR_NULL;
     if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
     if (!(mu > 0.0f) || !std::isfinite(mu)) return CONDENSA_ERR_DENSITY;
+    HostArena arena;
     Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    rc = build_tensor_table(tensors, n_tensors, &tb, arena);
     if (rc != CONDENSA_OK) return rc;
-    const Layout L = make_layout(CONDENSA_OP_LC_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
-    rc = check_workspace(workspace_dev, workspace_bytes, L);
-    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_LC_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL, cfg);
 
     std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    std::vector<ByteRange> ranges;
+    ranges.reserve(static_cast<size_t>(n_tensors) * 7 + 2);
     bool vec = tb.vec;
+    bool in_place_any = false;
     for (int t = 0; t < n_tensors; ++t) {
         TensorDesc& d = tb.td[t];
         if (d.n == 0) continue;
@@ -469,24 +615,34 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         o.theta = theta ? theta[t] : nullptr;
         o.theta16 = (pq && theta_f16) ? theta_f16[t] : nullptr;
         o.mask = mask ? mask[t] : nullptr;
-        const void* ins[2] = {d.w, d.lam};
-        const void* outs[5] = {o.theta, d.grad, o.mask, (d.lam_out != d.lam) ? d.lam_out : nullptr, o.theta16};
-        for (const void* o_ : outs)
-            for (const void* i_ : ins)
-                if (o_ != nullptr && o_ == i_) return CONDENSA_ERR_ARG;
-        if (static_cast<const void*>(d.lam) == static_cast<const void*>(d.w)) return CONDENSA_ERR_ARG;
+        // theta, grad, mask, theta16 and a separate lambda_out must be disjoint from everything else; lambda
+        // updated in place is a written range, so it must not overlap the weights either
+        const bool in_place = (d.lam_out == d.lam);
+        in_place_any = in_place_any || in_place;
+        ranges.push_back(byte_range(d.w, d.n * 4, false));
+        ranges.push_back(byte_range(d.lam, d.n * 4, in_place));
+        if (!in_place) ranges.push_back(byte_range(d.lam_out, d.n * 4, true));
+        ranges.push_back(byte_range(o.theta, d.n * 4, true));
+        ranges.push_back(byte_range(d.grad, d.n * 4, true));
+        ranges.push_back(byte_range(o.mask, d.n, true));
+        ranges.push_back(byte_range(o.theta16, d.n * 2, true));
         if (!aligned16(d.lam) || !aligned16(d.lam_out)) vec = false;
         if (o.theta && !aligned16(o.theta)) vec = false;
         if (d.grad && !aligned16(d.grad)) vec = false;
         if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
         if (o.theta16 && (reinterpret_cast<uintptr_t>(o.theta16) & 7u)) vec = false;
     }
-    const bool window = want_window(tb.N, false, 1, true);
+    ranges.push_back(byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true));
+    ranges.push_back(byte_range(result_dev, sizeof(condensa_select), true));
+    if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
+    const bool window = want_window(tb.N, false, 1, true, cfg);
     Slot slot;
     init_slot(&slot, tb.N, kept_count(density, tb.N), window ? 2u : 1u);
 
     std::vector<char> up(L.upload_bytes, 0);
-    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
     std::memcpy(up.data() + L.slots, &slot, sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -520,17 +676,15 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         if (tb.td[t].n > 0 && !aligned16(tb.td[t].lam)) vec_in = false;
     // Window path: selection and apply share one sweep unless lambda is updated in place (a failed window
     // needs the inputs again).
-    bool fuse = window && tb.n_chunks > 0 && slot.k > 0 && g_options[CONDENSA_OPT_FUSED_SWEEP].load() == 0;
-    for (int t = 0; t < n_tensors && fuse; ++t)
-        if (tb.td[t].n > 0 && tb.td[t].lam_out == tb.td[t].lam) fuse = false;
+    const bool fuse = window && tb.n_chunks > 0 && slot.k > 0 && !in_place_any && cfg[CONDENSA_OPT_FUSED_SWEEP] == 0;
     WindowArgs wargs{};
     FusedRequest fr{at<OutDesc>(workspace_dev, L.out), vec, pq, &wargs};
-    rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr)
-                : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st, fuse ? &fr : nullptr);
+    rc = vec_in ? run_selection<true, true>(a, L, workspace_dev, window, 1, 1, result_dev, st, cfg, fuse ? &fr : nullptr)
+                : run_selection<true, false>(a, L, workspace_dev, window, 1, 1, result_dev, st, cfg, fuse ? &fr : nullptr);
     if (rc != CONDENSA_OK) return rc;
 
     if (fuse) {
-        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
         if (pq) hipLaunchKernelGGL((k_window_fixup<true, true>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
         else    hipLaunchKernelGGL((k_window_fixup<true, false>), dim3(wargs.n_segs * kFixupParts), dim3(kBlock), 0, st, a, wargs);
@@ -543,9 +697,9 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         else            hipLaunchKernelGGL((k_lc_apply_gated<false, false>), grid, dim3(64), 0, st, a, od, n_tiles);
         CONDENSA_LAUNCH_CHECK();
     } else if (tb.n_chunks > 0) {
-        PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+        PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
         const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-        const int64_t at_opt = g_options[CONDENSA_OPT_APPLY_THREADS].load();
+        const int64_t at_opt = cfg[CONDENSA_OPT_APPLY_THREADS];
         const unsigned nc = static_cast<unsigned>(tb.n_chunks);
         // measured on the 1.2 G-weight workload: 64 threads 3.94 ms, 256 threads 4.28 ms, 128 threads 4.55 ms
         if (pq) {
@@ -568,36 +722,48 @@ extern "C" {
 condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
                                  float* const* lambda_out, float mu, double density, float* const* theta,
                                  float* const* grad, uint8_t* const* mask, condensa_select* result_dev,
-                                 void* workspace_dev, size_t workspace_bytes, void* stream) {
+                                 void* workspace_dev, size_t workspace_bytes, void* stream,
+                                 const condensa_config* config) {
     return lc_step_impl(false, tensors, n_tensors, lambda, lambda_out, mu, density, theta, nullptr, grad, mask,
-                        result_dev, workspace_dev, workspace_bytes, stream);
+                        result_dev, workspace_dev, workspace_bytes, stream, config);
 }
 
 condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
                                     float* const* lambda_out, float mu, double density, float* const* theta,
                                     uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
                                     condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
-                                    void* stream) {
+                                    void* stream, const condensa_config* config) {
     return lc_step_impl(true, tensors, n_tensors, lambda, lambda_out, mu, density, theta, theta_f16, grad, mask,
-                        result_dev, workspace_dev, workspace_bytes, stream);
+                        result_dev, workspace_dev, workspace_bytes, stream, config);
 }
 
 condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int kind,
                                        uint64_t* count_dev, void* workspace_dev, size_t workspace_bytes,
-                                       void* stream) {
+                                       void* stream, const condensa_config* config) {
+    Config cfg;
+    condensa_status rc = resolve_config(config, &cfg);
+    if (rc != CONDENSA_OK) return rc;
     if (count_dev == nullptr) return CONDENSA_ERR_NULL;
     if (kind < CONDENSA_COUNT_F32 || kind > CONDENSA_COUNT_CODES8) return CONDENSA_ERR_ARG;
+    HostArena arena;
     Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    rc = build_tensor_table(tensors, n_tensors, &tb, arena);
     if (rc != CONDENSA_OK) return rc;
-    const Layout L = make_layout(CONDENSA_OP_COUNT_NONZERO, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
+    const Layout L = make_layout(CONDENSA_OP_COUNT_NONZERO, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL, cfg);
     rc = check_workspace(workspace_dev, workspace_bytes, L);
     if (rc != CONDENSA_OK) return rc;
     bool vec = true;
-    for (int t = 0; t < n_tensors; ++t)
+    std::vector<ByteRange> ranges;
+    const u64 elem_bytes = kind == CONDENSA_COUNT_F32 ? 4 : (kind == CONDENSA_COUNT_CODES16 ? 2 : 1);
+    for (int t = 0; t < n_tensors; ++t) {
         if (tb.td[t].n > 0 && (reinterpret_cast<uintptr_t>(tb.td[t].w) & 15u)) vec = false;
+        ranges.push_back(byte_range(tb.td[t].w, tb.td[t].n * elem_bytes, false));
+    }
+    ranges.push_back(byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true));
+    ranges.push_back(byte_range(count_dev, sizeof(uint64_t), true));
+    if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
     std::vector<char> up(L.upload_bytes, 0);
-    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
@@ -641,31 +807,44 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
                                            float* const* theta, uint8_t* const* mask, double* sumsq_dev,
                                            float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                            condensa_select* results_dev, void* workspace_dev,
-                                           size_t workspace_bytes, void* stream) {
+                                           size_t workspace_bytes, void* stream, const Config& cfg) {
     const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
     if (per_tensor && n_tensors == 0) return CONDENSA_OK;
-    const Layout L = make_layout(op, tb.N, tb.F, n_tensors, 1, scope);
-    condensa_status rc = check_workspace(workspace_dev, workspace_bytes, L);
-    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(op, tb.N, tb.F, n_tensors, 1, scope, cfg);
 
     std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    std::vector<ByteRange> ranges;
+    ranges.reserve(static_cast<size_t>(n_tensors) * 3 + 6);
     bool vec = tb.vec;
     for (int t = 0; t < n_tensors; ++t) {
-        if (tb.td[t].n == 0) continue;
+        const u64 n = tb.td[t].n;
+        if (n == 0) continue;
         OutDesc& o = out[t];
         o.theta = theta ? theta[t] : nullptr;
         o.mask = mask ? mask[t] : nullptr;
-        if (static_cast<const void*>(o.mask) == tb.td[t].w) return CONDENSA_ERR_ARG;
+        const bool in_place = (o.theta == tb.td[t].w);       // the aggregates are complete before the apply sweep
+        if (!in_place) ranges.push_back(byte_range(o.theta, n * 4, true));
+        ranges.push_back(byte_range(o.mask, n, true));
+        ranges.push_back(byte_range(tb.td[t].w, n * 4, in_place));
         if (o.theta && !aligned16(o.theta)) vec = false;
         if (o.mask && (reinterpret_cast<uintptr_t>(o.mask) & 3u)) vec = false;
     }
+    ranges.push_back(byte_range(sumsq_dev, tb.F * 8, true));
+    ranges.push_back(byte_range(norms_dev, tb.F * 4, true));
+    ranges.push_back(byte_range(keep_idx_dev, tb.F * 4, true));
+    ranges.push_back(byte_range(structure_mask_dev, tb.F, true));
+    ranges.push_back(byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true));
+    ranges.push_back(byte_range(results_dev, static_cast<u64>(L.n_slots) * sizeof(condensa_select), true));
+    if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
+    condensa_status rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
     std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
     for (int g = 0; g < L.n_groups; ++g) {
         const u64 n = per_tensor ? tb.td[g].n_struct : tb.F;
         init_slot(&slots[g], n, kept_count(density, n), 1u);
     }
     std::vector<char> up(L.upload_bytes, 0);
-    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
     std::memcpy(up.data() + L.slots, slots.data(), slots.size() * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -695,12 +874,12 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
     const unsigned mtiles = static_cast<unsigned>((tb.F + kMaskTile - 1) / kMaskTile);
     // groups of at most kSmallGroup structures: one workgroup per group ranks, masks and lists them
-    bool small = tb.F > 0 && g_options[CONDENSA_OPT_SELECT_PATH].load() != 1;
+    bool small = tb.F > 0 && cfg[CONDENSA_OPT_SELECT_PATH] != 1;
     if (per_tensor) { for (int t = 0; t < n_tensors && small; ++t) if (tb.td[t].n_struct > kSmallGroup) small = false; }
     else if (tb.F > kSmallGroup) small = false;
     if (tb.F > 0) {
         {
-            PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st);
+            PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st, cfg);
             // every structure one contiguous row (filters, neurons) of some length: staged, coalesced reads
             constexpr u64 kFewRowsMax = 32768;           // up to 1024 workgroups of kFewRows rows
             bool rows = tb.N / tb.F >= 16;
@@ -730,7 +909,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             else      hipLaunchKernelGGL(k_struct_sumsq, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             CONDENSA_LAUNCH_CHECK();
         }
-        PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
+        PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
         if (small) {
             hipLaunchKernelGGL(k_struct_small, dim3(L.n_slots), dim3(kSmallThreads), 0, st, a, structure_mask_dev,
                                keep_idx_dev, results_dev);
@@ -767,7 +946,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             CONDENSA_LAUNCH_CHECK();
         }
         if ((theta || mask) && tb.n_chunks > 0) {
-            PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+            PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
             if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
             else     hipLaunchKernelGGL((k_struct_apply<false>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);
@@ -835,7 +1014,10 @@ static condensa_status structure_entry(StructKind kind, int op, const condensa_t
                                        float* const* theta, uint8_t* const* mask, double* sumsq_dev,
                                        float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                        condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
-                                       void* stream) {
+                                       void* stream, const condensa_config* config) {
+    Config cfg;
+    condensa_status rc = resolve_config(config, &cfg);
+    if (rc != CONDENSA_OK) return rc;
     if (results_dev == nullptr) return CONDENSA_ERR_NULL;
     if (scope != CONDENSA_SCOPE_GLOBAL && scope != CONDENSA_SCOPE_PER_TENSOR) return CONDENSA_ERR_ARG;
     if (!density_ok(density)) return CONDENSA_ERR_DENSITY;
@@ -845,13 +1027,14 @@ static condensa_status structure_entry(StructKind kind, int op, const condensa_t
         for (int i = 0; i < block_ndim; ++i)
             if (block[i] < 1) return CONDENSA_ERR_SHAPE;
     }
+    HostArena arena;
     Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    rc = build_tensor_table(tensors, n_tensors, &tb, arena);
     if (rc != CONDENSA_OK) return rc;
     rc = add_structure_geometry(tensors, n_tensors, kind, block, block_ndim, &tb);
     if (rc != CONDENSA_OK) return rc;
     return run_structure_prune(op, tb, n_tensors, density, scope, theta, mask, sumsq_dev, norms_dev, keep_idx_dev,
-                               structure_mask_dev, results_dev, workspace_dev, workspace_bytes, stream);
+                               structure_mask_dev, results_dev, workspace_dev, workspace_bytes, stream, cfg);
 }
 
 }  // namespace condensa
@@ -862,41 +1045,45 @@ condensa_status condensa_filter_prune(const condensa_tensor* tensors, int n_tens
                                       float* const* theta, uint8_t* const* mask, double* sumsq_dev,
                                       float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                       condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
-                                      void* stream) {
+                                      void* stream,
+                                      const condensa_config* config) {
     return structure_entry(kFilters, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope, theta,
                            mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
-                           workspace_bytes, stream);
+                           workspace_bytes, stream, config);
 }
 
 condensa_status condensa_neuron_prune(const condensa_tensor* tensors, int n_tensors, double density, int scope,
                                       float* const* theta, uint8_t* const* mask, double* sumsq_dev,
                                       float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                       condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
-                                      void* stream) {
+                                      void* stream,
+                                      const condensa_config* config) {
     return structure_entry(kNeurons, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope, theta,
                            mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
-                           workspace_bytes, stream);
+                           workspace_bytes, stream, config);
 }
 
 condensa_status condensa_structure_prune(const condensa_tensor* tensors, int n_tensors, double density, int scope,
                                          float* const* theta, uint8_t* const* mask, double* sumsq_dev,
                                          float* norms_dev, int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                          condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
-                                         void* stream) {
+                                         void* stream,
+                                      const condensa_config* config) {
     return structure_entry(kNeuronsAndFilters, CONDENSA_OP_FILTER_PRUNE, tensors, n_tensors, nullptr, 0, density, scope,
                            theta, mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev,
-                           workspace_dev, workspace_bytes, stream);
+                           workspace_dev, workspace_bytes, stream, config);
 }
 
 condensa_status condensa_block_prune(const condensa_tensor* tensors, int n_tensors, int block_h, int block_w,
                                      double density, int scope, float* const* theta, uint8_t* const* mask,
                                      double* sumsq_dev, float* norms_dev, int32_t* keep_idx_dev,
                                      uint8_t* structure_mask_dev, condensa_select* results_dev,
-                                     void* workspace_dev, size_t workspace_bytes, void* stream) {
+                                     void* workspace_dev, size_t workspace_bytes, void* stream,
+                                      const condensa_config* config) {
     const int32_t block[2] = {block_h, block_w};
     return structure_entry(kBlocks2D, CONDENSA_OP_BLOCK_PRUNE, tensors, n_tensors, block, 2, density, scope, theta,
                            mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev, workspace_dev,
-                           workspace_bytes, stream);
+                           workspace_bytes, stream, config);
 }
 
 condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_tensors, const int32_t* block_shape,
@@ -904,10 +1091,11 @@ condensa_status condensa_block_prune_nd(const condensa_tensor* tensors, int n_te
                                         uint8_t* const* mask, double* sumsq_dev, float* norms_dev,
                                         int32_t* keep_idx_dev, uint8_t* structure_mask_dev,
                                         condensa_select* results_dev, void* workspace_dev, size_t workspace_bytes,
-                                        void* stream) {
+                                        void* stream,
+                                      const condensa_config* config) {
     return structure_entry(kBlocksND, CONDENSA_OP_BLOCK_PRUNE, tensors, n_tensors, block_shape, block_ndim, density,
                            scope, theta, mask, sumsq_dev, norms_dev, keep_idx_dev, structure_mask_dev, results_dev,
-                           workspace_dev, workspace_bytes, stream);
+                           workspace_dev, workspace_bytes, stream, config);
 }
 
 }  // extern "C"
@@ -1050,16 +1238,21 @@ condensa_status condensa_profile_reset(void) {
 condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tensors, const float* const* grad_loss,
                                      const float* const* theta, const float* const* lambda,
                                      float* const* momentum_buf, float mu, float lr, float momentum,
-                                     void* workspace_dev, size_t workspace_bytes, void* stream) {
+                                     void* workspace_dev, size_t workspace_bytes, void* stream,
+                                     const condensa_config* config) {
+    Config cfg;
+    condensa_status rc = resolve_config(config, &cfg);
+    if (rc != CONDENSA_OK) return rc;
     if (n_tensors > 0 && (!grad_loss || !theta || !lambda || !momentum_buf)) return CONDENSA_ERR_NULL;
     if (!(mu >= 0.0f) || !std::isfinite(mu) || !std::isfinite(lr) || !std::isfinite(momentum)) return CONDENSA_ERR_DENSITY;
+    HostArena arena;
     Tables tb;
-    condensa_status rc = build_tensor_table(tensors, n_tensors, &tb);
+    rc = build_tensor_table(tensors, n_tensors, &tb, arena);
     if (rc != CONDENSA_OK) return rc;
-    const Layout L = make_layout(CONDENSA_OP_LC_SGD_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL);
-    rc = check_workspace(workspace_dev, workspace_bytes, L);
-    if (rc != CONDENSA_OK) return rc;
+    const Layout L = make_layout(CONDENSA_OP_LC_SGD_STEP, tb.N, 0, n_tensors, 1, CONDENSA_SCOPE_GLOBAL, cfg);
     std::vector<OutDesc> out(static_cast<size_t>(n_tensors > 0 ? n_tensors : 1), OutDesc{});
+    std::vector<ByteRange> ranges;
+    ranges.reserve(static_cast<size_t>(n_tensors) * 5 + 1);
     bool vec = tb.vec;
     for (int t = 0; t < n_tensors; ++t) {
         TensorDesc& d = tb.td[t];
@@ -1069,15 +1262,18 @@ condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tenso
         d.lam = lambda[t];
         d.lam_out = momentum_buf[t];
         out[t].theta = const_cast<float*>(theta[t]);
-        const void* ptrs[5] = {d.w, d.grad, d.lam, d.lam_out, out[t].theta};
+        const void* ptrs[5] = {d.w, d.lam_out, d.grad, d.lam, out[t].theta};
         for (int i = 0; i < 5; ++i) {
             if (!aligned16(ptrs[i])) vec = false;
-            for (int j = i + 1; j < 5; ++j)
-                if (ptrs[i] == ptrs[j]) return CONDENSA_ERR_ARG;       // five distinct buffers
+            ranges.push_back(byte_range(ptrs[i], d.n * 4, i < 2));     // the weights and the momentum buffer are written
         }
     }
+    ranges.push_back(byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true));
+    if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
+    rc = check_workspace(workspace_dev, workspace_bytes, L);
+    if (rc != CONDENSA_OK) return rc;
     std::vector<char> up(L.upload_bytes, 0);
-    std::memcpy(up.data() + L.td, tb.td.data(), tb.td.size() * sizeof(TensorDesc));
+    std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
@@ -1094,7 +1290,7 @@ condensa_status condensa_lc_sgd_step(const condensa_tensor* tensors, int n_tenso
     a.N = tb.N;
     a.n_tensors = n_tensors;
     a.mu = mu;
-    PhaseTimer timer(CONDENSA_PHASE_APPLY, st);
+    PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
     const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
     const unsigned grid = static_cast<unsigned>(tb.n_chunks * (kChunk / 256));
     if (vec) hipLaunchKernelGGL((k_lc_sgd<true>), dim3(grid), dim3(64), 0, st, a, od, lr, momentum);
@@ -1124,7 +1320,12 @@ condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim
     if (total > kMaxElems) return CONDENSA_ERR_SIZE;
     if (total == 0) return CONDENSA_OK;
     if (w_dev == nullptr || out_dev == nullptr) return CONDENSA_ERR_NULL;
-    if (static_cast<const void*>(w_dev) == static_cast<const void*>(out_dev)) return CONDENSA_ERR_ARG;
+    {
+        ByteRange r[4] = {byte_range(w_dev, c_out * c_in * ksize * 4, false), byte_range(out_dev, total * 4, true),
+                          byte_range(keep_out_dev, keep_out_dev ? n_out * 4 : 0, false),
+                          byte_range(keep_in_dev, keep_in_dev ? n_in * 4 : 0, false)};
+        if (ranges_conflict(r, 4)) return CONDENSA_ERR_ARG;
+    }
     u64 blocks = (total + kBlock - 1) / kBlock;
     if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(k_thin, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
@@ -1136,19 +1337,15 @@ condensa_status condensa_thin(const float* w_dev, const int64_t* shape, int ndim
 
 condensa_status condensa_set_option(int option, int64_t value) {
     if (option < 0 || option >= CONDENSA_OPT_COUNT) return CONDENSA_ERR_ARG;
-    if (value < 0) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_SELECT_PATH && value > 2) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_SAMPLE_LOG2 && value != 0 && (value < 10 || value > 26)) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_CAND_SHIFT && value > 30) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_PROFILE && value >= (1 << CONDENSA_PHASE_COUNT)) return CONDENSA_ERR_ARG;
-    if (option == CONDENSA_OPT_APPLY_THREADS && value != 0 && value != 64 && value != 128 && value != 256) return CONDENSA_ERR_ARG;
-    g_options[option].store(value);
+    return set_default_option(option, value);
     return CONDENSA_OK;
 }
 
 int64_t condensa_get_option(int option) {
     if (option < 0 || option >= CONDENSA_OPT_COUNT) return -1;
-    return g_options[option].load();
+    Config c;
+    resolve_config(nullptr, &c);
+    return c[option];
 }
 
 const char* condensa_status_string(condensa_status s) {

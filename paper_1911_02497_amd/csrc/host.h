@@ -1,8 +1,9 @@
-// Host-side plumbing shared by the entry points: status bookkeeping, option store, the pinned
-// staging ring that carries the small per-call tables to the device, workspace carving.
+// Host-side plumbing shared by the entry points: status bookkeeping, per-call configuration, the pinned
+// staging ring that carries the small per-call tables to the device, buffer-overlap checks, workspace carving.
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstring>
@@ -15,7 +16,15 @@
 namespace condensa {
 
 extern std::atomic<int> g_last_hip_error;
-extern std::atomic<int64_t> g_options[CONDENSA_OPT_COUNT];
+
+// The knobs of one call, resolved once at the entry point: the caller's condensa_config, or the
+// process-wide defaults when it passes NULL.  Everything below the entry point reads this copy only.
+struct Config {
+    int64_t v[CONDENSA_OPT_COUNT];
+    int64_t operator[](int option) const { return v[option]; }
+};
+condensa_status resolve_config(const condensa_config* c, Config* out);   // CONDENSA_ERR_ARG for invalid values
+condensa_status set_default_option(int option, int64_t value);
 
 #define CONDENSA_HIP(expr)                                                      \
     do {                                                                        \
@@ -48,15 +57,44 @@ inline bool density_ok(double d) { return d >= 0.0 && d <= 1.0; }   // false for
 // unless all ring slots are still in flight.
 condensa_status stage_upload(void* dst_dev, const void* src_host, size_t bytes, hipStream_t stream);
 
-// Phase timing: records an event pair around the launches made while the object lives.
+// Phase timing: records an event pair around the launches made while the object lives, when the call's
+// profile mask asks for that phase.  The pair belongs to the object until both events are recorded;
+// only then is it handed to the list that condensa_profile_read drains.
 class PhaseTimer {
 public:
-    PhaseTimer(int phase, hipStream_t stream);
+    PhaseTimer(int phase, hipStream_t stream, const Config& cfg);
     ~PhaseTimer();
+    PhaseTimer(const PhaseTimer&) = delete;
+    PhaseTimer& operator=(const PhaseTimer&) = delete;
 private:
-    int slot_ = -1;
+    hipEvent_t a_ = nullptr, b_ = nullptr;
+    int phase_;
     hipStream_t stream_;
 };
+
+// Byte ranges of the buffers of one call.  A call is rejected when an output overlaps any other range.
+// An input that the call also writes in place (theta == w, lambda updated in place) is entered once, as
+// an output.
+struct ByteRange {
+    uintptr_t begin, end;
+    bool written;
+};
+inline ByteRange byte_range(const void* p, u64 bytes, bool written) {
+    const uintptr_t b = reinterpret_cast<uintptr_t>(p);
+    return ByteRange{b, b + static_cast<uintptr_t>(p ? bytes : 0), written};
+}
+// Sorts `r` by start address; true when some written range overlaps another range.
+inline bool ranges_conflict(ByteRange* r, size_t n) {
+    std::sort(r, r + n, [](const ByteRange& x, const ByteRange& y) { return x.begin < y.begin; });
+    uintptr_t end_any = 0, end_written = 0;          // furthest end among the ranges seen so far
+    for (size_t i = 0; i < n; ++i) {
+        if (r[i].begin == r[i].end) continue;        // empty
+        if (r[i].written ? r[i].begin < end_any : r[i].begin < end_written) return true;
+        if (r[i].end > end_any) end_any = r[i].end;
+        if (r[i].written && r[i].end > end_written) end_written = r[i].end;
+    }
+    return false;
+}
 
 // Element count of a tensor; false if the descriptor is malformed.
 inline bool tensor_elems(const condensa_tensor& t, u64* n) {
@@ -88,6 +126,7 @@ struct Layout {
     int n_groups = 1, n_slots = 1;
 };
 
-Layout make_layout(int op, u64 total_elems, u64 n_structures, int n_tensors, int n_densities, int scope);
+Layout make_layout(int op, u64 total_elems, u64 n_structures, int n_tensors, int n_densities, int scope,
+                   const Config& cfg, bool no_window = false);
 
 }  // namespace condensa

@@ -704,7 +704,7 @@ constexpr int kFusedQuadsLC = 1, kFusedQuadsPrune = 4;
 
 template <bool LC, bool VEC>
 static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st,
-                                          const FusedRequest* fused) {
+                                          const Config& cfg, const FusedRequest* fused) {
     if (a.n_chunks == 0) return CONDENSA_OK;
     char* base = static_cast<char*>(ws);
     WindowArgs w{};
@@ -730,15 +730,14 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     w.sorted = reinterpret_cast<SortedWindows*>(base + L.sorted_windows);
     w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
-    const int64_t m = g_options[CONDENSA_OPT_WINDOW_MARGIN].load();
-    w.margin16 = static_cast<int>(m);
+    w.margin16 = static_cast<int>(cfg[CONDENSA_OPT_WINDOW_MARGIN]);
     w.tie_list = reinterpret_cast<u64*>(base + L.sample);        // the sample is dead once its ranking is done
     w.tie_cap = L.sample_cap / 2;
     u64* hist_main = a.histx;                                    // [J]
     u64* hist_aux = a.histx + static_cast<u64>(a.J) * kBins;     // [2J]
     condensa_status rc;
     {
-        PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st);
+        PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
         hipLaunchKernelGGL((k_sample<LC, VEC>), dim3(static_cast<unsigned>((w.n_units + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_window_ranks, dim3(1), dim3(kBlock), 0, st, a, w);
@@ -751,7 +750,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         if (rc != CONDENSA_OK) return rc;
     }
     {
-        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st);
+        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st, cfg);
         const dim3 fg(static_cast<unsigned>(sweep_groups));
         if (fuse && LC && fused->pq) {
             if (VEC && fused->vec_out) hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
@@ -768,7 +767,7 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         }
         CONDENSA_LAUNCH_CHECK();
     }
-    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st);
+    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
     hipLaunchKernelGGL(k_window_check, dim3(1), dim3(kBlock), 0, st, a, w);
     CONDENSA_LAUNCH_CHECK();
     {

@@ -6,6 +6,30 @@ import paper_1911_02497_amd as P
 
 DEV = "cuda:0"
 
+# The forms of the selection that every element-pruning and L-C case runs through, as per-call
+# configurations (condensa_config fields): nothing process-wide is touched by the tests.
+FORMS = {
+    "radix": {"select_path": 1},
+    "window": {"select_path": 2},
+    "window_narrow": {"select_path": 2, "window_margin": 0},
+    "window_two_sweeps": {"select_path": 2, "fused_sweep": 1},
+}
+
+
+class Form:
+    """Configuration of the running test case; the fixtures of the test modules set and clear it."""
+    config = None
+
+
+def with_form(fn, **defaults):
+    """The binding call ``fn`` with the running case's configuration passed as its ``config`` argument."""
+    def call(*a, **k):
+        k.setdefault("config", Form.config)
+        for name, value in defaults.items():
+            k.setdefault(name, value)
+        return fn(*a, **k)
+    return call
+
 
 def up(arrs):
     return [torch.from_numpy(np.ascontiguousarray(a)).to(DEV) for a in arrs]

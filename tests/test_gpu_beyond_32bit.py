@@ -77,7 +77,8 @@ def _check_prune_properties(ws, theta, mask, rec, k, what):
 
 # (selection path, two sweeps, window margin); a margin of zero makes the sampled window miss, so that the
 # one-sweep call ends in the radix levels and the gated full apply
-FORMS = {"one_sweep": (2, 0, None), "two_sweeps": (2, 1, None), "radix": (1, 0, None), "window_missed": (2, 0, 0)}
+FORMS = {"one_sweep": {"select_path": 2}, "two_sweeps": {"select_path": 2, "fused_sweep": 1},
+         "radix": {"select_path": 1}, "window_missed": {"select_path": 2, "window_margin": 0}}
 
 
 @pytest.mark.parametrize("form", sorted(FORMS))
@@ -85,13 +86,10 @@ def test_global_prune_of_more_than_2_32_weights(big_weights, form):
     ws = big_weights
     N = N_EACH * N_TENSORS
     assert N > (1 << 32)
-    path, two, margin = FORMS[form]
-    P.condensa_set_option(P.OPT_SELECT_PATH, path)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT if margin is None else margin)
+    cfg = FORMS[form]
     try:
         density = 0.1
-        res = P.condensa_prune(ws, [density])
+        res = P.condensa_prune(ws, [density], config=cfg)
         torch.cuda.synchronize()
         rec = P.select_records(res["results"])[0]
         assert rec["path"] in {"radix": (1,), "window_missed": (2, 3)}.get(form, (2,)), rec
@@ -111,7 +109,7 @@ def test_global_prune_of_more_than_2_32_weights(big_weights, form):
             seg[pos] = sign * T
         try:
             k2 = rec["n_gt"] + 1500
-            res = P.condensa_prune(ws, [k2 / N])
+            res = P.condensa_prune(ws, [k2 / N], config=cfg)
             torch.cuda.synchronize()
             rec2 = P.select_records(res["results"])[0]
             assert rec2["threshold_key"] == rec["threshold_key"] and rec2["n_tie"] == rec["n_tie"] + 2000, (rec, rec2)
@@ -122,9 +120,6 @@ def test_global_prune_of_more_than_2_32_weights(big_weights, form):
             for t, lo, pos, old in saved:
                 ws[t][lo:lo + (1 << 20)][pos] = old
     finally:
-        P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-        P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
-        P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
         _free()
 
 
@@ -181,7 +176,7 @@ def test_filter_prune_of_one_tensor_with_more_than_2_32_elements():
     w[4000] = w[100]                                  # two equal aggregates
     s_ref = torch.cat([w[r:r + 512].double().pow(2).sum(1) for r in range(0, rows, 512)])
     k = int(round(0.3 * rows))
-    res = P.condensa_filter_prune([w.view(rows, cols, 1, 1)], 0.3)
+    res = P.condensa_filter_prune([w.view(rows, cols, 1, 1)], 0.3, fill_keep_idx=True)
     torch.cuda.synchronize()
     _check_structure_result(res, w.view(rows, cols, 1, 1), s_ref, lambda sm: sm[:, None, None, None].expand(rows, cols, 1, 1), k,
                             "filters")
@@ -207,7 +202,7 @@ def test_block_prune_of_one_matrix_with_more_than_2_32_elements():
     del parts
     F = gr * gc_
     k = int(round(0.25 * F))
-    res = P.condensa_block_prune([w], b, b, 0.25)
+    res = P.condensa_block_prune([w], b, b, 0.25, fill_keep_idx=True)
     torch.cuda.synchronize()
 
     def expand(sm):

@@ -77,6 +77,24 @@ def test_lc_step_on_the_large_model_workload():
     if rec["n_tie_kept"] == rec["n_tie"]:
         assert tie_end == N
 
+    # The benchmark's exact output set and launch configuration: no mask, every output and the workspace
+    # preallocated and passed in.  It must reproduce the outputs just verified, bit for bit.
+    outputs = {"theta": [torch.empty_like(t) for t in w_dev], "grad": [torch.empty_like(t) for t in w_dev],
+               "lambda": [torch.empty_like(t) for t in w_dev],
+               "results": torch.zeros((1, 8), dtype=torch.int64, device=dev)}
+    ws_bytes = P.condensa_workspace_bytes(P.binding.OP_LC_STEP, N, 0, T, 1, P.SCOPE_GLOBAL)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    for _ in range(2):                                   # the second step reuses the workspace the first one left
+        res2 = P.condensa_lc_step(w_dev, l_dev, mu, d, outputs=outputs, mask=False, workspace=workspace)
+        torch.cuda.synchronize()
+        assert res2["mask"] is None
+        rec2 = P.select_records(res2["results"])[0]
+        assert rec2 == rec, (rec2, rec)
+        for name in ("theta", "lambda", "grad"):
+            for t in range(T):
+                assert res2[name][t].data_ptr() == outputs[name][t].data_ptr()
+                assert torch.equal(res2[name][t].view(torch.int32), res[name][t].view(torch.int32)), f"{name}, tensor {t} (no mask)"
+
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("density", [0.003, 0.1, 0.97])
@@ -95,10 +113,9 @@ def test_every_selection_form_gives_the_same_bits_at_full_size(density):
     ref = ref_rec = None
     try:
         for name, (path, two) in {"one_sweep": (2, 0), "two_sweeps": (2, 1), "radix": (1, 0)}.items():
-            P.condensa_set_option(P.OPT_SELECT_PATH, path)
-            P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
-            r = P.condensa_lc_step(ws, ls, 1e-3, density)
-            p = P.condensa_prune(ws, [density])
+            cfg = {"select_path": path, "fused_sweep": two}
+            r = P.condensa_lc_step(ws, ls, 1e-3, density, config=cfg)
+            p = P.condensa_prune(ws, [density], config=cfg)
             torch.cuda.synchronize()
             cur = (r["theta"], r["lambda"], r["grad"], r["mask"], p["theta"][0], p["mask"][0])
             rec = (P.select_records(r["results"])[0], P.select_records(p["results"])[0])
@@ -113,7 +130,5 @@ def test_every_selection_form_gives_the_same_bits_at_full_size(density):
                     assert torch.equal(as_bits(a), as_bits(b)), f"{name}: output {which} of tensor {t} differs"
             del r, p, cur
     finally:
-        P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-        P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
         del ref, ws, ls
         torch.cuda.empty_cache()

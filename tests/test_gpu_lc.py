@@ -5,9 +5,12 @@ import torch
 
 import oracle
 import paper_1911_02497_amd as P
-from gpu_util import DEV, assert_bits_equal, assert_select_equal, up
+from gpu_util import assert_bits_equal, assert_select_equal, DEV, Form, FORMS, up, with_form
 
 pytestmark = pytest.mark.gpu
+
+lc_step = with_form(P.condensa_lc_step)
+lc_step_pq = with_form(P.condensa_lc_step_pq)
 
 
 @pytest.fixture(params=["radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
@@ -15,17 +18,13 @@ def select_path(request):
     """Every case runs through the radix levels, the sampled window (selection and apply in one sweep
     where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
     regularly misses and falls back, and the window with separate selection and apply sweeps."""
-    P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else P.WINDOW_MARGIN_DEFAULT)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if request.param == "window_two_sweeps" else 0)
+    Form.config = FORMS[request.param]
     yield request.param
-    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+    Form.config = None
 
 
 def _check(ws, ls, mu, d, what="", **kw):
-    res = P.condensa_lc_step(up(ws), up(ls), mu, d, **kw)
+    res = lc_step(up(ws), up(ls), mu, d, **kw)
     torch.cuda.synchronize()
     ora = oracle.lc_step(ws, ls, mu, d)
     assert_select_equal(P.select_records(res["results"])[0], ora["select"], what)
@@ -73,7 +72,7 @@ def test_in_place_multiplier_update_and_optional_outputs():
     ws, ls = _gauss([(10000,), (333,)], 6, 0.01), _gauss([(10000,), (333,)], 7, 0.01)
     ora = oracle.lc_step(ws, ls, 1e-3, 0.2)
     dl = up(ls)
-    res = P.condensa_lc_step(up(ws), dl, 1e-3, 0.2, in_place=True, theta=False, mask=False)
+    res = lc_step(up(ws), dl, 1e-3, 0.2, in_place=True, theta=False, mask=False)
     torch.cuda.synchronize()
     for t in range(2):
         assert_bits_equal(dl[t], ora["lambda"][t], "in-place lambda")
@@ -84,10 +83,10 @@ def test_errors():
     w, l = torch.ones(8, device=DEV), torch.zeros(8, device=DEV)
     for mu in (0.0, -1.0, float("inf"), float("nan")):
         with pytest.raises(P.CondensaError) as e:
-            P.condensa_lc_step([w], [l], mu, 0.5)
+            lc_step([w], [l], mu, 0.5)
         assert e.value.code == -3
     with pytest.raises(P.CondensaError) as e:          # theta must not alias w
-        P.condensa_lc_step([w], [l], 1e-3, 0.5, outputs={"theta": [w]})
+        lc_step([w], [l], 1e-3, 0.5, outputs={"theta": [w]})
     assert e.value.code == -6
 
 
@@ -98,7 +97,7 @@ def test_pq_step_against_the_oracle():
     ws, ls = _gauss(shapes, 11, 0.01), _gauss(shapes, 12, 0.01)
     ws[1][0, :8] = np.float32(1e-9)                     # tiny values: underflow to zero in binary16 if kept
     for mu, d in ((1e-3, 0.1), (1e-3, 1.0), (50.0, 0.5)):
-        res = P.condensa_lc_step_pq(up(ws), up(ls), mu, d)
+        res = lc_step_pq(up(ws), up(ls), mu, d)
         torch.cuda.synchronize()
         ora = oracle.lc_step_pq(ws, ls, mu, d)
         assert_select_equal(P.select_records(res["results"])[0], ora["select"], f"mu={mu} d={d}")
@@ -156,7 +155,7 @@ def test_sgd_step_with_penalty_against_the_oracle():
             assert_bits_equal(dw[t], w_ora[t], f"w {t}")
             assert_bits_equal(db[t], b_ora[t], f"buf {t}")
     # the fused update equals the unfused one: penalty gradient from condensa_lc_step, then a plain momentum step
-    res = P.condensa_lc_step(up(ws), up(ls), 1e-3, 0.2)
+    res = lc_step(up(ws), up(ls), 1e-3, 0.2)
     torch.cuda.synchronize()
     theta = [t.cpu().numpy() for t in res["theta"]]
     lam2 = [t.cpu().numpy() for t in res["lambda"]]
@@ -185,15 +184,43 @@ def test_misaligned_tensors_and_partial_outputs():
 
     dw, dl = [shifted(a) for a in ws], [shifted(a) for a in ls]
     out_l = [shifted(np.zeros_like(a)) for a in ls]
-    res = P.condensa_lc_step(dw, dl, 1e-3, 0.25, lambda_out=out_l, grad=False)
+    res = lc_step(dw, dl, 1e-3, 0.25, lambda_out=out_l, grad=False)
     torch.cuda.synchronize()
     assert res["grad"] is None
     for t in range(2):
         assert_bits_equal(res["theta"][t], ora["theta"][t], f"theta {t}")
         assert_bits_equal(out_l[t], ora["lambda"][t], f"lambda {t}")
         assert np.array_equal(res["mask"][t].cpu().numpy(), ora["mask"][t])
-    res = P.condensa_lc_step(up(ws), up(ls), 1e-3, 0.25, theta=False, mask=False)
+    res = lc_step(up(ws), up(ls), 1e-3, 0.25, theta=False, mask=False)
     torch.cuda.synchronize()
     for t in range(2):
         assert_bits_equal(res["lambda"][t], ora["lambda"][t], f"lambda only {t}")
         assert_bits_equal(res["grad"][t], ora["grad"][t], f"grad only {t}")
+
+
+def test_same_step_twice_and_other_launch_shapes_give_the_same_bits():
+    """Determinism of the L-C step: the same call twice, the apply sweep in workgroups of 64, 128 and 256
+    threads, separate sweeps instead of one, and other sample / candidate sizes (other grids and segment
+    counts) agree in every bit of theta, lambda', g, the mask and the record."""
+    rng = np.random.default_rng(78)
+    shapes = ((1200, 1024), (8192 * 30 + 5,), (128, 64, 3, 3))
+    ws = [(rng.standard_normal(s) * 0.01).astype(np.float32) for s in shapes]
+    ls = [(rng.standard_normal(s) * 0.01).astype(np.float32) for s in shapes]
+    dw, dl = up(ws), up(ls)
+    fields = ("n", "k", "n_gt", "n_tie_kept", "n_tie", "threshold_key", "tie_end")
+    ref = lc_step(dw, dl, 1e-3, 0.1)
+    torch.cuda.synchronize()
+    ref_rec = P.select_records(ref["results"])[0]
+    base = dict(Form.config)
+    variants = [base] + [dict(base, apply_threads=n, fused_sweep=1) for n in (64, 128, 256)] + \
+               [dict(base, sample_log2=16), dict(base, cand_shift=3), dict(base, select_path=1, apply_threads=256)]
+    for cfg in variants:
+        got = P.condensa_lc_step(dw, dl, 1e-3, 0.1, config=cfg)
+        torch.cuda.synchronize()
+        rec = P.select_records(got["results"])[0]
+        assert all(rec[f] == ref_rec[f] for f in fields), (cfg, rec, ref_rec)
+        for name in ("theta", "lambda", "grad"):
+            for t in range(len(ws)):
+                assert torch.equal(got[name][t].view(torch.int32), ref[name][t].view(torch.int32)), (cfg, name, t)
+        for t in range(len(ws)):
+            assert torch.equal(got["mask"][t], ref["mask"][t]), (cfg, t)

@@ -6,9 +6,11 @@ import torch
 import oracle
 import paper_1911_02497_amd as P
 import workloads
-from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
+from gpu_util import assert_bits_equal, assert_select_equal, check_prune_against_oracle, DEV, Form, FORMS, up, with_form
 
 pytestmark = pytest.mark.gpu
+
+prune = with_form(P.condensa_prune)
 
 
 @pytest.fixture(params=["radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
@@ -16,17 +18,13 @@ def select_path(request):
     """Every case runs through the radix levels, the sampled window (selection and apply in one sweep
     where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
     regularly misses and falls back, and the window with separate selection and apply sweeps."""
-    P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "radix" else 2)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, 0 if request.param == "window_narrow" else P.WINDOW_MARGIN_DEFAULT)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 1 if request.param == "window_two_sweeps" else 0)
+    Form.config = FORMS[request.param]
     yield request.param
-    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+    Form.config = None
 
 
 def _prune_both(arrs, densities, scope=P.SCOPE_GLOBAL, what="", **kw):
-    res = P.condensa_prune(up(arrs), densities, scope=scope, **kw)
+    res = prune(up(arrs), densities, scope=scope, **kw)
     torch.cuda.synchronize()
     ora = oracle.prune(arrs, densities, scope)
     check_prune_against_oracle(res, ora, scope, len(arrs), what)
@@ -87,19 +85,20 @@ def test_vgg19_shapes_ten_densities_one_call():
     assert sum(w.size for w in ws) == 20024000
     ds = workloads.search_densities()
     dev = up(ws)
-    res = P.condensa_prune(dev, ds, theta=False, mask=False)          # thresholds only
+    res = prune(dev, ds, theta=False, mask=False)          # thresholds only
     torch.cuda.synchronize()
     ora = oracle.prune(ws, ds)
     recs = P.select_records(res["results"])
     for j in range(len(ds)):
         assert_select_equal(recs[j], ora[j]["select"], f"density {j}")
-    # masks for three of the densities in one apply sweep
-    sub = [ds[0], ds[4], ds[9]]
-    res = P.condensa_prune(dev, sub, theta=False, mask=True)
+    # the masks of all ten densities from one call (one selection, one apply sweep writing ten masks)
+    res = prune(dev, ds, theta=False, mask=True)
     torch.cuda.synchronize()
-    for j, jj in enumerate((0, 4, 9)):
+    recs = P.select_records(res["results"])
+    for j in range(len(ds)):
+        assert_select_equal(recs[j], ora[j]["select"], f"density {j} (mask call)")
         for t in range(len(ws)):
-            assert np.array_equal(res["mask"][j][t].cpu().numpy(), ora[jj]["mask"][t])
+            assert np.array_equal(res["mask"][j][t].cpu().numpy(), ora[j]["mask"][t]), f"mask of density {j}, tensor {t}"
 
 
 def test_in_place_and_misaligned():
@@ -107,10 +106,10 @@ def test_in_place_and_misaligned():
     w = rng.standard_normal(30011).astype(np.float32)
     ora = oracle.prune([w], [0.3])[0]
     dw = torch.from_numpy(w).to(DEV)
-    res = P.condensa_prune([dw], [0.3], in_place=True)
+    res = prune([dw], [0.3], in_place=True)
     assert_bits_equal(dw, ora["theta"][0], "in place")
     big = torch.from_numpy(np.concatenate([[9.0], w]).astype(np.float32)).to(DEV)
-    res = P.condensa_prune([big[1:]], [0.3])
+    res = prune([big[1:]], [0.3])
     assert_bits_equal(res["theta"][0][0], ora["theta"][0], "misaligned input")
     assert np.array_equal(res["mask"][0][0].cpu().numpy(), ora["mask"][0])
 
@@ -119,16 +118,16 @@ def test_argument_errors_have_no_side_effects():
     w = torch.ones(16, device=DEV)
     for bad in (-0.1, 1.5, float("nan")):
         with pytest.raises(P.CondensaError) as e:
-            P.condensa_prune([w], [bad])
+            prune([w], [bad])
         assert e.value.code == -3
     with pytest.raises(P.CondensaError) as e:
-        P.condensa_prune([w], [0.5] * 17)
+        prune([w], [0.5] * 17)
     assert e.value.code == -2
     with pytest.raises(P.CondensaError) as e:
-        P.condensa_prune([w], [0.5], workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+        prune([w], [0.5], workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
     assert e.value.code == -5
     with pytest.raises(P.CondensaError) as e:
-        P.condensa_prune([w], [0.5], scope=7)
+        prune([w], [0.5], scope=7)
     assert e.value.code == -6
     assert torch.all(w == 1)
 
@@ -146,3 +145,29 @@ def test_few_distinct_values_far_apart(levels, n, select_path):
         res, _ = _prune_both([w[: n // 3], w[n // 3:]], [density], what=f"{levels} levels d={density}")
         if select_path in ("window", "window_two_sweeps") and levels == 256:
             assert P.select_records(res["results"])[0]["path"] == 2, "expected to resolve inside the window"
+
+
+def test_same_call_twice_and_other_launch_shapes_give_the_same_bits():
+    """Determinism: the result is a function of the inputs alone.  The same call twice, and calls whose
+    launches are shaped differently (sample size and candidate capacity change the grids, the segment counts
+    and the order in which candidates are appended), must agree in every output bit and record field."""
+    rng = np.random.default_rng(77)
+    ws = [(rng.standard_normal(s) * 0.02).astype(np.float32) for s in ((1500, 1111), (8192 * 40 + 17,), (64, 64, 3, 3))]
+    ws[1][::97] = np.float32(0.0337)                               # ties at a magnitude near the threshold of d = 0.1
+    dev = up(ws)
+    fields = ("n", "k", "n_gt", "n_tie_kept", "n_tie", "threshold_key", "tie_end")
+    ref = prune(dev, [0.1, 0.4], theta_f16=True)
+    torch.cuda.synchronize()
+    ref_rec = P.select_records(ref["results"])
+    variants = [dict(Form.config), dict(Form.config, sample_log2=16), dict(Form.config, cand_shift=2),
+                dict(Form.config, sample_log2=19, cand_shift=4)]
+    for cfg in variants:
+        got = P.condensa_prune(dev, [0.1, 0.4], theta_f16=True, config=cfg)
+        torch.cuda.synchronize()
+        rec = P.select_records(got["results"])
+        for j in range(2):
+            assert all(rec[j][f] == ref_rec[j][f] for f in fields), (cfg, rec[j], ref_rec[j])
+            for t in range(len(ws)):
+                assert torch.equal(got["theta"][j][t].view(torch.int32), ref["theta"][j][t].view(torch.int32)), (cfg, j, t)
+                assert torch.equal(got["theta_f16"][j][t], ref["theta_f16"][j][t]), (cfg, j, t)
+                assert torch.equal(got["mask"][j][t], ref["mask"][j][t]), (cfg, j, t)

@@ -6,23 +6,19 @@ import torch
 
 import oracle
 import paper_1911_02497_amd as P
-from gpu_util import assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
+from gpu_util import assert_bits_equal, assert_select_equal, check_prune_against_oracle, Form, FORMS, up, with_form
 
 pytestmark = pytest.mark.gpu
 
-FORMS = {"radix": (1, None, 0), "window": (2, None, 0), "window_narrow": (2, 0, 0), "window_two_sweeps": (2, None, 1)}
-
+prune = with_form(P.condensa_prune)
+lc_step = with_form(P.condensa_lc_step)
+lc_step_pq = with_form(P.condensa_lc_step_pq)
 
 @pytest.fixture(params=sorted(FORMS), autouse=True)
 def form(request):
-    path, margin, two = FORMS[request.param]
-    P.condensa_set_option(P.OPT_SELECT_PATH, path)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT if margin is None else margin)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, two)
+    Form.config = FORMS[request.param]
     yield request.param
-    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
-    P.condensa_set_option(P.OPT_WINDOW_MARGIN, P.WINDOW_MARGIN_DEFAULT)
-    P.condensa_set_option(P.OPT_FUSED_SWEEP, 0)
+    Form.config = None
 
 
 def _random_tensors(rng, big=False):
@@ -62,7 +58,7 @@ def test_prune_random(seed):
             for _ in range(int(rng.integers(1, 4)))]
     scope = P.SCOPE_PER_TENSOR if rng.random() < 0.3 else P.SCOPE_GLOBAL
     f16 = bool(rng.random() < 0.5)
-    res = P.condensa_prune(up(ws), dens, scope=scope, theta_f16=f16)
+    res = prune(up(ws), dens, scope=scope, theta_f16=f16)
     torch.cuda.synchronize()
     ora = oracle.prune(ws, dens, scope)
     check_prune_against_oracle(res, ora, scope, len(ws), f"seed {seed} dens {dens}")
@@ -105,12 +101,12 @@ def test_three_thousand_small_tensors(scope):
     ws = [np.asarray(rng.standard_normal(s) * 0.05, dtype=np.float32) for s in sizes]
     dev = up(ws)
     dens = [0.25, 0.9]
-    res = P.condensa_prune(dev, dens, scope=scope)
+    res = prune(dev, dens, scope=scope)
     torch.cuda.synchronize()
     check_prune_against_oracle(res, oracle.prune(ws, dens, scope), scope, len(ws), f"3000 tensors scope {scope}")
     if scope == P.SCOPE_GLOBAL:
         ls = [np.asarray(rng.standard_normal(w.shape) * 0.01, dtype=np.float32) for w in ws]
-        got = P.condensa_lc_step(dev, up(ls), 0.5, 0.3)
+        got = lc_step(dev, up(ls), 0.5, 0.3)
         torch.cuda.synchronize()
         ora = oracle.lc_step(ws, ls, 0.5, 0.3)
         assert_select_equal(P.select_records(got["results"])[0], ora["select"], "3000 tensors lc")

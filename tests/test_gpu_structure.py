@@ -6,18 +6,24 @@ import torch
 import oracle
 import paper_1911_02497_amd as P
 import workloads
-from gpu_util import DEV, assert_bits_equal, assert_select_equal, check_prune_against_oracle, up
+from gpu_util import assert_bits_equal, assert_select_equal, check_prune_against_oracle, DEV, Form, FORMS, up, with_form
 
 pytestmark = pytest.mark.gpu
+
+filter_prune = with_form(P.condensa_filter_prune, fill_keep_idx=True)
+block_prune = with_form(P.condensa_block_prune, fill_keep_idx=True)
+block_prune_nd = with_form(P.condensa_block_prune_nd, fill_keep_idx=True)
+neuron_prune = with_form(P.condensa_neuron_prune, fill_keep_idx=True)
+structure_prune = with_form(P.condensa_structure_prune, fill_keep_idx=True)
 
 
 @pytest.fixture(params=["auto", "launch_per_level"], autouse=True)
 def ranking_form(request):
     """Every case runs with the default choice (one workgroup per group ranks, masks and lists groups of up
     to 4 096 structures) and with the general form (one histogram and one scan launch per radix level)."""
-    P.condensa_set_option(P.OPT_SELECT_PATH, 1 if request.param == "launch_per_level" else 0)
+    Form.config = {"select_path": 1} if request.param == "launch_per_level" else None
     yield request.param
-    P.condensa_set_option(P.OPT_SELECT_PATH, 0)
+    Form.config = None
 
 
 def _compare(res, ora, scope, arrs, what):
@@ -43,7 +49,7 @@ def _compare(res, ora, scope, arrs, what):
 @pytest.mark.parametrize("scope,density", [(P.SCOPE_PER_TENSOR, 0.5), (P.SCOPE_GLOBAL, 0.3)])
 def test_resnet56_filter_prune(scope, density):
     convs = workloads.resnet56_cifar_convs()
-    res = P.condensa_filter_prune(up(convs), density, scope)
+    res = filter_prune(up(convs), density, scope)
     torch.cuda.synchronize()
     ora = oracle.filter_prune(convs, density, scope)
     _compare(res, ora, scope, convs, "resnet56")
@@ -59,7 +65,7 @@ def test_filter_prune_planted_ties_zero_filters_and_edge_densities():
     a[3] = a[17]; a[30] = -a[17]; b[5] = 0; b[100] = 0; b[299] = b[0]
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
         for d in (0.0, 0.01, 0.33, 0.5, 0.99, 1.0):
-            res = P.condensa_filter_prune(up([a, b, c]), d, scope)
+            res = filter_prune(up([a, b, c]), d, scope)
             torch.cuda.synchronize()
             _compare(res, oracle.filter_prune([a, b, c], d, scope), scope, [a, b, c], f"d={d} scope={scope}")
 
@@ -67,7 +73,7 @@ def test_filter_prune_planted_ties_zero_filters_and_edge_densities():
 def test_filter_prune_all_equal_filters():
     a = np.ones((20000, 2, 1, 1), np.float32)            # every aggregate ties; more than one structure chunk
     for d in (0.25, 0.7):
-        res = P.condensa_filter_prune(up([a]), d, P.SCOPE_GLOBAL)
+        res = filter_prune(up([a]), d, P.SCOPE_GLOBAL)
         torch.cuda.synchronize()
         _compare(res, oracle.filter_prune([a], d, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, [a], f"all equal d={d}")
 
@@ -80,7 +86,7 @@ def test_filter_prune_with_many_filters():
           rng.standard_normal((4000, 7, 1, 1)).astype(np.float32)]
     ts[1][77] = ts[1][4000]                              # equal aggregates far apart
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
-        res = P.condensa_filter_prune(up(ts), 0.45, scope)
+        res = filter_prune(up(ts), 0.45, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.filter_prune(ts, 0.45, scope), scope, ts, f"many filters scope={scope}")
 
@@ -88,7 +94,7 @@ def test_filter_prune_with_many_filters():
 @pytest.mark.parametrize("bh,bw", [(8, 8), (32, 32)])
 def test_transformer_block_prune_global(bh, bw):
     ws = workloads.transformer_base()
-    res = P.condensa_block_prune(up(ws), bh, bw, 0.25, P.SCOPE_GLOBAL)
+    res = block_prune(up(ws), bh, bw, 0.25, P.SCOPE_GLOBAL)
     torch.cuda.synchronize()
     ora = oracle.block_prune(ws, bh, bw, 0.25, P.SCOPE_GLOBAL)
     _compare(res, ora, P.SCOPE_GLOBAL, ws, f"transformer {bh}x{bw}")
@@ -102,12 +108,12 @@ def test_block_prune_small_shapes_scopes_and_ties():
     ms[3][:] = 0
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
         for d in (0.0, 0.4, 1.0):
-            res = P.condensa_block_prune(up(ms), 5, 5, d, scope)
+            res = block_prune(up(ms), 5, 5, d, scope)
             torch.cuda.synchronize()
             _compare(res, oracle.block_prune(ms, 5, 5, d, scope), scope, ms, f"5x5 d={d} scope={scope}")
     m = rng.standard_normal((6, 12)).astype(np.float32)
     for bh, bw in ((1, 12), (6, 1), (2, 3), (1, 1), (6, 12)):
-        res = P.condensa_block_prune(up([m]), bh, bw, 0.5, P.SCOPE_GLOBAL)
+        res = block_prune(up([m]), bh, bw, 0.5, P.SCOPE_GLOBAL)
         torch.cuda.synchronize()
         _compare(res, oracle.block_prune([m], bh, bw, 0.5, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, [m], f"{bh}x{bw}")
 
@@ -122,7 +128,7 @@ def test_exactly_tiled_blocks_of_width_4_8_16_32(bh, bw):
     ms = [rng.standard_normal(s).astype(np.float32) for s in shapes]
     ms[2][0:bh, 0:bw] = ms[2][bh:2 * bh, bw:2 * bw]       # exact tie between two blocks
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
-        res = P.condensa_block_prune(up(ms), bh, bw, 0.37, scope)
+        res = block_prune(up(ms), bh, bw, 0.37, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.block_prune(ms, bh, bw, 0.37, scope), scope, ms, f"{bh}x{bw} scope={scope}")
 
@@ -130,10 +136,10 @@ def test_exactly_tiled_blocks_of_width_4_8_16_32(bh, bw):
 def test_shape_errors():
     m = torch.ones((6, 10), device=DEV)
     with pytest.raises(P.CondensaError) as e:
-        P.condensa_block_prune([m], 4, 5, 0.5)
+        block_prune([m], 4, 5, 0.5)
     assert e.value.code == -4
     with pytest.raises(P.CondensaError) as e:
-        P.condensa_filter_prune([m], 0.5)
+        filter_prune([m], 0.5)
     assert e.value.code == -4
 
 
@@ -145,11 +151,11 @@ def test_lstm_shaped_block_size_5():
     ms = [(rng.standard_normal((2600, 650)) * 0.05).astype(np.float32) for _ in range(4)]
     dev = up(ms)
     for block in ((5, 5), (1, 5)):
-        res = P.condensa_block_prune_nd(dev, block, 0.4, P.SCOPE_GLOBAL)
+        res = block_prune_nd(dev, block, 0.4, P.SCOPE_GLOBAL)
         torch.cuda.synchronize()
         _compare(res, oracle.block_prune_nd(ms, block, 0.4, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, ms, f"lstm {block}")
-    both = P.condensa_block_prune(dev, 5, 5, 0.4, P.SCOPE_GLOBAL)
-    nd = P.condensa_block_prune_nd(dev, (5, 5), 0.4, P.SCOPE_GLOBAL)
+    both = block_prune(dev, 5, 5, 0.4, P.SCOPE_GLOBAL)
+    nd = block_prune_nd(dev, (5, 5), 0.4, P.SCOPE_GLOBAL)
     torch.cuda.synchronize()
     assert torch.equal(both["structure_mask"], nd["structure_mask"])
 
@@ -170,7 +176,7 @@ def test_nd_and_ragged_blocks(shapes, block):
         ts[0].reshape(-1)[:50] = 0.0
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
         for d in (0.0, 0.3, 1.0):
-            res = P.condensa_block_prune_nd(up(ts), block, d, scope)
+            res = block_prune_nd(up(ts), block, d, scope)
             torch.cuda.synchronize()
             _compare(res, oracle.block_prune_nd(ts, block, d, scope), scope, ts, f"{shapes} {block} d={d} scope={scope}")
 
@@ -180,11 +186,11 @@ def test_neuron_prune_and_structure_prune():
     lin = [rng.standard_normal(s).astype(np.float32) for s in ((10, 512), (300, 77), (4096, 25))]
     lin[1][7] = lin[1][3]
     for scope in (P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR):
-        res = P.condensa_neuron_prune(up(lin), 0.5, scope)
+        res = neuron_prune(up(lin), 0.5, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.neuron_prune(lin, 0.5, scope), scope, lin, f"neurons scope={scope}")
     vgg = workloads.vgg19_cifar()                      # 16 convs + the [10, 512] classifier
-    res = P.condensa_structure_prune(up(vgg), 0.21, P.SCOPE_GLOBAL)    # sparsity 0.79 (Table 2, filter pruning of VGG19)
+    res = structure_prune(up(vgg), 0.21, P.SCOPE_GLOBAL)    # sparsity 0.79 (Table 2, filter pruning of VGG19)
     torch.cuda.synchronize()
     _compare(res, oracle.structure_prune(vgg, 0.21, P.SCOPE_GLOBAL), P.SCOPE_GLOBAL, vgg, "vgg structures")
 
@@ -192,8 +198,8 @@ def test_neuron_prune_and_structure_prune():
 def test_new_structure_entry_points_reject_bad_shapes():
     m = torch.ones((6, 10), device=DEV)
     c = torch.ones((4, 3, 3, 3), device=DEV)
-    for call in (lambda: P.condensa_neuron_prune([c], 0.5), lambda: P.condensa_structure_prune([torch.ones(5, device=DEV)], 0.5),
-                 lambda: P.condensa_block_prune_nd([m], (2, 2, 2), 0.5), lambda: P.condensa_block_prune_nd([m], (0, 2), 0.5)):
+    for call in (lambda: neuron_prune([c], 0.5), lambda: structure_prune([torch.ones(5, device=DEV)], 0.5),
+                 lambda: block_prune_nd([m], (2, 2, 2), 0.5), lambda: block_prune_nd([m], (0, 2), 0.5)):
         with pytest.raises(P.CondensaError) as e:
             call()
         assert e.value.code == -4
@@ -205,9 +211,9 @@ def test_marshalled_table_and_reused_outputs_give_the_same_results():
     arrs = workloads.resnet56_cifar_convs()
     table = P.tensor_table(up(arrs))
     ora = oracle.filter_prune(arrs, 0.3, P.SCOPE_GLOBAL)
-    first = P.condensa_filter_prune(table, 0.3, P.SCOPE_GLOBAL)
+    first = filter_prune(table, 0.3, P.SCOPE_GLOBAL)
     for density in (0.7, 0.3):                    # a different density in between overwrites every buffer
-        res = P.condensa_filter_prune(table, density, P.SCOPE_GLOBAL, outputs=first)
+        res = filter_prune(table, density, P.SCOPE_GLOBAL, outputs=first)
     torch.cuda.synchronize()
     assert res["theta"][0].data_ptr() == first["theta"][0].data_ptr()
     _compare(res, ora, P.SCOPE_GLOBAL, arrs, "reused outputs")
@@ -234,7 +240,7 @@ def test_random_structure_cases(seed):
             shape = tuple(int(rng.integers(1, 70 if nd <= 2 else 14)) for _ in range(nd))
             a = rng.integers(-2, 3, shape).astype(np.float32) if rng.random() < 0.4 else rng.standard_normal(shape).astype(np.float32)
             arrs.append(a)
-        res = P.condensa_block_prune_nd(up(arrs), block, density, scope)
+        res = block_prune_nd(up(arrs), block, density, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.block_prune_nd(arrs, block, density, scope), scope, arrs, f"seed {seed} block {block}")
     else:
@@ -249,6 +255,6 @@ def test_random_structure_cases(seed):
                 a[1] = a[0]
                 a[2] = 0
             arrs.append(a)
-        res = P.condensa_structure_prune(up(arrs), density, scope)
+        res = structure_prune(up(arrs), density, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.structure_prune(arrs, density, scope), scope, arrs, f"seed {seed} structures")

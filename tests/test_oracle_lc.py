@@ -181,3 +181,42 @@ def test_penalty_vanishes_at_the_constraint_and_mu_schedule():
     assert oracle.mu_schedule(1e-3, 1.1, 0) == float(np.float32(1e-3))
     assert abs(oracle.mu_schedule(1e-3, 1.1, 49) - 1e-3 * 1.1 ** 49) < 1e-9
     assert oracle.mu_schedule(1e-3, 1.1, 10) < oracle.mu_schedule(1e-3, 1.1, 11)
+
+
+def _fraction_to_binary32(q):
+    """The binary32 value nearest to the positive rational q (ties to even), in exact integer arithmetic:
+    no floating-point operation takes part, so nothing can round twice."""
+    from fractions import Fraction
+    assert q > 0
+    e = 0
+    while q / Fraction(2) ** e >= 1 << 24:
+        e += 1
+    while q / Fraction(2) ** e < 1 << 23:
+        e -= 1
+    assert e >= -149, "normal range only"
+    scaled = q / Fraction(2) ** e                       # in [2^23, 2^24)
+    m = scaled.numerator // scaled.denominator
+    rest = scaled - m
+    if rest > Fraction(1, 2) or (rest == Fraction(1, 2) and m % 2 == 1):
+        m += 1
+    return float(Fraction(m) * Fraction(2) ** e)        # exact: m has at most 25 bits
+
+
+def test_mu_schedule_against_exact_rational_arithmetic():
+    """mu_j = mu_0 a^j (L-C Optimizer Settings: mu_0 = 1e-3, a = 1.1).  The product of the two binary64
+    arguments is formed as an exact fraction and rounded once to binary32; the oracle's binary64 evaluation
+    and the library's host function must land on that value.  A wrong exponent (a^(j+1), a^(2j)), a swapped
+    argument or a premature rounding to binary32 misses it by many units in the last place."""
+    from fractions import Fraction
+    import paper_1911_02497_amd as P
+    for mu0, a in ((1e-3, 1.1), (5e-4, 1.25), (1e-3, 1.0), (0.37, 0.9)):
+        for j in (0, 1, 7, 29, 49):
+            want = _fraction_to_binary32(Fraction(mu0) * Fraction(a) ** j)
+            assert oracle.mu_schedule(mu0, a, j) == want, (mu0, a, j)
+            assert P.condensa_mu_schedule(mu0, a, j) == want, (mu0, a, j)      # host code of the library: no GPU needed
+    # the values themselves, written out from mu_0 = 1e-3, a = 1.1: 1e-3 * 1.1^7 = 1.9487171e-3, 1.1^49 = 106.718957...
+    assert abs(oracle.mu_schedule(1e-3, 1.1, 7) - 1.9487171e-3) < 1e-10
+    assert abs(oracle.mu_schedule(1e-3, 1.1, 49) - 0.106718957) < 1e-8
+    assert _fraction_to_binary32(Fraction(1, 3)) == float(np.float32(1.0) / np.float32(3.0))
+    assert _fraction_to_binary32(Fraction(16777217)) == 16777216.0                # a tie goes to the even neighbour
+    assert _fraction_to_binary32(Fraction(16777219)) == 16777220.0
