@@ -165,6 +165,27 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors,
     const condensa_config* config);
 
 /*
+ * condensa_prune for callers that cannot allocate device memory or provide a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  GLOBAL scope, same outputs and
+ * records as condensa_prune (bit for bit).  The call allocates nothing, on the device or through the
+ * runtime: its workspace is a 2 MiB array that is part of the library's device code (every GPU the
+ * library runs on holds its own copy until the process ends), the host tables live on the caller's
+ * stack and reach the device as kernel arguments, and no timing events are created.  Limits
+ * (CONDENSA_ERR_SIZE beyond them): at most CONDENSA_STATIC_MAX_ELEMS elements in total, at most
+ * CONDENSA_STATIC_MAX_TENSORS tensors and CONDENSA_STATIC_MAX_DENSITIES densities.  The selection always
+ * runs the radix levels over the weights (the form condensa_prune picks by itself below 2^26 elements).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race; order them on one stream.  The first call on a device looks up the array's address.
+ */
+#define CONDENSA_STATIC_MAX_ELEMS     (1ull << 26)
+#define CONDENSA_STATIC_MAX_TENSORS   128
+#define CONDENSA_STATIC_MAX_DENSITIES 4
+condensa_status condensa_prune_static(const condensa_tensor* tensors, int n_tensors,
+                                      const double* densities, int n_densities,
+                                      float* const* theta, uint16_t* const* theta_f16, uint8_t* const* mask,
+                                      condensa_select* results_dev, void* stream);
+
+/*
  * FilterPrune scheme / filter_prune operator (Table 1, FilterPrune row: whole filters, i.e. the 3-D
  * slices of a convolution weight, are scored and removed; Section 3.1: filter aggregation).  Every tensor must have ndim == 4; filter f of a
  * tensor is the contiguous run of Cin*kh*kw weights of output channel f.  Aggregate: sum of

@@ -46,6 +46,9 @@ _PROTOTYPES = {
     "condensa_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int,
                                                    ctypes.c_int, ctypes.c_int, ctypes.POINTER(Config)]),
     "condensa_config_init": (ctypes.c_int32, [ctypes.POINTER(Config)]),
+    "condensa_prune_static": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p]),
     "condensa_prune": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                         ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
@@ -272,10 +275,11 @@ def select_records(results) -> List[Dict[str, int]]:
 
 
 def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16=False, mask=True,
-                   in_place=False, workspace=None, stream=None, outputs=None, config=None):
+                   in_place=False, workspace=None, stream=None, outputs=None, config=None, static=False):
     """Marshals a call of the C entry point condensa_prune.  ``theta`` / ``theta_f16`` / ``mask`` choose
     which outputs are allocated ([density][tensor] lists of device tensors); ``in_place`` passes the
-    weights themselves as theta (one density only).  Returns the outputs and the record tensor."""
+    weights themselves as theta (one density only).  ``static`` calls condensa_prune_static instead (no
+    workspace, GLOBAL scope).  Returns the outputs and the record tensor."""
     import torch
     lib = library()
     dev = tensors[0].device if tensors else torch.device("cuda")
@@ -304,9 +308,15 @@ def condensa_prune(tensors, densities, scope=SCOPE_GLOBAL, theta=True, theta_f16
     results = outputs.get("results")
     if results is None:
         results = torch.zeros((max(n_rec, 1), len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
-    ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace, config)
-    _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
-                              _stream(stream), _cfg(config)))
+    if static:
+        if scope != SCOPE_GLOBAL or config is not None or workspace is not None:
+            raise ValueError("condensa_prune_static: GLOBAL scope, no workspace, built-in settings")
+        ws = None
+        _check(lib.condensa_prune_static(tab, nt, dens, J, p1, p2, p3, results.data_ptr(), _stream(stream)))
+    else:
+        ws, need = _workspace(OP_PRUNE, total, 0, nt, J, scope, dev, workspace, config)
+        _check(lib.condensa_prune(tab, nt, dens, J, scope, p1, p2, p3, results.data_ptr(), ws.data_ptr(), ws.numel(),
+                                  _stream(stream), _cfg(config)))
     return {"theta": th, "theta_f16": th16, "mask": mk, "results": results[:n_rec], "workspace": ws,
             "_keep": (k1, k2, k3),
             "_buffers": {"theta": None if in_place else th, "theta_f16": th16, "mask": mk, "results": results}}

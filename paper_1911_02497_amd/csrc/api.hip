@@ -402,6 +402,55 @@ static bool want_window(u64 N, bool per_tensor, int J, bool lc, const Config& cf
 
 namespace condensa {
 
+// ---- static scratch for callers that cannot allocate ---------------------------------------------------
+// One array per device, resident until the process ends.  Host code never uses the array's name as an
+// address: scratch_for_current_device() asks the runtime for the device address once per device.
+
+constexpr size_t kScratchBytes = static_cast<size_t>(2) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+}  // namespace
+
+static condensa_status scratch_for_current_device(void** out) {
+    int dev = -1;
+    CONDENSA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CONDENSA_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        CONDENSA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return CONDENSA_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CONDENSA_OK;
+}
+
+// Writes host words into device memory as kernel arguments: no staging buffer, nothing to allocate.
+struct PokeWords { u64 w[448]; };
+__global__ __launch_bounds__(kBlock) void k_poke(u64* dst, PokeWords src, u32 n) {
+    for (u32 i = threadIdx.x; i < n; i += kBlock) dst[i] = src.w[i];
+}
+
+static condensa_status poke_upload(void* dst_dev, const char* src_host, size_t bytes, hipStream_t st) {
+    constexpr size_t kPiece = sizeof(PokeWords);
+    for (size_t off = 0; off < bytes; off += kPiece) {
+        const size_t n = bytes - off < kPiece ? bytes - off : kPiece;      // bytes is a multiple of 256
+        PokeWords pw;
+        std::memcpy(pw.w, src_host + off, n);
+        hipLaunchKernelGGL(k_poke, dim3(1), dim3(kBlock), 0, st, reinterpret_cast<u64*>(static_cast<char*>(dst_dev) + off),
+                           pw, static_cast<u32>(n / 8));
+        CONDENSA_LAUNCH_CHECK();
+    }
+    return CONDENSA_OK;
+}
+
+// condensa_prune and its allocation-free form share everything but where the host tables live, how they
+// reach the device and where the workspace comes from.
 static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors, const double* densities,
                                   int n_densities, int scope, float* const* theta, uint16_t* const* theta_f16,
                                   uint8_t* const* mask, condensa_select* results_dev, void* workspace_dev,
@@ -418,6 +467,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     const int J = n_densities;
     const bool per_tensor = (scope == CONDENSA_SCOPE_PER_TENSOR);
     if (per_tensor && n_tensors == 0) return CONDENSA_OK;
+    // the allocation-free form keeps to the radix levels, whose workspace is small whatever the input
     const Layout L = make_layout(CONDENSA_OP_PRUNE, tb.N, 0, n_tensors, J, scope, cfg, no_alloc);
 
     // output table, overlap and alignment checks
@@ -475,7 +525,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     std::memcpy(up + L.out, out, n_out * sizeof(OutDesc));
     std::memcpy(up + L.slots, slots, static_cast<size_t>(L.n_slots) * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = stage_upload(workspace_dev, up, L.upload_bytes, st);
+    rc = no_alloc ? poke_upload(workspace_dev, up, L.upload_bytes, st) : stage_upload(workspace_dev, up, L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
     hipLaunchKernelGGL(k_prepare, dim3(fill_grid(L.zero_bytes / 8)), dim3(kBlock), 0, st,
                        at<u64>(workspace_dev, L.zero_begin), static_cast<u64>(L.zero_bytes / 8),
@@ -574,6 +624,39 @@ condensa_status condensa_prune(const condensa_tensor* tensors, int n_tensors, co
     HostArena arena;
     return prune_impl(tensors, n_tensors, densities, n_densities, scope, theta, theta_f16, mask, results_dev,
                       workspace_dev, workspace_bytes, stream, cfg, arena, false);
+}
+
+condensa_status condensa_prune_static(const condensa_tensor* tensors, int n_tensors, const double* densities,
+                                      int n_densities, float* const* theta, uint16_t* const* theta_f16,
+                                      uint8_t* const* mask, condensa_select* results_dev, void* stream) {
+    if (n_tensors < 0 || n_tensors > CONDENSA_STATIC_MAX_TENSORS) return CONDENSA_ERR_SIZE;
+    if (n_densities < 1 || n_densities > CONDENSA_STATIC_MAX_DENSITIES) return CONDENSA_ERR_SIZE;
+    if (n_tensors > 0 && tensors == nullptr) return CONDENSA_ERR_NULL;
+    u64 total = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        u64 n;
+        if (!tensor_elems(tensors[t], &n)) return CONDENSA_ERR_SHAPE;
+        total += n;
+        if (total > CONDENSA_STATIC_MAX_ELEMS) return CONDENSA_ERR_SIZE;
+    }
+    // built-in settings: nothing of the process-wide defaults applies (no event is created for phase timing)
+    Config cfg{};
+    cfg.v[CONDENSA_OPT_SELECT_PATH] = 1;
+    cfg.v[CONDENSA_OPT_WINDOW_MARGIN] = 80;
+    void* ws = nullptr;
+    const condensa_status rc = scratch_for_current_device(&ws);
+    if (rc != CONDENSA_OK) return rc;
+    // host tables on this stack frame: tensor table, output table, rankings, their upload image, byte ranges
+    constexpr size_t kHostBytes =
+        static_cast<size_t>(CONDENSA_STATIC_MAX_TENSORS + 1) * sizeof(TensorDesc) * 2 +
+        static_cast<size_t>(CONDENSA_STATIC_MAX_TENSORS) * CONDENSA_STATIC_MAX_DENSITIES * sizeof(OutDesc) * 2 +
+        static_cast<size_t>(CONDENSA_STATIC_MAX_DENSITIES + 2 * kMaxJ) * sizeof(Slot) * 2 +
+        (static_cast<size_t>(CONDENSA_STATIC_MAX_TENSORS) * (1 + 3 * CONDENSA_STATIC_MAX_DENSITIES) + 2) * sizeof(ByteRange) +
+        4096;
+    alignas(64) char host[kHostBytes];
+    HostArena arena(host, sizeof(host));
+    return prune_impl(tensors, n_tensors, densities, n_densities, CONDENSA_SCOPE_GLOBAL, theta, theta_f16, mask,
+                      results_dev, ws, kScratchBytes, stream, cfg, arena, true);
 }
 
 }  // extern "C" (reopened below)
