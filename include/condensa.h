@@ -442,6 +442,9 @@ condensa_status condensa_profile_reset(void);
 
 const char* condensa_status_string(condensa_status s);
 int         condensa_last_hip_error(void);   /* hipError_t of the last failing runtime call, 0 if none */
+/* Diagnostic: kernels the library has enqueued since it was loaded (all threads, all streams); the
+   difference around a call is that call's number of launches. */
+uint64_t    condensa_launch_count(void);
 int         condensa_version(void);
 
 #ifdef __cplusplus

@@ -107,6 +107,7 @@ _PROTOTYPES = {
     "condensa_profile_reset": (ctypes.c_int32, []),
     "condensa_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "condensa_last_hip_error": (ctypes.c_int, []),
+    "condensa_launch_count": (ctypes.c_uint64, []),
     "condensa_version": (ctypes.c_int, []),
 }
 
@@ -252,6 +253,10 @@ def condensa_set_option(option: int, value: int) -> None:
 
 def condensa_get_option(option: int) -> int:
     return int(library().condensa_get_option(option))
+
+
+def condensa_launch_count() -> int:
+    return int(library().condensa_launch_count())
 
 
 def condensa_profile_reset() -> None:

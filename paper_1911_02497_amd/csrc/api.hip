@@ -13,6 +13,7 @@
 namespace condensa {
 
 std::atomic<int> g_last_hip_error{0};
+std::atomic<uint64_t> g_launches{0};
 
 // ---- configuration ---------------------------------------------------------------------------------
 
@@ -1447,6 +1448,8 @@ const char* condensa_status_string(condensa_status s) {
 
 int condensa_last_hip_error(void) { return g_last_hip_error.load(); }
 
-int condensa_version(void) { return 100; }
+uint64_t condensa_launch_count(void) { return g_launches.load(); }
+
+int condensa_version(void) { return 200; }
 
 }  // extern "C"

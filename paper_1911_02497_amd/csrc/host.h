@@ -16,6 +16,7 @@
 namespace condensa {
 
 extern std::atomic<int> g_last_hip_error;
+extern std::atomic<uint64_t> g_launches;        // kernels enqueued since the library was loaded (diagnostic)
 
 // The knobs of one call, resolved once at the entry point: the caller's condensa_config, or the
 // process-wide defaults when it passes NULL.  Everything below the entry point reads this copy only.
@@ -35,7 +36,11 @@ condensa_status set_default_option(int option, int64_t value);
         }                                                                       \
     } while (0)
 
-#define CONDENSA_LAUNCH_CHECK() CONDENSA_HIP(hipGetLastError())
+#define CONDENSA_LAUNCH_CHECK()                                                 \
+    do {                                                                        \
+        ::condensa::g_launches.fetch_add(1, std::memory_order_relaxed);         \
+        CONDENSA_HIP(hipGetLastError());                                        \
+    } while (0)
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
