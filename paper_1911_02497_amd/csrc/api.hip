@@ -194,8 +194,11 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     L.zero_begin = off;
     L.ctl = off;    off += align_up(sizeof(Control));
     L.hist0 = off;  off += align_up(static_cast<size_t>(L.n_groups) * kBins * sizeof(u64));
-    // later-level histograms: one per ranking, and room for the 2J window-boundary rankings
-    const size_t n_hx = static_cast<size_t>(L.n_slots) + 2u * kMaxJ + 1u;    // + the shared level-0 histogram of the sample
+    // later-level histograms of the rankings over the data (one per ranking and level under GLOBAL scope),
+    // then the window path's: candidate rankings [3][J], the sample's boundary rankings [2][2J + 1] and its
+    // shared level 0 (see make_window_args)
+    size_t n_hx = 2u * static_cast<size_t>(L.n_slots);
+    if (!structure && !per_tensor) n_hx += 3u * J + 2u * (2u * J + 1u) + 1u;
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (2 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
@@ -316,6 +319,22 @@ static void init_slot(Slot* s, u64 n, u64 k, u32 path) {
     }
 }
 
+// One density on the window path: the three rankings of the sample that bound (kRankHi, kRankLo) and estimate
+// (kRankMid) the threshold of `main`.  Their ranks depend on the number of valid sample keys, which only the
+// device knows, so the host passes the rule and the device turns it into a rank (sample_rank).
+static void init_sample_slots(Slot* three, const Slot& main, int64_t margin16) {
+    for (u32 i = 0; i < 3; ++i) {
+        Slot& s = three[i];
+        std::memset(&s, 0, sizeof(Slot));
+        s.rank_rule = kRankHi + i;
+        s.margin16 = static_cast<u32>(margin16);
+        s.p = main.n ? static_cast<double>(main.k) / static_cast<double>(main.n) : 0.0;
+        s.hi = 0x7FFFFFFFu;                                     // every valid sample key takes part
+        s.state = main.state == kSelecting ? kSelecting : kDone;
+        s.prefix = (s.rank_rule == kRankHi && s.state == kDone) ? 0x7FFFFFFFu : 0u;
+    }
+}
+
 template <typename T>
 static T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
@@ -348,6 +367,7 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
             const size_t lds = static_cast<size_t>(level == 0 ? kBins : nj * (1 << level_of(31, level).bits)) * sizeof(u32);
             hipLaunchKernelGGL((k_hist_data<LC, VEC>), dim3(static_cast<unsigned>(blocks)), dim3(threads), lds, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
+            if (a.merged) continue;                            // the next kernel folds this level in itself
             hipLaunchKernelGGL(k_scan_level, dim3(n_slots), dim3(kBlock), 0, st, a.slots, a.hist0, a.histx, a.J, 31,
                                level, a.ctl, a.only_failed, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();
@@ -376,7 +396,8 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
                                      const FusedRequest* fused = nullptr) {
     condensa_status rc;
     if (use_window) {
-        rc = launch_window_path<LC, VEC>(a, L, ws, st, cfg, fused);
+        rc = a.J == 1 ? launch_window_path_single<LC, VEC>(a, L, ws, st, cfg, fused)
+                      : launch_window_path<LC, VEC>(a, L, ws, st, cfg);
         if (rc != CONDENSA_OK) return rc;
         a.only_failed = 1;
     }
@@ -512,7 +533,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     if (rc != CONDENSA_OK) return no_alloc ? CONDENSA_ERR_SIZE : rc;
 
     const bool window = !no_alloc && want_window(tb.N, per_tensor, J, false, cfg);
-    Slot* slots = arena.array<Slot>(static_cast<size_t>(L.n_slots));
+    Slot* slots = arena.array<Slot>(static_cast<size_t>(L.n_slots) + 3);
     char* up = arena.array<char>(L.upload_bytes);
     if (!slots || !up) return CONDENSA_ERR_SIZE;
     for (int g = 0; g < L.n_groups; ++g)
@@ -520,11 +541,13 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
             const u64 n = per_tensor ? tb.td[g].n : tb.N;
             init_slot(&slots[static_cast<size_t>(g) * J + j], n, kept_count(densities[j], n), window ? 2u : 1u);
         }
+    const size_t n_up_slots = static_cast<size_t>(L.n_slots) + ((window && J == 1) ? 3 : 0);
+    if (window && J == 1) init_sample_slots(slots + L.n_slots, slots[0], cfg[CONDENSA_OPT_WINDOW_MARGIN]);
 
     // one upload: [tensor table | output table | rankings]
     std::memcpy(up + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up + L.out, out, n_out * sizeof(OutDesc));
-    std::memcpy(up + L.slots, slots, static_cast<size_t>(L.n_slots) * sizeof(Slot));
+    std::memcpy(up + L.slots, slots, n_up_slots * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = no_alloc ? poke_upload(workspace_dev, up, L.upload_bytes, st) : stage_upload(workspace_dev, up, L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
@@ -549,6 +572,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     a.only_failed = 0;
     a.streaming = (tb.N * 4u >= (static_cast<u64>(512) << 20)) ? 1 : 0;            // well beyond the 256 MB last-level cache
     a.mu = 0.0f;
+    a.merged = per_tensor ? 0 : 1;
 
     // One density on the window path: selection and apply share one sweep unless theta overwrites the weights.
     const bool fuse = window && J == 1 && any_out && tb.n_chunks > 0 && slots[0].k > 0 && !in_place_any &&
@@ -722,13 +746,15 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     rc = check_workspace(workspace_dev, workspace_bytes, L);
     if (rc != CONDENSA_OK) return rc;
     const bool window = want_window(tb.N, false, 1, true, cfg);
-    Slot slot;
+    Slot slot4[4];
+    Slot& slot = slot4[0];
     init_slot(&slot, tb.N, kept_count(density, tb.N), window ? 2u : 1u);
+    if (window) init_sample_slots(slot4 + 1, slot, cfg[CONDENSA_OPT_WINDOW_MARGIN]);
 
     std::vector<char> up(L.upload_bytes, 0);
     std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
-    std::memcpy(up.data() + L.slots, &slot, sizeof(Slot));
+    std::memcpy(up.data() + L.slots, slot4, (window ? 4 : 1) * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
@@ -753,6 +779,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.only_failed = 0;
     a.streaming = (tb.N * 8u >= (static_cast<u64>(512) << 20)) ? 1 : 0;            // w and lambda: well beyond the 256 MB last-level cache
     a.mu = mu;
+    a.merged = 1;
 
     // the selection sweeps read w and lambda only, so their vector path depends on those alone
     bool vec_in = tb.vec;

@@ -80,7 +80,21 @@ struct OutDesc {           // outputs of tensor t for density j, entry j * n_ten
     u64 pad;
 };
 
-// State of one ranking (one density of one group).  Filled by the host, advanced level by level.
+// State of a ranking as the radix-level kernels hand it on: the level kernels of a GLOBAL-scope ranking do
+// not wait for a separate bin-search launch -- every workgroup of the kernel for level L folds the finished
+// histogram of level L - 1 into the state itself (all workgroups get the same result), and workgroup 0 stores
+// it for the kernel of level L + 1.  The stores alternate between two places so that no workgroup can read a
+// state while another one of the same kernel replaces it.
+struct SlotStep {
+    u64 prefix;            // key bits decided so far
+    u64 remaining;         // 1-based descending rank still to resolve inside the prefix
+    u64 n_tie;             // keys in the bin chosen last
+    u32 state;
+    u32 need_tie;
+};
+
+// State of one ranking (one density of one group).  Filled by the host, advanced level by level.  The fields
+// before `step` are only ever written by the host or by kernels that run one workgroup per ranking.
 struct Slot {
     u64 prefix;            // key bits decided so far
     u64 remaining;         // 1-based descending rank still to resolve inside the prefix
@@ -93,9 +107,14 @@ struct Slot {
     u32 need_tie;          // index search among ties required
     u32 path;
     u32 level_begin;       // radix levels below this one are already decided by the prefix
-    u64 pad1;
+    u32 rank_rule;         // 0: `remaining` is given.  Else this ranking bounds the threshold of another one on a
+                           // sample whose size is only known on the device: kRankHi / kRankLo / kRankMid
+    u32 margin16;          // rank_rule != 0: half-width of the window in 1/16 standard deviations of the sample rank
+    double p;              // rank_rule != 0: k / n of the ranking that is bounded
+    SlotStep step[2];      // step[L & 1]: state on entering level L, stored by the kernel of level L (L > level_begin)
 };
-static_assert(sizeof(Slot) == 88, "Slot layout");
+static_assert(sizeof(SlotStep) == 32 && sizeof(Slot) == 160, "Slot layout");
+enum : u32 { kRankGiven = 0, kRankHi = 1, kRankLo = 2, kRankMid = 3 };
 
 enum : u32 { kInactive = 0, kSelecting = 1, kDone = 2, kFailed = 3 };
 

@@ -36,7 +36,14 @@ struct DataArgs {
     int only_failed;       // 1: runs as the fallback of the window path (skip when nothing failed)
     int streaming;         // 1: the inputs exceed the caches, so repeated sweeps gain nothing from keeping lines
     float mu;
+    int merged;            // 1 (GLOBAL scope): every level kernel folds in the previous level's histogram itself
+                           // (wave_enter_level), one histogram per ranking and level; 0: k_scan_level runs between levels
 };
+
+// Histogram of radix level `level` (>= 1) of ranking s over the weights; level 0 is shared per group (hist0).
+__device__ inline u64* data_hist(const DataArgs& a, int level, u64 s) {
+    return a.histx + (a.merged ? static_cast<u64>(level - 1) * static_cast<u64>(a.J) + s : s) * kBins;
+}
 
 // ---- wavefront / workgroup scans ---------------------------------------------------------------
 
@@ -73,6 +80,101 @@ __device__ inline u64 block_excl_scan_u64(u64 v, u64* s_wave, u64* total) {
     }
     *total = all;
     return before + incl - v;
+}
+
+__device__ inline SlotStep slot_canonical(const Slot& s) {
+    SlotStep e;
+    e.prefix = s.prefix; e.remaining = s.remaining; e.n_tie = s.n_tie; e.state = s.state; e.need_tie = s.need_tie;
+    return e;
+}
+
+// Rank of a boundary ranking on a sample of S keys.  The number of sample keys above the true threshold is
+// (close to) binomial; sample units of 4 neighbours may be correlated, so the standard deviation is taken as
+// if every unit were one draw.  A bound that falls outside the sample ends the ranking at once: no upper
+// bound (prefix = largest key) or no lower bound (prefix = 0).
+__device__ inline void sample_rank(const Slot& s, u64 S, SlotStep* e) {
+    const double p = s.p;
+    const double ks = p * static_cast<double>(S);
+    const double sd = sqrt(4.0 * static_cast<double>(S) * p * (1.0 - p));
+    const double m = static_cast<double>(s.margin16) / 16.0 * sd + 2.0;
+    double r;
+    if (s.rank_rule == kRankHi) {
+        r = floor(ks - m);
+        if (S == 0 || r < 1.0) { e->state = kDone; e->prefix = 0x7FFFFFFFu; return; }
+    } else if (s.rank_rule == kRankLo) {
+        r = ceil(ks + m) + 1.0;
+        if (S == 0 || r > static_cast<double>(S)) { e->state = kDone; e->prefix = 0; return; }
+    } else {
+        r = floor(ks + 0.5);
+        if (S == 0) { e->state = kDone; e->prefix = 0; return; }
+        if (r < 1.0) r = 1.0;
+        if (r > static_cast<double>(S)) r = static_cast<double>(S);
+    }
+    e->remaining = static_cast<u64>(r);
+}
+
+// State of ranking `s` on entering radix level L: the stored state of level L - 1 with the histogram of that
+// level (`hist_prev`, complete: an earlier kernel filled it) folded in.  Bins are walked from the top; the bin
+// b with  #(keys in higher bins) < remaining <= #(keys in bins >= b)  extends the prefix.  After the last
+// level the prefix is the threshold key, `remaining` the number of ties to keep and n_tie the number of keys
+// equal to the threshold.  Called by all 64 lanes of a wavefront; every lane returns the same value.
+__device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, const u64* __restrict__ hist_prev) {
+    SlotStep cur = slot_canonical(s);
+    const int b = static_cast<int>(s.level_begin);
+    if (cur.state != kSelecting || L <= b) return cur;          // no level search under way, or level not reached yet
+    if (L - 1 > b) cur = s.step[(L - 1) & 1];
+    if (cur.state != kSelecting) return cur;                     // failed at an earlier level
+    const Level lv = level_of(key_bits, L - 1);
+    const int nb = 1 << lv.bits;
+    const int lane = threadIdx.x & 63;
+    constexpr int kPerMax = kBins / 64;
+    const int per = (nb + 63) / 64;                              // bins per lane, from the top
+    u64 cnt[kPerMax];
+    u64 sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPerMax; ++i) {
+        const int bin = nb - 1 - (lane * per + i);
+        cnt[i] = (i < per && bin >= 0) ? hist_prev[bin] : 0;
+        sum += cnt[i];
+    }
+    const u64 incl = wave_incl_scan_u64(sum);
+    const u64 total = (static_cast<u64>(__shfl(static_cast<u32>(incl >> 32), 63, 64)) << 32) | __shfl(static_cast<u32>(incl), 63, 64);
+    if (s.rank_rule != kRankGiven && L - 1 == b) {
+        sample_rank(s, total, &cur);
+        if (cur.state != kSelecting) return cur;
+    }
+    const u64 r = cur.remaining;
+    if (total < r) {                                             // the wanted rank is not in this population
+        cur.state = kFailed;
+        return cur;
+    }
+    u64 before = incl - sum;
+    const bool mine = before < r && r <= incl;
+    u32 bin_found = 0;
+    u64 rem = 0, c_found = 0;
+    if (mine) {
+#pragma unroll
+        for (int i = 0; i < kPerMax; ++i) {
+            if (before < r && r <= before + cnt[i]) {
+                bin_found = static_cast<u32>(nb - 1 - (lane * per + i));
+                rem = r - before;
+                c_found = cnt[i];
+            }
+            before += cnt[i];
+        }
+    }
+    const int src = __ffsll(static_cast<long long>(__ballot(mine))) - 1;   // exactly one lane
+    bin_found = __shfl(bin_found, src, 64);
+    rem = (static_cast<u64>(__shfl(static_cast<u32>(rem >> 32), src, 64)) << 32) | __shfl(static_cast<u32>(rem), src, 64);
+    c_found = (static_cast<u64>(__shfl(static_cast<u32>(c_found >> 32), src, 64)) << 32) | __shfl(static_cast<u32>(c_found), src, 64);
+    cur.prefix |= static_cast<u64>(bin_found) << lv.shift;
+    cur.remaining = rem;
+    cur.n_tie = c_found;
+    if (L - 1 == n_levels(key_bits) - 1) {
+        cur.state = kDone;
+        cur.need_tie = rem < c_found ? 1u : 0u;
+    }
+    return cur;
 }
 
 // First kernel of every call: clears the flag / counter / histogram region and writes the
@@ -114,9 +216,23 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
     __shared__ u16 s_tab[kBins];
     __shared__ u32 s_prefix[kSlotBatch];
     __shared__ u32 s_active[kSlotBatch];
+    __shared__ u32 s_mprefix[kMaxJ];      // merged form: the rankings' state on entering this level
+    __shared__ u32 s_mactive[kMaxJ];
     __shared__ u32 s_any;
 
     if (a.only_failed && a.ctl->window_failed == 0) return;
+    if (a.merged && level > 0) {          // one group; every workgroup derives the same state, workgroup 0 stores it
+        const int n_waves = static_cast<int>(blockDim.x) >> 6;
+        for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.J; j += n_waves) {
+            const SlotStep e = wave_enter_level(a.slots[j], level, 31, level == 1 ? a.hist0 : data_hist(a, level - 1, j));
+            if ((threadIdx.x & 63) == 0) {
+                s_mprefix[j] = static_cast<u32>(e.prefix);
+                s_mactive[j] = (e.state == kSelecting) ? 1u : 0u;
+                if (blockIdx.x == 0) a.slots[j].step[level & 1] = e;
+            }
+        }
+        __syncthreads();
+    }
     const u64 c0 = static_cast<u64>(blockIdx.x) * chunks_per_block;
     if (c0 >= a.n_chunks) return;
     const u64 c1 = (c0 + chunks_per_block < a.n_chunks) ? c0 + chunks_per_block : a.n_chunks;
@@ -153,7 +269,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
             const u32 v = s_hist[i];
             if (v) {
                 u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(group) * kBins + i
-                                        : a.histx + (static_cast<u64>(group) * a.J + j0 + i / nb) * kBins + (i % nb);
+                                        : data_hist(a, level, static_cast<u64>(group) * a.J + j0 + i / nb) + (i % nb);
                 atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
             }
         }
@@ -177,6 +293,10 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
                 __syncthreads();
                 if (level == 0) {
                     if (wtid < a.J && a.slots[g * a.J + wtid].state == kSelecting) s_any = 1;
+                } else if (wtid < nj && a.merged) {
+                    s_prefix[wtid] = s_mprefix[j0 + wtid];
+                    s_active[wtid] = s_mactive[j0 + wtid];
+                    if (s_active[wtid]) s_any = 1;
                 } else if (wtid < nj) {
                     const Slot& s = a.slots[g * a.J + j0 + wtid];
                     s_prefix[wtid] = static_cast<u32>(s.prefix);
@@ -324,8 +444,26 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
     __shared__ u32 s_T[kMaxJ];
     __shared__ u32 s_need[kMaxJ];
     __shared__ u32 s_cnt[kMaxJ];
+    __shared__ u32 s_mT[kMaxJ];           // merged form: thresholds and tie needs after the last level
+    __shared__ u32 s_mneed[kMaxJ];
     __shared__ u32 s_any;
-    if (a.ctl->need_tie == 0) return;
+    if (a.only_failed && a.ctl->window_failed == 0) return;
+    if (a.merged) {
+        const int last = n_levels(31) - 1;
+        if (threadIdx.x == 0) s_any = 0;
+        __syncthreads();
+        for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.J; j += kBlock / 64) {
+            const SlotStep e = wave_enter_level(a.slots[j], last + 1, 31, last == 0 ? a.hist0 : data_hist(a, last, j));
+            if ((threadIdx.x & 63) == 0) {
+                s_mT[j] = static_cast<u32>(e.prefix);
+                s_mneed[j] = (e.state == kDone && e.need_tie) ? 1u : 0u;
+                if (s_mneed[j]) s_any = 1;
+            }
+        }
+        __syncthreads();
+        if (!s_any) return;               // uniform: no ranking keeps only part of its ties
+        __syncthreads();
+    } else if (a.ctl->need_tie == 0) return;
     const Level L0 = level_of(31, 0);
     const int tid = threadIdx.x;
     long long cur_group = -1;
@@ -344,7 +482,11 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
         if (g != cur_group) {
             if (tid == 0) s_any = 0;
             __syncthreads();
-            if (tid < a.J) {
+            if (tid < a.J && a.merged) {
+                s_T[tid] = s_mT[tid];
+                s_need[tid] = s_mneed[tid];
+                if (s_need[tid]) s_any = 1;
+            } else if (tid < a.J) {
                 const Slot& s = a.slots[static_cast<u64>(g) * a.J + tid];
                 s_T[tid] = static_cast<u32>(s.prefix);
                 s_need[tid] = (s.state == kDone && s.need_tie) ? 1u : 0u;
@@ -411,14 +553,34 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
     __shared__ u64 s_wave[kBlock / 64];
     __shared__ u64 s_found[3];                 // chunk, rank inside it, flag
     __shared__ u64 s_run[3];                   // run of chunks that holds the wanted tie, ties before the run
+    __shared__ SlotStep s_e;
     const int s = blockIdx.x;
     const int g = s / a.J, j = s % a.J;
     const int tid = threadIdx.x;
     Slot& slot = a.slots[s];
-    const bool need = (slot.state == kDone && slot.need_tie);
+    if (a.merged) {
+        // the last level's histogram is folded in here, and this workgroup (the only one that touches the
+        // ranking in this kernel) makes the outcome the ranking's stored state
+        if (tid < 64) {
+            const int last = n_levels(31) - 1;
+            const SlotStep e = wave_enter_level(slot, last + 1, 31, last == 0 ? a.hist0 : data_hist(a, last, s));
+            if (tid == 0) {
+                s_e = e;
+                if (slot.state == kSelecting) {
+                    slot.prefix = e.prefix; slot.remaining = e.remaining; slot.n_tie = e.n_tie;
+                    slot.state = e.state; slot.need_tie = e.need_tie;
+                    if (e.state == kDone && !e.need_tie) slot.tie_end = slot.n;
+                }
+            }
+        }
+    } else if (tid == 0) {
+        s_e = slot_canonical(slot);
+    }
+    __syncthreads();
+    const bool need = (s_e.state == kDone && s_e.need_tie);
     if (need) {
-        const u64 r = slot.remaining;          // 1-based rank of the last kept tie
-        const u32 T = static_cast<u32>(slot.prefix);
+        const u64 r = s_e.remaining;           // 1-based rank of the last kept tie
+        const u32 T = static_cast<u32>(s_e.prefix);
         const u64 cb = a.per_tensor ? a.td[g].chunk_start : 0;
         const u64 ce = a.per_tensor ? a.td[g + 1].chunk_start : a.n_chunks;
         const u32* cnt = a.tiecnt + static_cast<u64>(j) * a.n_chunks;
@@ -510,11 +672,11 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
         condensa_select out;
         out.n = slot.n;
         out.k = slot.k;
-        if (slot.state == kDone) {
-            out.n_gt = slot.k - slot.remaining;
-            out.n_tie_kept = slot.remaining;
-            out.n_tie = slot.n_tie;
-            out.threshold_key = slot.prefix;
+        if (s_e.state == kDone) {
+            out.n_gt = slot.k - s_e.remaining;
+            out.n_tie_kept = s_e.remaining;
+            out.n_tie = s_e.n_tie;
+            out.threshold_key = s_e.prefix;
             out.tie_end = slot.tie_end;
         } else {                                  // k == 0: nothing is kept
             out.n_gt = 0; out.n_tie_kept = 0; out.n_tie = 0;

@@ -43,8 +43,10 @@ struct WindowArgs {
     float* cand_w;         // [cand_cap] fused sweep: weight of each candidate
     float* cand_lam;       // [cand_cap] fused sweep: multiplier of each candidate (L-C step)
     const OutDesc* out;    // fused sweep: output table
-    int want_mid;          // fused sweep: also rank the sample key at the expected position of the threshold
     struct SortedWindows* sorted;   // several densities: the windows in sweep order, written by k_window_sort
+    u64* hist_main;        // histograms of the candidate rankings
+    u64* hist_aux;         // histograms of the sample's boundary rankings, later of the index rankings
+    u64* hist_shared0;     // level 0 of the sample, shared by its boundary rankings
 };
 
 struct ArrayArgs {
@@ -59,12 +61,15 @@ struct ArrayArgs {
     u64* hist;             // [n_slots][kBins]
     u64* shared0;          // NULL, or: all rankings have the same filter and no prefix at level 0, count once here
     const u32* gate;       // NULL, or skip the kernel when *gate == 0
-    const u64* alt_idx;    // index ranking: NULL, or a short list holding exactly the entries that take part,
-    const u64* alt_cnt;    //   used instead of the array when it is complete (*alt_cnt <= alt_cap)
-    u64 alt_cap;
     int n_slots;
     int key_bits;
+    int merged;            // 1: hist holds one histogram per level and ranking ([level][n_slots]) and every level
+                           // kernel folds in the previous level itself (wave_enter_level); 0: k_scan_level in between
 };
+
+__device__ inline u64* array_hist(const ArrayArgs& a, int level, int slot) {
+    return a.hist + (a.merged ? static_cast<u64>(level) * a.n_slots + slot : static_cast<u64>(slot)) * kBins;
+}
 
 __device__ inline u32 mix32(u32 x) {
     x ^= x >> 16; x *= 0x9E3779B1u;
@@ -140,20 +145,6 @@ __global__ __launch_bounds__(kBlock) void k_window_ranks(DataArgs a, WindowArgs 
     }
     w.wslots[2 * j] = hi;
     w.wslots[2 * j + 1] = lo;
-    if (w.want_mid && j == 0) {                          // one density: the estimate of the threshold itself
-        Slot mid{};
-        mid.n = S;
-        mid.hi = 0x7FFFFFFFu;
-        mid.state = kDone;
-        if (main.state == kSelecting && S > 0) {
-            double r = floor(static_cast<double>(main.k) / static_cast<double>(main.n) * static_cast<double>(S) + 0.5);
-            if (r < 1.0) r = 1.0;
-            if (r > static_cast<double>(S)) r = static_cast<double>(S);
-            mid.state = kSelecting;
-            mid.remaining = static_cast<u64>(r);
-        }
-        w.wslots[2 * a.J] = mid;
-    }
 }
 
 // ---- histogram of one radix level over a key array -------------------------------------------------
@@ -164,12 +155,23 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
     __shared__ u32 s_hist[kArrayWords];
     __shared__ u64 s_prefix[kArrayBatchMax];
     __shared__ u32 s_lo[kArrayBatchMax], s_hi[kArrayBatchMax], s_active[kArrayBatchMax];
+    __shared__ u64 s_mprefix[2 * kMaxJ + 1];   // merged form: the rankings' state on entering this level
+    __shared__ u32 s_mactive[2 * kMaxJ + 1];
     __shared__ u32 s_any;
     if (a.gate && *a.gate == 0) return;
-    const bool use_alt = IDX && a.alt_cnt != nullptr && *a.alt_cnt <= a.alt_cap;
-    const u64 alt_n = use_alt ? *a.alt_cnt : 0;
+    if (a.merged) {
+        for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.n_slots; j += kArrayThreads / 64) {
+            const u64* prev = (level == 1 && a.shared0) ? a.shared0 : array_hist(a, level > 0 ? level - 1 : 0, j);
+            const SlotStep e = wave_enter_level(a.slots[j], level, a.key_bits, prev);
+            if ((threadIdx.x & 63) == 0) {
+                s_mprefix[j] = e.prefix;
+                s_mactive[j] = (e.state == kSelecting && static_cast<u32>(level) >= a.slots[j].level_begin) ? 1u : 0u;
+                if (blockIdx.x == 0 && level > 0) a.slots[j].step[level & 1] = e;
+            }
+        }
+        __syncthreads();
+    }
     const int nt = static_cast<int>(blockDim.x);
-    if (use_alt && static_cast<u64>(blockIdx.x) * nt >= alt_n) return;          // nothing for this workgroup
     const Level L = level_of(a.key_bits, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
@@ -193,10 +195,11 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
             }
         } else if (tid < nj) {
             const Slot& s = a.slots[j0 + tid];
-            s_prefix[tid] = s.prefix;
+            s_prefix[tid] = a.merged ? s_mprefix[j0 + tid] : s.prefix;
             s_lo[tid] = static_cast<u32>(s.lo);
             s_hi[tid] = static_cast<u32>(s.hi);
-            const bool on = (s.state == kSelecting && static_cast<u32>(level) >= s.level_begin);
+            const bool on = a.merged ? s_mactive[j0 + tid] != 0
+                                     : (s.state == kSelecting && static_cast<u32>(level) >= s.level_begin);
             s_active[tid] = on ? 1u : 0u;
             if (on) s_any = 1;
         }
@@ -233,14 +236,7 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
                 }
             }
         };
-        if (use_alt) {                                   // every listed entry passes the key filter
-            for (u64 i = static_cast<u64>(blockIdx.x) * nt + tid; i < alt_n; i += static_cast<u64>(gridDim.x) * nt) {
-                const u64 rk = a.N - 1 - a.alt_idx[i];
-                const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
-                for (int j = 0; j < nj; ++j)
-                    if (s_active[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0) atomicAdd(&my_hist[j * nb + digit], 1u);
-            }
-        } else if (a.seg_cnt) {
+        if (a.seg_cnt) {
             for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
                 u64 cnt = a.seg_cnt[seg];
                 if (cnt > a.seg_cap) cnt = a.seg_cap;
@@ -250,7 +246,7 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
             take_range(0, a.n_host, static_cast<u64>(blockIdx.x) * nt + tid, static_cast<u64>(gridDim.x) * nt);
         }
         __syncthreads();
-        u64* dst = share ? a.shared0 : a.hist + static_cast<u64>(j0) * kBins;
+        u64* dst = share ? a.shared0 : array_hist(a, level, j0);
         for (int i = tid; i < words; i += nt) {
             u32 v = 0;
             for (int cpy = 0; cpy < copies; ++cpy) v += s_hist[cpy * words + i];
@@ -512,37 +508,6 @@ __global__ __launch_bounds__(64) void k_window_sweep_wave(DataArgs a, WindowArgs
     }
 }
 
-// Flat indices of the candidates equal to the threshold, for the index ranking; one reservation per
-// wavefront.  The count keeps running past the capacity so that an incomplete list is recognised.
-__global__ __launch_bounds__(kBlock) void k_window_collect(DataArgs a, WindowArgs w) {
-    if (a.ctl->need_tie_w == 0) return;
-    const Slot& slot = a.slots[0];
-    if (!(slot.state == kDone && slot.need_tie)) return;
-    const u32 T = static_cast<u32>(slot.prefix);
-    const int lane = threadIdx.x & 63;
-    for (u32 seg = blockIdx.x; seg < w.n_segs; seg += gridDim.x) {
-        u64 cnt = w.seg_cnt[seg];
-        if (cnt > w.seg_cap) cnt = w.seg_cap;
-        const u64 first = static_cast<u64>(seg) * w.seg_cap;
-        const u64 rounds = (cnt + kBlock - 1) / kBlock;    // uniform over the workgroup
-        for (u64 r = 0; r < rounds; ++r) {
-            const u64 i = r * kBlock + threadIdx.x;
-            const bool hit = (i < cnt) && w.cand_key[first + i] == T;
-            const u64 ballot = __ballot(hit);
-            if (ballot == 0) continue;                     // uniform over the wavefront
-            const u32 n_hit = static_cast<u32>(__popcll(ballot));
-            const int leader = __ffsll(static_cast<long long>(ballot)) - 1;
-            u64 b = 0;
-            if (lane == leader) b = atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->tie_count), static_cast<unsigned long long>(n_hit));
-            const u32 blo = __shfl(static_cast<u32>(b), leader, 64), bhi = __shfl(static_cast<u32>(b >> 32), leader, 64);
-            if (hit) {
-                const u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + __popcll(ballot & ((static_cast<u64>(1) << lane) - 1));
-                if (pos < w.tie_cap) w.tie_list[pos] = w.cand_idx[first + i];
-            }
-        }
-    }
-}
-
 // After the sweep: rank to find inside each window, or failure (window missed / list overflowed).
 __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs w) {
     __shared__ u64 s_wave[kBlock / 64];
@@ -649,6 +614,159 @@ __global__ __launch_bounds__(kBlock) void k_window_finish(DataArgs a, WindowArgs
     }
 }
 
+// ---- one density: the same steps with the level searches folded into the kernels that follow -----------
+
+static inline int bits_for(u64 max_value) {
+    int b = 1;
+    while (b < 63 && (max_value >> b) != 0) ++b;
+    return b;
+}
+
+// After the two levels of the sample ranking (one wavefront per boundary ranking): the boundary keys, rounded
+// outwards over the low bits that two levels leave undecided.  A third level over the sample would narrow a
+// window of 2^15..2^17 keys by at most 2^10 at either end.
+__global__ __launch_bounds__(kBlock) void k_window_bounds(ArrayArgs ar) {
+    const int j = threadIdx.x >> 6;
+    if (j >= ar.n_slots) return;
+    Slot& s = ar.slots[j];
+    const SlotStep e = wave_enter_level(s, 2, 31, array_hist(ar, 1, j));
+    if ((threadIdx.x & 63) != 0) return;
+    const u32 low = (1u << level_of(31, 1).shift) - 1u;
+    u32 key = s.rank_rule == kRankHi ? 0x7FFFFFFFu : 0u;                 // no bound
+    if (e.state == kSelecting) {
+        const u32 p = static_cast<u32>(e.prefix);
+        key = s.rank_rule == kRankHi ? (p | low) : s.rank_rule == kRankLo ? p : (p | ((low + 1u) >> 1));
+    } else if (e.state == kDone) {
+        key = static_cast<u32>(e.prefix);
+    }
+    s.prefix = key;
+    s.state = kDone;
+}
+
+// One density: flat indices of the candidates equal to the threshold, for the index search among ties; one
+// reservation per wavefront, and the count keeps running past the capacity so that an incomplete list is
+// recognised.  The threshold comes out of the last level's histogram, which every workgroup folds in itself.
+__global__ __launch_bounds__(kBlock) void k_window_ties(DataArgs a, WindowArgs w, ArrayArgs ar) {
+    __shared__ SlotStep s_e;
+    if (threadIdx.x < 64) {
+        const SlotStep e = wave_enter_level(a.slots[0], n_levels(31), 31, array_hist(ar, n_levels(31) - 1, 0));
+        if (threadIdx.x == 0) s_e = e;
+    }
+    __syncthreads();
+    if (!(s_e.state == kDone && s_e.need_tie)) return;
+    const u32 T = static_cast<u32>(s_e.prefix);
+    const int lane = threadIdx.x & 63;
+    for (u32 seg = blockIdx.x; seg < w.n_segs; seg += gridDim.x) {
+        u64 cnt = w.seg_cnt[seg];
+        if (cnt > w.seg_cap) cnt = w.seg_cap;
+        const u64 first = static_cast<u64>(seg) * w.seg_cap;
+        const u64 rounds = (cnt + kBlock - 1) / kBlock;    // uniform over the workgroup
+        for (u64 r = 0; r < rounds; ++r) {
+            const u64 i = r * kBlock + threadIdx.x;
+            const bool hit = (i < cnt) && w.cand_key[first + i] == T;
+            const u64 ballot = __ballot(hit);
+            if (ballot == 0) continue;                     // uniform over the wavefront
+            const u32 n_hit = static_cast<u32>(__popcll(ballot));
+            const int leader = __ffsll(static_cast<long long>(ballot)) - 1;
+            u64 b = 0;
+            if (lane == leader) b = atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->tie_count), static_cast<unsigned long long>(n_hit));
+            const u32 blo = __shfl(static_cast<u32>(b), leader, 64), bhi = __shfl(static_cast<u32>(b >> 32), leader, 64);
+            if (hit) {
+                const u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + __popcll(ballot & ((static_cast<u64>(1) << lane) - 1));
+                if (pos < w.tie_cap) w.tie_list[pos] = w.cand_idx[first + i];
+            }
+        }
+    }
+}
+
+// One density, one workgroup: makes the outcome of the candidate ranking the ranking's stored state.  When
+// only part of the ties is kept, the r-th lowest flat index among them is found here, by radix levels on the
+// index over the short tie list (lowest first).  A window that missed, a candidate list that overflowed or a
+// tie list that does not hold every tie re-arms the ranking for the radix levels over the weights.
+constexpr int kFinishThreads = 1024;
+__global__ __launch_bounds__(kFinishThreads) void k_window_finish1(DataArgs a, WindowArgs w, ArrayArgs ar, int idx_bits) {
+    __shared__ SlotStep s_e;
+    __shared__ u32 s_hist[kBins];
+    __shared__ u64 s_pick[2];              // chosen bin, rank inside it
+    const int tid = threadIdx.x;
+    Slot& s = a.slots[0];
+    const u32 state0 = s.state;
+    if (state0 != kSelecting && state0 != kFailed) return;               // k == 0: nothing was ranked
+    if (tid < 64) {
+        const SlotStep e = wave_enter_level(s, n_levels(31), 31, array_hist(ar, n_levels(31) - 1, 0));
+        if (tid == 0) s_e = e;
+    }
+    __syncthreads();
+    const SlotStep e = s_e;
+    bool ok = (e.state == kDone);
+    u64 tie_end = s.n;
+    if (ok && e.need_tie) {
+        const u64 n_t = a.ctl->tie_count;
+        if (n_t != e.n_tie || n_t > w.tie_cap) {
+            ok = false;                                                  // the list does not hold every tie
+        } else {
+            u64 prefix = 0, r = e.remaining;
+            for (int level = 0; level < n_levels(idx_bits); ++level) {   // uniform
+                const Level lv = level_of(idx_bits, level);
+                const int nb = 1 << lv.bits;
+                for (int i = tid; i < nb; i += kFinishThreads) s_hist[i] = 0;
+                __syncthreads();
+                for (u64 i = tid; i < n_t; i += kFinishThreads) {
+                    const u64 idx = w.tie_list[i];
+                    if (((idx ^ prefix) >> lv.hi_shift) == 0) atomicAdd(&s_hist[static_cast<u32>(idx >> lv.shift) & (nb - 1)], 1u);
+                }
+                __syncthreads();
+                if (tid < 64) {                                          // ascending walk: the bin that holds the r-th lowest
+                    constexpr int kPerMax = kBins / 64;
+                    const int per = (nb + 63) / 64;
+                    u64 sum = 0;
+                    u32 c[kPerMax];
+#pragma unroll
+                    for (int i = 0; i < kPerMax; ++i) {
+                        const int bin = tid * per + i;
+                        c[i] = (i < per && bin < nb) ? s_hist[bin] : 0u;
+                        sum += c[i];
+                    }
+                    const u64 incl = wave_incl_scan_u64(sum);
+                    u64 before = incl - sum;
+                    if (before < r && r <= incl) {
+#pragma unroll
+                        for (int i = 0; i < kPerMax; ++i) {
+                            if (before < r && r <= before + c[i]) { s_pick[0] = static_cast<u64>(tid * per + i); s_pick[1] = r - before; }
+                            before += c[i];
+                        }
+                    }
+                }
+                __syncthreads();
+                prefix |= s_pick[0] << lv.shift;
+                r = s_pick[1];
+                __syncthreads();
+            }
+            tie_end = prefix + 1;
+        }
+    }
+    if (tid != 0) return;
+    if (ok) {
+        s.prefix = e.prefix;
+        s.remaining = e.remaining;
+        s.n_tie = e.n_tie;
+        s.need_tie = 0;
+        s.tie_end = tie_end;
+        s.state = kDone;
+    } else {
+        s.prefix = 0;
+        s.remaining = s.k;
+        s.n_tie = 0;
+        s.tie_end = s.n;
+        s.need_tie = 0;
+        s.lo = s.hi = 0;
+        s.level_begin = 0;
+        s.path = 3;
+        s.state = kSelecting;
+        atomicOr(&a.ctl->window_failed, 1u);
+    }
+}
+
 // Workgroups of 256 threads for the candidate-segment kernels (one per 2048 entries, at most 1024).
 static inline unsigned array_grid(u64 n) {
     u64 b = (n + kBlock * 8 - 1) / (kBlock * 8);
@@ -664,12 +782,6 @@ static inline unsigned hist_array_grid(u64 n) {
     if (b > 256) b = 256;       // measured: 256 and 512 equal, 128 slower
     if (b == 0) b = 1;
     return static_cast<unsigned>(b);
-}
-
-static inline int bits_for(u64 max_value) {
-    int b = 1;
-    while (b < 63 && (max_value >> b) != 0) ++b;
-    return b;
 }
 
 template <bool IDX>
@@ -702,10 +814,10 @@ struct FusedRequest {
 // (1.79 ms; 2: 1.91, 1: 2.37).
 constexpr int kFusedQuadsLC = 1, kFusedQuadsPrune = 4;
 
-template <bool LC, bool VEC>
-static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st,
-                                          const Config& cfg, const FusedRequest* fused) {
-    if (a.n_chunks == 0) return CONDENSA_OK;
+// Window arguments shared by the two launch sequences below; *sweep_groups gets the sweep's grid.
+template <bool LC>
+static WindowArgs make_window_args(const DataArgs& a, const Layout& L, void* ws, const Config& cfg,
+                                   const FusedRequest* fused, u64* sweep_groups) {
     char* base = static_cast<char*>(ws);
     WindowArgs w{};
     w.sample = reinterpret_cast<u32*>(base + L.sample);
@@ -721,20 +833,102 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     constexpr int kWaveQuads = LC ? 4 : 8;                       // 8 KB of input per wavefront: measured best of 4, 8, 16 KB
     constexpr int kFusedQuads = LC ? kFusedQuadsLC : kFusedQuadsPrune;
     const bool fuse = fused != nullptr && a.J == 1;
-    const u64 sweep_groups = fuse ? a.n_chunks * (kChunk / (256 * kFusedQuads))
-                                  : (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
+    *sweep_groups = fuse ? a.n_chunks * (kChunk / (256 * kFusedQuads))
+                         : (a.J == 1) ? a.n_chunks * (kChunk / (256 * kWaveQuads)) : a.n_chunks;
     w.cand_w = reinterpret_cast<float*>(base + L.cand_w);
     w.cand_lam = reinterpret_cast<float*>(base + L.cand_lam);
     w.out = fuse ? fused->out : nullptr;
-    w.want_mid = fuse ? 1 : 0;
     w.sorted = reinterpret_cast<SortedWindows*>(base + L.sorted_windows);
-    w.n_segs = static_cast<u32>(sweep_groups < static_cast<u64>(kSegs) ? sweep_groups : static_cast<u64>(kSegs));
+    w.n_segs = static_cast<u32>(*sweep_groups < static_cast<u64>(kSegs) ? *sweep_groups : static_cast<u64>(kSegs));
     w.seg_cap = L.cand_cap / w.n_segs;
     w.margin16 = static_cast<int>(cfg[CONDENSA_OPT_WINDOW_MARGIN]);
     w.tie_list = reinterpret_cast<u64*>(base + L.sample);        // the sample is dead once its ranking is done
     w.tie_cap = L.sample_cap / 2;
-    u64* hist_main = a.histx;                                    // [J]
-    u64* hist_aux = a.histx + static_cast<u64>(a.J) * kBins;     // [2J]
+    w.hist_main = a.histx + static_cast<u64>(2 * a.J) * kBins;           // behind the radix levels' own histograms
+    w.hist_aux = w.hist_main + static_cast<u64>(3 * a.J) * kBins;
+    w.hist_shared0 = w.hist_aux + static_cast<u64>(2 * (2 * a.J + 1)) * kBins;
+    return w;
+}
+
+// The one-sweep or selection-only sweep kernel of a single density.
+template <bool LC, bool VEC>
+static condensa_status launch_single_sweep(const DataArgs& a, const WindowArgs& w, const FusedRequest* fused,
+                                           u64 sweep_groups, hipStream_t st) {
+    constexpr int kWaveQuads = LC ? 4 : 8;
+    constexpr int kFusedQuads = LC ? kFusedQuadsLC : kFusedQuadsPrune;
+    const dim3 fg(static_cast<unsigned>(sweep_groups));
+    if (fused && LC && fused->pq) {
+        if (VEC && fused->vec_out) hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
+        else                       hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
+    } else if (fused && VEC && fused->vec_out)
+        hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
+    else if (fused)
+        hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
+    else
+        hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), fg, dim3(64), 0, st, a, w);
+    CONDENSA_LAUNCH_CHECK();
+    return CONDENSA_OK;
+}
+
+// One density: 13 launches where the general sequence below needs 27.  The sample is ranked over two levels
+// (the host has filled in the three boundary rankings; their ranks follow from the sample's size on the device),
+// the candidates over the levels that their window leaves open, every level search folded into the kernel that
+// follows it, and the index search among ties runs on the short tie list inside the finishing workgroup.
+template <bool LC, bool VEC>
+static condensa_status launch_window_path_single(const DataArgs& a, const Layout& L, void* ws, hipStream_t st,
+                                                 const Config& cfg, const FusedRequest* fused) {
+    if (a.n_chunks == 0) return CONDENSA_OK;
+    u64 sweep_groups = 0;
+    WindowArgs w = make_window_args<LC>(a, L, ws, cfg, fused, &sweep_groups);
+    condensa_status rc;
+    {
+        PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
+        hipLaunchKernelGGL((k_sample<LC, VEC>), dim3(static_cast<unsigned>((w.n_units + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+        ArrayArgs ar{};
+        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 3;
+        ar.hist = w.hist_aux; ar.key_bits = 31; ar.shared0 = w.hist_shared0; ar.merged = 1;
+        for (int level = 0; level < 2; ++level) {
+            hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(ar.n_host)), dim3(kArrayThreads), 0, st, ar, level);
+            CONDENSA_LAUNCH_CHECK();
+        }
+        hipLaunchKernelGGL(k_window_bounds, dim3(1), dim3(kBlock), 0, st, ar);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    {
+        PhaseTimer timer(CONDENSA_PHASE_SWEEP, st, cfg);
+        rc = launch_single_sweep<LC, VEC>(a, w, fused, sweep_groups, st);
+        if (rc != CONDENSA_OK) return rc;
+    }
+    PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
+    hipLaunchKernelGGL(k_window_check, dim3(1), dim3(kBlock), 0, st, a, w);
+    CONDENSA_LAUNCH_CHECK();
+    ArrayArgs cr{};
+    cr.keys = w.cand_key; cr.seg_cnt = w.seg_cnt; cr.seg_cap = w.seg_cap; cr.n_segs = w.n_segs;
+    cr.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; cr.slots = a.slots; cr.n_slots = 1;
+    cr.hist = w.hist_main; cr.key_bits = 31; cr.merged = 1;
+    for (int level = 0; level < n_levels(31); ++level) {
+        hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(cr.n_host)), dim3(kArrayThreads), 0, st, cr, level);
+        CONDENSA_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_window_ties, dim3(array_grid(cr.n_host)), dim3(kBlock), 0, st, a, w, cr);
+    CONDENSA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_window_finish1, dim3(1), dim3(kFinishThreads), 0, st, a, w, cr, bits_for(a.N - 1));
+    CONDENSA_LAUNCH_CHECK();
+    if (fused && fused->w_out) *fused->w_out = w;
+    return CONDENSA_OK;
+}
+
+// Any number of densities: every level search is a launch of its own (k_scan_level), the boundary ranks come
+// from k_window_ranks, and the index search among ties ranks the candidate list itself.
+template <bool LC, bool VEC>
+static condensa_status launch_window_path(const DataArgs& a, const Layout& L, void* ws, hipStream_t st,
+                                          const Config& cfg) {
+    if (a.n_chunks == 0) return CONDENSA_OK;
+    u64 sweep_groups = 0;
+    WindowArgs w = make_window_args<LC>(a, L, ws, cfg, nullptr, &sweep_groups);
+    u64* hist_main = w.hist_main;                                // [J]
+    u64* hist_aux = w.hist_aux;                                  // [2J]
     condensa_status rc;
     {
         PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
@@ -743,28 +937,17 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
         hipLaunchKernelGGL(k_window_ranks, dim3(1), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
         ArrayArgs ar{};
-        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J + (fuse ? 1 : 0);
+        ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 2 * a.J;
         ar.hist = hist_aux; ar.key_bits = 31;
-        ar.shared0 = a.histx + static_cast<u64>(a.J + 2 * kMaxJ) * kBins;     // boundary rankings share level 0
+        ar.shared0 = w.hist_shared0;                                  // boundary rankings share level 0
         rc = rank_array<false>(ar, a.ctl, &a.ctl->unused_flag, st);
         if (rc != CONDENSA_OK) return rc;
     }
     {
         PhaseTimer timer(CONDENSA_PHASE_SWEEP, st, cfg);
-        const dim3 fg(static_cast<unsigned>(sweep_groups));
-        if (fuse && LC && fused->pq) {
-            if (VEC && fused->vec_out) hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
-            else                       hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, LC>), fg, dim3(64), 0, st, a, w);
-        } else if (fuse && VEC && fused->vec_out)
-            hipLaunchKernelGGL((k_window_fused<LC, true, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
-        else if (fuse)
-            hipLaunchKernelGGL((k_window_fused<LC, false, kFusedQuads, false>), fg, dim3(64), 0, st, a, w);
-        else if (a.J == 1) hipLaunchKernelGGL((k_window_sweep_wave<LC, VEC, kWaveQuads>), dim3(static_cast<unsigned>(sweep_groups)), dim3(64), 0, st, a, w);
-        else {
-            hipLaunchKernelGGL(k_window_sort, dim3(1), dim3(64), 0, st, a, w);
-            CONDENSA_LAUNCH_CHECK();
-            hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks)), dim3(kBlock), 0, st, a, w);
-        }
+        hipLaunchKernelGGL(k_window_sort, dim3(1), dim3(64), 0, st, a, w);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_window_sweep<LC, VEC>), dim3(static_cast<unsigned>(sweep_groups)), dim3(kBlock), 0, st, a, w);
         CONDENSA_LAUNCH_CHECK();
     }
     PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
@@ -780,24 +963,17 @@ static condensa_status launch_window_path(const DataArgs& a, const Layout& L, vo
     }
     hipLaunchKernelGGL(k_window_tie_setup, dim3(1), dim3(kBlock), 0, st, a, w);
     CONDENSA_LAUNCH_CHECK();
-    if (a.J == 1) {
-        // the index search then runs on the short list of ties instead of the whole candidate list
-        hipLaunchKernelGGL(k_window_collect, dim3(array_grid(static_cast<u64>(w.n_segs) * kBlock * 8)), dim3(kBlock), 0, st, a, w);
-        CONDENSA_LAUNCH_CHECK();
-    }
     {
         ArrayArgs ar{};
         ar.keys = w.cand_key; ar.idx = w.cand_idx; ar.seg_cnt = w.seg_cnt; ar.seg_cap = w.seg_cap; ar.n_segs = w.n_segs;
         ar.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; ar.N = a.N;
         ar.slots = w.wslots; ar.n_slots = a.J; ar.hist = hist_aux; ar.key_bits = bits_for(a.N - 1);
         ar.gate = &a.ctl->need_tie_w;
-        if (a.J == 1) { ar.alt_idx = w.tie_list; ar.alt_cnt = &a.ctl->tie_count; ar.alt_cap = w.tie_cap; }
         rc = rank_array<true>(ar, a.ctl, &a.ctl->unused_flag, st);
         if (rc != CONDENSA_OK) return rc;
     }
     hipLaunchKernelGGL(k_window_finish, dim3(1), dim3(kBlock), 0, st, a, w);
     CONDENSA_LAUNCH_CHECK();
-    if (fuse && fused->w_out) *fused->w_out = w;
     return CONDENSA_OK;
 }
 
