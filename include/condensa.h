@@ -344,12 +344,16 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors,
  *      theta = widen(binary16(prune(v)));  e = w - theta;  p = mu * e;  lambda' = lambda - p;  g = p - lambda'.
  * `theta`, if given, receives D(theta) in fp32.  The mask still marks the k selected positions, also
  * where a kept value underflows to zero in binary16.
+ *  nnz_dev    NULL, or device uint64: receives the memory-footprint objective of the compressed model
+ *             (Evaluation, Objective 1) as the number of stored binary16 codes other than +0 and -0, i.e. k
+ *             less the kept values that underflow.  It is counted inside the sweeps that write theta: no extra
+ *             pass over the model and no host round trip; footprint in bytes = 2 * nnz.
  */
 condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensors,
                                     float* const* lambda, float* const* lambda_out,
                                     float mu, double density,
                                     float* const* theta, uint16_t* const* theta_f16,
-                                    float* const* grad, uint8_t* const* mask,
+                                    float* const* grad, uint8_t* const* mask, uint64_t* nnz_dev,
                                     condensa_select* result_dev,
                                     void* workspace_dev, size_t workspace_bytes, void* stream,
     const condensa_config* config);

@@ -90,7 +90,7 @@ _PROTOTYPES = {
     "condensa_lc_step_pq": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_float, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-                                             ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
+                                             ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_count_nonzero": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.POINTER(Config)]),
     "condensa_lc_sgd_step": (ctypes.c_int32, [ctypes.POINTER(Tensor), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
@@ -467,7 +467,7 @@ def condensa_dequantize_fp8(q, fmt, stream=None):
 
 
 def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=False, theta=True, grad=True,
-                     mask=True, outputs=None, workspace=None, stream=None, pq=False, config=None):
+                     mask=True, outputs=None, workspace=None, stream=None, pq=False, config=None, nnz=False):
     """Marshals condensa_lc_step.  By default fresh lambda_out tensors are allocated (lambda is left
     untouched); ``in_place`` updates lambda itself.  ``outputs`` may carry preallocated
     theta / grad / mask / lambda_out lists to reuse."""
@@ -494,16 +494,21 @@ def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=Fa
     if results is None:
         results = torch.zeros((1, len(SELECT_FIELDS)), dtype=torch.int64, device=dev)
     ws, need = _workspace(OP_LC_STEP, total, 0, nt, 1, SCOPE_GLOBAL, dev, workspace, config)
-    th16, k4 = None, None
+    th16, k4, count = None, None, None
     if pq:
         th16 = outputs.get("theta_f16") or [torch.empty(t.shape, dtype=torch.int16, device=dev) for t in tensors]
         k4, p4 = _ptr_table(th16)
+        if nnz:                              # the footprint objective, counted inside the step
+            count = outputs.get("nnz")
+            if count is None:
+                count = torch.zeros(1, dtype=torch.int64, device=dev)
         _check(lib.condensa_lc_step_pq(tab, nt, pl, plo, float(mu), float(density), p1, p4, p2, p3,
+                                       None if count is None else count.data_ptr(),
                                        results.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream), _cfg(config)))
     else:
         _check(lib.condensa_lc_step(tab, nt, pl, plo, float(mu), float(density), p1, p2, p3, results.data_ptr(),
                                     ws.data_ptr(), ws.numel(), _stream(stream), _cfg(config)))
-    return {"theta": th, "theta_f16": th16, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo,
+    return {"theta": th, "theta_f16": th16, "grad": gr, "mask": mk, "lambda": lambdas if in_place else lo, "nnz": count,
             "results": results, "workspace": ws, "_keep": (kl, klo, k1, k2, k3, k4)}
 
 

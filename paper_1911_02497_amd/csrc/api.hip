@@ -200,6 +200,8 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     size_t n_hx = 2u * static_cast<size_t>(L.n_slots);
     if (!structure && !per_tensor) n_hx += 3u * J + 2u * (2u * J + 1u) + 1u;
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
+    // coarse sums of every histogram from hist0 on (the two regions above are contiguous: their sizes are multiples of 16 KB)
+    L.histc = off;  off += align_up((static_cast<size_t>(L.n_groups) + n_hx) * kCoarse * sizeof(u64));
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (2 + kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
@@ -561,6 +563,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     a.slots = at<Slot>(workspace_dev, L.slots);
     a.hist0 = at<u64>(workspace_dev, L.hist0);
     a.histx = at<u64>(workspace_dev, L.histx);
+    a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
@@ -691,8 +694,8 @@ namespace condensa {
 static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int n_tensors, float* const* lambda,
                                     float* const* lambda_out, float mu, double density, float* const* theta,
                                     uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
-                                    condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
-                                    void* stream, const condensa_config* config) {
+                                    uint64_t* nnz_dev, condensa_select* result_dev, void* workspace_dev,
+                                    size_t workspace_bytes, void* stream, const condensa_config* config) {
     Config cfg;
     condensa_status rc = resolve_config(config, &cfg);
     if (rc != CONDENSA_OK) return rc;
@@ -742,6 +745,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     }
     ranges.push_back(byte_range(workspace_dev, workspace_bytes < L.total ? workspace_bytes : L.total, true));
     ranges.push_back(byte_range(result_dev, sizeof(condensa_select), true));
+    ranges.push_back(byte_range(nnz_dev, sizeof(uint64_t), true));
     if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
     rc = check_workspace(workspace_dev, workspace_bytes, L);
     if (rc != CONDENSA_OK) return rc;
@@ -768,6 +772,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.slots = at<Slot>(workspace_dev, L.slots);
     a.hist0 = at<u64>(workspace_dev, L.hist0);
     a.histx = at<u64>(workspace_dev, L.histx);
+    a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
@@ -780,6 +785,9 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.streaming = (tb.N * 8u >= (static_cast<u64>(512) << 20)) ? 1 : 0;            // w and lambda: well beyond the 256 MB last-level cache
     a.mu = mu;
     a.merged = 1;
+    // counters of the apply sweeps' non-zero codes: the last row of the segment counters (rows 1.. belong to the
+    // sweeps of several densities, which the L-C step never runs)
+    a.nnz_seg = (pq && nnz_dev) ? at<u64>(workspace_dev, L.seg) + static_cast<size_t>(kSegs) * (1 + kMaxJ) : nullptr;
 
     // the selection sweeps read w and lambda only, so their vector path depends on those alone
     bool vec_in = tb.vec;
@@ -823,6 +831,11 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         else                           hipLaunchKernelGGL((k_lc_apply<false, 256, false>), dim3(nc * (kChunk / 1024)), dim3(256), 0, st, a, od);
         CONDENSA_LAUNCH_CHECK();
     }
+    if (pq && nnz_dev) {
+        hipLaunchKernelGGL(k_nnz_finish, dim3(1), dim3(kBlock), 0, st, a, at<u64>(workspace_dev, L.seg) + kSegs,
+                           (fuse && tb.n_chunks > 0) ? 1 : 0, nnz_dev);
+        CONDENSA_LAUNCH_CHECK();
+    }
     return CONDENSA_OK;
 }
 
@@ -836,16 +849,16 @@ condensa_status condensa_lc_step(const condensa_tensor* tensors, int n_tensors, 
                                  void* workspace_dev, size_t workspace_bytes, void* stream,
                                  const condensa_config* config) {
     return lc_step_impl(false, tensors, n_tensors, lambda, lambda_out, mu, density, theta, nullptr, grad, mask,
-                        result_dev, workspace_dev, workspace_bytes, stream, config);
+                        nullptr, result_dev, workspace_dev, workspace_bytes, stream, config);
 }
 
 condensa_status condensa_lc_step_pq(const condensa_tensor* tensors, int n_tensors, float* const* lambda,
                                     float* const* lambda_out, float mu, double density, float* const* theta,
                                     uint16_t* const* theta_f16, float* const* grad, uint8_t* const* mask,
-                                    condensa_select* result_dev, void* workspace_dev, size_t workspace_bytes,
-                                    void* stream, const condensa_config* config) {
+                                    uint64_t* nnz_dev, condensa_select* result_dev, void* workspace_dev,
+                                    size_t workspace_bytes, void* stream, const condensa_config* config) {
     return lc_step_impl(true, tensors, n_tensors, lambda, lambda_out, mu, density, theta, theta_f16, grad, mask,
-                        result_dev, workspace_dev, workspace_bytes, stream, config);
+                        nnz_dev, result_dev, workspace_dev, workspace_bytes, stream, config);
 }
 
 condensa_status condensa_count_nonzero(const condensa_tensor* tensors, int n_tensors, int kind,

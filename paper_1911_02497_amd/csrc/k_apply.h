@@ -134,6 +134,7 @@ __device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restric
     const u64 end = s.tie_end;
     const OutDesc o = out[t];
     const float mu = a.mu;
+    u32 nz = 0;                                                          // PQ: stored codes other than +-0
     if (VEC && wg0 + kTile <= n) {                                       // uniform
         float4 x[QUADS], y[QUADS];
 #pragma unroll
@@ -150,6 +151,7 @@ __device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restric
             u8 m[4];
             u16 h[4];
             lc_update4<PQ>(w, l, mu, T, td.flat_start + e0, end, th, ln, gr, m, h);
+            if (PQ) nz += ((h[0] & 0x7FFFu) != 0) + ((h[1] & 0x7FFFu) != 0) + ((h[2] & 0x7FFFu) != 0) + ((h[3] & 0x7FFFu) != 0);
             if (o.theta) st4_stream(o.theta + e0, th[0], th[1], th[2], th[3]);
             if (PQ && o.theta16) {
                 st_code4_stream(o.theta16 + e0, h[0], h[1], h[2], h[3]);
@@ -161,13 +163,14 @@ __device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restric
     } else {
         for (int q = 0; q < QUADS; ++q) {
             const u64 e0 = wg0 + q * (THREADS * 4) + tid * 4;
-            if (e0 >= n) return;
+            if (e0 >= n) break;
             float w[4], l[4], th[4], ln[4], gr[4];
             u8 m[4];
             u16 h[4];
             load4<VEC>(td.w, e0, n, w);
             load4<VEC>(td.lam, e0, n, l);
             lc_update4<PQ>(w, l, mu, T, td.flat_start + e0, end, th, ln, gr, m, h);
+            if (PQ) for (int k = 0; k < 4; ++k) nz += (e0 + k < n) && (h[k] & 0x7FFFu) != 0;
             if (o.theta) store4<VEC>(o.theta, e0, n, th);
             if (PQ && o.theta16) store4_u16<VEC>(o.theta16, e0, n, h);
             store4<VEC>(td.lam_out, e0, n, ln);
@@ -175,6 +178,25 @@ __device__ inline void lc_apply_tile(const DataArgs& a, const OutDesc* __restric
             if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
         }
     }
+    if (PQ && a.nnz_seg) {                                               // one atomic per wavefront, spread over the segments
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) nz += __shfl_down(nz, d, 64);
+        if ((tid & 63) == 0 && nz)
+            atomicAdd(reinterpret_cast<unsigned long long*>(&a.nnz_seg[(tile * (THREADS / 64) + (tid >> 6)) % kNnzSegs]), static_cast<unsigned long long>(nz));
+    }
+}
+
+// Footprint objective of the prune + binary16 L-C step (Evaluation, Objective 1): the number of stored codes
+// other than +-0, from the counters that the sweeps left.  One-sweep form that held: the sweep's own count
+// (upper halves of the `above` counters) corrected by the fix-up pass; otherwise the apply sweep's count.
+__global__ __launch_bounds__(kBlock) void k_nnz_finish(DataArgs a, const u64* __restrict__ seg_above, int one_sweep, u64* nnz_out) {
+    __shared__ u64 s_wave[kBlock / 64];
+    const bool sweep = one_sweep && a.ctl->window_failed == 0;
+    u64 v = 0;
+    for (int i = threadIdx.x; i < kNnzSegs; i += kBlock) v += sweep ? (seg_above[i] >> 32) : a.nnz_seg[i];
+    u64 total;
+    block_excl_scan_u64(v, s_wave, &total);
+    if (threadIdx.x == 0) *nnz_out = sweep ? total + a.ctl->nnz_delta : total;
 }
 
 template <bool VEC, int THREADS, bool PQ, int QUADS = 1>

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
         }
     }
     u32 key[QUADS][4];
-    u32 cmask = 0, above = 0;
+    u32 cmask = 0, above = 0, nz = 0;                                   // nz (PQ): stored codes other than +-0
 #pragma unroll
     for (int q = 0; q < QUADS; ++q) {
         const u64 e0 = base + static_cast<u64>(q) * 256 + lane * 4;
@@ -89,6 +89,7 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
             if (PQ) {
                 h16[k] = f32_to_f16_rne(th[k]);
                 th[k] = f16_bits_to_f32(h16[k]);
+                nz += ((full || e0 + k < n) && (h16[k] & 0x7FFFu) != 0) ? 1u : 0u;
             }
             if (LC) {
                 const float e = __fsub_rn(wk[q][k], th[k]);
@@ -127,12 +128,19 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
         }
     }
     // counts and candidates, as in k_window_sweep_wave; a candidate also keeps its inputs
+    // (PQ: the non-zero count rides in the upper half of the same counter -- a segment holds fewer than 2^32 elements)
     const u32 seg = blockIdx.x % w.n_segs;
     u32 s = above;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d, 64);
-    if (lane == 0 && s)
-        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_region[seg]), static_cast<unsigned long long>(s));
+    u64 s64 = s;
+    if (PQ) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) nz += __shfl_down(nz, d, 64);
+        s64 |= static_cast<u64>(nz) << 32;
+    }
+    if (lane == 0 && s64)
+        atomicAdd(reinterpret_cast<unsigned long long*>(&w.seg_region[seg]), static_cast<unsigned long long>(s64));
     const u32 cnt = __popc(cmask);
     u32 incl = cnt;
 #pragma unroll
@@ -192,6 +200,7 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
     // `parts` workgroups share a segment (the per-candidate work is a chain of dependent loads, so the
     // kernel's time is set by how many candidates one thread walks through)
     const u32 parts = gridDim.x / w.n_segs;
+    long long nz_delta = 0;                                // PQ: change of the count of non-zero codes
     {
         const u32 seg = blockIdx.x % w.n_segs, part = blockIdx.x / w.n_segs;
         if (part >= parts) return;
@@ -218,6 +227,9 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
                     const u16 h = f32_to_f16_rne(th);
                     th = f16_bits_to_f32(h);
                     if (o.theta16) o.theta16[e] = h;
+                    // the sweep counted the code of the other decision: the kept value's code, or +0
+                    const u16 hv = keep ? h : f32_to_f16_rne(lc_shift(wv, lv, mu));
+                    if ((hv & 0x7FFFu) != 0) nz_delta += keep ? 1 : -1;
                 }
                 const float d = __fsub_rn(wv, th);
                 const float p = __fmul_rn(mu, d);
@@ -233,6 +245,8 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
             if (o.mask) o.mask[e] = keep ? 1 : 0;
         }
     }
+    if (PQ && nz_delta != 0)
+        atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->nnz_delta), static_cast<unsigned long long>(nz_delta));
 }
 
 // Full apply sweeps that run only when the window failed: a fixed, modest grid walks the tiles, so that

@@ -16,7 +16,9 @@ struct Control {
     u64 sample_count;      // valid sample elements
     u64 above[kMaxJ];      // window sweep: keys above each window's upper bound
     u64 tie_count;         // candidates equal to the threshold (the tie list holds the first tie_cap)
-    u64 pad[3];
+    u64 nnz_delta;         // prune + binary16 L-C step: what the fix-up pass changes about the one-sweep kernel's
+                           // count of non-zero codes (two's complement)
+    u64 pad[2];
 };
 static_assert(sizeof(Control) == 32 + 8 * kMaxJ + 32, "Control layout");
 
@@ -38,7 +40,19 @@ struct DataArgs {
     float mu;
     int merged;            // 1 (GLOBAL scope): every level kernel folds in the previous level's histogram itself
                            // (wave_enter_level), one histogram per ranking and level; 0: k_scan_level runs between levels
+    u64* coarse;           // merged form: kCoarse sums per histogram, in the order of the histograms from hist0 on
+    u64* nnz_seg;          // prune + binary16 L-C step: non-zero codes written by the apply sweep, per counter segment (or NULL)
 };
+constexpr int kNnzSegs = 1024;   // counter segments of the apply sweeps (one address would serialise ~10^6 atomics)
+
+// Every histogram of the merged form comes with kCoarse sums over runs of consecutive bins, so that the
+// workgroups that fold a level in read ~100 counters instead of 2048 (hundreds of workgroups walking the same
+// 16 KB at once queue up on a few cache channels).
+constexpr int kCoarse = 64;
+__device__ inline int coarse_run(int nb) { return (nb + kCoarse - 1) / kCoarse; }    // bins per coarse sum
+__device__ inline u64* coarse_of(u64* hist_base, u64* coarse_base, const u64* fine) {
+    return coarse_base + static_cast<u64>(fine - hist_base) / kBins * kCoarse;
+}
 
 // Histogram of radix level `level` (>= 1) of ranking s over the weights; level 0 is shared per group (hist0).
 __device__ inline u64* data_hist(const DataArgs& a, int level, u64 s) {
@@ -114,11 +128,12 @@ __device__ inline void sample_rank(const Slot& s, u64 S, SlotStep* e) {
 }
 
 // State of ranking `s` on entering radix level L: the stored state of level L - 1 with the histogram of that
-// level (`hist_prev`, complete: an earlier kernel filled it) folded in.  Bins are walked from the top; the bin
-// b with  #(keys in higher bins) < remaining <= #(keys in bins >= b)  extends the prefix.  After the last
-// level the prefix is the threshold key, `remaining` the number of ties to keep and n_tie the number of keys
-// equal to the threshold.  Called by all 64 lanes of a wavefront; every lane returns the same value.
-__device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, const u64* __restrict__ hist_prev) {
+// level (`hist_prev` and its coarse sums, complete: an earlier kernel filled them) folded in.  Bins are walked
+// from the top; the bin b with  #(keys in higher bins) < remaining <= #(keys in bins >= b)  extends the prefix.
+// After the last level the prefix is the threshold key, `remaining` the number of ties to keep and n_tie the
+// number of keys equal to the threshold.  Called by all 64 lanes of a wavefront; every lane returns the same value.
+__device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, const u64* __restrict__ hist_prev,
+                                            const u64* __restrict__ coarse_prev) {
     SlotStep cur = slot_canonical(s);
     const int b = static_cast<int>(s.level_begin);
     if (cur.state != kSelecting || L <= b) return cur;          // no level search under way, or level not reached yet
@@ -126,19 +141,13 @@ __device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, 
     if (cur.state != kSelecting) return cur;                     // failed at an earlier level
     const Level lv = level_of(key_bits, L - 1);
     const int nb = 1 << lv.bits;
+    const int run = coarse_run(nb);
     const int lane = threadIdx.x & 63;
-    constexpr int kPerMax = kBins / 64;
-    const int per = (nb + 63) / 64;                              // bins per lane, from the top
-    u64 cnt[kPerMax];
-    u64 sum = 0;
-#pragma unroll
-    for (int i = 0; i < kPerMax; ++i) {
-        const int bin = nb - 1 - (lane * per + i);
-        cnt[i] = (i < per && bin >= 0) ? hist_prev[bin] : 0;
-        sum += cnt[i];
-    }
-    const u64 incl = wave_incl_scan_u64(sum);
-    const u64 total = (static_cast<u64>(__shfl(static_cast<u32>(incl >> 32), 63, 64)) << 32) | __shfl(static_cast<u32>(incl), 63, 64);
+    // coarse sums, highest bins first: lane l takes run kCoarse - 1 - l
+    const int crun = kCoarse - 1 - lane;
+    const u64 csum = (crun * run < nb) ? coarse_prev[crun] : 0;
+    const u64 cincl = wave_incl_scan_u64(csum);
+    const u64 total = (static_cast<u64>(__shfl(static_cast<u32>(cincl >> 32), 63, 64)) << 32) | __shfl(static_cast<u32>(cincl), 63, 64);
     if (s.rank_rule != kRankGiven && L - 1 == b) {
         sample_rank(s, total, &cur);
         if (cur.state != kSelecting) return cur;
@@ -148,31 +157,27 @@ __device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, 
         cur.state = kFailed;
         return cur;
     }
-    u64 before = incl - sum;
-    const bool mine = before < r && r <= incl;
-    u32 bin_found = 0;
-    u64 rem = 0, c_found = 0;
-    if (mine) {
-#pragma unroll
-        for (int i = 0; i < kPerMax; ++i) {
-            if (before < r && r <= before + cnt[i]) {
-                bin_found = static_cast<u32>(nb - 1 - (lane * per + i));
-                rem = r - before;
-                c_found = cnt[i];
-            }
-            before += cnt[i];
-        }
-    }
-    const int src = __ffsll(static_cast<long long>(__ballot(mine))) - 1;   // exactly one lane
-    bin_found = __shfl(bin_found, src, 64);
-    rem = (static_cast<u64>(__shfl(static_cast<u32>(rem >> 32), src, 64)) << 32) | __shfl(static_cast<u32>(rem), src, 64);
-    c_found = (static_cast<u64>(__shfl(static_cast<u32>(c_found >> 32), src, 64)) << 32) | __shfl(static_cast<u32>(c_found), src, 64);
+    const bool mine = (cincl - csum) < r && r <= cincl;          // exactly one lane
+    const int src = __ffsll(static_cast<long long>(__ballot(mine))) - 1;
+    const int run_found = kCoarse - 1 - src;
+    u64 before = cincl - csum;
+    before = (static_cast<u64>(__shfl(static_cast<u32>(before >> 32), src, 64)) << 32) | __shfl(static_cast<u32>(before), src, 64);
+    // the bins of that run, highest first: lane l takes bin (run_found + 1) * run - 1 - l
+    const int bin = (run_found + 1) * run - 1 - lane;
+    const u64 f = (lane < run && bin < nb) ? hist_prev[bin] : 0;
+    const u64 fincl = wave_incl_scan_u64(f);
+    const bool mine2 = before + (fincl - f) < r && r <= before + fincl;
+    const int src2 = __ffsll(static_cast<long long>(__ballot(mine2))) - 1;
+    const u64 rem_l = r - (before + (fincl - f));
+    const u64 rem = (static_cast<u64>(__shfl(static_cast<u32>(rem_l >> 32), src2, 64)) << 32) | __shfl(static_cast<u32>(rem_l), src2, 64);
+    const u64 cnt = (static_cast<u64>(__shfl(static_cast<u32>(f >> 32), src2, 64)) << 32) | __shfl(static_cast<u32>(f), src2, 64);
+    const u32 bin_found = static_cast<u32>((run_found + 1) * run - 1 - src2);
     cur.prefix |= static_cast<u64>(bin_found) << lv.shift;
     cur.remaining = rem;
-    cur.n_tie = c_found;
+    cur.n_tie = cnt;
     if (L - 1 == n_levels(key_bits) - 1) {
         cur.state = kDone;
-        cur.need_tie = rem < c_found ? 1u : 0u;
+        cur.need_tie = rem < cnt ? 1u : 0u;
     }
     return cur;
 }
@@ -224,7 +229,8 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
     if (a.merged && level > 0) {          // one group; every workgroup derives the same state, workgroup 0 stores it
         const int n_waves = static_cast<int>(blockDim.x) >> 6;
         for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.J; j += n_waves) {
-            const SlotStep e = wave_enter_level(a.slots[j], level, 31, level == 1 ? a.hist0 : data_hist(a, level - 1, j));
+            const u64* prev = level == 1 ? a.hist0 : data_hist(a, level - 1, j);
+            const SlotStep e = wave_enter_level(a.slots[j], level, 31, prev, coarse_of(a.hist0, a.coarse, prev));
             if ((threadIdx.x & 63) == 0) {
                 s_mprefix[j] = static_cast<u32>(e.prefix);
                 s_mactive[j] = (e.state == kSelecting) ? 1u : 0u;
@@ -271,6 +277,19 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
                 u64* dst = (level == 0) ? a.hist0 + static_cast<u64>(group) * kBins + i
                                         : data_hist(a, level, static_cast<u64>(group) * a.J + j0 + i / nb) + (i % nb);
                 atomicAdd(reinterpret_cast<unsigned long long*>(dst), static_cast<unsigned long long>(v));
+            }
+        }
+        if (a.merged) {                                    // the coarse sums of the same counts
+            const int run = coarse_run(nb);
+            for (int i = wtid; i < n_hist * kCoarse; i += wide) {
+                const int h = i / kCoarse, c = i % kCoarse;
+                u32 v = 0;
+                for (int t = c * run; t < (c + 1) * run && t < nb; ++t) v += s_hist[h * nb + t];
+                if (v) {
+                    u64* fine = (level == 0) ? a.hist0 + static_cast<u64>(group) * kBins
+                                             : data_hist(a, level, static_cast<u64>(group) * a.J + j0 + h);
+                    atomicAdd(reinterpret_cast<unsigned long long*>(coarse_of(a.hist0, a.coarse, fine) + c), static_cast<unsigned long long>(v));
+                }
             }
         }
     };
@@ -453,7 +472,8 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
         if (threadIdx.x == 0) s_any = 0;
         __syncthreads();
         for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.J; j += kBlock / 64) {
-            const SlotStep e = wave_enter_level(a.slots[j], last + 1, 31, last == 0 ? a.hist0 : data_hist(a, last, j));
+            const u64* prev = last == 0 ? a.hist0 : data_hist(a, last, j);
+            const SlotStep e = wave_enter_level(a.slots[j], last + 1, 31, prev, coarse_of(a.hist0, a.coarse, prev));
             if ((threadIdx.x & 63) == 0) {
                 s_mT[j] = static_cast<u32>(e.prefix);
                 s_mneed[j] = (e.state == kDone && e.need_tie) ? 1u : 0u;
@@ -563,7 +583,8 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
         // ranking in this kernel) makes the outcome the ranking's stored state
         if (tid < 64) {
             const int last = n_levels(31) - 1;
-            const SlotStep e = wave_enter_level(slot, last + 1, 31, last == 0 ? a.hist0 : data_hist(a, last, s));
+            const u64* prev = last == 0 ? a.hist0 : data_hist(a, last, s);
+            const SlotStep e = wave_enter_level(slot, last + 1, 31, prev, coarse_of(a.hist0, a.coarse, prev));
             if (tid == 0) {
                 s_e = e;
                 if (slot.state == kSelecting) {

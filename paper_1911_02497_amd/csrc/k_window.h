@@ -65,6 +65,8 @@ struct ArrayArgs {
     int key_bits;
     int merged;            // 1: hist holds one histogram per level and ranking ([level][n_slots]) and every level
                            // kernel folds in the previous level itself (wave_enter_level); 0: k_scan_level in between
+    u64* hist_base;        // merged form: first histogram of the workspace and the coarse sums of all of them
+    u64* coarse;
 };
 
 __device__ inline u64* array_hist(const ArrayArgs& a, int level, int slot) {
@@ -118,6 +120,59 @@ __global__ __launch_bounds__(kBlock) void k_sample(DataArgs a, WindowArgs w) {
     if (tid == 0 && s_valid) atomicAdd(reinterpret_cast<unsigned long long*>(&a.ctl->sample_count), static_cast<unsigned long long>(s_valid));
 }
 
+// One density: the sample and the level-0 histogram of its keys in one kernel (the boundary rankings share
+// that level), so the sample is not read back for it.  Few wide workgroups: each flushes its LDS counts with
+// global atomics, which are slow on one address.
+constexpr int kSampleHistThreads = 1024;
+template <bool LC, bool VEC>
+__global__ __launch_bounds__(kSampleHistThreads) void k_sample_hist(DataArgs a, WindowArgs w, ArrayArgs ar) {
+    __shared__ u32 s_hist[kBins];
+    const int tid = threadIdx.x;
+    const Level L0 = level_of(31, 0);
+    for (int i = tid; i < kBins; i += kSampleHistThreads) s_hist[i] = 0;
+    __syncthreads();
+    for (u64 u = static_cast<u64>(blockIdx.x) * kSampleHistThreads + tid; u < w.n_units; u += static_cast<u64>(gridDim.x) * kSampleHistThreads) {
+        const u64 jitter = (w.stride > 1) ? static_cast<u64>(mix32(static_cast<u32>(u) ^ static_cast<u32>(u >> 32))) % w.stride : 0;
+        const u64 p = u * w.stride + jitter;             // quad position in chunk space
+        const u64 c = p / (kChunk / 4);
+        const u64 q = p % (kChunk / 4);
+        u32 key[4] = {kNoKey, kNoKey, kNoKey, kNoKey};
+        if (c < a.n_chunks) {
+            const int t = static_cast<int>(a.chunk_map[c]);
+            const TensorDesc& td = a.td[t];
+            const u64 e0 = (c - td.chunk_start) * kChunk + q * 4;
+            if (e0 < td.n) {
+                float v[4];
+                load4<VEC>(td.w, e0, td.n, v);
+                if (LC) {
+                    float l[4];
+                    load4<VEC>(td.lam, e0, td.n, l);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (e0 + k < td.n) {
+                        key[k] = mag_key(v[k]);
+                        atomicAdd(&s_hist[key[k] >> L0.shift], 1u);
+                    }
+            }
+        }
+        *reinterpret_cast<uint4*>(w.sample + u * 4) = make_uint4(key[0], key[1], key[2], key[3]);
+    }
+    __syncthreads();
+    const int run = coarse_run(kBins);
+    for (int i = tid; i < kBins; i += kSampleHistThreads) {
+        const u32 v = s_hist[i];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(ar.shared0 + i), static_cast<unsigned long long>(v));
+    }
+    if (tid < kCoarse) {
+        u32 v = 0;
+        for (int t = tid * run; t < (tid + 1) * run; ++t) v += s_hist[t];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(coarse_of(ar.hist_base, ar.coarse, ar.shared0) + tid), static_cast<unsigned long long>(v));
+    }
+}
+
 // Sample ranks that bound each density's threshold.  The number of sample keys above the true
 // threshold is (close to) binomial; sample units of kSampleUnit neighbours may be correlated, so the
 // standard deviation is taken as if every unit were one draw.
@@ -162,7 +217,7 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
     if (a.merged) {
         for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.n_slots; j += kArrayThreads / 64) {
             const u64* prev = (level == 1 && a.shared0) ? a.shared0 : array_hist(a, level > 0 ? level - 1 : 0, j);
-            const SlotStep e = wave_enter_level(a.slots[j], level, a.key_bits, prev);
+            const SlotStep e = wave_enter_level(a.slots[j], level, a.key_bits, prev, coarse_of(a.hist_base, a.coarse, prev));
             if ((threadIdx.x & 63) == 0) {
                 s_mprefix[j] = e.prefix;
                 s_mactive[j] = (e.state == kSelecting && static_cast<u32>(level) >= a.slots[j].level_begin) ? 1u : 0u;
@@ -252,6 +307,17 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
             for (int cpy = 0; cpy < copies; ++cpy) v += s_hist[cpy * words + i];
             if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + static_cast<u64>(i / nb) * kBins + (i % nb)),
                              static_cast<unsigned long long>(v));
+        }
+        if (a.merged) {                                  // the coarse sums of the same counts
+            const int run = coarse_run(nb);
+            for (int i = tid; i < nj * kCoarse; i += nt) {
+                const int h = i / kCoarse, c = i % kCoarse;
+                u32 v = 0;
+                for (int t = c * run; t < (c + 1) * run && t < nb; ++t)
+                    for (int cpy = 0; cpy < copies; ++cpy) v += s_hist[cpy * words + h * nb + t];
+                if (v) atomicAdd(reinterpret_cast<unsigned long long*>(coarse_of(a.hist_base, a.coarse, dst + static_cast<u64>(h) * kBins) + c),
+                                 static_cast<unsigned long long>(v));
+            }
         }
     }
 }
@@ -532,7 +598,11 @@ __global__ __launch_bounds__(kBlock) void k_window_check(DataArgs a, WindowArgs 
     const int n = static_cast<int>(s_win.n);
     for (int r = 0; r < n; ++r) {                        // region n (below every window) is not needed
         u64 part = 0;
-        for (u32 seg = tid; seg < w.n_segs; seg += kBlock) part += w.seg_region[static_cast<u64>(r) * kSegs + seg];
+        // one density: the upper halves belong to the one-sweep kernel's count of non-zero codes
+        for (u32 seg = tid; seg < w.n_segs; seg += kBlock) {
+            const u64 v = w.seg_region[static_cast<u64>(r) * kSegs + seg];
+            part += (a.J == 1) ? (v & 0xFFFFFFFFull) : v;
+        }
         u64 sum;
         block_excl_scan_u64(part, s_wave, &sum);
         if (tid == 0) s_region[r] = sum;
@@ -629,7 +699,8 @@ __global__ __launch_bounds__(kBlock) void k_window_bounds(ArrayArgs ar) {
     const int j = threadIdx.x >> 6;
     if (j >= ar.n_slots) return;
     Slot& s = ar.slots[j];
-    const SlotStep e = wave_enter_level(s, 2, 31, array_hist(ar, 1, j));
+    const u64* prev = array_hist(ar, 1, j);
+    const SlotStep e = wave_enter_level(s, 2, 31, prev, coarse_of(ar.hist_base, ar.coarse, prev));
     if ((threadIdx.x & 63) != 0) return;
     const u32 low = (1u << level_of(31, 1).shift) - 1u;
     u32 key = s.rank_rule == kRankHi ? 0x7FFFFFFFu : 0u;                 // no bound
@@ -649,7 +720,8 @@ __global__ __launch_bounds__(kBlock) void k_window_bounds(ArrayArgs ar) {
 __global__ __launch_bounds__(kBlock) void k_window_ties(DataArgs a, WindowArgs w, ArrayArgs ar) {
     __shared__ SlotStep s_e;
     if (threadIdx.x < 64) {
-        const SlotStep e = wave_enter_level(a.slots[0], n_levels(31), 31, array_hist(ar, n_levels(31) - 1, 0));
+        const u64* prev = array_hist(ar, n_levels(31) - 1, 0);
+        const SlotStep e = wave_enter_level(a.slots[0], n_levels(31), 31, prev, coarse_of(ar.hist_base, ar.coarse, prev));
         if (threadIdx.x == 0) s_e = e;
     }
     __syncthreads();
@@ -693,7 +765,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_window_finish1(DataArgs a, W
     const u32 state0 = s.state;
     if (state0 != kSelecting && state0 != kFailed) return;               // k == 0: nothing was ranked
     if (tid < 64) {
-        const SlotStep e = wave_enter_level(s, n_levels(31), 31, array_hist(ar, n_levels(31) - 1, 0));
+        const u64* prev = array_hist(ar, n_levels(31) - 1, 0);
+        const SlotStep e = wave_enter_level(s, n_levels(31), 31, prev, coarse_of(ar.hist_base, ar.coarse, prev));
         if (tid == 0) s_e = e;
     }
     __syncthreads();
@@ -883,15 +956,16 @@ static condensa_status launch_window_path_single(const DataArgs& a, const Layout
     condensa_status rc;
     {
         PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
-        hipLaunchKernelGGL((k_sample<LC, VEC>), dim3(static_cast<unsigned>((w.n_units + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a, w);
-        CONDENSA_LAUNCH_CHECK();
         ArrayArgs ar{};
         ar.keys = w.sample; ar.n_host = w.n_units * kSampleUnit; ar.slots = w.wslots; ar.n_slots = 3;
         ar.hist = w.hist_aux; ar.key_bits = 31; ar.shared0 = w.hist_shared0; ar.merged = 1;
-        for (int level = 0; level < 2; ++level) {
-            hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(ar.n_host)), dim3(kArrayThreads), 0, st, ar, level);
-            CONDENSA_LAUNCH_CHECK();
-        }
+        ar.hist_base = a.hist0; ar.coarse = a.coarse;
+        u64 sample_groups = (w.n_units + kSampleHistThreads - 1) / kSampleHistThreads;
+        if (sample_groups > 512) sample_groups = 512;
+        hipLaunchKernelGGL((k_sample_hist<LC, VEC>), dim3(static_cast<unsigned>(sample_groups)), dim3(kSampleHistThreads), 0, st, a, w, ar);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(ar.n_host)), dim3(kArrayThreads), 0, st, ar, 1);
+        CONDENSA_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_window_bounds, dim3(1), dim3(kBlock), 0, st, ar);
         CONDENSA_LAUNCH_CHECK();
     }
@@ -906,7 +980,7 @@ static condensa_status launch_window_path_single(const DataArgs& a, const Layout
     ArrayArgs cr{};
     cr.keys = w.cand_key; cr.seg_cnt = w.seg_cnt; cr.seg_cap = w.seg_cap; cr.n_segs = w.n_segs;
     cr.n_host = static_cast<u64>(w.n_segs) * kBlock * 8; cr.slots = a.slots; cr.n_slots = 1;
-    cr.hist = w.hist_main; cr.key_bits = 31; cr.merged = 1;
+    cr.hist = w.hist_main; cr.key_bits = 31; cr.merged = 1; cr.hist_base = a.hist0; cr.coarse = a.coarse;
     for (int level = 0; level < n_levels(31); ++level) {
         hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(cr.n_host)), dim3(kArrayThreads), 0, st, cr, level);
         CONDENSA_LAUNCH_CHECK();

@@ -120,14 +120,14 @@ def test_overlapping_buffers_are_rejected():
     th, keep = table(A, Bf)
     assert lib.condensa_prune(t2, 2, dens, 1, 0, th, None, None, res, ws, tiny, None, None) == -5
 
-    def lc(lam=LAM, lam_out=A, theta=Bf, grad=C, mask=D, f16=None):
+    def lc(lam=LAM, lam_out=A, theta=Bf, grad=C, mask=D, f16=None, nnz=None):
         tabs = {k: table(v) if v is not None else (None, None) for k, v in
                 dict(lam=lam, lam_out=lam_out, theta=theta, grad=grad, mask=mask, f16=f16).items()}
         if f16 is None:
             return lib.condensa_lc_step(t, 1, tabs["lam"][0], tabs["lam_out"][0], 1e-3, 0.5, tabs["theta"][0],
                                         tabs["grad"][0], tabs["mask"][0], res, ws, tiny, None, None)
         return lib.condensa_lc_step_pq(t, 1, tabs["lam"][0], tabs["lam_out"][0], 1e-3, 0.5, tabs["theta"][0],
-                                       tabs["f16"][0], tabs["grad"][0], tabs["mask"][0], res, ws, tiny, None, None)
+                                       tabs["f16"][0], tabs["grad"][0], tabs["mask"][0], nnz, res, ws, tiny, None, None)
 
     assert lc() == -5
     assert lc(lam_out=None) == -5                                 # lambda updated in place
@@ -142,6 +142,8 @@ def test_overlapping_buffers_are_rejected():
     assert lc(mask=LAM + 100) == -6
     assert lc(f16=E) == -5
     assert lc(f16=Bf + 2) == -6
+    assert lc(f16=E, nnz=ctypes.c_void_p(E + 2 * n)) == -5          # the count directly behind the codes: fine
+    assert lc(f16=E, nnz=ctypes.c_void_p(E + 2 * n - 8)) == -6      # ... inside them
 
     # structure pruning: in-place theta is allowed, everything else must be disjoint
     t4 = (B.Tensor * 1)()

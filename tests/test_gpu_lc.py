@@ -97,7 +97,7 @@ def test_pq_step_against_the_oracle():
     ws, ls = _gauss(shapes, 11, 0.01), _gauss(shapes, 12, 0.01)
     ws[1][0, :8] = np.float32(1e-9)                     # tiny values: underflow to zero in binary16 if kept
     for mu, d in ((1e-3, 0.1), (1e-3, 1.0), (50.0, 0.5)):
-        res = lc_step_pq(up(ws), up(ls), mu, d)
+        res = lc_step_pq(up(ws), up(ls), mu, d, nnz=True)
         torch.cuda.synchronize()
         ora = oracle.lc_step_pq(ws, ls, mu, d)
         assert_select_equal(P.select_records(res["results"])[0], ora["select"], f"mu={mu} d={d}")
@@ -108,6 +108,8 @@ def test_pq_step_against_the_oracle():
                 assert_bits_equal(res[name][t], ora[name][t], f"{name} {t} mu={mu} d={d}")
         nnz = int(P.condensa_count_nonzero(res["theta_f16"]).item())
         assert nnz == oracle.count_nonzero(ora["theta_f16"])
+        # the same objective as a by-product of the step: k less the kept values that underflow in binary16
+        assert int(res["nnz"].item()) == oracle.count_nonzero(ora["theta_f16"]), f"fused non-zero count, mu={mu} d={d}"
         nnz32 = int(P.condensa_count_nonzero(res["theta"]).item())
         assert nnz32 == oracle.count_nonzero(ora["theta"])
 

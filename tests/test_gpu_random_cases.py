@@ -78,7 +78,7 @@ def test_lc_step_random(seed):
     d = float(rng.choice([0.0, 1.0, rng.random(), rng.random() ** 3]))
     # the composed scheme only where theta stays finite in binary16 (inf - inf would compare NaN payloads)
     pq = bool(rng.random() < 0.4) and max((float(np.abs(w).max()) if w.size else 0.0) for w in ws) < 1e4
-    res = (P.condensa_lc_step_pq if pq else P.condensa_lc_step)(up(ws), up(ls), mu, d)
+    res = lc_step_pq(up(ws), up(ls), mu, d, nnz=True) if pq else lc_step(up(ws), up(ls), mu, d)
     torch.cuda.synchronize()
     ora = (oracle.lc_step_pq if pq else oracle.lc_step)(ws, ls, mu, d)
     what = f"seed {seed} mu {mu} d {d} pq {pq}"
@@ -89,6 +89,8 @@ def test_lc_step_random(seed):
             assert_bits_equal(res[name][t], ora[name][t], f"{what} {name} {t}")
         if pq:
             assert np.array_equal(res["theta_f16"][t].cpu().numpy().view(np.uint16), ora["theta_f16"][t]), f"{what} f16 {t}"
+    if pq:
+        assert int(res["nnz"].item()) == oracle.count_nonzero(ora["theta_f16"]), f"{what} fused non-zero count"
 
 
 @pytest.mark.parametrize("scope", [P.SCOPE_GLOBAL, P.SCOPE_PER_TENSOR])
