@@ -145,7 +145,8 @@ def make_workload(name, args, P, workloads, torch, dev, resident=None):
     import oracle
     up = lambda arrs: P.tensor_table([torch.from_numpy(a).to(dev) for a in arrs])  # noqa: E731  (marshalled once)
     cfg = P.condensa_config(select_path=args.select_path, fused_sweep=1 if args.two_sweeps else 0,
-                            window_margin=args.window_margin, profile=(1 << 1) if name == "prune_stress" else 0)
+                            window_margin=args.window_margin, apply_threads=args.apply_threads,
+                            profile=(1 << 1) if name == "prune_stress" else 0)
     prev, ws = [None], [None]
     F, J, scope_ws, sample, host = 0, 1, P.SCOPE_GLOBAL, None, None
     if name.endswith("_stress") and resident is None:

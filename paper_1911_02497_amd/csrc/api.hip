@@ -9,6 +9,7 @@
 #include "k_select.h"
 #include "k_structure.h"
 #include "k_window.h"
+#include "k_struct_fused.h"
 
 namespace condensa {
 
@@ -189,7 +190,7 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     size_t off = 0;
     L.td = off;     off += align_up(static_cast<size_t>(n_tensors + 1) * sizeof(TensorDesc));
     L.out = off;    off += align_up(static_cast<size_t>(J) * (n_tensors > 0 ? n_tensors : 1) * sizeof(OutDesc));
-    L.slots = off;  off += align_up(static_cast<size_t>(L.n_slots) * sizeof(Slot) + (structure ? 0 : 2 * kMaxJ * sizeof(Slot)));
+    L.slots = off;  off += align_up(static_cast<size_t>(L.n_slots) * sizeof(Slot) + (structure ? 3 : 2 * kMaxJ) * sizeof(Slot));
     L.upload_bytes = off;
     L.zero_begin = off;
     L.ctl = off;    off += align_up(sizeof(Control));
@@ -199,10 +200,12 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     // shared level 0 (see make_window_args)
     size_t n_hx = 2u * static_cast<size_t>(L.n_slots);
     if (!structure && !per_tensor) n_hx += 3u * J + 2u * (2u * J + 1u) + 1u;
+    if (structure && !per_tensor) n_hx += 2u * 3u + 1u;     // one-sweep block pruning: the block sample's boundary rankings
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
     // coarse sums of every histogram from hist0 on (the two regions above are contiguous: their sizes are multiples of 16 KB)
     L.histc = off;  off += align_up((static_cast<size_t>(L.n_groups) + n_hx) * kCoarse * sizeof(u64));
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (2 + kMaxJ) * sizeof(u64)); }
+    if (structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * 2 * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
     const u64 tie_chunks = structure ? L.max_schunks : ((op == CONDENSA_OP_COUNT_NONZERO || op == CONDENSA_OP_LC_SGD_STEP) ? 0 : L.max_chunks);
@@ -211,6 +214,14 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
         L.smask = off;  off += align_up(static_cast<size_t>(F) + 1);
+        if (!per_tensor) {                                  // one-sweep block pruning: sample keys and the list of window blocks
+            u64 sc = F / 8;
+            sc = sc < (1u << 12) ? (1u << 12) : (sc > (1u << 17) ? (1u << 17) : sc);
+            L.sample_cap = sc;
+            L.cand_cap = F / 8 < 4096 ? 4096 : F / 8;
+            L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
+            L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
+        }
     } else if (!per_tensor && !no_window && op != CONDENSA_OP_COUNT_NONZERO && op != CONDENSA_OP_LC_SGD_STEP) {
         L.sample_cap = window_sample_size(N, cfg);
         L.cand_cap = window_cand_capacity(N, J, cfg);
@@ -962,15 +973,32 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     if (ranges_conflict(ranges.data(), ranges.size())) return CONDENSA_ERR_ARG;
     condensa_status rc = check_workspace(workspace_dev, workspace_bytes, L);
     if (rc != CONDENSA_OK) return rc;
-    std::vector<Slot> slots(static_cast<size_t>(L.n_slots));
+    std::vector<Slot> slots(static_cast<size_t>(L.n_slots) + 3);
     for (int g = 0; g < L.n_groups; ++g) {
         const u64 n = per_tensor ? tb.td[g].n_struct : tb.F;
         init_slot(&slots[g], n, kept_count(density, n), 1u);
     }
+    // One sweep for aggregation AND apply (k_struct_fused.h): 8x8 blocks, every matrix a whole number of 64-block
+    // runs wide, 128-bit accesses everywhere, outputs apart from the weights, a threshold strictly inside the
+    // population, and enough blocks for the sample to pay (or the form asked for).
+    bool fused = !per_tensor && (theta || mask) && vec && tb.F > kSmallGroup && slots[0].k > 0 && slots[0].k < tb.F &&
+                 (cfg[CONDENSA_OPT_SELECT_PATH] == 2 || (cfg[CONDENSA_OPT_SELECT_PATH] == 0 && tb.F >= (static_cast<u64>(1) << 20))) &&
+                 cfg[CONDENSA_OPT_FUSED_SWEEP] == 0;
+    for (int t = 0; t < n_tensors && fused; ++t) {
+        const TensorDesc& d = tb.td[t];
+        if (d.n == 0) continue;
+        const bool ok = d.d[0] == 1 && d.d[1] == 1 && d.b[2] == 8 && d.b[3] == 8 && d.d[2] % 8 == 0 && d.d[3] % 512 == 0 &&
+                        aligned16(d.w) && d.n <= 0xFFFFFFFFull && out[t].theta != d.w;
+        if (!ok) fused = false;
+    }
+    if (fused) {
+        init_sample_slots(&slots[L.n_slots], slots[0], cfg[CONDENSA_OPT_WINDOW_MARGIN]);
+        slots[0].path = 2;
+    }
     std::vector<char> up(L.upload_bytes, 0);
     std::memcpy(up.data() + L.td, tb.td, static_cast<size_t>(tb.n_td) * sizeof(TensorDesc));
     std::memcpy(up.data() + L.out, out.data(), out.size() * sizeof(OutDesc));
-    std::memcpy(up.data() + L.slots, slots.data(), slots.size() * sizeof(Slot));
+    std::memcpy(up.data() + L.slots, slots.data(), (static_cast<size_t>(L.n_slots) + (fused ? 3 : 0)) * sizeof(Slot));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = stage_upload(workspace_dev, up.data(), L.upload_bytes, st);
     if (rc != CONDENSA_OK) return rc;
@@ -1001,6 +1029,34 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     bool small = tb.F > 0 && cfg[CONDENSA_OPT_SELECT_PATH] != 1;
     if (per_tensor) { for (int t = 0; t < n_tensors && small; ++t) if (tb.td[t].n_struct > kSmallGroup) small = false; }
     else if (tb.F > kSmallGroup) small = false;
+    StructWindowArgs sw{};
+    if (fused) {
+        sw.sample = at<u32>(workspace_dev, L.sample);
+        sw.n_units = L.sample_cap < tb.F ? L.sample_cap : tb.F;
+        sw.stride = tb.F / sw.n_units;
+        sw.wslots = a.slots + L.n_slots;
+        sw.seg_cnt = at<u64>(workspace_dev, L.seg);
+        sw.seg_above = sw.seg_cnt + kSegs;
+        sw.cand_id = at<u32>(workspace_dev, L.cand_key);
+        sw.n_segs = sblocks < static_cast<unsigned>(kSegs) ? sblocks : static_cast<unsigned>(kSegs);   // at most the sweep's grid
+        sw.seg_cap = L.cand_cap / sw.n_segs;
+        sw.out = at<OutDesc>(workspace_dev, L.out);
+        PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
+        ArrayArgs ar{};
+        ar.keys = sw.sample; ar.n_host = sw.n_units; ar.slots = sw.wslots; ar.n_slots = 3;
+        ar.hist = a.histx + static_cast<u64>(2 * L.n_slots) * kBins;          // [2][3], behind the aggregate rankings' histograms
+        ar.shared0 = ar.hist + static_cast<u64>(6) * kBins;
+        ar.key_bits = 31; ar.merged = 1;
+        ar.hist_base = at<u64>(workspace_dev, L.hist0); ar.coarse = at<u64>(workspace_dev, L.histc);
+        u64 sg = (sw.n_units + kSampleHistThreads - 1) / kSampleHistThreads;
+        if (sg > 512) sg = 512;
+        hipLaunchKernelGGL(k_struct_sample_hist, dim3(static_cast<unsigned>(sg)), dim3(kSampleHistThreads), 0, st, a, sw, ar);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_hist_array<false>), dim3(hist_array_grid(ar.n_host)), dim3(kArrayThreads), 0, st, ar, 1);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_window_bounds, dim3(1), dim3(kBlock), 0, st, ar);
+        CONDENSA_LAUNCH_CHECK();
+    }
     if (tb.F > 0) {
         {
             PhaseTimer timer(CONDENSA_PHASE_AGGREGATE, st, cfg);
@@ -1023,7 +1079,13 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
                 if (!ok) tiles = false;
                 tile_w = d.b[3];
             }
-            if (rows && tb.F <= kFewRowsMax)
+            if (fused && cfg[CONDENSA_OPT_APPLY_THREADS] == 256)
+                hipLaunchKernelGGL((k_struct_tiles_fused<256>), dim3(sblocks), dim3(256), 0, st, a, sw, sumsq_dev, norms_dev);
+            else if (fused && cfg[CONDENSA_OPT_APPLY_THREADS] == 128)
+                hipLaunchKernelGGL((k_struct_tiles_fused<128>), dim3(static_cast<unsigned>((tb.F + 127) / 128)), dim3(128), 0, st, a, sw, sumsq_dev, norms_dev);
+            else if (fused)
+                hipLaunchKernelGGL((k_struct_tiles_fused<64>), dim3(static_cast<unsigned>((tb.F + 63) / 64)), dim3(64), 0, st, a, sw, sumsq_dev, norms_dev);
+            else if (rows && tb.F <= kFewRowsMax)
                 hipLaunchKernelGGL(k_struct_sumsq_rows_few, dim3(static_cast<unsigned>((tb.F + kFewRows - 1) / kFewRows)), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else if (rows) hipLaunchKernelGGL(k_struct_sumsq_rows, dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
             else if (tiles && tile_w == 4)  hipLaunchKernelGGL((k_struct_sumsq_tiles<1>), dim3(sblocks), dim3(kBlock), 0, st, a, sumsq_dev, norms_dev);
@@ -1069,7 +1131,17 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             hipLaunchKernelGGL(k_struct_keep_idx, dim3(mtiles), dim3(kBlock), 0, st, a, keep_idx_dev);
             CONDENSA_LAUNCH_CHECK();
         }
-        if ((theta || mask) && tb.n_chunks > 0) {
+        if (fused) {
+            PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
+            const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
+            hipLaunchKernelGGL(k_struct_window_check, dim3(1), dim3(kBlock), 0, st, a, sw);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_struct_fixup, dim3(sw.n_segs * kFixupParts), dim3(kBlock), 0, st, a, sw);
+            CONDENSA_LAUNCH_CHECK();
+            const u64 n_tiles = tb.n_chunks * kSubPerChunk;
+            hipLaunchKernelGGL((k_struct_apply_gated<true>), dim3(static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096)), dim3(kBlock), 0, st, a, od, n_tiles);
+            CONDENSA_LAUNCH_CHECK();
+        } else if ((theta || mask) && tb.n_chunks > 0) {
             PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
             if (vec) hipLaunchKernelGGL((k_struct_apply<true>), dim3(static_cast<unsigned>(tb.n_chunks * kSubPerChunk)), dim3(kBlock), 0, st, a, od);

@@ -827,9 +827,9 @@ __global__ __launch_bounds__(kBlock) void k_struct_keep_idx(StructArgs a, int32_
 
 // theta = w on kept structures, +0 elsewhere; element mask = structure mask broadcast
 template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const OutDesc* __restrict__ out) {
-    const u64 c = blockIdx.x / kSubPerChunk;
-    const u32 sub = blockIdx.x % kSubPerChunk;
+__device__ inline void struct_apply_tile(const StructArgs& a, const OutDesc* __restrict__ out, u64 tile) {
+    const u64 c = tile / kSubPerChunk;
+    const u32 sub = static_cast<u32>(tile % kSubPerChunk);
     if (c >= a.n_chunks) return;
     const int tid = threadIdx.x;
     const int t = static_cast<int>(a.chunk_map[c]);
@@ -906,6 +906,11 @@ __global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const Out
         if (o.theta) store4<VEC>(o.theta, e0, n, th);
         if (o.mask) store4_u8<VEC>(o.mask, e0, n, m);
     }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_struct_apply(StructArgs a, const OutDesc* __restrict__ out) {
+    struct_apply_tile<VEC>(a, out, blockIdx.x);
 }
 
 // Thinning gather: out[o', i', r] = w[keep_out[o'] - off_out, keep_in[i'] - off_in, r]; NULL list = identity.

@@ -17,11 +17,13 @@ neuron_prune = with_form(P.condensa_neuron_prune, fill_keep_idx=True)
 structure_prune = with_form(P.condensa_structure_prune, fill_keep_idx=True)
 
 
-@pytest.fixture(params=["auto", "launch_per_level"], autouse=True)
+@pytest.fixture(params=["auto", "launch_per_level", "one_sweep"], autouse=True)
 def ranking_form(request):
     """Every case runs with the default choice (one workgroup per group ranks, masks and lists groups of up
-    to 4 096 structures) and with the general form (one histogram and one scan launch per radix level)."""
-    Form.config = {"select_path": 1} if request.param == "launch_per_level" else None
+    to 4 096 structures), with the general form (one histogram and one scan launch per radix level), and with
+    aggregation and apply in one sweep wherever the call allows it (8x8 blocks that tile matrices a multiple of
+    512 wide, more than 4 096 of them; every other call takes the general form)."""
+    Form.config = {"launch_per_level": {"select_path": 1}, "one_sweep": {"select_path": 2}}.get(request.param)
     yield request.param
     Form.config = None
 
@@ -131,6 +133,60 @@ def test_exactly_tiled_blocks_of_width_4_8_16_32(bh, bw):
         res = block_prune(up(ms), bh, bw, 0.37, scope)
         torch.cuda.synchronize()
         _compare(res, oracle.block_prune(ms, bh, bw, 0.37, scope), scope, ms, f"{bh}x{bw} scope={scope}")
+
+
+def test_block_prune_8x8_aggregation_and_apply_in_one_sweep():
+    """The one-sweep form on its own: matrices a multiple of 512 wide, duplicated blocks at the threshold
+    (ties cut by id), a third of the blocks all zero (a tie class that overflows the window's list at high
+    density: the gated apply takes over), a window of zero margin that misses, theta or mask alone, and the
+    in-place call, which must take the two-sweep form."""
+    rng = np.random.default_rng(808)
+    ms = [(rng.standard_normal(s) * 0.02).astype(np.float32) for s in ((64, 1024), (256, 512), (8, 512), (512, 2048))]
+    ms[3][8:16, 16:24] = ms[3][0:8, 0:8]                  # exact ties between blocks
+    ms[3][304:312, 1000:1008] = ms[3][0:8, 0:8]
+    ms[0][:, 512:] = 0.0                                  # 512 blocks of all zeros
+    dev = up(ms)
+    n_blocks = sum(m.size for m in ms) // 64
+    assert n_blocks > 4096
+    for cfg, dens in (({"select_path": 2}, (0.25, 0.5, 0.9, 0.985, 1.0 / n_blocks)),
+                      ({"select_path": 2, "window_margin": 0}, (0.3,)),
+                      ({"select_path": 2, "fused_sweep": 1}, (0.3,)),
+                      ({"select_path": 0}, (0.3,))):
+        for d in dens:
+            ora = oracle.block_prune(ms, 8, 8, d, P.SCOPE_GLOBAL)
+            res = P.condensa_block_prune(dev, 8, 8, d, P.SCOPE_GLOBAL, config=cfg, fill_keep_idx=True)
+            torch.cuda.synchronize()
+            _compare(res, ora, P.SCOPE_GLOBAL, ms, f"one sweep {cfg} d={d}")
+            want_path = 2 if (cfg.get("select_path") == 2 and not cfg.get("fused_sweep")) else 1
+            assert P.select_records(res["results"])[0]["path"] == want_path, (cfg, d)
+    # the threshold on a duplicated block: the tie rule decides inside the window
+    key = float((ms[3][0:8, 0:8].astype(np.float64) ** 2).sum())
+    sums = np.concatenate([(m.reshape(m.shape[0] // 8, 8, m.shape[1] // 8, 8).astype(np.float64) ** 2).sum(axis=(1, 3)).reshape(-1) for m in ms])
+    d_tie = (int((sums > key).sum()) + 2) / n_blocks      # keep two of the three tied blocks
+    ora = oracle.block_prune(ms, 8, 8, d_tie, P.SCOPE_GLOBAL)
+    if ora["select"]["n_tie"] == 3:                       # (the row-major sums above agree with the oracle's up to rounding)
+        assert ora["select"]["n_tie_kept"] == 2
+    res = P.condensa_block_prune(dev, 8, 8, d_tie, P.SCOPE_GLOBAL, config={"select_path": 2}, fill_keep_idx=True)
+    torch.cuda.synchronize()
+    _compare(res, ora, P.SCOPE_GLOBAL, ms, "one sweep, threshold on tied blocks")
+    # single outputs
+    ora = oracle.block_prune(ms, 8, 8, 0.4, P.SCOPE_GLOBAL)
+    res = P.condensa_block_prune(dev, 8, 8, 0.4, P.SCOPE_GLOBAL, config={"select_path": 2}, mask=False)
+    torch.cuda.synchronize()
+    for t in range(len(ms)):
+        assert_bits_equal(res["theta"][t], ora["theta"][t], f"theta only {t}")
+    res = P.condensa_block_prune(dev, 8, 8, 0.4, P.SCOPE_GLOBAL, config={"select_path": 2}, theta=False)
+    torch.cuda.synchronize()
+    for t in range(len(ms)):
+        assert np.array_equal(res["mask"][t].cpu().numpy(), ora["mask"][t]), f"mask only {t}"
+    assert P.select_records(res["results"])[0]["path"] == 2
+    # in place: the weights are the output, so they are read twice
+    inplace = up(ms)
+    res = P.condensa_block_prune(inplace, 8, 8, 0.4, P.SCOPE_GLOBAL, config={"select_path": 2}, outputs={"_buffers": {"theta": inplace}})
+    torch.cuda.synchronize()
+    assert P.select_records(res["results"])[0]["path"] == 1
+    for t in range(len(ms)):
+        assert_bits_equal(inplace[t], ora["theta"][t], f"in place {t}")
 
 
 def test_shape_errors():
