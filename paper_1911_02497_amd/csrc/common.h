@@ -155,35 +155,65 @@ __device__ inline float4 ld4_stream(const float* p) {
     const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     return make_float4(t.x, t.y, t.z, t.w);
 }
-// The store carries the system-scope bits together with the non-temporal one (write straight through,
-// keep nothing): on the L-C mix of 2 streams read and 3 written this measured 1.5-2 % faster than the
-// non-temporal bit alone, which is all the compiler's builtin sets.  Nothing in a kernel reads these
-// locations again, so the statement needs no ordering against the kernel's other accesses.  The s_nop
-// covers the two wait states that gfx940-class hardware wants between a vector store of more than 64
-// bits and a vector write of its data registers: the compiler cannot see inside the statement and might
-// reuse those registers in the very next instruction.
-__device__ inline void st4_stream(float* p, float a, float b, float c, float d) {
-    f32x4 t;
-    t.x = a; t.y = b; t.z = c; t.w = d;
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
+// The stores carry the system-scope bits together with the non-temporal one (write straight through, keep
+// nothing): on the L-C mix of 2 streams read and 3 written this measured 1.5-2 % faster than the non-temporal
+// bit alone, which is all that __builtin_nontemporal_store sets.  They are raw buffer stores, the one store
+// form whose cache-policy bits the compiler exposes (sc0 = 1, nt = 2, sc1 = 16), so the compiler schedules them
+// and keeps the wait states that the hardware wants between a wide store and a rewrite of its data registers
+// -- nothing here is hand-written assembly.  The buffer descriptor is built around the address of the
+// wavefront's first active lane and every lane adds its distance from it; all callers store to addresses that
+// ascend with the lane, within a few KB.  A lane that broke that rule would fall outside the descriptor's
+// 2 GB range and its store would be dropped, which the parity tests would show.
+// Building the library with -DCONDENSA_PLAIN_STREAM_STORES swaps in the compiler's own non-temporal global
+// stores, to cross-check a parity failure against.
+constexpr int kStreamPolicy = 1 | 2 | 16;
+__device__ inline u32 stream_offset(const void* p, __amdgpu_buffer_rsrc_t* rsrc) {
+    const u64 a = reinterpret_cast<u64>(p);
+    // (the builtin returns a signed int: without the casts its lower half would be sign-extended into the upper one)
+    const u32 base_hi = static_cast<u32>(__builtin_amdgcn_readfirstlane(static_cast<int>(a >> 32)));
+    const u32 base_lo = static_cast<u32>(__builtin_amdgcn_readfirstlane(static_cast<int>(a)));
+    const u64 base = (static_cast<u64>(base_hi) << 32) | static_cast<u64>(base_lo);
+    *rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+    return static_cast<u32>(a - base);
 }
-
-// Four mask bytes / four 16-bit codes as one store with the streaming hint (p 4- / 8-byte aligned).
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void st_words4_stream(void* p, u32x4 t) {          // sixteen bytes (p 16-byte aligned)
+#if defined(CONDENSA_PLAIN_STREAM_STORES)
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+#else
+    __amdgpu_buffer_rsrc_t r;
+    const u32 off = stream_offset(p, &r);
+    __builtin_amdgcn_raw_buffer_store_b128(t, r, off, 0, kStreamPolicy);
+#endif
+}
+__device__ inline void st4_stream(float* p, float a, float b, float c, float d) {
+    u32x4 t;
+    t.x = __float_as_uint(a); t.y = __float_as_uint(b); t.z = __float_as_uint(c); t.w = __float_as_uint(d);
+    st_words4_stream(p, t);
+}
+// Four mask bytes / four 16-bit codes as one store (p 4- / 8-byte aligned).
 __device__ inline void st_mask4_stream(u8* p, u8 a, u8 b, u8 c, u8 d) {
     const u32 t = static_cast<u32>(a) | (static_cast<u32>(b) << 8) | (static_cast<u32>(c) << 16) | (static_cast<u32>(d) << 24);
-    asm volatile("global_store_dword %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
+#if defined(CONDENSA_PLAIN_STREAM_STORES)
+    __builtin_nontemporal_store(t, reinterpret_cast<u32*>(p));
+#else
+    __amdgpu_buffer_rsrc_t r;
+    const u32 off = stream_offset(p, &r);
+    __builtin_amdgcn_raw_buffer_store_b32(t, r, off, 0, kStreamPolicy);
+#endif
 }
 __device__ inline void st_code4_stream(u16* p, u16 a, u16 b, u16 c, u16 d) {
-    typedef u32 u32x2 __attribute__((ext_vector_type(2)));
     u32x2 t;
     t.x = static_cast<u32>(a) | (static_cast<u32>(b) << 16);
     t.y = static_cast<u32>(c) | (static_cast<u32>(d) << 16);
-    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
-}
-// sixteen bytes of packed codes
-typedef u32 u32x4 __attribute__((ext_vector_type(4)));
-__device__ inline void st_words4_stream(void* p, u32x4 t) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
+#if defined(CONDENSA_PLAIN_STREAM_STORES)
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+#else
+    __amdgpu_buffer_rsrc_t r;
+    const u32 off = stream_offset(p, &r);
+    __builtin_amdgcn_raw_buffer_store_b64(t, r, off, 0, kStreamPolicy);
+#endif
 }
 
 // Loads up to four consecutive elements e0 .. e0+3 of an n-element array; missing ones read 0.
