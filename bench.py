@@ -95,6 +95,7 @@ def parse():
     ap.add_argument("--summarize-trace", metavar="DIR", help="rocprofv3 --kernel-trace --stats output directory")
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="output directories of the rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs")
+    ap.add_argument("--summarize-counters", metavar="DIR", help="output directory of a rocprofv3 --pmc run: per-kernel averages of every counter")
     ap.add_argument("--title", default="", help="summaries: heading")
     ap.add_argument("--command", default="", help="summaries: the profiled command, quoted in the file")
     ap.add_argument("--bytes-per-launch", action="append", default=[], metavar="KERNEL=BYTES",
@@ -424,6 +425,39 @@ def summarize_pmc(args):
     print("wrote", args.out)
 
 
+def summarize_counters(args):
+    """Per-kernel averages of whatever counters one rocprofv3 --pmc run collected, plus the ratios that the
+    design notes quote: LDS bank-conflict cycles per LDS-active cycle and mean waves per SIMD."""
+    files = glob.glob(os.path.join(args.summarize_counters, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        sys.exit(f"no *counter_collection.csv under {args.summarize_counters}")
+    acc, order = {}, []
+    for r in csv.DictReader(open(sorted(files)[0])):
+        k, c = _short(r["Kernel_Name"]), r["Counter_Name"]
+        if c not in order:
+            order.append(c)
+        acc.setdefault(k, {}).setdefault(c, []).append(float(r["Counter_Value"]))
+    lines = [f"# rocprofv3 --pmc summary: {args.title}", "",
+             "Command (from /tmp with TMPDIR=/tmp; $R = repository root):", "", "    " + args.command, "",
+             "Averages per dispatch, one MI355X (256 compute units, 4 SIMDs each, at most 8 waves per SIMD):", "",
+             "| kernel | dispatches | " + " | ".join(order) + " | LDS conflict cycles / LDS active cycles | mean waves per SIMD |",
+             "|---|---:|" + "---:|" * (len(order) + 2)]
+    def avg(k, c):
+        v = acc[k].get(c)
+        return sum(v) / len(v) if v else None
+    for k in sorted(acc, key=lambda k: -(avg(k, "SQ_BUSY_CYCLES") or 0))[:16]:
+        n = len(next(iter(acc[k].values())))
+        conf, act = avg(k, "SQ_LDS_BANK_CONFLICT"), avg(k, "SQ_LDS_IDX_ACTIVE")
+        wc, gui = avg(k, "SQ_WAVE_CYCLES"), avg(k, "GRBM_GUI_ACTIVE")
+        ratio = f"{conf / act:.3f}" if conf is not None and act else "-"
+        # OccupancyPercent = 400 SQ_WAVE_CYCLES / GRBM_GUI_ACTIVE / CU_NUM / 32 of at most 8 waves per SIMD
+        occ = f"{wc / gui / 256:.2f}" if wc is not None and gui else "-"
+        lines.append(f"| `{k}` | {n} | " + " | ".join(f"{avg(k, c):,.0f}" if avg(k, c) is not None else "-" for c in order) +
+                     f" | {ratio} | {occ} |")
+    open(args.out, "w").write("\n".join(lines) + "\n")
+    print("wrote", args.out)
+
+
 # ---- the benchmark ---------------------------------------------------------------------------------------------
 
 def main():
@@ -432,6 +466,8 @@ def main():
         return summarize_trace(args)
     if args.summarize_pmc:
         return summarize_pmc(args)
+    if args.summarize_counters:
+        return summarize_counters(args)
     if args.gpus != 1:
         print("bench.py: the path runs on ONE GPU only (no sharding or collectives exist); use --gpus 1",
               file=sys.stderr)

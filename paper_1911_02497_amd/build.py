@@ -18,7 +18,12 @@ FLAGS = [
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-o", LIB, SRC]
+    flags = list(FLAGS)
+    if os.environ.get("CONDENSA_PLAIN_STREAM_STORES") == "1":
+        # the compiler's own non-temporal stores instead of the buffer stores with system-scope bits: a build to
+        # cross-check a parity failure against (csrc/common.h)
+        flags.append("-DCONDENSA_PLAIN_STREAM_STORES")
+    cmd = [hipcc] + flags + ["-o", LIB, SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
