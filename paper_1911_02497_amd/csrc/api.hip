@@ -206,10 +206,13 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     L.histc = off;  off += align_up((static_cast<size_t>(L.n_groups) + n_hx) * kCoarse * sizeof(u64));
     if (!structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * (2 + kMaxJ) * sizeof(u64)); }
     if (structure && !per_tensor) { L.seg = off; off += align_up(static_cast<size_t>(kSegs) * 2 * sizeof(u64)); }
-    L.zero_bytes = off - L.zero_begin;
-    L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
+    // per-chunk tie counts and the flags of the chunks that can hold ties: cleared with the counters, because the
+    // tie search only visits flagged chunks and leaves the others' counts alone
     const u64 tie_chunks = structure ? L.max_schunks : ((op == CONDENSA_OP_COUNT_NONZERO || op == CONDENSA_OP_LC_SGD_STEP) ? 0 : L.max_chunks);
     L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
+    if (!structure) { L.tiehit = off; off += align_up(static_cast<size_t>(tie_chunks + 1) * sizeof(u32)); }
+    L.zero_bytes = off - L.zero_begin;
+    L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
     if (structure) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
@@ -369,7 +372,9 @@ static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipSt
             // global atomics: few wide workgroups keep that flush small (level 0 of 20 M weights: 36 -> 19 us).
             const bool wide = !a.per_tensor;
             const unsigned threads = wide ? 1024 : kBlock;
-            const u64 cap = wide ? 256 : 2048;                 // measured best of 128..1024
+            // measured: best of 128..1024 workgroups at 1.2 G weights; on 20 M weights (10 rankings) 256 x 1024
+            // threads take 192 us per call against 221 (512 x 512), 275 (512 x 256) and 351 (1024 x 256)
+            const u64 cap = wide ? 256 : 2048;
             const u64 per_iter = threads / kBlock;
             u64 blocks = (a.n_chunks + per_iter - 1) / per_iter;
             if (blocks > cap) blocks = cap;
@@ -576,6 +581,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     a.histx = at<u64>(workspace_dev, L.histx);
     a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
+    a.tiehit = at<u32>(workspace_dev, L.tiehit);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;
@@ -785,6 +791,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.histx = at<u64>(workspace_dev, L.histx);
     a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
+    a.tiehit = at<u32>(workspace_dev, L.tiehit);
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;

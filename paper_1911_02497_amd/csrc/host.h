@@ -120,7 +120,7 @@ struct Layout {
     size_t td = 0, out = 0, slots = 0, upload_bytes = 0;   // [td | out | slots] is uploaded in one copy
     size_t zero_begin = 0, zero_bytes = 0;                 // [ctl | hist0 | histx] is cleared by one kernel
     size_t ctl = 0, hist0 = 0, histx = 0, histc = 0, seg = 0;   // histc: coarse sums; seg: window-path segment counters
-    size_t tiecnt = 0, chunk_map = 0;
+    size_t tiecnt = 0, tiehit = 0, chunk_map = 0;
     size_t skeys = 0, sblock = 0, smask = 0;                // structure keys, per-block kept counts, keep flags
     size_t sample = 0, cand_key = 0, cand_idx = 0;          // window path
     size_t cand_w = 0, cand_lam = 0;                        // inputs of the candidates (fused sweep)

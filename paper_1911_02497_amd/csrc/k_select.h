@@ -42,6 +42,8 @@ struct DataArgs {
                            // (wave_enter_level), one histogram per ranking and level; 0: k_scan_level runs between levels
     u64* coarse;           // merged form: kCoarse sums per histogram, in the order of the histograms from hist0 on
     u64* nnz_seg;          // prune + binary16 L-C step: non-zero codes written by the apply sweep, per counter segment (or NULL)
+    u32* tiehit;           // [n_chunks] set by the last radix level where a chunk holds a key that agrees with some
+                           // ranking on all earlier digits: only those chunks can hold ties of a threshold
 };
 constexpr int kNnzSegs = 1024;   // counter segments of the apply sweeps (one address would serialise ~10^6 atomics)
 
@@ -255,18 +257,28 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
 
     u32 p0 = 0;                                           // the prefix when a batch holds a single ranking
     bool single = false;
+    // Last level: a chunk that holds a key matching a ranking's earlier digits is flagged (plain stores of 1:
+    // whoever writes, writes the same), so that the tie search reads those chunks only.
+    const bool last = (level == n_levels(31) - 1) && level > 0;
+    u32* hit = nullptr;
     auto count_key = [&](u32 key) {
         if (level == 0) {
             atomicAdd(&s_hist[key >> L.shift], 1u);
         } else if (single) {                              // one ranking: compare with its prefix, no table look-up
-            if (((key ^ p0) >> L.hi_shift) == 0) atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
+            if (((key ^ p0) >> L.hi_shift) == 0) {
+                atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
+                if (last) *hit = 1u;
+            }
         } else {
             u32 m = s_tab[key >> L0.shift];
             const u32 digit = (key >> L.shift) & (nb - 1);
             while (m) {
                 const int j = __ffs(m) - 1;
                 m &= m - 1;
-                if (((key ^ s_prefix[j]) >> L.hi_shift) == 0) atomicAdd(&s_hist[j * nb + digit], 1u);
+                if (((key ^ s_prefix[j]) >> L.hi_shift) == 0) {
+                    atomicAdd(&s_hist[j * nb + digit], 1u);
+                    if (last) *hit = 1u;
+                }
             }
         }
     };
@@ -336,6 +348,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
             p0 = single ? s_prefix[0] : 0u;
             const u64 c = cb + sub;
             if (c >= c1) continue;                        // no barrier below this point in the iteration
+            hit = a.tiehit + c;
             const int t = static_cast<int>(a.chunk_map[c]);
             const TensorDesc& td = a.td[t];
             const u64 base = (c - td.chunk_start) * kChunk;
@@ -496,6 +509,8 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
         }
     };
     for (u64 c = blockIdx.x; c < a.n_chunks; c += gridDim.x) {
+        if (a.tiehit[c] == 0) continue;                   // uniform: no key of this chunk reached the last level's bins,
+                                                          // so it holds no tie and its count stays at the cleared 0
         const int t = static_cast<int>(a.chunk_map[c]);
         const long long g = a.per_tensor ? t : 0;
         __syncthreads();
