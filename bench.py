@@ -62,7 +62,7 @@ def measured_traffic(kernel, tensors, other_outputs):
         return None
     if rec.get("sources_sha256") != kernel_sources_hash() or rec.get("tensors") != tensors or other_outputs:
         return None
-    return rec.get("traffic_bytes_per_launch", {}).get(kernel)
+    return next((v for k, v in rec.get("traffic_bytes_per_launch", {}).items() if kernel.startswith(k)), None)
 
 
 def parse():
@@ -92,7 +92,9 @@ def parse():
                     help="half-width of the sampled window in 1/16 standard deviations (default 80 = 5 sigma)")
     ap.add_argument("--two-sweeps", action="store_true",
                     help="window path: separate selection and apply sweeps (default: one sweep does both)")
-    ap.add_argument("--summarize-trace", metavar="DIR", help="rocprofv3 --kernel-trace --stats output directory")
+    ap.add_argument("--summarize-trace", metavar="DIR", nargs="+",
+                    help="rocprofv3 --kernel-trace --stats output directories (several: one section each, named after the "
+                         "directory, with {W} in --command standing for that name)")
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="output directories of the rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs")
     ap.add_argument("--summarize-counters", metavar="DIR", help="output directory of a rocprofv3 --pmc run: per-kernel averages of every counter")
@@ -339,33 +341,47 @@ def _short(name):
     return name.split("(")[0]
 
 
-def summarize_trace(args):
-    files = glob.glob(os.path.join(args.summarize_trace, "**", "*kernel_stats.csv"), recursive=True)
+def _trace_section(directory, command, bytes_per_launch, top):
+    files = glob.glob(os.path.join(directory, "**", "*kernel_stats.csv"), recursive=True)
     if not files:
-        sys.exit(f"no *kernel_stats.csv under {args.summarize_trace}")
+        sys.exit(f"no *kernel_stats.csv under {directory}")
     rows = list(csv.DictReader(open(sorted(files)[0])))
-    lines = [f"# rocprofv3 kernel-trace summary: {args.title}", "",
-             "Command (from /tmp with TMPDIR=/tmp; $R = repository root):", "", "    " + args.command, "",
-             "Per-kernel statistics (`*_kernel_stats.csv`), one MI355X:", "",
+    lines = ["    " + command, "",
              "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---:|---:|---:|---:|---:|"]
-    for r in rows[:24]:
+    for r in rows[:top]:
         lines.append("| `%s` | %s | %.1f | %.1f | %.1f | %.2f |" % (
             _short(r["Name"]), r["Calls"], float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3,
             float(r["Percentage"])))
     if rows and "TotalDurationNs" in rows[0]:
-        total_us = sum(float(r["TotalDurationNs"]) for r in rows) / 1e3
-        lines += ["", f"All kernels of the run: {total_us:.0f} us in {sum(int(r['Calls']) for r in rows)} launches."]
-    for spec in args.bytes_per_launch:
+        ours = [r for r in rows if "condensa::" in r["Name"]]
+        calls = max((int(r["Calls"]) for r in ours if "k_prepare" in r["Name"]), default=0)
+        total_us = sum(float(r["TotalDurationNs"]) for r in ours) / 1e3
+        if calls:
+            lines += ["", f"The library's kernels: {sum(int(r['Calls']) for r in ours) / calls:.0f} launches and {total_us / calls:.1f} us "
+                          f"of kernel time per call ({calls} calls in the run)."]
+    for spec in bytes_per_launch:
         kernel, nbytes = spec.rsplit("=", 1)
         hit = [r for r in rows if kernel in r["Name"]]
         if not hit:
-            lines += ["", f"`{kernel}`: not in this trace."]
             continue
         us = float(hit[0]["AverageNs"]) / 1e3
         gbps = int(nbytes) / (us * 1e-6) / 1e9
         lines += ["", f"`{_short(hit[0]['Name'])}`: {us:.1f} us average for {int(nbytes):,} algorithmic bytes per launch -> "
                       f"{gbps:.0f} GB/s = {100 * gbps / HBM_PEAK_GBPS:.1f} % of the 8 TB/s peak."]
-    open(args.out, "w").write("\n".join(lines) + "\n")
+    return lines
+
+
+def summarize_trace(args):
+    dirs = args.summarize_trace
+    lines = [f"# rocprofv3 kernel-trace summary: {args.title}", "",
+             "Per-kernel statistics (`*_kernel_stats.csv`) of one MI355X; commands run from /tmp with TMPDIR=/tmp, "
+             "$R = repository root.", ""]
+    for d in dirs:
+        name = os.path.basename(os.path.normpath(d))
+        if len(dirs) > 1:
+            lines += [f"## {name}", ""]
+        lines += _trace_section(d, args.command.replace("{W}", name), args.bytes_per_launch, 24 if len(dirs) == 1 else 8) + [""]
+    open(args.out, "w").write("\n".join(lines))
     print("wrote", args.out)
 
 
@@ -378,7 +394,12 @@ def _pmc_averages(directory, counter):
         if r.get("Counter_Name") != counter:
             continue
         acc.setdefault(_short(r["Kernel_Name"]), []).append(float(r["Counter_Value"]))
-    return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
+    out = {}
+    for k, v in acc.items():
+        if "copybuffer" in k.lower():               # the table upload of a call is a copy too: keep the big ones only
+            v = [x for x in v if x >= 0.5 * max(v)]
+        out[k] = (sum(v) / len(v), len(v))
+    return out
 
 
 def summarize_pmc(args):
@@ -396,7 +417,8 @@ def summarize_pmc(args):
              "Commands (from /tmp with TMPDIR=/tmp; $R = repository root), one counter per run:", ""]
     lines += ["    " + c for c in args.command.split(" && ")]
     lines += ["", f"Calibration: `--calibrate-copy` launches four device-to-device copies of one 4096x4608 fp32 tensor "
-                  f"(`{copy[0]}`), each reading and writing 75 497 472 B = {copy_kib:,.0f} KiB.  FETCH_SIZE reads "
+                  f"(`{copy[0]}`; smaller dispatches of that kernel, the calls' table uploads, are left out), each "
+                  f"reading and writing 75 497 472 B = {copy_kib:,.0f} KiB.  FETCH_SIZE reads "
                   f"{fetch[copy[0]][0]:,.1f} for them -> scale factor {f_scale:.5f}; WRITE_SIZE reads {write[copy[0]][0]:,.1f} "
                   f"-> factor {w_scale:.5f}.", "",
               "| kernel | dispatches | FETCH_SIZE raw (avg) | fetched bytes (scaled) | WRITE_SIZE raw (avg) | written bytes (scaled) | traffic / launch | algorithmic bytes / launch |",
@@ -528,7 +550,7 @@ def main():
 
     def step():
         return P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=args.mask,
-                                  workspace=workspace, config=cfg, pq=pq)
+                                  workspace=workspace, config=cfg, pq=pq, nnz=pq)
 
     l0 = P.condensa_launch_count()
     step()
@@ -569,6 +591,25 @@ def main():
     # ---- the other half of the target and the small workloads, on the same device ---------------------------
     extras = None
     if not args.no_extras and not pq and T == 64:
+        # the L-C step of the composed prune + binary16 scheme with the footprint objective counted inside it
+        # (22 B/weight: the binary16 codes are written too)
+        outputs["theta_f16"] = [torch.empty(t.shape, dtype=torch.int16, device=dev) for t in w_dev]
+        cfg_pq = P.condensa_config(select_path=args.select_path, apply_threads=args.apply_threads,
+                                   fused_sweep=1 if args.two_sweeps else 0, window_margin=args.window_margin)
+        res_pq = [None]
+
+        def step_pq():
+            res_pq[0] = P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, mask=False, workspace=workspace,
+                                           config=cfg_pq, pq=True, nnz=True)
+        tpq = timed_calls(step_pq, args.steps, args.warmup, torch)
+        outputs["nnz"] = res_pq[0]["nnz"]
+        pq_bytes = (22 if one_sweep else 30) * N
+        pq_rec = {"workload": "L-C step of Compose([Prune, Quantize(float16)]) on the same tensors, theta_f16 and the non-zero count written too",
+                  "ms_per_step": round(tpq["mean"], 4), "ms_per_step_median": round(tpq["median"], 4), "ms_per_step_min": round(tpq["min"], 4),
+                  "nonzero_codes": int(res_pq[0]["nnz"].item()), "kept": rec["k"],
+                  "algorithmic_bytes_per_step": pq_bytes, "algorithmic_GBps": round(pq_bytes / (tpq["mean"] * 1e-3) / 1e9, 1),
+                  "frac_of_hbm_peak": round(pq_bytes / (tpq["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del outputs["theta_f16"], res_pq
         del outputs["grad"], outputs["lambda"]      # 9.7 GB back; the weights stay resident for the pruning call
         prune_rec, _ = time_workload("prune_stress", args, P, workloads, torch, dev, args.steps, args.warmup,
                                      resident=w_dev, with_oracle=not args.no_cpu_baseline)
@@ -576,7 +617,7 @@ def main():
         for name in SMALL_WORKLOADS:
             r, _ = time_workload(name, args, P, workloads, torch, dev, 50, 5, with_oracle=not args.no_cpu_baseline)
             small.append(r)
-        extras = {"global_prune": prune_rec, "small_workloads": small,
+        extras = {"global_prune": prune_rec, "lc_step_pq": pq_rec, "small_workloads": small,
                   "note": "global_prune: condensa_prune (theta + mask, d = 0.1) on the weights the L-C step ran on; "
                           "small_workloads: wall time per call through the binding (50 calls after 5), launch- and cache-bound"}
 
