@@ -200,7 +200,9 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     // shared level 0 (see make_window_args)
     size_t n_hx = 2u * static_cast<size_t>(L.n_slots);
     if (!structure && !per_tensor) n_hx += 3u * J + 2u * (2u * J + 1u) + 1u;
-    if (structure && !per_tensor) n_hx += 2u * 3u + 1u;     // one-sweep block pruning: the block sample's boundary rankings
+    // structures under GLOBAL scope: one histogram per level of the 63-bit ranking, then (one-sweep block pruning) the
+    // block sample's boundary rankings [2][3] and their shared level 0
+    if (structure && !per_tensor) n_hx = kStructLevels + 2u * 3u + 1u;
     L.histx = off;  off += align_up(n_hx * kBins * sizeof(u64));
     // coarse sums of every histogram from hist0 on (the two regions above are contiguous: their sizes are multiples of 16 KB)
     L.histc = off;  off += align_up((static_cast<size_t>(L.n_groups) + n_hx) * kCoarse * sizeof(u64));
@@ -211,8 +213,14 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     const u64 tie_chunks = structure ? L.max_schunks : ((op == CONDENSA_OP_COUNT_NONZERO || op == CONDENSA_OP_LC_SGD_STEP) ? 0 : L.max_chunks);
     L.tiecnt = off; off += align_up(static_cast<size_t>(J) * tie_chunks * sizeof(u32));
     if (!structure) { L.tiehit = off; off += align_up(static_cast<size_t>(tie_chunks + 1) * sizeof(u32)); }
+    const bool tie_lists = !structure && !per_tensor && tie_chunks > 0;
+    if (tie_lists) { L.tl_cnt = off; off += align_up(static_cast<size_t>(kMaxJ) * sizeof(u64)); }
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
+    if (tie_lists) {
+        L.tl_key = off; off += align_up(static_cast<size_t>(J) * kTieListCap * sizeof(u32));
+        L.tl_idx = off; off += align_up(static_cast<size_t>(J) * kTieListCap * sizeof(u64));
+    }
     if (structure) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
         L.sblock = off; off += align_up(static_cast<size_t>(F / kBlock + 2) * sizeof(u32));
@@ -399,7 +407,9 @@ static condensa_status launch_ties_and_results(const DataArgs& a, int n_slots, i
                                                condensa_select* results, hipStream_t st, const Config& cfg) {
     PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
     if (a.n_chunks > 0) {
-        const unsigned tie_blocks = static_cast<unsigned>(a.n_chunks < 4096 ? a.n_chunks : 4096);
+        // merged form: every workgroup first folds in the last level for each ranking, so fewer of them
+        const u64 tie_cap = a.merged ? 1024 : 4096;
+        const unsigned tie_blocks = static_cast<unsigned>(a.n_chunks < tie_cap ? a.n_chunks : tie_cap);
         hipLaunchKernelGGL((k_tie_count<LC, VEC>), dim3(tie_blocks), dim3(kBlock), 0, st, a);
         CONDENSA_LAUNCH_CHECK();
     }
@@ -582,6 +592,11 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
     a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.tiehit = at<u32>(workspace_dev, L.tiehit);
+    if (L.tl_key) {
+        a.tl_cnt = at<u64>(workspace_dev, L.tl_cnt);
+        a.tl_key = at<u32>(workspace_dev, L.tl_key);
+        a.tl_idx = at<u64>(workspace_dev, L.tl_idx);
+    }
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;
@@ -792,6 +807,11 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
     a.coarse = at<u64>(workspace_dev, L.histc);
     a.tiecnt = at<u32>(workspace_dev, L.tiecnt);
     a.tiehit = at<u32>(workspace_dev, L.tiehit);
+    if (L.tl_key) {
+        a.tl_cnt = at<u64>(workspace_dev, L.tl_cnt);
+        a.tl_key = at<u32>(workspace_dev, L.tl_key);
+        a.tl_idx = at<u64>(workspace_dev, L.tl_idx);
+    }
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
     a.n_chunks = tb.n_chunks;
@@ -1029,6 +1049,9 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     a.n_chunks = tb.n_chunks;
     a.n_tensors = n_tensors;
     a.per_tensor = per_tensor ? 1 : 0;
+    a.merged = per_tensor ? 0 : 1;
+    a.hist_base = at<u64>(workspace_dev, L.hist0);
+    a.coarse = at<u64>(workspace_dev, L.histc);
 
     const unsigned sblocks = static_cast<unsigned>((tb.F + kBlock - 1) / kBlock);
     const unsigned mtiles = static_cast<unsigned>((tb.F + kMaskTile - 1) / kMaskTile);
@@ -1051,7 +1074,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         PhaseTimer timer(CONDENSA_PHASE_SAMPLE, st, cfg);
         ArrayArgs ar{};
         ar.keys = sw.sample; ar.n_host = sw.n_units; ar.slots = sw.wslots; ar.n_slots = 3;
-        ar.hist = a.histx + static_cast<u64>(2 * L.n_slots) * kBins;          // [2][3], behind the aggregate rankings' histograms
+        ar.hist = a.histx + static_cast<u64>(kStructLevels) * kBins;          // [2][3], behind the aggregate ranking's histograms
         ar.shared0 = ar.hist + static_cast<u64>(6) * kBins;
         ar.key_bits = 31; ar.merged = 1;
         ar.hist_base = at<u64>(workspace_dev, L.hist0); ar.coarse = at<u64>(workspace_dev, L.histc);
@@ -1114,6 +1137,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         for (int level = 0; level < n_levels(63) && !small; ++level) {
             hipLaunchKernelGGL(k_hist_keys, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
+            if (a.merged) continue;                            // the next kernel folds this level in itself
             hipLaunchKernelGGL(k_scan_level, dim3(L.n_slots), dim3(kBlock), 0, st, a.slots,
                                static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();

@@ -116,11 +116,14 @@ inline bool tensor_elems(const condensa_tensor& t, u64* n) {
 }
 
 // Carving of the caller's workspace.  Offsets are multiples of 256 bytes.
+constexpr unsigned kStructLevels = 6;     // radix levels of a 63-bit structure key (11+11+11+10+10+10 bits)
+
 struct Layout {
     size_t td = 0, out = 0, slots = 0, upload_bytes = 0;   // [td | out | slots] is uploaded in one copy
     size_t zero_begin = 0, zero_bytes = 0;                 // [ctl | hist0 | histx] is cleared by one kernel
     size_t ctl = 0, hist0 = 0, histx = 0, histc = 0, seg = 0;   // histc: coarse sums; seg: window-path segment counters
     size_t tiecnt = 0, tiehit = 0, chunk_map = 0;
+    size_t tl_cnt = 0, tl_key = 0, tl_idx = 0;              // short lists of the keys that reach the last radix level's bins
     size_t skeys = 0, sblock = 0, smask = 0;                // structure keys, per-block kept counts, keep flags
     size_t sample = 0, cand_key = 0, cand_idx = 0;          // window path
     size_t cand_w = 0, cand_lam = 0;                        // inputs of the candidates (fused sweep)

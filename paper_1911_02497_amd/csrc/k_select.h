@@ -44,7 +44,25 @@ struct DataArgs {
     u64* nnz_seg;          // prune + binary16 L-C step: non-zero codes written by the apply sweep, per counter segment (or NULL)
     u32* tiehit;           // [n_chunks] set by the last radix level where a chunk holds a key that agrees with some
                            // ranking on all earlier digits: only those chunks can hold ties of a threshold
+    // Merged form: the last radix level also lists (key, flat index) of the keys that agree with ranking j on
+    // all earlier digits - a thousand of 20 M weights - so that the ties of the threshold are usually found
+    // in that list, without another sweep over the weights (NULL: no lists).
+    u64* tl_cnt;           // [kMaxJ] entries offered per ranking; above kTieListCap: the list is incomplete
+    u32* tl_key;           // [J][kTieListCap]
+    u64* tl_idx;           // [J][kTieListCap]
 };
+constexpr u32 kTieListCap = 4096;      // entries per ranking's list
+constexpr u32 kTieListGroup = 128;     // entries one workgroup may offer to the lists.  It buffers them in LDS and reserves
+                                       // room with one atomic per ranking at its end (an atomic per entry would queue a
+                                       // thousand of them on one address: +13 us on the 20 M-weight call); a workgroup
+                                       // that finds more declares every list incomplete, and the sweep over the weights
+                                       // counts the ties as before
+constexpr u32 kTieListTies = 512;      // ties of one threshold resolved from the list (ranked in LDS by one workgroup)
+
+// The tie search of ranking j can use its list: every key of the last level's bins is in it, and the ties fit.
+__device__ inline bool tie_list_usable(const DataArgs& a, int j, u64 n_tie) {
+    return a.tl_cnt != nullptr && a.tl_cnt[j] <= kTieListCap && n_tie <= kTieListTies;
+}
 constexpr int kNnzSegs = 1024;   // counter segments of the apply sweeps (one address would serialise ~10^6 atomics)
 
 // Every histogram of the merged form comes with kCoarse sums over runs of consecutive bins, so that the
@@ -185,7 +203,8 @@ __device__ inline SlotStep wave_enter_level(const Slot& s, int L, int key_bits, 
 }
 
 // First kernel of every call: clears the flag / counter / histogram region and writes the
-// chunk -> tensor map (a kernel rather than a memset, so that the call can be captured in a graph).
+// chunk -> tensor map (a kernel rather than a memset: memset nodes do not belong in work that a caller may
+// capture in a graph, as the caller of the allocation-free entry point may).
 __global__ __launch_bounds__(kBlock) void k_prepare(u64* zero, u64 n_words, const TensorDesc* td, int n_tensors,
                                                     u32* chunk_map, u64 n_chunks) {
     const u64 stride = static_cast<u64>(gridDim.x) * kBlock;
@@ -225,9 +244,15 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
     __shared__ u32 s_active[kSlotBatch];
     __shared__ u32 s_mprefix[kMaxJ];      // merged form: the rankings' state on entering this level
     __shared__ u32 s_mactive[kMaxJ];
+    __shared__ u32 s_ln;                  // last level: entries this workgroup found for the rankings' lists
+    __shared__ u32 s_lkey[kTieListGroup];
+    __shared__ u64 s_lidx[kTieListGroup];
+    __shared__ u32 s_lj[kTieListGroup];
+    __shared__ u64 s_lbase[kMaxJ];
     __shared__ u32 s_any;
 
     if (a.only_failed && a.ctl->window_failed == 0) return;
+    if (threadIdx.x == 0) s_ln = 0;       // ordered before its use by the barriers below
     if (a.merged && level > 0) {          // one group; every workgroup derives the same state, workgroup 0 stores it
         const int n_waves = static_cast<int>(blockDim.x) >> 6;
         for (int j = static_cast<int>(threadIdx.x) >> 6; j < a.J; j += n_waves) {
@@ -261,13 +286,27 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
     // whoever writes, writes the same), so that the tie search reads those chunks only.
     const bool last = (level == n_levels(31) - 1) && level > 0;
     u32* hit = nullptr;
-    auto count_key = [&](u32 key) {
+    const bool listing = last && a.merged && a.tl_cnt != nullptr;
+    int list_j0 = 0;                                      // first ranking of the batch being counted
+    u64 chunk_flat = 0;                                   // flat index of the current chunk's first element
+    // last level: the key (element `off` of the current chunk) agrees with ranking j on every earlier digit
+    auto list_key = [&](int j, u32 key, u32 off) {
+        *hit = 1u;
+        if (!listing) return;
+        const u32 mine = atomicAdd(&s_ln, 1u);
+        if (mine < kTieListGroup) {
+            s_lkey[mine] = key;
+            s_lidx[mine] = chunk_flat + off;
+            s_lj[mine] = static_cast<u32>(j);
+        }
+    };
+    auto count_key = [&](u32 key, u32 off) {
         if (level == 0) {
             atomicAdd(&s_hist[key >> L.shift], 1u);
         } else if (single) {                              // one ranking: compare with its prefix, no table look-up
             if (((key ^ p0) >> L.hi_shift) == 0) {
                 atomicAdd(&s_hist[(key >> L.shift) & (nb - 1)], 1u);
-                if (last) *hit = 1u;
+                if (last) list_key(list_j0, key, off);
             }
         } else {
             u32 m = s_tab[key >> L0.shift];
@@ -277,7 +316,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
                 m &= m - 1;
                 if (((key ^ s_prefix[j]) >> L.hi_shift) == 0) {
                     atomicAdd(&s_hist[j * nb + digit], 1u);
-                    if (last) *hit = 1u;
+                    if (last) list_key(list_j0 + j, key, off);
                 }
             }
         }
@@ -310,6 +349,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
         const int j0 = batch * kSlotBatch;
         const int nj = (level == 0) ? a.J : ((a.J - j0 < kSlotBatch) ? a.J - j0 : kSlotBatch);
         const int n_hist = (level == 0) ? 1 : nj;
+        list_j0 = j0;
         long long cur_group = -1;
         for (u64 cb = c0; cb < c1; cb += n_sub) {         // uniform over the workgroup
             // wide workgroups run under GLOBAL scope only, where every chunk belongs to group 0
@@ -353,6 +393,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
             const TensorDesc& td = a.td[t];
             const u64 base = (c - td.chunk_start) * kChunk;
             const u64 n = td.n;
+            chunk_flat = td.flat_start + base;
             if (VEC && base + kChunk <= n) {              // whole chunk inside the tensor: loads first
                 constexpr int kHalf = LC ? kQuadsPerThread / 2 : kQuadsPerThread;
 #pragma unroll
@@ -373,7 +414,8 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
                             for (int k = 0; k < 4; ++k) v[k] = lc_shift(v[k], l[k], a.mu);
                         }
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) count_key(mag_key(v[k]));
+                        for (int k = 0; k < 4; ++k)
+                            count_key(mag_key(v[k]), static_cast<u32>((h * kHalf + q) * (kBlock * 4) + tid * 4 + k));
                     }
                 }
             } else {
@@ -391,7 +433,7 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         if (e0 + k >= n) break;
-                        count_key(mag_key(v[k]));
+                        count_key(mag_key(v[k]), static_cast<u32>(e0 - base) + k);
                     }
                 }
             }
@@ -400,6 +442,31 @@ __global__ __launch_bounds__(1024) void k_hist_data(DataArgs a, int level, u64 c
             __syncthreads();
             flush(cur_group, j0, n_hist);
             __syncthreads();
+        }
+    }
+    if (listing) {                                         // hand the buffered entries to the rankings' lists
+        __syncthreads();
+        const u32 n_l = s_ln;                              // uniform
+        if (n_l > kTieListGroup) {
+            if (wtid < a.J)
+                atomicAdd(reinterpret_cast<unsigned long long*>(&a.tl_cnt[wtid]), static_cast<unsigned long long>(kTieListCap) + 1);
+        } else if (n_l > 0) {
+            if (wtid < a.J) {                              // one reservation per ranking
+                u32 mine = 0;
+                for (u32 i = 0; i < n_l; ++i) mine += (s_lj[i] == static_cast<u32>(wtid)) ? 1u : 0u;
+                s_lbase[wtid] = mine ? atomicAdd(reinterpret_cast<unsigned long long*>(&a.tl_cnt[wtid]), static_cast<unsigned long long>(mine)) : 0;
+            }
+            __syncthreads();
+            if (static_cast<u32>(wtid) < n_l) {            // a workgroup has at least 256 threads, a buffer 128 entries
+                const u32 j = s_lj[wtid];
+                u32 before = 0;
+                for (int i = 0; i < wtid; ++i) before += (s_lj[i] == j) ? 1u : 0u;
+                const u64 pos = s_lbase[j] + before;
+                if (pos < kTieListCap) {
+                    a.tl_key[static_cast<u64>(j) * kTieListCap + pos] = s_lkey[wtid];
+                    a.tl_idx[static_cast<u64>(j) * kTieListCap + pos] = s_lidx[wtid];
+                }
+            }
         }
     }
 }
@@ -489,7 +556,8 @@ __global__ __launch_bounds__(kBlock) void k_tie_count(DataArgs a) {
             const SlotStep e = wave_enter_level(a.slots[j], last + 1, 31, prev, coarse_of(a.hist0, a.coarse, prev));
             if ((threadIdx.x & 63) == 0) {
                 s_mT[j] = static_cast<u32>(e.prefix);
-                s_mneed[j] = (e.state == kDone && e.need_tie) ? 1u : 0u;
+                // rankings whose ties are all in their short list are finished by k_tie_locate alone
+                s_mneed[j] = (e.state == kDone && e.need_tie && !tie_list_usable(a, j, e.n_tie)) ? 1u : 0u;
                 if (s_mneed[j]) s_any = 1;
             }
         }
@@ -614,7 +682,32 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate(DataArgs a, condensa_sele
     }
     __syncthreads();
     const bool need = (s_e.state == kDone && s_e.need_tie);
-    if (need) {
+    const bool from_list = need && a.merged && tie_list_usable(a, j, s_e.n_tie);     // uniform
+    if (from_list) {
+        // The ties are among the few keys that the last level listed: gather their flat indices in LDS and
+        // rank each by counting the lower ones (flat indices are distinct, so exactly one has rank r).
+        __shared__ u64 s_tie[kTieListTies];
+        __shared__ u32 s_n;
+        const u64 r = s_e.remaining;
+        const u32 T = static_cast<u32>(s_e.prefix);
+        const u32 n_list = static_cast<u32>(a.tl_cnt[j]);
+        if (tid == 0) s_n = 0;
+        __syncthreads();
+        for (u32 i = tid; i < n_list; i += kBlock)
+            if (a.tl_key[static_cast<u64>(j) * kTieListCap + i] == T) {
+                const u32 pos = atomicAdd(&s_n, 1u);
+                if (pos < kTieListTies) s_tie[pos] = a.tl_idx[static_cast<u64>(j) * kTieListCap + i];
+            }
+        __syncthreads();
+        const u32 m = s_n < kTieListTies ? s_n : kTieListTies;
+        for (u32 i = tid; i < m; i += kBlock) {
+            const u64 mine = s_tie[i];
+            u64 lower = 0;
+            for (u32 e = 0; e < m; ++e) lower += (s_tie[e] < mine) ? 1u : 0u;
+            if (lower + 1 == r) slot.tie_end = mine + 1;
+        }
+        __syncthreads();
+    } else if (need) {
         const u64 r = s_e.remaining;           // 1-based rank of the last kept tie
         const u32 T = static_cast<u32>(s_e.prefix);
         const u64 cb = a.per_tensor ? a.td[g].chunk_start : 0;

@@ -23,7 +23,16 @@ struct StructArgs {
     u64 n_chunks;
     int n_tensors;
     int per_tensor;
+    // GLOBAL scope, groups too large for k_struct_small: one histogram per radix level (histx[level]), and each
+    // level's kernel folds in the level before it (wave_enter_level) instead of a k_scan_level launch in between
+    int merged;
+    u64* hist_base;        // merged form: first histogram of the workspace, the origin of the coarse sums
+    u64* coarse;           // merged form: kCoarse sums per histogram
 };
+
+// merged form: histogram of radix level `level` of the one ranking, and its coarse sums
+__device__ inline u64* struct_hist(const StructArgs& a, int level) { return a.histx + static_cast<u64>(level) * kBins; }
+__device__ inline u64* struct_coarse(const StructArgs& a, int level) { return coarse_of(a.hist_base, a.coarse, struct_hist(a, level)); }
 
 __device__ inline int tensor_of_struct(const TensorDesc* __restrict__ td, int n_tensors, u64 u) {
     int lo = 0, hi = n_tensors - 1;
@@ -386,12 +395,39 @@ __global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u
     __shared__ u32 s_hist[kBins];
     __shared__ u64 s_prefix;
     __shared__ u32 s_active;
+    __shared__ u64 s_mprefix;             // merged form: the ranking's state on entering this level
+    __shared__ u32 s_mactive;
     const u64 c0 = static_cast<u64>(blockIdx.x) * chunks_per_block;
     if (c0 >= a.n_schunks) return;
     const u64 c1 = (c0 + chunks_per_block < a.n_schunks) ? c0 + chunks_per_block : a.n_schunks;
     const Level L = level_of(63, level);
     const int nb = 1 << L.bits;
     const int tid = threadIdx.x;
+    if (a.merged) {                       // every workgroup derives the same state, workgroup 0 stores it
+        if (tid < 64) {
+            const SlotStep e = (level == 0) ? slot_canonical(a.slots[0])
+                                            : wave_enter_level(a.slots[0], level, 63, struct_hist(a, level - 1), struct_coarse(a, level - 1));
+            if (tid == 0) {
+                s_mprefix = e.prefix;
+                s_mactive = (e.state == kSelecting) ? 1u : 0u;
+                if (blockIdx.x == 0 && level > 0) a.slots[0].step[level & 1] = e;
+            }
+        }
+        __syncthreads();
+    }
+    auto flush = [&](long long group) {
+        u64* dst = a.merged ? struct_hist(a, level) : a.histx + static_cast<u64>(group) * kBins;
+        for (int i = tid; i < nb; i += kBlock) {
+            const u32 v = s_hist[i];
+            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + i), static_cast<unsigned long long>(v));
+        }
+        if (a.merged && tid < kCoarse) {  // the coarse sums of the same counts
+            const int run = coarse_run(nb);
+            u32 v = 0;
+            for (int t = tid * run; t < (tid + 1) * run && t < nb; ++t) v += s_hist[t];
+            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(struct_coarse(a, level) + tid), static_cast<unsigned long long>(v));
+        }
+    };
     long long cur_group = -1;
     for (u64 c = c0; c < c1; ++c) {
         const int t = tensor_of_schunk(a.td, a.n_tensors, c);
@@ -399,14 +435,13 @@ __global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u
         if (g != cur_group) {
             if (cur_group >= 0) {
                 __syncthreads();
-                for (int i = tid; i < nb; i += kBlock) {
-                    const u32 v = s_hist[i];
-                    if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.histx + static_cast<u64>(cur_group) * kBins + i),
-                                     static_cast<unsigned long long>(v));
-                }
+                flush(cur_group);
             }
             __syncthreads();
-            if (tid == 0) {
+            if (tid == 0 && a.merged) {
+                s_prefix = s_mprefix;
+                s_active = s_mactive;
+            } else if (tid == 0) {
                 const Slot& s = a.slots[g];
                 s_prefix = s.prefix;
                 s_active = (s.state == kSelecting) ? 1u : 0u;
@@ -429,35 +464,56 @@ __global__ __launch_bounds__(kBlock) void k_hist_keys(StructArgs a, int level, u
                 const u64 i = i0 + static_cast<u64>(u) * kBlock;
                 key[u] = (i < end) ? kp[i] : ~prefix;      // a filler that fails the prefix test at every level
             }
+            // Aggregates of one model crowd into a few bins at the upper levels (sums of 64 squares of one weight
+            // distribution differ in their low exponent and mantissa bits only), and 64 lanes adding to one LDS
+            // word queue up; the lanes that share the first active lane's digit are added by that lane at once.
+            const int lane = tid & 63;
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (i0 + static_cast<u64>(u) * kBlock < end && ((key[u] ^ prefix) >> L.hi_shift) == 0)
-                    atomicAdd(&s_hist[(key[u] >> L.shift) & (nb - 1)], 1u);
+            for (int u = 0; u < 8; ++u) {
+                const bool on = i0 + static_cast<u64>(u) * kBlock < end && ((key[u] ^ prefix) >> L.hi_shift) == 0;
+                const u32 digit = static_cast<u32>(key[u] >> L.shift) & (nb - 1);
+                const u64 active = __ballot(on);
+                if (active == 0) continue;                 // uniform over the wavefront
+                const int leader = __ffsll(static_cast<long long>(active)) - 1;
+                const u32 d0 = __shfl(digit, leader, 64);
+                const u64 same = __ballot(on && digit == d0);
+                if (lane == leader) atomicAdd(&s_hist[d0], static_cast<u32>(__popcll(same)));
+                else if (on && digit != d0) atomicAdd(&s_hist[digit], 1u);
+            }
         }
     }
     if (cur_group >= 0) {
         __syncthreads();
-        for (int i = tid; i < nb; i += kBlock) {
-            const u32 v = s_hist[i];
-            if (v) atomicAdd(reinterpret_cast<unsigned long long*>(a.histx + static_cast<u64>(cur_group) * kBins + i),
-                             static_cast<unsigned long long>(v));
-        }
+        flush(cur_group);
     }
 }
 
 __global__ __launch_bounds__(kBlock) void k_tie_count_keys(StructArgs a) {
     __shared__ u32 s_cnt;
-    if (a.ctl->need_tie == 0) return;
+    __shared__ SlotStep s_e;
     const u64 c = blockIdx.x;
     if (c >= a.n_schunks) return;
     const int tid = threadIdx.x;
+    u64 T;
     const int t = tensor_of_schunk(a.td, a.n_tensors, c);
-    const u64 g = a.per_tensor ? t : 0;
-    const Slot& s = a.slots[g];
-    if (!(s.state == kDone && s.need_tie)) return;
+    if (a.merged) {                       // the last level is folded in here; k_tie_locate_keys stores the outcome
+        if (tid < 64) {
+            const int last = n_levels(63) - 1;
+            const SlotStep e = wave_enter_level(a.slots[0], last + 1, 63, struct_hist(a, last), struct_coarse(a, last));
+            if (tid == 0) s_e = e;
+        }
+        __syncthreads();
+        if (!(s_e.state == kDone && s_e.need_tie)) return;
+        T = s_e.prefix;
+    } else {
+        if (a.ctl->need_tie == 0) return;
+        const u64 g = a.per_tensor ? t : 0;
+        const Slot& s = a.slots[g];
+        if (!(s.state == kDone && s.need_tie)) return;
+        T = s.prefix;
+    }
     if (tid == 0) s_cnt = 0;
     __syncthreads();
-    const u64 T = s.prefix;
     const TensorDesc& td = a.td[t];
     const u64 base = (c - td.pad) * kChunk;
     u32 mine = 0;
@@ -472,13 +528,33 @@ __global__ __launch_bounds__(kBlock) void k_tie_count_keys(StructArgs a) {
 __global__ __launch_bounds__(kBlock) void k_tie_locate_keys(StructArgs a, condensa_select* results) {
     __shared__ u64 s_wave[kBlock / 64];
     __shared__ u64 s_found[3];
+    __shared__ SlotStep s_e;
     const int g = blockIdx.x;
     const int tid = threadIdx.x;
     Slot& slot = a.slots[g];
-    const bool need = (slot.state == kDone && slot.need_tie);
+    if (a.merged) {
+        // the last level's histogram is folded in here, and this workgroup (the only one that touches the
+        // ranking in this kernel) makes the outcome the ranking's stored state
+        if (tid < 64) {
+            const int last = n_levels(63) - 1;
+            const SlotStep e = wave_enter_level(slot, last + 1, 63, struct_hist(a, last), struct_coarse(a, last));
+            if (tid == 0) {
+                s_e = e;
+                if (slot.state == kSelecting) {
+                    slot.prefix = e.prefix; slot.remaining = e.remaining; slot.n_tie = e.n_tie;
+                    slot.state = e.state; slot.need_tie = e.need_tie;
+                    if (e.state == kDone && !e.need_tie) slot.tie_end = slot.n;
+                }
+            }
+        }
+    } else if (tid == 0) {
+        s_e = slot_canonical(slot);
+    }
+    __syncthreads();
+    const bool need = (s_e.state == kDone && s_e.need_tie);
     if (need) {
-        const u64 r = slot.remaining;
-        const u64 T = slot.prefix;
+        const u64 r = s_e.remaining;
+        const u64 T = s_e.prefix;
         const u64 cb = a.per_tensor ? a.td[g].pad : 0;
         const u64 ce = a.per_tensor ? a.td[g + 1].pad : a.n_schunks;
         const u64 per = (ce - cb + kBlock - 1) / kBlock;
@@ -535,11 +611,11 @@ __global__ __launch_bounds__(kBlock) void k_tie_locate_keys(StructArgs a, conden
         condensa_select out;
         out.n = slot.n;
         out.k = slot.k;
-        if (slot.state == kDone) {
-            out.n_gt = slot.k - slot.remaining;
-            out.n_tie_kept = slot.remaining;
-            out.n_tie = slot.n_tie;
-            out.threshold_key = slot.prefix;
+        if (s_e.state == kDone) {
+            out.n_gt = slot.k - s_e.remaining;
+            out.n_tie_kept = s_e.remaining;
+            out.n_tie = s_e.n_tie;
+            out.threshold_key = s_e.prefix;
             out.tie_end = slot.tie_end;
         } else {
             out.n_gt = 0; out.n_tie_kept = 0; out.n_tie = 0;

@@ -269,36 +269,60 @@ __global__ __launch_bounds__(kArrayThreads) void k_hist_array(ArrayArgs a, int l
         __syncthreads();
         u32* my_hist = s_hist + (tid & (copies - 1)) * words;
         // entries are fetched eight at a time so that their loads overlap (the loop is latency bound)
-        auto take_range = [&](u64 first, u64 count, u64 start, u64 step) {
-            constexpr int kUnroll = 8;
-            for (u64 i0 = start; i0 < count; i0 += step * kUnroll) {
+        constexpr int kUnroll = 8;
+        auto count_entry = [&](u32 ck, u64 ix) {
+            const u64 rk = IDX ? (a.N - 1 - ix) : static_cast<u64>(ck);
+            const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
+            for (int j = 0; j < nj; ++j)
+                if (s_active[j] && ck >= s_lo[j] && ck <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
+                    atomicAdd(&my_hist[j * nb + digit], 1u);
+        };
+        if (a.seg_cnt) {
+            // A workgroup owns every gridDim.x-th segment.  Four segments are read together, two entries of
+            // each per thread and step: the segments are short (a thousand entries), and walking them one
+            // after the other would pay one round trip for the count and one for the entries of each.
+            constexpr int kSegBatch = 4, kPer = kUnroll / kSegBatch;
+            for (u32 seg0 = blockIdx.x; seg0 < a.n_segs; seg0 += gridDim.x * kSegBatch) {
+                u64 cnt[kSegBatch], first[kSegBatch], most = 0;
+#pragma unroll
+                for (int b = 0; b < kSegBatch; ++b) {
+                    const u64 seg = static_cast<u64>(seg0) + static_cast<u64>(b) * gridDim.x;
+                    u64 c = (seg < a.n_segs) ? a.seg_cnt[seg < a.n_segs ? seg : 0] : 0;
+                    if (c > a.seg_cap) c = a.seg_cap;
+                    cnt[b] = c;
+                    first[b] = seg * a.seg_cap;
+                    most = c > most ? c : most;
+                }
+                for (u64 i0 = tid; i0 < most; i0 += static_cast<u64>(nt) * kPer) {
+                    u32 ck[kUnroll];
+                    u64 ix[kUnroll];
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) {
+                        const int b = u % kSegBatch;
+                        const u64 i = i0 + static_cast<u64>(nt) * (u / kSegBatch);
+                        ck[u] = (i < cnt[b]) ? a.keys[first[b] + i] : kNoKey;
+                        ix[u] = (IDX && i < cnt[b]) ? a.idx[first[b] + i] : 0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u)
+                        if (i0 + static_cast<u64>(nt) * (u / kSegBatch) < cnt[u % kSegBatch]) count_entry(ck[u], ix[u]);
+                }
+            }
+        } else {
+            const u64 step = static_cast<u64>(gridDim.x) * nt;
+            for (u64 i0 = static_cast<u64>(blockIdx.x) * nt + tid; i0 < a.n_host; i0 += step * kUnroll) {
                 u32 ck[kUnroll];
                 u64 ix[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     const u64 i = i0 + step * u;
-                    ck[u] = (i < count) ? a.keys[first + i] : kNoKey;
-                    ix[u] = (IDX && i < count) ? a.idx[first + i] : 0;
+                    ck[u] = (i < a.n_host) ? a.keys[i] : kNoKey;
+                    ix[u] = (IDX && i < a.n_host) ? a.idx[i] : 0;
                 }
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    if (i0 + step * u >= count) break;
-                    const u64 rk = IDX ? (a.N - 1 - ix[u]) : static_cast<u64>(ck[u]);
-                    const u32 digit = static_cast<u32>(rk >> L.shift) & (nb - 1);
-                    for (int j = 0; j < nj; ++j)
-                        if (s_active[j] && ck[u] >= s_lo[j] && ck[u] <= s_hi[j] && ((rk ^ s_prefix[j]) >> L.hi_shift) == 0)
-                            atomicAdd(&my_hist[j * nb + digit], 1u);
-                }
+                for (int u = 0; u < kUnroll; ++u)
+                    if (i0 + step * u < a.n_host) count_entry(ck[u], ix[u]);
             }
-        };
-        if (a.seg_cnt) {
-            for (u32 seg = blockIdx.x; seg < a.n_segs; seg += gridDim.x) {
-                u64 cnt = a.seg_cnt[seg];
-                if (cnt > a.seg_cap) cnt = a.seg_cap;
-                take_range(static_cast<u64>(seg) * a.seg_cap, cnt, tid, nt);
-            }
-        } else {
-            take_range(0, a.n_host, static_cast<u64>(blockIdx.x) * nt + tid, static_cast<u64>(gridDim.x) * nt);
         }
         __syncthreads();
         u64* dst = share ? a.shared0 : array_hist(a, level, j0);
@@ -758,7 +782,7 @@ __global__ __launch_bounds__(kBlock) void k_window_ties(DataArgs a, WindowArgs w
 constexpr int kFinishThreads = 1024;
 __global__ __launch_bounds__(kFinishThreads) void k_window_finish1(DataArgs a, WindowArgs w, ArrayArgs ar, int idx_bits) {
     __shared__ SlotStep s_e;
-    __shared__ u32 s_hist[kBins];
+    __shared__ __align__(8) u32 s_hist[kBins];
     __shared__ u64 s_pick[2];              // chosen bin, rank inside it
     const int tid = threadIdx.x;
     Slot& s = a.slots[0];
@@ -777,6 +801,20 @@ __global__ __launch_bounds__(kFinishThreads) void k_window_finish1(DataArgs a, W
         const u64 n_t = a.ctl->tie_count;
         if (n_t != e.n_tie || n_t > w.tie_cap) {
             ok = false;                                                  // the list does not hold every tie
+        } else if (n_t <= static_cast<u64>(kFinishThreads)) {
+            // the usual case, a handful of ties: one index per thread, ranked by counting the lower ones
+            u64* s_idx = reinterpret_cast<u64*>(s_hist);                 // kBins words hold kFinishThreads indices
+            const u64 mine = (static_cast<u64>(tid) < n_t) ? w.tie_list[tid] : ~static_cast<u64>(0);
+            s_idx[tid] = mine;
+            if (tid == 0) s_pick[0] = s.n - 1;
+            __syncthreads();
+            if (static_cast<u64>(tid) < n_t) {
+                u64 lower = 0;
+                for (u64 i = 0; i < n_t; ++i) lower += (s_idx[i] < mine) ? 1u : 0u;
+                if (lower + 1 == e.remaining) s_pick[0] = mine;          // flat indices are distinct: one thread
+            }
+            __syncthreads();
+            tie_end = s_pick[0] + 1;
         } else {
             u64 prefix = 0, r = e.remaining;
             for (int level = 0; level < n_levels(idx_bits); ++level) {   // uniform

@@ -147,6 +147,34 @@ def test_few_distinct_values_far_apart(levels, n, select_path):
             assert P.select_records(res["results"])[0]["path"] == 2, "expected to resolve inside the window"
 
 
+@pytest.mark.parametrize("cluster,ties", [(600, 9), (3000, 300), (3000, 700), (20000, 40), (300000, 2)])
+def test_ties_among_keys_that_agree_on_all_but_the_last_digit(cluster, ties):
+    """The radix levels list the keys that agree with a threshold on every digit but the last and usually find
+    the ties in that list.  Clusters of `cluster` magnitudes whose bit patterns differ only in their low ten
+    bits, with `ties` copies of one of them, exercise the list (few keys, few ties), the ranking of several
+    hundred ties inside it, more ties than the list resolves, more keys than the list holds, and more keys in
+    one workgroup's share than it may offer - the last three fall back to the sweep that counts ties per chunk.
+    Two densities put their thresholds into the cluster, one of them on the tied magnitude with part of it kept."""
+    rng = np.random.default_rng(cluster + ties)
+    n = 8192 * 50 + 123
+    w = (rng.standard_normal(n) * 0.001).astype(np.float32)
+    pos = rng.choice(n, cluster, replace=False)
+    bits = (np.uint32(0x3D000000) + rng.integers(0, 1024, cluster).astype(np.uint32))      # |x| ~ 0.031, one bin of 2^10 keys
+    tied = np.uint32(0x3D000000 + 517)
+    bits[:ties] = tied
+    signs = rng.integers(0, 2, cluster).astype(np.uint32) << np.uint32(31)
+    w[pos] = (bits | signs).view(np.float32)
+    mag = np.abs(w).view(np.uint32)
+    n_gt = int((mag > tied).sum())
+    n_eq = int((mag == tied).sum())
+    assert n_eq >= ties
+    d_tied = (n_gt + max(1, n_eq // 2)) / n                     # keeps half of the tied magnitudes
+    d_other = (cluster // 3) / n                                # a threshold elsewhere in the cluster
+    half = n // 2 + 5
+    res, ora = _prune_both([w[:half], w[half:]], [d_tied, d_other], what=f"cluster {cluster} ties {ties}")
+    assert ora[0]["select"]["n_tie"] == n_eq and ora[0]["select"]["n_tie_kept"] == max(1, n_eq // 2)
+
+
 def test_same_call_twice_and_other_launch_shapes_give_the_same_bits():
     """Determinism: the result is a function of the inputs alone.  The same call twice, and calls whose
     launches are shaped differently (sample size and candidate capacity change the grids, the segment counts
