@@ -229,9 +229,12 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
             u64 sc = F / 8;
             sc = sc < (1u << 12) ? (1u << 12) : (sc > (1u << 17) ? (1u << 17) : sc);
             L.sample_cap = sc;
-            L.cand_cap = F / 8 < 4096 ? 4096 : F / 8;
+            // room for an eighth of the blocks, and for all of them while that costs under a megabyte
+            L.cand_cap = F / 8;
+            if (L.cand_cap < (1u << 16)) L.cand_cap = F < (1u << 16) ? (F < 4096 ? 4096 : F) : (1u << 16);
             L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
-            L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));
+            L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));      // ids of the listed blocks
+            L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));      // their aggregate keys
         }
     } else if (!per_tensor && !no_window && op != CONDENSA_OP_COUNT_NONZERO && op != CONDENSA_OP_LC_SGD_STEP) {
         L.sample_cap = window_sample_size(N, cfg);
@@ -1068,6 +1071,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         sw.seg_cnt = at<u64>(workspace_dev, L.seg);
         sw.seg_above = sw.seg_cnt + kSegs;
         sw.cand_id = at<u32>(workspace_dev, L.cand_key);
+        sw.cand_key = at<u64>(workspace_dev, L.cand_idx);
         sw.n_segs = sblocks < static_cast<unsigned>(kSegs) ? sblocks : static_cast<unsigned>(kSegs);   // at most the sweep's grid
         sw.seg_cap = L.cand_cap / sw.n_segs;
         sw.out = at<OutDesc>(workspace_dev, L.out);
@@ -1131,6 +1135,18 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
                                keep_idx_dev, results_dev);
             CONDENSA_LAUNCH_CHECK();
         }
+        if (fused) {
+            // rank k - (blocks above the window) among the listed blocks; the levels over all aggregates below are
+            // then the fallback and return at once
+            hipLaunchKernelGGL(k_struct_window_check, dim3(1), dim3(kBlock), 0, st, a, sw);
+            CONDENSA_LAUNCH_CHECK();
+            const unsigned lg = sw.n_segs < 256 ? sw.n_segs : 256;
+            for (int level = 0; level < n_levels(63); ++level) {
+                hipLaunchKernelGGL(k_hist_listed_keys, dim3(lg), dim3(kArrayThreads), 0, st, a, sw, level);
+                CONDENSA_LAUNCH_CHECK();
+            }
+            a.only_failed = 1;
+        }
         u64 blocks = tb.n_schunks < 1024 ? tb.n_schunks : 1024;
         const u64 cpb = (tb.n_schunks + blocks - 1) / blocks;
         blocks = (tb.n_schunks + cpb - 1) / cpb;
@@ -1165,8 +1181,6 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         if (fused) {
             PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-            hipLaunchKernelGGL(k_struct_window_check, dim3(1), dim3(kBlock), 0, st, a, sw);
-            CONDENSA_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_struct_fixup, dim3(sw.n_segs * kFixupParts), dim3(kBlock), 0, st, a, sw);
             CONDENSA_LAUNCH_CHECK();
             const u64 n_tiles = tb.n_chunks * kSubPerChunk;

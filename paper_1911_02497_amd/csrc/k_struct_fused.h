@@ -7,11 +7,12 @@
 // that computes the aggregates already writes the final theta and mask of every block outside the window
 // (kept above hi, zeroed below lo) -- an 8x8 block sits in the registers of the thread that adds it up.
 // Blocks inside the window get a provisional decision (kept iff above `mid`, the sample's estimate of the
-// threshold) and are listed.  The exact ranking then runs on the stored aggregates as in the plain form, so
-// the threshold, the tie rule, the structure mask and the kept-id list never depend on the sample; a fix-up
-// pass rewrites the listed blocks whose final decision differs, and if the threshold turns out to lie
-// outside the window, or the list overflowed, a gated full apply sweep rewrites everything.
-// 9.3 instead of 13 bytes per weight.
+// threshold) and are listed with their aggregates.  The sweep also counts the blocks above the window, so the
+// exact ranking only has to find rank k - above among the listed blocks (a percent of all blocks) instead of
+// rank k among all of them; when that rank does not fall inside the list, or the list overflowed, the ranking
+// over all stored aggregates runs as in the plain form and a gated full apply sweep rewrites everything.
+// Threshold, tie rule, structure mask and kept-id list never depend on the sample.  A fix-up pass rewrites the
+// listed blocks whose final decision differs from the provisional one.  9.3 instead of 13 bytes per weight.
 #pragma once
 #include "k_structure.h"
 #include "k_window.h"
@@ -26,6 +27,7 @@ struct StructWindowArgs {
     u64* seg_cnt;          // [kSegs] listed blocks per segment (may exceed seg_cap)
     u64* seg_above;        // [kSegs] blocks above the window
     u32* cand_id;          // [n_segs][seg_cap] ids of the blocks inside the window
+    u64* cand_key;         // [n_segs][seg_cap] their aggregate keys
     u64 seg_cap;
     u32 n_segs;
     const OutDesc* out;
@@ -163,23 +165,120 @@ __global__ __launch_bounds__(THREADS) void k_struct_tiles_fused(StructArgs a, St
     const u32 blo = __shfl(static_cast<u32>(b), leader, 64), bhi = __shfl(static_cast<u32>(b >> 32), leader, 64);
     if (listed) {
         const u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + __popcll(lb & ((static_cast<u64>(1) << lane) - 1));
-        if (pos < w.seg_cap) w.cand_id[static_cast<u64>(seg) * w.seg_cap + pos] = static_cast<u32>(u);
+        if (pos < w.seg_cap) {
+            w.cand_id[static_cast<u64>(seg) * w.seg_cap + pos] = static_cast<u32>(u);
+            w.cand_key[static_cast<u64>(seg) * w.seg_cap + pos] = key;
+        }
     }
 }
 
-// After the exact ranking: does the window hold the threshold, and is the list complete?
+// After the sweep: the rank to find among the listed blocks, or failure (the threshold lies outside the window,
+// or the list overflowed), which leaves the ranking as the host armed it, for the levels over all aggregates.
 __global__ __launch_bounds__(kBlock) void k_struct_window_check(StructArgs a, StructWindowArgs w) {
+    __shared__ u64 s_wave[kBlock / 64];
     __shared__ u32 s_over;
-    if (threadIdx.x == 0) s_over = 0;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_over = 0;
     __syncthreads();
+    u64 cnt = 0, abv = 0;
     bool over = false;
-    for (u32 seg = threadIdx.x; seg < w.n_segs; seg += kBlock) over = over || (w.seg_cnt[seg] > w.seg_cap);
+    for (u32 seg = tid; seg < w.n_segs; seg += kBlock) {
+        const u64 c = w.seg_cnt[seg];
+        over = over || (c > w.seg_cap);
+        cnt += c;
+        abv += w.seg_above[seg];
+    }
     if (over) s_over = 1;
+    u64 listed, above;
+    block_excl_scan_u64(cnt, s_wave, &listed);
+    block_excl_scan_u64(abv, s_wave, &above);
     __syncthreads();
-    if (threadIdx.x != 0) return;
-    const Slot& s = a.slots[0];
-    const bool ok = !s_over && s.state == kDone && s.prefix >= window_lo63(w.wslots) && s.prefix <= window_hi63(w.wslots);
-    if (!ok) atomicOr(&a.ctl->window_failed, 1u);
+    if (tid != 0) return;
+    Slot& s = a.slots[0];
+    if (s.state != kSelecting) return;
+    if (s_over || above >= s.k || s.k - above > listed) {
+        s.path = 3;                                        // reported: the window did not resolve this ranking
+        atomicOr(&a.ctl->window_failed, 1u);
+        return;
+    }
+    const u64 lo = window_lo63(w.wslots), hi = window_hi63(w.wslots);
+    s.remaining = s.k - above;
+    s.lo = lo;
+    s.hi = hi;
+    // leading digits shared by lo and hi are shared by every listed block: those levels need no counting
+    u32 begin = 0;
+    u64 prefix = 0;
+    const int nl = n_levels(63);
+    for (int level = 0; level < nl - 1; ++level) {
+        const Level L = level_of(63, level);
+        if (((lo ^ hi) >> L.shift) != 0) break;
+        prefix = (lo >> L.shift) << L.shift;
+        begin = level + 1;
+    }
+    s.prefix = prefix;
+    s.level_begin = begin;
+}
+
+// Histogram of one radix level over the listed blocks' keys; the level before it is folded in first, as in
+// k_hist_keys.  Few wide workgroups, each taking four of the short segments at a time.
+__global__ __launch_bounds__(kArrayThreads) void k_hist_listed_keys(StructArgs a, StructWindowArgs w, int level) {
+    __shared__ u32 s_hist[kBins];
+    __shared__ u64 s_prefix;
+    __shared__ u32 s_active;
+    if (a.ctl->window_failed != 0) return;                 // the levels over all aggregates run instead
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        const SlotStep e = (level == 0) ? slot_canonical(a.slots[0])
+                                        : wave_enter_level(a.slots[0], level, 63, struct_hist(a, level - 1), struct_coarse(a, level - 1));
+        if (tid == 0) {
+            s_prefix = e.prefix;
+            s_active = (e.state == kSelecting && static_cast<u32>(level) >= a.slots[0].level_begin) ? 1u : 0u;
+            if (blockIdx.x == 0 && level > 0) a.slots[0].step[level & 1] = e;
+        }
+    }
+    for (int i = tid; i < kBins; i += kArrayThreads) s_hist[i] = 0;
+    __syncthreads();
+    if (!s_active) return;                                 // uniform: a level that lo and hi share, or nothing to rank
+    const Level L = level_of(63, level);
+    const int nb = 1 << L.bits;
+    const u64 prefix = s_prefix;
+    constexpr int kSegBatch = 4, kPer = 2;
+    for (u32 seg0 = blockIdx.x; seg0 < w.n_segs; seg0 += gridDim.x * kSegBatch) {
+        u64 cnt[kSegBatch], first[kSegBatch], most = 0;
+#pragma unroll
+        for (int b = 0; b < kSegBatch; ++b) {
+            const u64 seg = static_cast<u64>(seg0) + static_cast<u64>(b) * gridDim.x;
+            u64 c = (seg < w.n_segs) ? w.seg_cnt[seg] : 0;
+            if (c > w.seg_cap) c = w.seg_cap;
+            cnt[b] = c;
+            first[b] = seg * w.seg_cap;
+            most = c > most ? c : most;
+        }
+        for (u64 i0 = tid; i0 < most; i0 += static_cast<u64>(kArrayThreads) * kPer) {
+            u64 key[kSegBatch * kPer];
+#pragma unroll
+            for (int u = 0; u < kSegBatch * kPer; ++u) {
+                const u64 i = i0 + static_cast<u64>(kArrayThreads) * (u / kSegBatch);
+                key[u] = (i < cnt[u % kSegBatch]) ? w.cand_key[first[u % kSegBatch] + i] : ~prefix;   // a filler that fails the prefix test
+            }
+#pragma unroll
+            for (int u = 0; u < kSegBatch * kPer; ++u)
+                if (i0 + static_cast<u64>(kArrayThreads) * (u / kSegBatch) < cnt[u % kSegBatch] && ((key[u] ^ prefix) >> L.hi_shift) == 0)
+                    atomicAdd(&s_hist[(key[u] >> L.shift) & (nb - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    u64* dst = struct_hist(a, level);
+    for (int i = tid; i < nb; i += kArrayThreads) {
+        const u32 v = s_hist[i];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(dst + i), static_cast<unsigned long long>(v));
+    }
+    if (tid < kCoarse) {
+        const int run = coarse_run(nb);
+        u32 v = 0;
+        for (int t = tid * run; t < (tid + 1) * run && t < nb; ++t) v += s_hist[t];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(struct_coarse(a, level) + tid), static_cast<unsigned long long>(v));
+    }
 }
 
 // Rewrites the listed blocks whose final decision differs from the provisional one (one thread per block).
@@ -195,7 +294,7 @@ __global__ __launch_bounds__(kBlock) void k_struct_fixup(StructArgs a, StructWin
     if (cnt > w.seg_cap) cnt = w.seg_cap;
     for (u64 i = static_cast<u64>(part) * kBlock + threadIdx.x; i < cnt; i += static_cast<u64>(parts) * kBlock) {
         const u64 id = w.cand_id[static_cast<u64>(seg) * w.seg_cap + i];
-        const u64 key = a.keys[id];
+        const u64 key = w.cand_key[static_cast<u64>(seg) * w.seg_cap + i];
         const bool was_kept = key > mid;
         const bool keep = key > T || (key == T && id < tie_end);
         if (keep == was_kept) continue;

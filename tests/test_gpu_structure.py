@@ -157,8 +157,10 @@ def test_block_prune_8x8_aggregation_and_apply_in_one_sweep():
             res = P.condensa_block_prune(dev, 8, 8, d, P.SCOPE_GLOBAL, config=cfg, fill_keep_idx=True)
             torch.cuda.synchronize()
             _compare(res, ora, P.SCOPE_GLOBAL, ms, f"one sweep {cfg} d={d}")
-            want_path = 2 if (cfg.get("select_path") == 2 and not cfg.get("fused_sweep")) else 1
-            assert P.select_records(res["results"])[0]["path"] == want_path, (cfg, d)
+            # path 2: resolved among the listed blocks; 3: the window missed (zero margin) and the levels over all
+            # aggregates with the gated apply took over; 1: two sweeps
+            want = (2, 3) if cfg.get("window_margin") == 0 else (2,) if (cfg.get("select_path") == 2 and not cfg.get("fused_sweep")) else (1,)
+            assert P.select_records(res["results"])[0]["path"] in want, (cfg, d)
     # the threshold on a duplicated block: the tie rule decides inside the window
     key = float((ms[3][0:8, 0:8].astype(np.float64) ** 2).sum())
     sums = np.concatenate([(m.reshape(m.shape[0] // 8, 8, m.shape[1] // 8, 8).astype(np.float64) ** 2).sum(axis=(1, 3)).reshape(-1) for m in ms])
@@ -187,6 +189,25 @@ def test_block_prune_8x8_aggregation_and_apply_in_one_sweep():
     assert P.select_records(res["results"])[0]["path"] == 1
     for t in range(len(ms)):
         assert_bits_equal(inplace[t], ora["theta"][t], f"in place {t}")
+
+
+def test_block_prune_one_sweep_with_more_tied_blocks_than_the_list_holds():
+    """2^20 blocks of which 40 % are copies of one block, and a density that cuts inside that tie class: the
+    window's list (an eighth of the blocks) overflows, the ranking over all aggregates and the gated apply take
+    over (path 3), and the lowest-id rule decides among 400 000 tied blocks."""
+    rng = np.random.default_rng(909)
+    m = (rng.standard_normal((2048, 32768)) * 0.02).astype(np.float32)          # 256 x 4096 blocks
+    blocks = m.reshape(256, 8, 4096, 8)
+    tied = rng.random((256, 4096)) < 0.4
+    blocks[:] = np.where(tied[:, None, :, None], blocks[0:1, :, 0:1, :], blocks)
+    sums = (blocks.astype(np.float64) ** 2).sum(axis=(1, 3))
+    d = (int((sums > sums[0, 0]).sum()) + int(tied.sum()) // 2) / sums.size        # keeps about half of the tied blocks
+    ora = oracle.block_prune([m], 8, 8, d, P.SCOPE_GLOBAL)
+    assert ora["select"]["n_tie"] > (1 << 20) // 8 and 0 < ora["select"]["n_tie_kept"] < ora["select"]["n_tie"]
+    res = P.condensa_block_prune(up([m]), 8, 8, d, P.SCOPE_GLOBAL, config={"select_path": 2}, fill_keep_idx=True)
+    torch.cuda.synchronize()
+    _compare(res, ora, P.SCOPE_GLOBAL, [m], "one sweep, tie class beyond the list")
+    assert P.select_records(res["results"])[0]["path"] == 3
 
 
 def test_shape_errors():
