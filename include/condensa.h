@@ -112,7 +112,8 @@ typedef struct {
  */
 typedef struct {
     int32_t select_path;    /* 0 auto, 1 radix levels over the data only (structure calls: one launch per
-                               level), 2 sampled window even for small N                              */
+                               level), 2 sampled window even for small N (8x8 block pruning: aggregation
+                               and apply in one sweep whatever the number of blocks, where shapes allow) */
     int32_t sample_log2;    /* log2 of the sample size of the window path (10..26); 0 = auto           */
     int32_t window_margin;  /* half-width of the sampled window in 1/16 standard deviations of the sample
                                rank; default 80 (= 5 sigma of a sample whose units of 4 neighbours are
