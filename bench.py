@@ -39,6 +39,7 @@ N_STRESS = 64 * 4096 * 4608
 # The HBM-counter summary that `roofline.traffic` is read from, and the sources whose hash ties it to the
 # kernel it was taken from (reported as null once they differ).
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "lc_step_large_model_hbm_counters.md")
+PRUNE_TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "prune_large_model_hbm_counters.md")
 KERNEL_SOURCES = ("paper_1911_02497_amd/csrc/common.h", "paper_1911_02497_amd/csrc/k_fused.h")
 SMALL_WORKLOADS = ("single_prune_fp16", "vgg_thresholds", "vgg_masks", "resnet_filter_global",
                    "resnet_filter_per_tensor", "transformer_block8", "transformer_block32")
@@ -52,11 +53,11 @@ def kernel_sources_hash():
     return m.hexdigest()
 
 
-def measured_traffic(kernel, tensors, other_outputs):
+def measured_traffic(kernel, tensors, other_outputs, profile=TRAFFIC_PROFILE):
     """HBM bytes per launch of `kernel` from the committed counter summary, or None when the summary is
     missing, describes another workload, or was taken from other kernel sources."""
     try:
-        text = open(TRAFFIC_PROFILE).read()
+        text = open(profile).read()
         rec = json.loads(text.split("```json", 1)[1].split("```", 1)[0])
     except (OSError, IndexError, ValueError):
         return None
@@ -232,6 +233,12 @@ def time_workload(name, args, P, workloads, torch, dev, steps, warmup, resident=
     call()
     launches = P.condensa_launch_count() - l0
     torch.cuda.synchronize()
+    if args.calibrate_copy and name.endswith("_stress"):     # 4 plain copies of one 4096x4608 fp32 tensor, for the counters
+        src = torch.empty((4096, 4608), dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     t = timed_calls(call, steps, warmup, torch, before_timed=P.condensa_profile_reset)
     phases = P.condensa_profile_read()
     N, bpe = info["N"], info["bytes_per_elem"]
@@ -253,7 +260,9 @@ def time_workload(name, args, P, workloads, torch, dev, steps, warmup, resident=
         k_gbps = k_bpe * N / (k_ms * 1e-3) / 1e9
         rec["roofline"] = {"bound": "hbm", "kernel": "k_window_fused<prune>" if bpe == 9 else "selection sweep(s)",
                            "achieved": round(k_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                           "frac": round(k_gbps / HBM_PEAK_GBPS, 4), "traffic": None, "avg_launch_ms": round(k_ms, 4),
+                           "frac": round(k_gbps / HBM_PEAK_GBPS, 4),
+                           "traffic": measured_traffic("k_window_fused", info["tensors"], False, PRUNE_TRAFFIC_PROFILE) if bpe == 9 else None,
+                           "avg_launch_ms": round(k_ms, 4),
                            "launches_averaged": phases["sweep"]["intervals"], "algorithmic_bytes_per_launch": k_bpe * N}
     if with_oracle:
         hs = info["sample"]()
