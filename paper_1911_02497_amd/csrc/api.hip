@@ -1065,7 +1065,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     StructWindowArgs sw{};
     if (fused) {
         sw.sample = at<u32>(workspace_dev, L.sample);
-        sw.n_units = L.sample_cap < tb.F ? L.sample_cap : tb.F;
+        sw.n_units = (L.sample_cap < tb.F ? L.sample_cap : tb.F) & ~static_cast<u64>(3);   // whole units of four blocks
         sw.stride = tb.F / sw.n_units;
         sw.wslots = a.slots + L.n_slots;
         sw.seg_cnt = at<u64>(workspace_dev, L.seg);
@@ -1168,8 +1168,18 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         CONDENSA_LAUNCH_CHECK();
     }
     if (tb.F > 0) {
-        if (!small) {
-            hipLaunchKernelGGL(k_struct_mask, dim3(mtiles), dim3(kBlock), 0, st, a, structure_mask_dev);
+        if (fused) {
+            // the sweep left the keep flags of the blocks outside the window, the fix-up settles the listed ones
+            // (and rewrites their theta and mask); the flags come from the keys only if the window failed
+            PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
+            hipLaunchKernelGGL(k_struct_fixup, dim3(sw.n_segs * kFixupParts), dim3(kBlock), 0, st, a, sw);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_struct_mask, dim3(mtiles), dim3(kBlock), 0, st, a, structure_mask_dev, static_cast<int>(kMaskFromFlags));
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_struct_mask, dim3(mtiles), dim3(kBlock), 0, st, a, structure_mask_dev, static_cast<int>(kMaskIfFailed));
+            CONDENSA_LAUNCH_CHECK();
+        } else if (!small) {
+            hipLaunchKernelGGL(k_struct_mask, dim3(mtiles), dim3(kBlock), 0, st, a, structure_mask_dev, static_cast<int>(kMaskFromKeys));
             CONDENSA_LAUNCH_CHECK();
         }
         if (keep_idx_dev && !small) {
@@ -1181,8 +1191,6 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
         if (fused) {
             PhaseTimer timer(CONDENSA_PHASE_APPLY, st, cfg);
             const OutDesc* od = at<OutDesc>(workspace_dev, L.out);
-            hipLaunchKernelGGL(k_struct_fixup, dim3(sw.n_segs * kFixupParts), dim3(kBlock), 0, st, a, sw);
-            CONDENSA_LAUNCH_CHECK();
             const u64 n_tiles = tb.n_chunks * kSubPerChunk;
             hipLaunchKernelGGL((k_struct_apply_gated<true>), dim3(static_cast<unsigned>(n_tiles < 4096 ? n_tiles : 4096)), dim3(kBlock), 0, st, a, od, n_tiles);
             CONDENSA_LAUNCH_CHECK();

@@ -53,7 +53,9 @@ __device__ inline double block_sumsq(const TensorDesc& td, u32 s) {
     return acc;
 }
 
-// The sample (one block per stride, jittered) and the level-0 histogram of its keys.
+// The sample and the level-0 histogram of its keys.  Four neighbouring blocks are taken per stride of four
+// (jittered): their rows share 128-byte lines, so the sample costs a third of what single blocks at four times
+// as many places cost, and the window's margin already counts a unit of four neighbours as one draw.
 __global__ __launch_bounds__(kSampleHistThreads) void k_struct_sample_hist(StructArgs a, StructWindowArgs w, ArrayArgs ar) {
     __shared__ u32 s_hist[kBins];
     const int tid = threadIdx.x;
@@ -61,8 +63,9 @@ __global__ __launch_bounds__(kSampleHistThreads) void k_struct_sample_hist(Struc
     for (int i = tid; i < kBins; i += kSampleHistThreads) s_hist[i] = 0;
     __syncthreads();
     for (u64 u = static_cast<u64>(blockIdx.x) * kSampleHistThreads + tid; u < w.n_units; u += static_cast<u64>(gridDim.x) * kSampleHistThreads) {
-        const u64 jitter = (w.stride > 1) ? static_cast<u64>(mix32(static_cast<u32>(u) ^ static_cast<u32>(u >> 32))) % w.stride : 0;
-        const u64 id = u * w.stride + jitter;
+        const u64 q = u >> 2;
+        const u64 jitter = (w.stride > 1) ? static_cast<u64>(mix32(static_cast<u32>(q) ^ static_cast<u32>(q >> 32))) % w.stride : 0;
+        const u64 id = (q * w.stride + jitter) * 4 + (u & 3);
         u32 key = kNoKey;
         if (id < a.F) {
             const int t = tensor_of_struct_guess(a.td, a.n_tensors, a.F, id);
@@ -130,6 +133,7 @@ __global__ __launch_bounds__(THREADS) void k_struct_tiles_fused(StructArgs a, St
     if (norms) norms[u] = static_cast<float>(sqrt(acc));
     const bool keep = key > mid;                           // final outside the window, provisional inside
     const bool listed = key >= lo && key <= hi;
+    a.smask[u] = keep ? 1 : 0;                             // the structure mask starts from the same decision
     // the first float4 a lane fetched belongs to the block of the even lane of its pair, the second to the odd one's
     const u64 kb = __ballot(keep);
     const bool keep_a = (kb >> (lane & ~1u)) & 1ull, keep_b = (kb >> (lane | 1u)) & 1ull;
@@ -298,6 +302,7 @@ __global__ __launch_bounds__(kBlock) void k_struct_fixup(StructArgs a, StructWin
         const bool was_kept = key > mid;
         const bool keep = key > T || (key == T && id < tie_end);
         if (keep == was_kept) continue;
+        a.smask[id] = keep ? 1 : 0;
         const int t = tensor_of_struct_guess(a.td, a.n_tensors, a.F, id);
         const TensorDesc& td = a.td[t];
         const u32 d3 = td.d[3];

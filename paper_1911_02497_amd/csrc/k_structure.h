@@ -798,13 +798,35 @@ __device__ inline u32 wg_incl_scan_u32(u32 v, u32* s_wave, u32* total) {
     return before + inc;
 }
 
-// keep flag of every structure and the number of kept structures of every tile of kMaskTile
-__global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask) {
+// keep flag of every structure and the number of kept structures of every tile of kMaskTile.
+// The one-sweep form of block pruning (k_struct_fused.h) leaves the flags in `smask` itself: its sweep decides
+// every block outside the window, its fix-up the listed ones.  There kMaskFromFlags only counts and copies
+// them (18.9 MB instead of 151 MB of keys), and kMaskIfFailed derives them from the keys when the window failed.
+enum : int { kMaskFromKeys = 0, kMaskFromFlags = 1, kMaskIfFailed = 2 };
+__global__ __launch_bounds__(kBlock) void k_struct_mask(StructArgs a, u8* user_mask, int mode) {
     __shared__ u32 s_wave[kBlock / 64];
+    if (mode == kMaskFromFlags && a.ctl->window_failed != 0) return;
+    if (mode == kMaskIfFailed && a.ctl->window_failed == 0) return;
     const int tid = threadIdx.x;
     const u64 u0 = (static_cast<u64>(blockIdx.x) * kBlock + tid) * kMaskPer;
     u32 keep[kMaskPer] = {0, 0, 0, 0};
-    if (u0 < a.F) {
+    if (u0 < a.F && mode == kMaskFromFlags) {
+        const bool full = u0 + kMaskPer <= a.F;
+        if (full) {
+            const uchar4 m4 = *reinterpret_cast<const uchar4*>(a.smask + u0);
+            keep[0] = m4.x; keep[1] = m4.y; keep[2] = m4.z; keep[3] = m4.w;
+            if (user_mask) {
+                if ((reinterpret_cast<uintptr_t>(user_mask) & 3u) == 0) *reinterpret_cast<uchar4*>(user_mask + u0) = m4;
+                else for (int k = 0; k < kMaskPer; ++k) user_mask[u0 + k] = static_cast<u8>(keep[k]);
+            }
+        } else {
+            for (int k = 0; k < kMaskPer; ++k)
+                if (u0 + k < a.F) {
+                    keep[k] = a.smask[u0 + k];
+                    if (user_mask) user_mask[u0 + k] = static_cast<u8>(keep[k]);
+                }
+        }
+    } else if (u0 < a.F) {
         const bool full = u0 + kMaskPer <= a.F;
         u64 key[kMaskPer] = {0, 0, 0, 0};
         if (full) {
