@@ -321,12 +321,15 @@ def oracle_baseline(args, workloads, mu, density, T):
     a = (t1 * n2 - t2 * n1) / det if det else 0.0
     b = (t1 - a * n1 * math.log2(n1)) / n1
     full = a * N_STRESS * math.log2(N_STRESS) + b * N_STRESS if a > 0 and b > 0 else None
+    # whatever the split between the sort and the linear passes: between "all linear" and "all n log n" from the larger sample
+    bounds = [t2 * N_STRESS / n2, t2 * N_STRESS * math.log2(N_STRESS) / (n2 * math.log2(n2))]
     rec = {"value": round(n2 / t2, 1), "unit": "weights/s", "cores": 1, "kind": "oracle",
            "sample": f"one L-C step of the oracle on the first {b_t} of the {T} tensors ({n2} weights): {t2:.1f} s; "
                      f"on the first {a_t} ({n1} weights): {t1:.1f} s = {n1 / t1:.0f} weights/s",
            "model": "t = a n log2 n + b n through the two samples" if full else "the two samples do not separate the sort from the linear passes",
            "full_workload_estimate_s": round(full, 1) if full else None,
-           "full_workload_estimate_weights_per_s": round(N_STRESS / full, 1) if full else None}
+           "full_workload_estimate_weights_per_s": round(N_STRESS / full, 1) if full else None,
+           "full_workload_bounds_s": [round(bounds[0], 1), round(bounds[1], 1)]}
     rec.update(host_info())
     if args.cpu_all_cores:
         from concurrent.futures import ThreadPoolExecutor
