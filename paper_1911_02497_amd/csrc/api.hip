@@ -7,6 +7,7 @@
 #include "k_quantize.h"
 #include "k_fused.h"
 #include "k_select.h"
+#include "k_small.h"
 #include "k_structure.h"
 #include "k_window.h"
 #include "k_struct_fused.h"
@@ -218,8 +219,12 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
     L.zero_bytes = off - L.zero_begin;
     L.chunk_map = off; off += align_up(static_cast<size_t>(L.max_chunks + 1) * sizeof(u32));
     if (tie_lists) {
-        L.tl_key = off; off += align_up(static_cast<size_t>(J) * kTieListCap * sizeof(u32));
-        L.tl_idx = off; off += align_up(static_cast<size_t>(J) * kTieListCap * sizeof(u64));
+        // small calls on the automatic path finish on one list that can hold every element (k_small.h)
+        if (!no_window && N > 0 && N <= kSmallCallElems && cfg[CONDENSA_OPT_SELECT_PATH] == 0) L.small_cap = N;
+        u64 entries = static_cast<u64>(J) * kTieListCap;
+        if (entries < L.small_cap) entries = L.small_cap;
+        L.tl_key = off; off += align_up(static_cast<size_t>(entries) * sizeof(u32));
+        L.tl_idx = off; off += align_up(static_cast<size_t>(entries) * sizeof(u64));
     }
     if (structure) {
         L.skeys = off;  off += align_up(static_cast<size_t>(F) * sizeof(u64));
@@ -374,11 +379,12 @@ static unsigned fill_grid(u64 words) {
 
 // Radix levels over the weights: 3 x (histogram sweep + bin search).
 template <bool LC, bool VEC>
-static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st, const Config& cfg) {
+static condensa_status launch_radix_levels(const DataArgs& a, int n_slots, hipStream_t st, const Config& cfg,
+                                           int levels = n_levels(31)) {
     if (a.n_chunks > 0) {
         // as the gated fallback of the window path these launches are (normally empty) resolve work
         PhaseTimer timer(a.only_failed ? CONDENSA_PHASE_RESOLVE : CONDENSA_PHASE_SWEEP, st, cfg);
-        for (int level = 0; level < n_levels(31); ++level) {
+        for (int level = 0; level < levels; ++level) {
             // Every workgroup flushes the non-zero bins of its LDS histograms (J of them past level 0) with
             // global atomics: few wide workgroups keep that flush small (level 0 of 20 M weights: 36 -> 19 us).
             const bool wide = !a.per_tensor;
@@ -431,6 +437,17 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
                       : launch_window_path<LC, VEC>(a, L, ws, st, cfg);
         if (rc != CONDENSA_OK) return rc;
         a.only_failed = 1;
+    }
+    if (!use_window && a.small_cap >= a.N && a.n_chunks > 0 && a.merged) {
+        // a small call: level 0, then the keys of the thresholds' bins as a list, then one workgroup per ranking
+        rc = launch_radix_levels<LC, VEC>(a, n_slots, st, cfg, 1);
+        if (rc != CONDENSA_OK) return rc;
+        PhaseTimer timer(CONDENSA_PHASE_RESOLVE, st, cfg);
+        hipLaunchKernelGGL((k_small_collect<LC, VEC>), dim3(static_cast<unsigned>(a.n_chunks < 1024 ? a.n_chunks : 1024)), dim3(kBlock), 0, st, a);
+        CONDENSA_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_small_finish, dim3(n_slots), dim3(kSmallFinishThreads), 0, st, a, results, bits_for(a.N - 1));
+        CONDENSA_LAUNCH_CHECK();
+        return CONDENSA_OK;
     }
     rc = launch_radix_levels<LC, VEC>(a, n_slots, st, cfg);
     if (rc != CONDENSA_OK) return rc;
@@ -599,6 +616,7 @@ static condensa_status prune_impl(const condensa_tensor* tensors, int n_tensors,
         a.tl_cnt = at<u64>(workspace_dev, L.tl_cnt);
         a.tl_key = at<u32>(workspace_dev, L.tl_key);
         a.tl_idx = at<u64>(workspace_dev, L.tl_idx);
+        a.small_cap = L.small_cap;
     }
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);
@@ -814,6 +832,7 @@ static condensa_status lc_step_impl(bool pq, const condensa_tensor* tensors, int
         a.tl_cnt = at<u64>(workspace_dev, L.tl_cnt);
         a.tl_key = at<u32>(workspace_dev, L.tl_key);
         a.tl_idx = at<u64>(workspace_dev, L.tl_idx);
+        a.small_cap = L.small_cap;
     }
     a.ctl = at<Control>(workspace_dev, L.ctl);
     a.chunk_map = at<u32>(workspace_dev, L.chunk_map);

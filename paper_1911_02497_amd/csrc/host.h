@@ -124,6 +124,7 @@ struct Layout {
     size_t ctl = 0, hist0 = 0, histx = 0, histc = 0, seg = 0;   // histc: coarse sums; seg: window-path segment counters
     size_t tiecnt = 0, tiehit = 0, chunk_map = 0;
     size_t tl_cnt = 0, tl_key = 0, tl_idx = 0;              // short lists of the keys that reach the last radix level's bins
+    u64 small_cap = 0;                                      // small calls: entries of the one list that replaces them (0: not a small call)
     size_t skeys = 0, sblock = 0, smask = 0;                // structure keys, per-block kept counts, keep flags
     size_t sample = 0, cand_key = 0, cand_idx = 0;          // window path
     size_t cand_w = 0, cand_lam = 0;                        // inputs of the candidates (fused sweep)

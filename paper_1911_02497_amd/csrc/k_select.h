@@ -50,6 +50,8 @@ struct DataArgs {
     u64* tl_cnt;           // [kMaxJ] entries offered per ranking; above kTieListCap: the list is incomplete
     u32* tl_key;           // [J][kTieListCap]
     u64* tl_idx;           // [J][kTieListCap]
+    u64 small_cap;         // > 0: a small call (k_small.h) - tl_key / tl_idx hold this many entries as ONE list of the
+                           // keys that share their leading digit with a threshold, counted by tl_cnt[0]
 };
 constexpr u32 kTieListCap = 4096;      // entries per ranking's list
 constexpr u32 kTieListGroup = 128;     // entries one workgroup may offer to the lists.  It buffers them in LDS and reserves

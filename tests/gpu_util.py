@@ -9,6 +9,7 @@ DEV = "cuda:0"
 # The forms of the selection that every element-pruning and L-C case runs through, as per-call
 # configurations (condensa_config fields): nothing process-wide is touched by the tests.
 FORMS = {
+    "auto": {"select_path": 0},          # what a caller gets: small calls finish on a list after the first radix level
     "radix": {"select_path": 1},
     "window": {"select_path": 2},
     "window_narrow": {"select_path": 2, "window_margin": 0},

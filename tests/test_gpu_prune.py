@@ -13,9 +13,10 @@ pytestmark = pytest.mark.gpu
 prune = with_form(P.condensa_prune)
 
 
-@pytest.fixture(params=["radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
+@pytest.fixture(params=["auto", "radix", "window", "window_narrow", "window_two_sweeps"], autouse=True)
 def select_path(request):
-    """Every case runs through the radix levels, the sampled window (selection and apply in one sweep
+    """Every case runs through the automatic choice (small calls: the first radix level, then a list of the
+    keys around the thresholds), the radix levels, the sampled window (selection and apply in one sweep
     where the call allows it), a window whose margin is cut to a couple of sample ranks so that it
     regularly misses and falls back, and the window with separate selection and apply sweeps."""
     Form.config = FORMS[request.param]
