@@ -11,6 +11,7 @@
 #include "k_structure.h"
 #include "k_window.h"
 #include "k_struct_fused.h"
+#include "k_struct_list.h"
 
 namespace condensa {
 
@@ -237,6 +238,7 @@ Layout make_layout(int op, u64 N, u64 F, int n_tensors, int J, int scope, const 
             // room for an eighth of the blocks, and for all of them while that costs under a megabyte
             L.cand_cap = F / 8;
             if (L.cand_cap < (1u << 16)) L.cand_cap = F < (1u << 16) ? (F < 4096 ? 4096 : F) : (1u << 16);
+            if (F <= kSmallCallElems && L.cand_cap < F) L.cand_cap = F;   // the list of k_struct_list.h holds every structure
             L.sample = off;   off += align_up(L.sample_cap * sizeof(u32));
             L.cand_key = off; off += align_up(L.cand_cap * sizeof(u32));      // ids of the listed blocks
             L.cand_idx = off; off += align_up(L.cand_cap * sizeof(u64));      // their aggregate keys
@@ -1081,6 +1083,7 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
     bool small = tb.F > 0 && cfg[CONDENSA_OPT_SELECT_PATH] != 1;
     if (per_tensor) { for (int t = 0; t < n_tensors && small; ++t) if (tb.td[t].n_struct > kSmallGroup) small = false; }
     else if (tb.F > kSmallGroup) small = false;
+    bool finished = false;                                  // the ranking's record is written (k_struct_list_finish)
     StructWindowArgs sw{};
     if (fused) {
         sw.sample = at<u32>(workspace_dev, L.sample);
@@ -1166,10 +1169,12 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
             }
             a.only_failed = 1;
         }
+        // moderate rankings on the automatic path: two levels over all aggregates, then a list (k_struct_list.h)
+        const bool listed = !per_tensor && !small && !fused && tb.F <= kSmallCallElems && cfg[CONDENSA_OPT_SELECT_PATH] == 0;
         u64 blocks = tb.n_schunks < 1024 ? tb.n_schunks : 1024;
         const u64 cpb = (tb.n_schunks + blocks - 1) / blocks;
         blocks = (tb.n_schunks + cpb - 1) / cpb;
-        for (int level = 0; level < n_levels(63) && !small; ++level) {
+        for (int level = 0; level < (listed ? kStructListLevels : n_levels(63)) && !small; ++level) {
             hipLaunchKernelGGL(k_hist_keys, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, st, a, level, cpb);
             CONDENSA_LAUNCH_CHECK();
             if (a.merged) continue;                            // the next kernel folds this level in itself
@@ -1177,12 +1182,23 @@ static condensa_status run_structure_prune(int op, Tables& tb, int n_tensors, do
                                static_cast<const u64*>(nullptr), a.histx, 1, 63, level, a.ctl, 0, &a.ctl->need_tie);
             CONDENSA_LAUNCH_CHECK();
         }
-        if (!small) {
+        if (listed) {
+            StructListArgs l{};
+            l.count = at<u64>(workspace_dev, L.seg);
+            l.key = at<u64>(workspace_dev, L.cand_idx);
+            l.id = at<u32>(workspace_dev, L.cand_key);
+            l.cap = L.cand_cap;
+            hipLaunchKernelGGL(k_struct_list_collect, dim3(static_cast<unsigned>(tb.n_schunks < 1024 ? tb.n_schunks : 1024)), dim3(kBlock), 0, st, a, l);
+            CONDENSA_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_struct_list_finish, dim3(1), dim3(kSmallFinishThreads), 0, st, a, l, results_dev, bits_for(tb.F - 1));
+            CONDENSA_LAUNCH_CHECK();
+            finished = true;
+        } else if (!small) {
             hipLaunchKernelGGL(k_tie_count_keys, dim3(static_cast<unsigned>(tb.n_schunks)), dim3(kBlock), 0, st, a);
             CONDENSA_LAUNCH_CHECK();
         }
     }
-    if (!small) {
+    if (!small && !finished) {
         hipLaunchKernelGGL(k_tie_locate_keys, dim3(L.n_slots), dim3(kBlock), 0, st, a, results_dev);
         CONDENSA_LAUNCH_CHECK();
     }

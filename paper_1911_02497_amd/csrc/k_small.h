@@ -175,38 +175,31 @@ __global__ __launch_bounds__(kBlock) void k_small_collect(DataArgs a) {
     }
 }
 
-// One workgroup per ranking finishes on the list: level 0 is folded in, the two remaining levels are counted in
-// LDS over the listed keys that share the ranking's leading digit, the tie rule picks the r-th lowest flat index
-// among the keys equal to the threshold, and the outcome becomes the ranking's stored state and result record.
-__global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a, condensa_select* results, int idx_bits) {
+// A 1024-thread workgroup finishes one ranking on a list of (key, index) entries that holds every key sharing the
+// ranking's digits above `first_level` (and possibly other keys): `e` is the ranking's state on entering that
+// level.  The remaining levels are counted in LDS over the matching entries, the tie rule picks the r-th lowest
+// index among the entries equal to the threshold, and the outcome becomes the ranking's stored state and its
+// result record.  Called by every thread of the workgroup with the same arguments.
+template <typename KEY, typename IDX>
+__device__ inline void finish_on_list(Slot& slot, SlotStep e, const KEY* __restrict__ keys, const IDX* __restrict__ ids,
+                                      u64 n_list, int key_bits, int first_level, int idx_bits, condensa_select* record) {
     __shared__ __align__(8) u32 s_hist[kBins];
-    __shared__ SlotStep s_e;
     __shared__ u32 s_bin, s_found, s_n;
     __shared__ u64 s_rem, s_cnt;
-    const int j = blockIdx.x;
     const int tid = threadIdx.x;
-    Slot& slot = a.slots[j];
-    if (tid < 64) {
-        const SlotStep e = wave_enter_level(slot, 1, 31, a.hist0, coarse_of(a.hist0, a.coarse, a.hist0));
-        if (tid == 0) s_e = e;
-    }
-    __syncthreads();
-    SlotStep e = s_e;
     u64 tie_end = slot.n;                                  // every tie kept, unless found otherwise below
     if (e.state == kSelecting) {                           // uniform over the workgroup
-        u64 n_list = a.tl_cnt[0];
-        if (n_list > a.small_cap) n_list = a.small_cap;    // (cannot happen: the list holds every element)
         u64 prefix = e.prefix, r = e.remaining, n_tie = 0;
         bool ok = true;
-        for (int level = 1; level < n_levels(31) && ok; ++level) {
-            const Level lv = level_of(31, level);
+        for (int level = first_level; level < n_levels(key_bits) && ok; ++level) {
+            const Level lv = level_of(key_bits, level);
             const int nb = 1 << lv.bits;
             for (int i = tid; i < nb; i += kSmallFinishThreads) s_hist[i] = 0;
             if (tid == 0) s_found = 0;
             __syncthreads();
             for (u64 i = tid; i < n_list; i += kSmallFinishThreads) {
-                const u32 key = a.tl_key[i];
-                if (((static_cast<u64>(key) ^ prefix) >> lv.hi_shift) == 0) atomicAdd(&s_hist[(key >> lv.shift) & (nb - 1)], 1u);
+                const u64 key = keys[i];
+                if (((key ^ prefix) >> lv.hi_shift) == 0) atomicAdd(&s_hist[static_cast<u32>(key >> lv.shift) & (nb - 1)], 1u);
             }
             __syncthreads();
             if (tid < 64) wave_pick_desc(s_hist, nb, r, &s_bin, &s_rem, &s_cnt, &s_found);
@@ -220,19 +213,19 @@ __global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a
             __syncthreads();
         }
         if (!ok) {
-            e.state = kFailed;                             // the counts of level 0 and the list disagree: reported, not hidden
+            e.state = kFailed;                             // the counts of the levels and the list disagree: reported, not hidden
         } else {
             e.prefix = prefix; e.remaining = r; e.n_tie = n_tie; e.state = kDone; e.need_tie = 0;
-            const u32 T = static_cast<u32>(prefix);
+            const u64 T = prefix;
             if (r < n_tie && n_tie <= static_cast<u64>(kSmallFinishThreads)) {
                 // a handful of ties: their indices in LDS, each ranked by counting the lower ones
                 u64* s_idx = reinterpret_cast<u64*>(s_hist);
                 if (tid == 0) { s_n = 0; s_rem = slot.n - 1; }
                 __syncthreads();
                 for (u64 i = tid; i < n_list; i += kSmallFinishThreads)
-                    if (a.tl_key[i] == T) {
+                    if (static_cast<u64>(keys[i]) == T) {
                         const u32 p = atomicAdd(&s_n, 1u);
-                        if (p < static_cast<u32>(kSmallFinishThreads)) s_idx[p] = a.tl_idx[i];
+                        if (p < static_cast<u32>(kSmallFinishThreads)) s_idx[p] = static_cast<u64>(ids[i]);
                     }
                 __syncthreads();
                 const u32 m = s_n < static_cast<u32>(kSmallFinishThreads) ? s_n : static_cast<u32>(kSmallFinishThreads);
@@ -240,12 +233,12 @@ __global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a
                     const u64 mine = s_idx[tid];
                     u64 lower = 0;
                     for (u32 i = 0; i < m; ++i) lower += (s_idx[i] < mine) ? 1u : 0u;
-                    if (lower + 1 == r) s_rem = mine;      // flat indices are distinct: one thread
+                    if (lower + 1 == r) s_rem = mine;      // indices are distinct: one thread
                 }
                 __syncthreads();
                 tie_end = s_rem + 1;
             } else if (r < n_tie) {
-                // many ties: radix levels on the flat index over the listed keys equal to the threshold, lowest first
+                // many ties: radix levels on the index over the entries equal to the threshold, lowest first
                 u64 iprefix = 0, ir = r;
                 for (int level = 0; level < n_levels(idx_bits); ++level) {     // uniform
                     const Level lv = level_of(idx_bits, level);
@@ -254,8 +247,8 @@ __global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a
                     if (tid == 0) s_found = 0;
                     __syncthreads();
                     for (u64 i = tid; i < n_list; i += kSmallFinishThreads) {
-                        if (a.tl_key[i] != T) continue;
-                        const u64 idx = a.tl_idx[i];
+                        if (static_cast<u64>(keys[i]) != T) continue;
+                        const u64 idx = static_cast<u64>(ids[i]);
                         if (((idx ^ iprefix) >> lv.hi_shift) == 0) atomicAdd(&s_hist[static_cast<u32>(idx >> lv.shift) & (nb - 1)], 1u);
                     }
                     __syncthreads();
@@ -290,7 +283,22 @@ __global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a
         out.tie_end = 0;
     }
     out.path = slot.path;
-    results[j] = out;
+    *record = out;
+}
+
+// One workgroup per ranking: level 0 is folded in, the rest happens on the list.
+__global__ __launch_bounds__(kSmallFinishThreads) void k_small_finish(DataArgs a, condensa_select* results, int idx_bits) {
+    __shared__ SlotStep s_e;
+    const int j = blockIdx.x;
+    Slot& slot = a.slots[j];
+    if (threadIdx.x < 64) {
+        const SlotStep e = wave_enter_level(slot, 1, 31, a.hist0, coarse_of(a.hist0, a.coarse, a.hist0));
+        if (threadIdx.x == 0) s_e = e;
+    }
+    __syncthreads();
+    u64 n_list = a.tl_cnt[0];
+    if (n_list > a.small_cap) n_list = a.small_cap;        // (cannot happen: the list holds every element)
+    finish_on_list<u32, u64>(slot, s_e, a.tl_key, a.tl_idx, n_list, 31, 1, idx_bits, results + j);
 }
 
 }  // namespace condensa

@@ -192,18 +192,19 @@ def test_block_prune_8x8_aggregation_and_apply_in_one_sweep():
 
 
 def test_block_prune_one_sweep_with_more_tied_blocks_than_the_list_holds():
-    """2^20 blocks of which 40 % are copies of one block, and a density that cuts inside that tie class: the
-    window's list (an eighth of the blocks) overflows, the ranking over all aggregates and the gated apply take
-    over (path 3), and the lowest-id rule decides among 400 000 tied blocks."""
+    """2.4 M blocks (more than the list of a moderate call would hold in full) of which 40 % are copies of one
+    block, and a density that cuts inside that tie class: the window's list (an eighth of the blocks) overflows,
+    the ranking over all aggregates and the gated apply take over (path 3), and the lowest-id rule decides among
+    900 000 tied blocks."""
     rng = np.random.default_rng(909)
-    m = (rng.standard_normal((2048, 32768)) * 0.02).astype(np.float32)          # 256 x 4096 blocks
-    blocks = m.reshape(256, 8, 4096, 8)
-    tied = rng.random((256, 4096)) < 0.4
+    m = (rng.standard_normal((4096, 36864)) * 0.02).astype(np.float32)          # 512 x 4608 blocks
+    blocks = m.reshape(512, 8, 4608, 8)
+    tied = rng.random((512, 4608)) < 0.4
     blocks[:] = np.where(tied[:, None, :, None], blocks[0:1, :, 0:1, :], blocks)
     sums = (blocks.astype(np.float64) ** 2).sum(axis=(1, 3))
     d = (int((sums > sums[0, 0]).sum()) + int(tied.sum()) // 2) / sums.size        # keeps about half of the tied blocks
     ora = oracle.block_prune([m], 8, 8, d, P.SCOPE_GLOBAL)
-    assert ora["select"]["n_tie"] > (1 << 20) // 8 and 0 < ora["select"]["n_tie_kept"] < ora["select"]["n_tie"]
+    assert ora["select"]["n_tie"] > sums.size // 8 and 0 < ora["select"]["n_tie_kept"] < ora["select"]["n_tie"]
     res = P.condensa_block_prune(up([m]), 8, 8, d, P.SCOPE_GLOBAL, config={"select_path": 2}, fill_keep_idx=True)
     torch.cuda.synchronize()
     _compare(res, ora, P.SCOPE_GLOBAL, [m], "one sweep, tie class beyond the list")
