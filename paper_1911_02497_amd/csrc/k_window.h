@@ -981,7 +981,7 @@ static condensa_status launch_single_sweep(const DataArgs& a, const WindowArgs& 
     return CONDENSA_OK;
 }
 
-// One density: 13 launches where the general sequence below needs 27.  The sample is ranked over two levels
+// One density: 10 launches where the general sequence below needs 24 or more.  The sample is ranked over two levels
 // (the host has filled in the three boundary rankings; their ranks follow from the sample's size on the device),
 // the candidates over the levels that their window leaves open, every level search folded into the kernel that
 // follows it, and the index search among ties runs on the short tie list inside the finishing workgroup.
