@@ -164,20 +164,21 @@ def make_workload(name, args, P, workloads, torch, dev, resident=None):
         cpu = lambda hs: oracle.prune(hs, [0.1])  # noqa: E731
     elif name in ("filter_stress", "block_stress"):
         # structure pruning of the large-model weights: the matrices as 4096 filters of 512x3x3, or 8x8 blocks
+        as_filters = lambda t: t.reshape(t.shape[0], t.shape[1] // 9, 3, 3)  # noqa: E731  (a view, on the host and on the device)
         if name == "filter_stress":
-            host = [h.reshape(h.shape[0], h.shape[1] // 9, 3, 3) for h in host]
-            d = up(host)
+            d = P.tensor_table([as_filters(t) for t in resident]) if resident is not None else up([as_filters(h) for h in host])
             call = lambda: P.condensa_filter_prune(d, 0.5, P.SCOPE_GLOBAL, workspace=ws[0], outputs=prev[0], config=cfg)  # noqa: E731
-            op, F, desc = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in host), "global filter prune d=0.5, theta + mask"
-            cpu = lambda hs: oracle.filter_prune(hs, 0.5, P.SCOPE_GLOBAL)  # noqa: E731
+            op, F, desc = P.binding.OP_FILTER_PRUNE, sum(t.shape[0] for t in d), "global filter prune d=0.5, theta + mask"
+            cpu = lambda hs: oracle.filter_prune([as_filters(h) for h in hs], 0.5, P.SCOPE_GLOBAL)  # noqa: E731
         else:
-            d = up(host)
+            d = resident if resident is not None else up(host)
             call = lambda: P.condensa_block_prune(d, 8, 8, 0.5, P.SCOPE_GLOBAL, workspace=ws[0], outputs=prev[0], config=cfg)  # noqa: E731
-            op, F = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // 8) * (t.shape[1] // 8) for t in host)
+            op, F = P.binding.OP_BLOCK_PRUNE, sum((t.shape[0] // 8) * (t.shape[1] // 8) for t in d)
             desc = "global block prune 8x8 d=0.5, theta + mask"
             cpu = lambda hs: oracle.block_prune(hs, 8, 8, 0.5, P.SCOPE_GLOBAL)  # noqa: E731
-        head = host[:8]
-        sample = lambda: head  # noqa: E731
+        n_cpu = 8 if resident is None else 2
+        head = host[:n_cpu] if host is not None else None
+        sample = (lambda: head) if head is not None else (lambda: workloads.lc_stress(indices=range(n_cpu), threads=2)[0])  # noqa: E731
         bytes_per_elem = 13                       # the weights are read twice (aggregate, apply): 4 + 4 + 4 theta + 1 mask
     elif name == "single_prune_fp16":
         host = workloads.single_matrix()
@@ -630,12 +631,19 @@ def main():
         del outputs["grad"], outputs["lambda"]      # 9.7 GB back; the weights stay resident for the pruning call
         prune_rec, _ = time_workload("prune_stress", args, P, workloads, torch, dev, args.steps, args.warmup,
                                      resident=w_dev, with_oracle=not args.no_cpu_baseline)
+        structure = []
+        for name in ("filter_stress", "block_stress"):
+            r, _ = time_workload(name, args, P, workloads, torch, dev, args.steps, args.warmup, resident=w_dev,
+                                 with_oracle=not args.no_cpu_baseline)
+            structure.append(r)
         small = []
         for name in SMALL_WORKLOADS:
             r, _ = time_workload(name, args, P, workloads, torch, dev, 50, 5, with_oracle=not args.no_cpu_baseline)
             small.append(r)
-        extras = {"global_prune": prune_rec, "lc_step_pq": pq_rec, "small_workloads": small,
+        extras = {"global_prune": prune_rec, "lc_step_pq": pq_rec, "structure_prune": structure, "small_workloads": small,
                   "note": "global_prune: condensa_prune (theta + mask, d = 0.1) on the weights the L-C step ran on; "
+                          "structure_prune: the same weights as 262144 filters of 512x3x3 and as 18.9 M blocks of 8x8, d = 0.5, "
+                          "against 13 B/weight (the block call reads the weights once and moves 9.3 B/weight); "
                           "small_workloads: wall time per call through the binding (50 calls after 5), launch- and cache-bound"}
 
     # ---- CPU oracle on bounded samples of the same workload ---------------------------------------------------
