@@ -277,6 +277,55 @@ def time_workload(name, args, P, workloads, torch, dev, steps, warmup, resident=
     return rec, t
 
 
+def time_other_entry_points(P, torch, w_dev, dev):
+    """The remaining entry points on the resident stress weights (or on a part of them): codecs, the non-zero
+    count, the L-step update, thinning of one VGG-sized layer.  Kernel time by events on the stream the calls
+    use, outputs allocated by the binding (torch's caching allocator: no device allocation after the first call)."""
+    out = []
+
+    def timed(name, fn, nbytes, n, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        out.append({"entry_point": name, "elements": n, "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes,
+                    "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)})
+
+    ws = list(w_dev)
+    N = sum(t.numel() for t in ws)
+    flat = torch.cat([w.reshape(-1) for w in ws[:16]])        # 302 M weights as one tensor
+    n1 = flat.numel()
+    timed("condensa_quantize (binary16 codes + values)", lambda: P.condensa_quantize(flat), 10 * n1, n1)
+    timed("condensa_quantize (binary16 codes only)", lambda: P.condensa_quantize(flat, want_dq=False), 6 * n1, n1)
+    q16 = P.condensa_quantize(flat, want_dq=False)[0]
+    timed("condensa_dequantize (binary16)", lambda: P.condensa_dequantize(q16), 6 * n1, n1)
+    timed("condensa_quantize_bf16 (codes + values)", lambda: P.condensa_quantize_bf16(flat), 10 * n1, n1)
+    timed("condensa_quantize_fp8 E4M3 (codes + values)", lambda: P.condensa_quantize_fp8(flat, P.FP8_E4M3), 9 * n1, n1)
+    q8 = P.condensa_quantize_fp8(flat, P.FP8_E4M3, want_dq=False)[0]
+    timed("condensa_dequantize_fp8 E4M3", lambda: P.condensa_dequantize_fp8(q8, P.FP8_E4M3), 5 * n1, n1)
+    del flat, q16, q8
+    timed("condensa_count_nonzero (fp32)", lambda: P.condensa_count_nonzero(w_dev), 4 * N, N)
+    half = [w.clone() for w in ws[:32]]                       # the update writes the weights: work on copies
+    gl = [torch.randn_like(w) for w in half]
+    th = [torch.zeros_like(w) for w in half]
+    lam = [torch.zeros_like(w) for w in half]
+    buf = [torch.zeros_like(w) for w in half]
+    n2 = sum(w.numel() for w in half)
+    timed("condensa_lc_sgd_step", lambda: P.condensa_lc_sgd_step(half, gl, th, lam, buf, 1e-3, 0.01, 0.9), 28 * n2, n2)
+    del half, gl, th, lam, buf
+    conv = torch.randn(512, 512, 3, 3, device=dev)
+    keep = torch.arange(0, 512, 2, dtype=torch.int32, device=dev)
+    n3 = 256 * 256 * 9
+    timed("condensa_thin (512x512x3x3 -> 256x256x3x3)", lambda: P.condensa_thin(conv, keep, keep), 8 * n3, n3, reps=20)
+    return out
+
+
 def run_single_workload(args, P, workloads, torch, dev):
     """One entry point alone, same JSON shape as the benchmark line (what the profiler runs wrap)."""
     rec, t = time_workload(args.workload, args, P, workloads, torch, dev, args.steps, args.warmup,
@@ -640,7 +689,9 @@ def main():
         for name in SMALL_WORKLOADS:
             r, _ = time_workload(name, args, P, workloads, torch, dev, 50, 5, with_oracle=not args.no_cpu_baseline)
             small.append(r)
+        others = time_other_entry_points(P, torch, w_dev, dev)
         extras = {"global_prune": prune_rec, "lc_step_pq": pq_rec, "structure_prune": structure, "small_workloads": small,
+                  "other_entry_points": others,
                   "note": "global_prune: condensa_prune (theta + mask, d = 0.1) on the weights the L-C step ran on; "
                           "structure_prune: the same weights as 262144 filters of 512x3x3 and as 18.9 M blocks of 8x8, d = 0.5, "
                           "against 13 B/weight (the block call reads the weights once and moves 9.3 B/weight); "
