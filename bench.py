@@ -676,6 +676,17 @@ def main():
                   "nonzero_codes": int(res_pq[0]["nnz"].item()), "kept": rec["k"],
                   "algorithmic_bytes_per_step": pq_bytes, "algorithmic_GBps": round(pq_bytes / (tpq["mean"] * 1e-3) / 1e9, 1),
                   "frac_of_hbm_peak": round(pq_bytes / (tpq["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        # the same step keeping theta only as binary16 codes (what a P+Q pipeline stores): 8 read + 2 + 4 + 4 written
+        def step_pq_codes():
+            P.condensa_lc_step(w_dev, lam_dev, mu, density, outputs=outputs, theta=False, mask=False, workspace=workspace,
+                               config=cfg_pq, pq=True, nnz=True)
+        tpc = timed_calls(step_pq_codes, args.steps, args.warmup, torch)
+        pc_bytes = (18 if one_sweep else 26) * N
+        pq_rec["codes_only"] = {"workload": "the same step without the fp32 theta (theta as binary16 codes only)",
+                                "ms_per_step": round(tpc["mean"], 4), "ms_per_step_median": round(tpc["median"], 4),
+                                "ms_per_step_min": round(tpc["min"], 4), "algorithmic_bytes_per_step": pc_bytes,
+                                "algorithmic_GBps": round(pc_bytes / (tpc["mean"] * 1e-3) / 1e9, 1),
+                                "frac_of_hbm_peak": round(pc_bytes / (tpc["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         del outputs["theta_f16"], res_pq
         del outputs["grad"], outputs["lambda"]      # 9.7 GB back; the weights stay resident for the pruning call
         prune_rec, _ = time_workload("prune_stress", args, P, workloads, torch, dev, args.steps, args.warmup,
