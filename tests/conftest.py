@@ -10,7 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C-ABI library)")
-    config.addinivalue_line("markers", "slow: long CPU sweep, opt-in through CONDENSA_SLOW=1")
+    config.addinivalue_line("markers", "slow: long exhaustive sweep, opt-in through CONDENSA_SLOW=1")
 
 
 def pytest_collection_modifyitems(config, items):

@@ -46,6 +46,29 @@ def test_stratified_bit_patterns_and_band_sweeps():
         _compare(b.view(np.float32), f"exponent band {e}")
 
 
+@pytest.mark.slow
+def test_every_binary32_pattern_against_numpy():
+    """All 2^32 input patterns (opt-in: CONDENSA_SLOW=1, about four minutes).  The kernels round numbers with the
+    conversion instruction; numpy's conversion, against which the oracle is pinned over the same 2^32 patterns on
+    the CPU, is the fast independent reference here.  NaN inputs (whose payload rule is the oracle's, not numpy's)
+    are compared with the oracle on a sample."""
+    step = 1 << 28
+    for start in range(0, 1 << 32, step):
+        print(f"patterns from {start:#010x}", flush=True)     # (a long quiet test looks hung to a watchdog)
+        bits = np.arange(start, start + step, dtype=np.uint64).astype(np.uint32)
+        x = bits.view(np.float32)
+        q, dq = _run(x)
+        nan = np.isnan(x)
+        with np.errstate(over="ignore"):
+            ref = x.astype(np.float16)
+        assert np.array_equal(q[~nan], ref.view(np.uint16)[~nan]), hex(start)
+        assert np.array_equal(dq[~nan].view(np.uint32), ref.astype(np.float32).view(np.uint32)[~nan]), hex(start)
+        if nan.any():
+            idx = np.flatnonzero(nan)[:: 4099]
+            oq, odq = oracle.quantize_f16(x[idx])
+            assert np.array_equal(q[idx], oq) and np.array_equal(dq[idx].view(np.uint32), odq.view(np.uint32)), hex(start)
+
+
 def test_ragged_sizes_and_misaligned_views():
     rng = np.random.default_rng(5)
     for n in (1, 2, 3, 5, 255, 1023, 1025, 8191, 70001):
