@@ -23,6 +23,9 @@ def build(verbose: bool = False) -> str:
         # the compiler's own non-temporal stores instead of the buffer stores with system-scope bits: a build to
         # cross-check a parity failure against (csrc/common.h)
         flags.append("-DCONDENSA_PLAIN_STREAM_STORES")
+    if os.environ.get("CONDENSA_INTEGER_F16") == "1":
+        # binary16 rounding and widening in integer arithmetic throughout, instead of the conversion instructions
+        flags.append("-DCONDENSA_INTEGER_F16")
     cmd = [hipcc] + flags + ["-o", LIB, SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops"
