@@ -478,9 +478,10 @@ def condensa_lc_step(tensors, lambdas, mu, density, lambda_out=None, in_place=Fa
     tab = _tensor_table(tensors)
     total = _total(tensors)
     outputs = outputs or {}
-    th = outputs.get("theta") or ([torch.empty_like(t) for t in tensors] if theta else None)
-    gr = outputs.get("grad") or ([torch.empty_like(t) for t in tensors] if grad else None)
-    mk = outputs.get("mask") or ([torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors] if mask else None)
+    # an output that is switched off is not written, whether or not `outputs` holds buffers for it
+    th = (outputs.get("theta") or [torch.empty_like(t) for t in tensors]) if theta else None
+    gr = (outputs.get("grad") or [torch.empty_like(t) for t in tensors]) if grad else None
+    mk = (outputs.get("mask") or [torch.empty(t.shape, dtype=torch.uint8, device=dev) for t in tensors]) if mask else None
     if in_place:
         lo = None
     else:

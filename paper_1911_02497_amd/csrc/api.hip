@@ -462,6 +462,7 @@ static condensa_status run_selection(DataArgs a, const Layout& L, void* ws, bool
 // of densities.  One density breaks even near 2^26 element reads, four near 2^27.5, ten near 2^30.
 static bool want_window(u64 N, bool per_tensor, int J, bool lc, const Config& cfg) {
     if (per_tensor) return false;
+    if ((N >> kCandTensorShift) != 0) return false;        // candidates carry their tensor above a 44-bit flat index
     const int64_t mode = cfg[CONDENSA_OPT_SELECT_PATH];
     if (mode == 1) return false;
     if (mode == 2) return N >= 1;

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
             if (cmask & (1u << (q * 4 + k))) {
                 if (pos < w.seg_cap) {
                     w.cand_key[first + pos] = key[q][k];
-                    w.cand_idx[first + pos] = td.flat_start + base + static_cast<u64>(q) * 256 + lane * 4 + k;
+                    w.cand_idx[first + pos] = cand_pack(td.flat_start + base + static_cast<u64>(q) * 256 + lane * 4 + k, t);
                     w.cand_w[first + pos] = wk[q][k];
                     if (LC) w.cand_lam[first + pos] = lk[q][k];
                 }
@@ -171,17 +171,6 @@ __global__ __launch_bounds__(64) void k_window_fused(DataArgs a, WindowArgs w) {
             }
         }
     }
-}
-
-// Tensor that owns flat index i: largest t with flat_start[t] <= i (empty tensors share a start with
-// their successor and are skipped by taking the largest).
-__device__ inline int tensor_of_flat(const TensorDesc* __restrict__ td, int n_tensors, u64 i) {
-    int lo = 0, hi = n_tensors - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (td[mid].flat_start <= i) lo = mid; else hi = mid - 1;
-    }
-    return lo;
 }
 
 constexpr unsigned kFixupParts = 4;   // workgroups per candidate segment in the fix-up pass (2, 4, 8 measure alike:
@@ -212,10 +201,11 @@ __global__ __launch_bounds__(kBlock) void k_window_fixup(DataArgs a, WindowArgs 
             const bool was_kept = key > mid;
             if (was_kept && key > T) continue;             // most candidates: decided without their index
             if (!was_kept && key < T) continue;
-            const u64 idx = w.cand_idx[first + i];
+            const u64 packed = w.cand_idx[first + i];
+            const u64 idx = cand_flat(packed);
             const bool keep = keep_rule(key, T, idx, tie_end);
             if (keep == was_kept) continue;
-            const int t = tensor_of_flat(a.td, a.n_tensors, idx);
+            const int t = cand_tensor(packed);
             const TensorDesc& td = a.td[t];
             const u64 e = idx - td.flat_start;
             const OutDesc o = w.out[t];

@@ -23,12 +23,20 @@ constexpr int kArrayThreads = 1024;     // workgroup of the array kernels: wide,
                                        // LDS histograms with (slow, memory-side) global atomics
 constexpr int kSegs = 1024;            // candidate list segments / counter sets (see k_window_sweep)
 
+// The one-density fused sweep stores a candidate's tensor above its flat index, so that the fix-up pass need not
+// search the tensor table for it (flat indices stay below 2^44, tensor numbers below 2^20: checked by the host).
+constexpr int kCandTensorShift = 44;
+static_assert(CONDENSA_MAX_TENSORS <= (1 << (64 - kCandTensorShift)), "tensor numbers must fit above the flat index");
+__device__ inline u64 cand_pack(u64 flat, int t) { return flat | (static_cast<u64>(t) << kCandTensorShift); }
+__device__ inline u64 cand_flat(u64 packed) { return packed & ((static_cast<u64>(1) << kCandTensorShift) - 1); }
+__device__ inline int cand_tensor(u64 packed) { return static_cast<int>(packed >> kCandTensorShift); }
+
 struct SortedWindows;
 
 struct WindowArgs {
     u32* sample;           // [n_units * kSampleUnit]
     u32* cand_key;         // [cand_cap]
-    u64* cand_idx;         // [cand_cap]
+    u64* cand_idx;         // [cand_cap] flat indices (fused sweep: cand_pack)
     Slot* wslots;          // [2J] boundary rankings, later [J] index rankings
     u64* seg_cnt;          // [kSegs] candidates appended to each segment (may exceed seg_cap)
     u64* seg_region;       // [kMaxJ + 1][kSegs] keys per region (region i: i windows have an upper bound >= key)
@@ -769,7 +777,7 @@ __global__ __launch_bounds__(kBlock) void k_window_ties(DataArgs a, WindowArgs w
             const u32 blo = __shfl(static_cast<u32>(b), leader, 64), bhi = __shfl(static_cast<u32>(b >> 32), leader, 64);
             if (hit) {
                 const u64 pos = ((static_cast<u64>(bhi) << 32) | blo) + __popcll(ballot & ((static_cast<u64>(1) << lane) - 1));
-                if (pos < w.tie_cap) w.tie_list[pos] = w.cand_idx[first + i];
+                if (pos < w.tie_cap) w.tie_list[pos] = cand_flat(w.cand_idx[first + i]);
             }
         }
     }
