@@ -115,6 +115,28 @@ def test_pq_step_against_the_oracle():
         assert nnz32 == oracle.count_nonzero(ora["theta"])
 
 
+def test_pq_step_with_theta_as_codes_only_leaves_reused_buffers_alone():
+    """theta=False with an earlier call's buffers passed back in: the fp32 theta is not written (its buffer
+    keeps what it held), the codes, the multipliers, the penalty gradient and the count are the oracle's."""
+    shapes = [(8192 * 3 + 5,), (129, 67)]
+    ws, ls = _gauss(shapes, 21, 0.01), _gauss(shapes, 22, 0.01)
+    dw, dl = up(ws), up(ls)
+    first = lc_step_pq(dw, dl, 1e-3, 0.5, nnz=True)
+    torch.cuda.synchronize()
+    for t in first["theta"]:
+        t.fill_(7.0)
+    res = lc_step_pq(dw, dl, 1e-3, 0.1, nnz=True, theta=False, mask=False, outputs=first)
+    torch.cuda.synchronize()
+    ora = oracle.lc_step_pq(ws, ls, 1e-3, 0.1)
+    assert res["theta"] is None and res["mask"] is None
+    for t in range(len(ws)):
+        assert bool((first["theta"][t] == 7.0).all()), "the switched-off output was written"
+        assert np.array_equal(res["theta_f16"][t].cpu().numpy().view(np.uint16), ora["theta_f16"][t]), f"theta16 {t}"
+        assert_bits_equal(res["lambda"][t], ora["lambda"][t], f"lambda {t}")
+        assert_bits_equal(res["grad"][t], ora["grad"][t], f"grad {t}")
+    assert int(res["nnz"].item()) == oracle.count_nonzero(ora["theta_f16"])
+
+
 def test_count_nonzero_edge_cases():
     x = torch.tensor([0.0, -0.0, 1e-30, -2.0, 3.0, float("nan")], device=DEV)
     assert int(P.condensa_count_nonzero([x]).item()) == 4
